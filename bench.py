@@ -1,0 +1,171 @@
+#!/usr/bin/env python3
+"""Benchmark of the Flattened Window Attention block on one MI355X.
+
+One "step" = one pass of the whole hot path over one synthetic frame: the sorts of the block
+(window keys, radix argsort, grouping; each distinct (axis, shift) pair once) followed by the
+layer stack (gather, LayerNorm, QKV, softmax attention, out-proj, FFN, scatter per layer).
+Inputs are resident in HBM before the timed region.  Prints ONE JSON line.
+
+    python bench.py [--gpus 1] [--steps K] [--warmup W] [--config 2] [--no-cpu] [--sweep]
+"""
+import argparse
+import json
+import os
+import sys
+import time
+
+ROOT = os.path.dirname(os.path.abspath(__file__))
+sys.path.insert(0, ROOT)
+
+PEAK_HBM_GBS = 8000.0          # MI355X HBM3E
+PEAK_BF16_TFLOPS = 2500.0      # dense bf16 MFMA
+PEAK_F32_TFLOPS = 157.3        # fp32 vector / MFMA
+
+
+def layer_flops_per_voxel(C, F, G):
+    # QKV 6C^2 + QK^T 2GC + PV 2GC + out-proj 2C^2 + FFN 4CF (multiply-add = 2 flops)
+    return 8 * C * C + 4 * G * C + 4 * C * F
+
+
+def time_region(fn, steps, warmup):
+    import torch
+    for _ in range(warmup):
+        fn()
+    torch.cuda.synchronize()
+    e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+    t0 = time.perf_counter()
+    e0.record()
+    for _ in range(steps):
+        fn()
+    e1.record()
+    torch.cuda.synchronize()
+    wall = (time.perf_counter() - t0) * 1e3
+    return e0.elapsed_time(e1) / steps, wall / steps
+
+
+def cpu_baseline(c, budget_s=20.0):
+    """The oracle as it stands, timed on this host: whole frames of the same workload."""
+    import numpy as np
+    import oracle
+    try:
+        from threadpoolctl import threadpool_info
+        cores = max([int(t.get("num_threads", 1)) for t in threadpool_info()] + [1])
+    except Exception:
+        cores = 1
+    og = oracle.Geometry(c["B"], c["grid"], c["grid"], c["window"], c["window"])
+
+    def one_frame():
+        perms, offs = {}, {}
+        for key in dict.fromkeys(c["schedule"]):
+            perms[key], offs[key], _ = oracle.flatten(c["coords"], og, key[0], key[1], c["G"])
+        oracle.stack(c["feats"], perms, offs, c["layer_params"], c["schedule"])
+
+    t0 = time.perf_counter()
+    one_frame()
+    first = time.perf_counter() - t0
+    reps = int(max(1, min(10, (budget_s - first) // max(first, 1e-3))))
+    t0 = time.perf_counter()
+    for _ in range(reps):
+        one_frame()
+    dt = (time.perf_counter() - t0) / reps
+    return {"value": c["n"] / dt, "unit": "voxels/s", "cores": cores, "kind": "oracle",
+            "sample": f"{reps} whole frame(s) of the same workload after 1 warm-up frame "
+                      f"({c['n']} voxels, {len(c['schedule'])} layers, float64 numpy + tuple sort)"}
+
+
+def main():
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=50)
+    ap.add_argument("--warmup", type=int, default=10)
+    ap.add_argument("--config", type=int, default=2)
+    ap.add_argument("--no-cpu", action="store_true")
+    ap.add_argument("--sweep", action="store_true", help="also print per-kernel lines for larger batches (stderr)")
+    a = ap.parse_args()
+    if a.gpus != 1:
+        print("bench.py measures one GPU: this build has no multi-GPU path (run with --gpus 1)", file=sys.stderr)
+        sys.exit(2)
+
+    import numpy as np
+    import torch
+    import ffsynth
+    import paper_2301_08739_amd as ff
+
+    ff.load_library()
+    assert torch.cuda.is_available(), "bench.py needs a GPU"
+    dev = torch.device("cuda:0")
+    c = ffsynth.make_config(a.config)
+    n, C, F, G, L = c["n"], c["C"], c["F"], c["G"], len(c["schedule"])
+    dt = ff.FF_F32 if c["dtype"] == "f32" else ff.FF_BF16
+    tdt = torch.float32 if dt == ff.FF_F32 else torch.bfloat16
+    esz = 4 if dt == ff.FF_F32 else 2
+    geom = ff.Geometry(c["B"], c["grid"], c["grid"], c["window"], c["window"])
+    coords = torch.from_numpy(c["coords"]).to(dev)
+    feats = torch.from_numpy(c["feats"]).to(dev).to(tdt)
+    layers = [ff.LayerWeights(p, dt, dev) for p in c["layer_params"]]
+    out = torch.empty_like(feats)
+    ws = torch.empty(ff.ff_fwa_block_workspace_bytes(n, geom, G, layers, dt) + 512, dtype=torch.uint8, device=dev)
+
+    def step():
+        ff.ff_fwa_block(coords, geom, G, layers, dt, feats, out=out, workspace=ws)
+
+    ms, wall_ms = time_region(step, a.steps, a.warmup)
+
+    # ---- per-part timings, same launch configuration as inside the block ----
+    perm, goff, ng, _ = ff.ff_flatten(coords, geom, 0, 0, G)
+    torch.cuda.synchronize()
+    max_groups = -(-n // G) + c["B"]
+    fws = torch.empty(ff.ff_flatten_workspace_bytes(n, geom) + 512, dtype=torch.uint8, device=dev)
+    lws = torch.empty(ff.ff_group_attention_workspace_bytes(n, G, layers[0], dt) + 512, dtype=torch.uint8, device=dev)
+    gth = torch.empty_like(feats)
+    reps = max(a.steps, 20)
+    ms_flat, _ = time_region(lambda: ff.ff_flatten(coords, geom, 0, 1, G, workspace=fws), reps, 5)
+    ms_layer, _ = time_region(lambda: ff.ff_group_attention(feats, perm, goff, ng, max_groups, layers[0], G, dt,
+                                                            out=out, workspace=lws), reps, 5)
+    ms_gather, _ = time_region(lambda: ff.ff_gather(feats, perm, dt, out=gth), reps, 5)
+    ms_scatter, _ = time_region(lambda: ff.ff_scatter(gth, perm, dt, out=out), reps, 5)
+
+    flops_layer = layer_flops_per_voxel(C, F, G) * n
+    passes = -(-max(1, sum(int(np.ceil(np.log2(max(v, 2)))) for v in (
+        c["B"] if c["B"] > 1 else 1,)) + 0) // 8)  # placeholder, replaced below
+    # live key bits -> radix passes (8 bits each), shifted geometry
+    def bits(v):
+        return int(v - 1).bit_length() if v > 1 else 0
+    s = c["window"] // 2
+    nw = -(-(c["grid"] + s) // c["window"])
+    live = bits(c["B"]) + 2 * bits(nw) + 2 * bits(c["window"])
+    passes = -(-live // 8)
+    bytes_flat = (28 + 24 * passes) * n
+    bytes_rows = (2 * C * esz + 4) * n
+    peak_tf = PEAK_F32_TFLOPS if dt == ff.FF_F32 else PEAK_BF16_TFLOPS
+    ach_tf = flops_layer / (ms_layer * 1e-3) / 1e12
+
+    res = {
+        "metric": "FWA block voxels/sec at 30k pillars C=128 G=64; %HBM BW sort, %MFMA attn",
+        "value": n / (ms * 1e-3), "unit": "voxels/s", "n_gpus": 1, "steps": a.steps, "warmup": a.warmup,
+        "ms_per_step": ms, "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
+        "dtype": "f32" if dt == ff.FF_F32 else "bf16", "data": "synthetic",
+        "config": {"workload": f"config {a.config} ({c['name']}): {n} pillars on {c['grid']}x{c['grid']}, "
+                               f"B={c['B']}, window {c['window']}x{c['window']}, G={G}, C={C}, heads={c['heads']}, "
+                               f"F={F}, {L} layers (x, y, shifted x, shifted y ...), "
+                               f"{len(dict.fromkeys(c['schedule']))} sorts + {L} layers per step"},
+        "roofline": {"bound": "mfma", "kernel": "group attention layer (ff_group_attention, one launch)",
+                     "achieved": ach_tf, "peak": peak_tf, "unit": "TFLOP/s", "frac": ach_tf / peak_tf,
+                     "traffic": None, "ms": ms_layer, "flops": flops_layer},
+        "parts": {
+            "flatten": {"ms": ms_flat, "bytes": bytes_flat, "GBps": bytes_flat / (ms_flat * 1e-3) / 1e9,
+                        "frac_hbm": bytes_flat / (ms_flat * 1e-3) / 1e9 / PEAK_HBM_GBS, "radix_passes_credited": passes},
+            "gather": {"ms": ms_gather, "bytes": bytes_rows, "GBps": bytes_rows / (ms_gather * 1e-3) / 1e9,
+                       "frac_hbm": bytes_rows / (ms_gather * 1e-3) / 1e9 / PEAK_HBM_GBS},
+            "scatter": {"ms": ms_scatter, "bytes": bytes_rows, "GBps": bytes_rows / (ms_scatter * 1e-3) / 1e9,
+                        "frac_hbm": bytes_rows / (ms_scatter * 1e-3) / 1e9 / PEAK_HBM_GBS},
+            "wall_ms_per_step": wall_ms,
+        },
+    }
+    if not a.no_cpu:
+        res["cpu_baseline"] = cpu_baseline(c)
+    print(json.dumps(res), flush=True)
+
+
+if __name__ == "__main__":
+    main()

@@ -1,0 +1,158 @@
+/*
+ * flatformer.h -- C ABI of the MI355X (gfx950) Flattened Window Attention library.
+ *
+ * The library implements the hot path of FlatFormer's Flattened Window Attention
+ * (paper Sec. 4.2): window-based sorting of sparse BEV pillars, equal-size
+ * grouping of the sorted order, and a pre-LayerNorm transformer layer applied
+ * independently inside every group.
+ *
+ * Conventions shared by every entry point
+ *  - Pointers are DEVICE pointers unless the parameter is a struct passed by the
+ *    host (ff_geom, ff_layer_weights: host structs whose pointer members are
+ *    device pointers).  `stream` is a hipStream_t passed as void* (NULL = the
+ *    default stream).
+ *  - Ownership: the caller allocates and owns every buffer, including the
+ *    workspace.  The library never allocates or frees device memory and never
+ *    synchronises the stream; outputs are valid once the stream reaches the
+ *    point after the call.
+ *  - Errors: every function returns an ff_status (0 = success, negative =
+ *    failure).  Preconditions that can be checked on the host are checked before
+ *    anything is launched; on FF_ERR_ARG / FF_ERR_UNSUPPORTED / FF_ERR_WORKSPACE
+ *    nothing has been written.  The library never throws and never aborts.
+ *  - Row-major everywhere.  Linear layers follow y = x * W^T + b with W stored
+ *    [out_features, in_features].
+ */
+#ifndef FLATFORMER_H
+#define FLATFORMER_H
+
+#include <stddef.h>
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+typedef enum {
+  FF_OK = 0,
+  FF_ERR_ARG = -1,         /* null pointer, negative size, inconsistent shape   */
+  FF_ERR_UNSUPPORTED = -2, /* valid request outside the built kernels' limits   */
+  FF_ERR_WORKSPACE = -3,   /* workspace missing, misaligned or too small        */
+  FF_ERR_LAUNCH = -4       /* the HIP runtime refused a launch                  */
+} ff_status;
+
+typedef enum { FF_F32 = 0, FF_BF16 = 1 } ff_dtype;
+
+typedef enum {
+  FF_TAIL_MASK = 0, /* a frame's last group may be short; it attends over its real members only */
+  FF_TAIL_DROP = 1  /* short groups are left out ('Drop Residual', Sec. 4.3); not built yet      */
+} ff_tail;
+
+/* Geometry of the BEV grid.  coords[:,0] in [0,num_frames), coords[:,1] in
+ * [0,grid_x), coords[:,2] in [0,grid_y).  Window sizes 1..256.  Limits:
+ * num_frames <= 65535 and at most 65535 windows per axis (the exported key has
+ * 16-bit frame and window fields and 8-bit in-window fields). */
+typedef struct {
+  int32_t num_frames;
+  int32_t grid_x, grid_y;
+  int32_t win_x, win_y;
+} ff_geom;
+
+/* ---- window-based sorting + equal-size grouping (Sec. 4.2.1, Eq. (1)) -------------------
+ *
+ * For pillar i with (b, x, y):  X = x + sx, Y = y + sy, where (sx, sy) = (win_x/2, win_y/2)
+ * rounded down when `shift` is set (Sec. 4.2.2 'Window Shift') and (0,0) otherwise;
+ * (Wx, Lx) = divmod(X, win_x), (Wy, Ly) = divmod(Y, win_y).  The sort tuple is
+ * (b, Wx, Wy, Lx, Ly) for axis 0 and (b, Wy, Wx, Ly, Lx) for axis 1 ('Alternate Sorting
+ * Axis'); equal tuples keep ascending original index.  The exported key packs the tuple as
+ * b<<48 | t1<<32 | t2<<16 | t3<<8 | t4.
+ *
+ *   perm[p]          original index of the pillar at sorted position p            [n]
+ *   group_offsets    start of every group in the sorted order, then n             [>= ceil(n/G)+num_frames+1]
+ *                    (only the first *num_groups + 1 entries are written)
+ *   num_groups       number of groups = sum over frames of ceil(n_b / G)          [1]
+ *   keys_sorted      exported key of every sorted position, or NULL               [n]
+ *
+ * Groups never cross frames; within a frame they are consecutive runs of G sorted pillars,
+ * the last one possibly shorter ('Equal-Size Grouping').  n == 0 is legal (num_groups = 0,
+ * group_offsets[0] = 0).  Duplicate coordinates are legal.  Coordinates outside the geometry
+ * give an unspecified (but still bijective) perm; no memory outside the buffers is touched.
+ *
+ * Limit: bits(key fields actually used) + bits(n-1) must not exceed 64 (FF_ERR_UNSUPPORTED
+ * otherwise); every configuration with n < 2^24 and fewer than 2^40 cells satisfies it.
+ * workspace: ff_flatten_workspace_bytes(n, g) bytes, 256-byte aligned.
+ */
+size_t ff_flatten_workspace_bytes(int64_t n, const ff_geom* g);
+
+int ff_flatten(const int32_t* coords /* [n,3] (b,x,y) */, int64_t n, const ff_geom* g,
+               int axis /* 0: x-major, 1: y-major */, int shift /* 0 | 1 */,
+               int G, int tail /* ff_tail */,
+               int32_t* perm, int32_t* group_offsets, int32_t* num_groups,
+               uint64_t* keys_sorted, void* workspace, size_t workspace_bytes, void* stream);
+
+/* ---- group attention layer (Sec. 4.2.2, Eq. (2)) --------------------------------------------
+ *
+ *   F'  = F  + MHSA(LN1(F))      softmax(Q K^T / sqrt(d)) V per head, inside each group
+ *   F'' = F' + FFN(LN2(F'))      FFN = Linear(C->F) -> GELU(erf form) -> Linear(F->C)
+ *
+ * All parameter arrays have the element type `dtype` of the call.  LayerNorm uses the
+ * biased variance and ln_eps.  w_qkv rows [0,C) are the query projection, [C,2C) key,
+ * [2C,3C) value; head h owns rows h*d..(h+1)*d-1 of each third, d = C / heads.
+ * The positional-embedding term of Eq. (2) is not part of this entry point.
+ */
+typedef struct {
+  const void *ln1_g, *ln1_b; /* [C]            */
+  const void *w_qkv, *b_qkv; /* [3C, C], [3C]  */
+  const void *w_o, *b_o;     /* [C, C],  [C]   */
+  const void *ln2_g, *ln2_b; /* [C]            */
+  const void *w1, *b1;       /* [F, C],  [F]   */
+  const void *w2, *b2;       /* [C, F],  [C]   */
+  int32_t C, F, heads;
+  float ln_eps;
+} ff_layer_weights;
+
+/* Flags of ff_group_attention. */
+#define FF_FLAG_OUT_F32 1u      /* store `out` as float32 even when dtype is FF_BF16 */
+#define FF_FLAG_FORCE_GENERIC 2u /* use the plain fp32-arithmetic kernels for any dtype */
+
+size_t ff_group_attention_workspace_bytes(int64_t n, int G, const ff_layer_weights* w, int dtype);
+
+/* feats [n,C] and out [n,C] are in pillar order and must not overlap: a group reads rows that
+ * other groups write.  Row perm[p] of feats is member p of the sorted order; group g owns
+ * sorted positions group_offsets[g] .. group_offsets[g+1]-1 (1..G of them).  num_groups is the
+ * device scalar written by ff_flatten; max_groups is a host upper bound used to size the launch
+ * (e.g. ceil(n/G) + num_frames).  Every row that belongs to a group is written exactly once.
+ * dtype FF_F32: fp32 arithmetic throughout.  FF_BF16: bf16 storage, bf16 MFMA operands, fp32
+ * accumulation, statistics, softmax and GELU.
+ * Limits (FF_ERR_UNSUPPORTED otherwise): C % heads == 0, C*sizeof(dtype) % 16 == 0, 1 <= G <= 1024. */
+int ff_group_attention(const void* feats, void* out, int64_t n,
+                       const int32_t* perm, const int32_t* group_offsets,
+                       const int32_t* num_groups, int32_t max_groups,
+                       const ff_layer_weights* w, int G, int dtype, uint32_t flags,
+                       void* workspace, size_t workspace_bytes, void* stream);
+
+/* ---- row gather / scatter (the 'reshape' of Sec. 4.2.1 made explicit) ---------------------------
+ * gather:  dst[p, :] = src[perm[p], :]     scatter:  dst[perm[p], :] = src[p, :]
+ * C * sizeof(dtype) must be a multiple of 16; src and dst must not overlap. */
+int ff_gather(const void* src, void* dst, const int32_t* perm, int64_t n, int C, int dtype, void* stream);
+int ff_scatter(const void* src, void* dst, const int32_t* perm, int64_t n, int C, int dtype, void* stream);
+
+/* ---- the whole block: sorts computed once and reused, then the layer stack ------------------
+ * Layer l sorts along axis l % 2 with the shift on when (l / 2) % 2 == 1 (x, y, shifted x,
+ * shifted y, x, ...); each distinct (axis, shift) pair is flattened once and reused by every
+ * layer that needs it ('Reuse Sorting', Sec. 4.3).  layers: host array of num_layers structs.
+ * feats_in / feats_out: [n, C] in pillar order, must not overlap. */
+size_t ff_fwa_block_workspace_bytes(int64_t n, const ff_geom* g, int G,
+                                    const ff_layer_weights* layers, int num_layers, int dtype);
+
+int ff_fwa_block(const int32_t* coords, int64_t n, const ff_geom* g, int G,
+                 const ff_layer_weights* layers, int num_layers, int dtype,
+                 const void* feats_in, void* feats_out,
+                 void* workspace, size_t workspace_bytes, void* stream);
+
+const char* ff_status_string(int status);
+int ff_version(void);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* FLATFORMER_H */

@@ -1,0 +1,20 @@
+"""MI355X-native Flattened Window Attention: thin Python binding over libflatformer.so.
+
+Every step of the path (key generation, radix argsort, grouping, gather, the attention layer,
+scatter) runs in the library's HIP kernels; this package only marshals arguments.  PyTorch is
+used for device memory and streams.  There is no CPU fallback: calling anything here without the
+built library raises.
+"""
+from .binding import (Geometry, LayerWeights, FF_F32, FF_BF16, FF_FLAG_OUT_F32, FF_FLAG_FORCE_GENERIC,
+                      FlatformerError, load_library, library_path, exported_symbols,
+                      ff_flatten, ff_flatten_workspace_bytes, ff_group_attention,
+                      ff_group_attention_workspace_bytes, ff_gather, ff_scatter, ff_fwa_block,
+                      ff_fwa_block_workspace_bytes, ff_status_string, ff_version)
+
+__all__ = [
+    "Geometry", "LayerWeights", "FF_F32", "FF_BF16", "FF_FLAG_OUT_F32", "FF_FLAG_FORCE_GENERIC",
+    "FlatformerError", "load_library", "library_path", "exported_symbols",
+    "ff_flatten", "ff_flatten_workspace_bytes", "ff_group_attention",
+    "ff_group_attention_workspace_bytes", "ff_gather", "ff_scatter", "ff_fwa_block",
+    "ff_fwa_block_workspace_bytes", "ff_status_string", "ff_version",
+]

@@ -1,0 +1,214 @@
+"""ctypes binding of include/flatformer.h.  Argument marshalling only."""
+import ctypes as C
+import os
+
+import torch
+
+HERE = os.path.dirname(os.path.abspath(__file__))
+_LIB_PATH = os.path.join(HERE, "libflatformer.so")
+_lib = None
+
+FF_F32, FF_BF16 = 0, 1
+FF_TAIL_MASK, FF_TAIL_DROP = 0, 1
+FF_FLAG_OUT_F32, FF_FLAG_FORCE_GENERIC = 1, 2
+
+
+class FlatformerError(RuntimeError):
+    pass
+
+
+class Geometry(C.Structure):
+    """ff_geom"""
+    _fields_ = [("num_frames", C.c_int32), ("grid_x", C.c_int32), ("grid_y", C.c_int32),
+                ("win_x", C.c_int32), ("win_y", C.c_int32)]
+
+
+class _LayerWeightsC(C.Structure):
+    _fields_ = [(k, C.c_void_p) for k in ("ln1_g", "ln1_b", "w_qkv", "b_qkv", "w_o", "b_o",
+                                          "ln2_g", "ln2_b", "w1", "b1", "w2", "b2")] + \
+               [("C", C.c_int32), ("F", C.c_int32), ("heads", C.c_int32), ("ln_eps", C.c_float)]
+
+
+_PARAMS = ("ln1_g", "ln1_b", "w_qkv", "b_qkv", "w_o", "b_o", "ln2_g", "ln2_b", "w1", "b1", "w2", "b2")
+
+
+class LayerWeights:
+    """Device tensors of one layer plus the ff_layer_weights struct that points at them."""
+
+    def __init__(self, params, dtype, device="cuda"):
+        tdt = torch.float32 if dtype == FF_F32 else torch.bfloat16
+        self.dtype = dtype
+        self.tensors = {k: torch.as_tensor(params[k], dtype=torch.float32).to(device=device, dtype=tdt).contiguous()
+                        for k in _PARAMS}
+        self.C, self.F, self.heads = int(params["C"]), int(params["F"]), int(params["heads"])
+        self.ln_eps = float(params["ln_eps"])
+
+    def struct(self):
+        s = _LayerWeightsC()
+        for k in _PARAMS:
+            setattr(s, k, self.tensors[k].data_ptr())
+        s.C, s.F, s.heads, s.ln_eps = self.C, self.F, self.heads, self.ln_eps
+        return s
+
+
+_SIGS = {
+    "ff_flatten_workspace_bytes": (C.c_size_t, [C.c_int64, C.POINTER(Geometry)]),
+    "ff_flatten": (C.c_int, [C.c_void_p, C.c_int64, C.POINTER(Geometry), C.c_int, C.c_int, C.c_int, C.c_int,
+                             C.c_void_p, C.c_void_p, C.c_void_p, C.c_void_p, C.c_void_p, C.c_size_t, C.c_void_p]),
+    "ff_group_attention_workspace_bytes": (C.c_size_t, [C.c_int64, C.c_int, C.POINTER(_LayerWeightsC), C.c_int]),
+    "ff_group_attention": (C.c_int, [C.c_void_p, C.c_void_p, C.c_int64, C.c_void_p, C.c_void_p, C.c_void_p,
+                                     C.c_int32, C.POINTER(_LayerWeightsC), C.c_int, C.c_int, C.c_uint32,
+                                     C.c_void_p, C.c_size_t, C.c_void_p]),
+    "ff_gather": (C.c_int, [C.c_void_p, C.c_void_p, C.c_void_p, C.c_int64, C.c_int, C.c_int, C.c_void_p]),
+    "ff_scatter": (C.c_int, [C.c_void_p, C.c_void_p, C.c_void_p, C.c_int64, C.c_int, C.c_int, C.c_void_p]),
+    "ff_fwa_block_workspace_bytes": (C.c_size_t, [C.c_int64, C.POINTER(Geometry), C.c_int,
+                                                   C.POINTER(_LayerWeightsC), C.c_int, C.c_int]),
+    "ff_fwa_block": (C.c_int, [C.c_void_p, C.c_int64, C.POINTER(Geometry), C.c_int, C.POINTER(_LayerWeightsC),
+                               C.c_int, C.c_int, C.c_void_p, C.c_void_p, C.c_void_p, C.c_size_t, C.c_void_p]),
+    "ff_status_string": (C.c_char_p, [C.c_int]),
+    "ff_version": (C.c_int, []),
+}
+
+
+def library_path():
+    return _LIB_PATH
+
+
+def exported_symbols():
+    return tuple(_SIGS)
+
+
+def load_library():
+    """Load libflatformer.so (built by paper_2301_08739_amd.build).  Raises if it is missing."""
+    global _lib
+    if _lib is None:
+        if not os.path.exists(_LIB_PATH):
+            raise FlatformerError(f"{_LIB_PATH} not built: run `python -m paper_2301_08739_amd.build`")
+        lib = C.CDLL(_LIB_PATH)
+        for name, (res, args) in _SIGS.items():
+            fn = getattr(lib, name)
+            fn.restype, fn.argtypes = res, args
+        _lib = lib
+    return _lib
+
+
+def ff_status_string(status):
+    return load_library().ff_status_string(int(status)).decode()
+
+
+def ff_version():
+    return load_library().ff_version()
+
+
+def _check(st, what):
+    if st != 0:
+        raise FlatformerError(f"{what}: {ff_status_string(st)} ({st})")
+
+
+def _stream():
+    return C.c_void_p(torch.cuda.current_stream().cuda_stream)
+
+
+def _ptr(t):
+    return C.c_void_p(0 if t is None else t.data_ptr())
+
+
+def _workspace(nbytes, device):
+    return torch.empty(max(int(nbytes), 256) + 256, dtype=torch.uint8, device=device)
+
+
+def _aligned_ptr(ws):
+    p = ws.data_ptr()
+    return (p + 255) // 256 * 256
+
+
+def ff_flatten_workspace_bytes(n, geom):
+    return load_library().ff_flatten_workspace_bytes(int(n), C.byref(geom))
+
+
+def ff_flatten(coords, geom, axis, shift, G, tail=FF_TAIL_MASK, want_keys=False, workspace=None):
+    """coords: int32 cuda tensor [n,3].  Returns (perm, group_offsets, num_groups, keys_sorted|None),
+    all device tensors; group_offsets has capacity ceil(n/G)+num_frames+1."""
+    lib = load_library()
+    assert coords.dtype == torch.int32 and coords.is_contiguous() and coords.is_cuda
+    n = coords.shape[0]
+    dev = coords.device
+    cap = -(-n // max(G, 1)) + geom.num_frames + 1
+    perm = torch.empty(n, dtype=torch.int32, device=dev)
+    goff = torch.full((cap,), -1, dtype=torch.int32, device=dev)
+    ng = torch.full((1,), -1, dtype=torch.int32, device=dev)
+    keys = torch.empty(n, dtype=torch.int64, device=dev) if want_keys else None
+    need = lib.ff_flatten_workspace_bytes(n, C.byref(geom))
+    ws = workspace if workspace is not None else _workspace(need, dev)
+    st = lib.ff_flatten(_ptr(coords), n, C.byref(geom), axis, shift, G, tail, _ptr(perm), _ptr(goff), _ptr(ng),
+                        _ptr(keys), C.c_void_p(_aligned_ptr(ws)), ws.numel() - 256, _stream())
+    _check(st, "ff_flatten")
+    return perm, goff, ng, keys
+
+
+def ff_group_attention_workspace_bytes(n, G, weights, dtype):
+    s = weights.struct()
+    return load_library().ff_group_attention_workspace_bytes(int(n), int(G), C.byref(s), dtype)
+
+
+def ff_group_attention(feats, perm, group_offsets, num_groups, max_groups, weights, G, dtype,
+                       flags=0, out=None, workspace=None):
+    """feats [n,C] (float32 or bfloat16 per dtype) -> out [n,C] in pillar order."""
+    lib = load_library()
+    assert feats.is_cuda and feats.is_contiguous()
+    n = feats.shape[0]
+    if out is None:
+        odt = torch.float32 if (dtype == FF_F32 or (flags & FF_FLAG_OUT_F32)) else torch.bfloat16
+        out = torch.empty((n, weights.C), dtype=odt, device=feats.device)
+    s = weights.struct()
+    need = lib.ff_group_attention_workspace_bytes(n, G, C.byref(s), dtype)
+    ws = workspace if workspace is not None else _workspace(need, feats.device)
+    st = lib.ff_group_attention(_ptr(feats), _ptr(out), n, _ptr(perm), _ptr(group_offsets), _ptr(num_groups),
+                                int(max_groups), C.byref(s), G, dtype, flags,
+                                C.c_void_p(_aligned_ptr(ws)), ws.numel() - 256, _stream())
+    _check(st, "ff_group_attention")
+    return out
+
+
+def _rows(fn_name, src, perm, dtype, out):
+    lib = load_library()
+    n, Cc = src.shape
+    if out is None:
+        out = torch.empty_like(src)
+    st = getattr(lib, fn_name)(_ptr(src), _ptr(out), _ptr(perm), n, Cc, dtype, _stream())
+    _check(st, fn_name)
+    return out
+
+
+def ff_gather(src, perm, dtype, out=None):
+    return _rows("ff_gather", src, perm, dtype, out)
+
+
+def ff_scatter(src, perm, dtype, out=None):
+    return _rows("ff_scatter", src, perm, dtype, out)
+
+
+def _layer_array(layers):
+    arr = (_LayerWeightsC * len(layers))()
+    for i, l in enumerate(layers):
+        arr[i] = l.struct()
+    return arr
+
+
+def ff_fwa_block_workspace_bytes(n, geom, G, layers, dtype):
+    arr = _layer_array(layers)
+    return load_library().ff_fwa_block_workspace_bytes(int(n), C.byref(geom), G, arr, len(layers), dtype)
+
+
+def ff_fwa_block(coords, geom, G, layers, dtype, feats_in, out=None, workspace=None):
+    lib = load_library()
+    n = coords.shape[0]
+    arr = _layer_array(layers)
+    if out is None:
+        out = torch.empty_like(feats_in)
+    need = lib.ff_fwa_block_workspace_bytes(n, C.byref(geom), G, arr, len(layers), dtype)
+    ws = workspace if workspace is not None else _workspace(need, coords.device)
+    st = lib.ff_fwa_block(_ptr(coords), n, C.byref(geom), G, arr, len(layers), dtype, _ptr(feats_in), _ptr(out),
+                          C.c_void_p(_aligned_ptr(ws)), ws.numel() - 256, _stream())
+    _check(st, "ff_fwa_block")
+    return out

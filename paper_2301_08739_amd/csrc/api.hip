@@ -1,0 +1,165 @@
+// extern "C" entry points: argument checks, workspace carving and launch order.  No kernel lives
+// here; see flatten.hip, rows.hip, layer_generic.hip, layer_mfma.hip.
+#include "common.h"
+
+using namespace ff;
+
+namespace {
+
+int check_weights(const ff_layer_weights* w, int dtype) {
+  if (!w) return FF_ERR_ARG;
+  if (dtype != FF_F32 && dtype != FF_BF16) return FF_ERR_ARG;
+  if (w->C < 1 || w->F < 1 || w->heads < 1) return FF_ERR_ARG;
+  if (!w->ln1_g || !w->ln1_b || !w->w_qkv || !w->b_qkv || !w->w_o || !w->b_o || !w->ln2_g || !w->ln2_b ||
+      !w->w1 || !w->b1 || !w->w2 || !w->b2)
+    return FF_ERR_ARG;
+  if (w->C % w->heads) return FF_ERR_UNSUPPORTED;
+  if (((size_t)w->C * (dtype == FF_F32 ? 4 : 2)) % 16) return FF_ERR_UNSUPPORTED;
+  return FF_OK;
+}
+
+size_t elem_size(int dtype) { return dtype == FF_F32 ? 4 : 2; }
+
+}  // namespace
+
+extern "C" {
+
+size_t ff_flatten_workspace_bytes(int64_t n, const ff_geom* g) { return flatten_workspace_bytes(n, g); }
+
+int ff_flatten(const int32_t* coords, int64_t n, const ff_geom* g, int axis, int shift, int G, int tail,
+               int32_t* perm, int32_t* group_offsets, int32_t* num_groups, uint64_t* keys_sorted,
+               void* workspace, size_t workspace_bytes, void* stream) {
+  if (tail == FF_TAIL_DROP) return FF_ERR_UNSUPPORTED;
+  if (tail != FF_TAIL_MASK) return FF_ERR_ARG;
+  if (shift != 0 && shift != 1) return FF_ERR_ARG;
+  return flatten_launch(coords, n, g, axis, shift, G, perm, group_offsets, num_groups, keys_sorted,
+                        workspace, workspace_bytes, (hipStream_t)stream);
+}
+
+size_t ff_group_attention_workspace_bytes(int64_t n, int G, const ff_layer_weights* w, int dtype) {
+  (void)G;
+  if (n < 0 || check_weights(w, dtype) != FF_OK) return 0;
+  return layer_generic_workspace_bytes(n, w);
+}
+
+int ff_group_attention(const void* feats, void* out, int64_t n, const int32_t* perm,
+                       const int32_t* group_offsets, const int32_t* num_groups, int32_t max_groups,
+                       const ff_layer_weights* w, int G, int dtype, uint32_t flags,
+                       void* workspace, size_t workspace_bytes, void* stream) {
+  int st = check_weights(w, dtype);
+  if (st != FF_OK) return st;
+  if (n < 0 || n > 0x7fffffffLL || max_groups < 0 || G < 1) return FF_ERR_ARG;
+  if (G > 1024) return FF_ERR_UNSUPPORTED;
+  if (n > 0 && (!feats || !out || !perm || !group_offsets || !num_groups)) return FF_ERR_ARG;
+  if (n > 0) {  // overlap of the two [n, C] buffers
+    const size_t in_bytes = (size_t)n * w->C * elem_size(dtype);
+    const size_t out_bytes = (size_t)n * w->C * ((flags & FF_FLAG_OUT_F32) ? 4 : elem_size(dtype));
+    const char *a = (const char*)feats, *b = (const char*)out;
+    if (a < b + out_bytes && b < a + in_bytes) return FF_ERR_ARG;
+  }
+  return layer_generic_launch(feats, out, n, perm, group_offsets, num_groups, max_groups, w, G, dtype,
+                              (flags & FF_FLAG_OUT_F32) != 0, workspace, workspace_bytes, (hipStream_t)stream);
+}
+
+int ff_gather(const void* src, void* dst, const int32_t* perm, int64_t n, int C, int dtype, void* stream) {
+  return rows_launch(false, src, dst, perm, n, C, dtype, (hipStream_t)stream);
+}
+
+int ff_scatter(const void* src, void* dst, const int32_t* perm, int64_t n, int C, int dtype, void* stream) {
+  return rows_launch(true, src, dst, perm, n, C, dtype, (hipStream_t)stream);
+}
+
+// Workspace layout of ff_fwa_block:
+//   [flatten scratch][perm x S][group_offsets x S][num_groups x S][feature buffer A][feature buffer B][layer scratch]
+// with S = number of distinct (axis, shift) pairs the schedule uses (at most 4).
+namespace {
+struct BlockPlan {
+  int sorts;  // distinct sort configurations used by layers 0..L-1 (schedule order x, y, sx, sy)
+  int64_t max_groups;
+  size_t off_flat, off_perm, off_goff, off_ng, off_a, off_b, off_layer, total;
+  size_t flat_bytes, layer_bytes;
+};
+
+int make_block_plan(int64_t n, const ff_geom* g, int G, const ff_layer_weights* layers, int num_layers,
+                    int dtype, BlockPlan* p) {
+  if (n < 0 || n > 0x7fffffffLL || !g || G < 1 || num_layers < 1 || !layers) return FF_ERR_ARG;
+  for (int l = 0; l < num_layers; ++l) {
+    int st = check_weights(&layers[l], dtype);
+    if (st != FF_OK) return st;
+    if (layers[l].C != layers[0].C) return FF_ERR_ARG;
+  }
+  p->flat_bytes = flatten_workspace_bytes(n, g);
+  if (p->flat_bytes == 0) { FlattenPlan fp; int st = make_flatten_plan(n, g, 0, 1, &fp); if (st != FF_OK) return st; }
+  p->sorts = num_layers < 4 ? num_layers : 4;
+  p->max_groups = ceil_div(n, G) + g->num_frames;
+  p->layer_bytes = 0;
+  for (int l = 0; l < num_layers; ++l) {
+    size_t b = ff_group_attention_workspace_bytes(n, G, &layers[l], dtype);
+    if (b > p->layer_bytes) p->layer_bytes = b;
+  }
+  const size_t feat_bytes = align_up((size_t)n * layers[0].C * elem_size(dtype), 256);
+  size_t off = 0;
+  p->off_flat = off;  off += align_up(p->flat_bytes, 256);
+  p->off_perm = off;  off += p->sorts * align_up((size_t)n * 4, 256);
+  p->off_goff = off;  off += p->sorts * align_up((size_t)(p->max_groups + 1) * 4, 256);
+  p->off_ng = off;    off += 256;
+  p->off_a = off;     off += feat_bytes;
+  p->off_b = off;     off += feat_bytes;
+  p->off_layer = off; off += align_up(p->layer_bytes, 256);
+  p->total = off;
+  return FF_OK;
+}
+}  // namespace
+
+size_t ff_fwa_block_workspace_bytes(int64_t n, const ff_geom* g, int G, const ff_layer_weights* layers,
+                                    int num_layers, int dtype) {
+  BlockPlan p;
+  if (make_block_plan(n, g, G, layers, num_layers, dtype, &p) != FF_OK) return 0;
+  return p.total;
+}
+
+int ff_fwa_block(const int32_t* coords, int64_t n, const ff_geom* g, int G, const ff_layer_weights* layers,
+                 int num_layers, int dtype, const void* feats_in, void* feats_out, void* workspace,
+                 size_t workspace_bytes, void* stream) {
+  BlockPlan p;
+  int st = make_block_plan(n, g, G, layers, num_layers, dtype, &p);
+  if (st != FF_OK) return st;
+  if (!workspace || ((uintptr_t)workspace & 255) || workspace_bytes < p.total) return FF_ERR_WORKSPACE;
+  if (n > 0 && (!coords || !feats_in || !feats_out || feats_in == feats_out)) return FF_ERR_ARG;
+  char* ws = (char*)workspace;
+  const size_t perm_stride = align_up((size_t)n * 4, 256);
+  const size_t goff_stride = align_up((size_t)(p.max_groups + 1) * 4, 256);
+  for (int s = 0; s < p.sorts; ++s) {
+    st = ff_flatten(coords, n, g, s % 2, (s / 2) % 2, G, FF_TAIL_MASK, (int32_t*)(ws + p.off_perm + s * perm_stride),
+                    (int32_t*)(ws + p.off_goff + s * goff_stride), (int32_t*)(ws + p.off_ng) + s, nullptr,
+                    ws + p.off_flat, p.flat_bytes, stream);
+    if (st != FF_OK) return st;
+  }
+  const void* cur = feats_in;
+  void* bufs[2] = {ws + p.off_a, ws + p.off_b};
+  for (int l = 0; l < num_layers; ++l) {
+    const int s = l % 4;
+    void* dst = (l == num_layers - 1) ? feats_out : bufs[l & 1];
+    st = ff_group_attention(cur, dst, n, (const int32_t*)(ws + p.off_perm + s * perm_stride),
+                            (const int32_t*)(ws + p.off_goff + s * goff_stride), (const int32_t*)(ws + p.off_ng) + s,
+                            (int32_t)p.max_groups, &layers[l], G, dtype, 0, ws + p.off_layer, p.layer_bytes, stream);
+    if (st != FF_OK) return st;
+    cur = dst;
+  }
+  return FF_OK;
+}
+
+const char* ff_status_string(int status) {
+  switch (status) {
+    case FF_OK: return "ok";
+    case FF_ERR_ARG: return "invalid argument";
+    case FF_ERR_UNSUPPORTED: return "unsupported configuration";
+    case FF_ERR_WORKSPACE: return "workspace missing, misaligned or too small";
+    case FF_ERR_LAUNCH: return "kernel launch failed";
+    default: return "unknown status";
+  }
+}
+
+int ff_version(void) { return 100; }
+
+}  // extern "C"

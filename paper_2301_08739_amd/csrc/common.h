@@ -1,0 +1,72 @@
+// Internal helpers shared by the HIP translation units of libflatformer.
+#pragma once
+#include <hip/hip_runtime.h>
+#include <stdint.h>
+#include <stddef.h>
+#include "../../include/flatformer.h"
+
+namespace ff {
+
+constexpr int kWave = 64;
+
+inline size_t align_up(size_t x, size_t a) { return (x + a - 1) / a * a; }
+inline int64_t ceil_div(int64_t a, int64_t b) { return (a + b - 1) / b; }
+// number of bits needed to represent values 0..v (0 for v == 0)
+inline int bit_width_u64(uint64_t v) { int b = 0; while (v) { ++b; v >>= 1; } return b; }
+
+inline int launch_status() { return hipGetLastError() == hipSuccess ? FF_OK : FF_ERR_LAUNCH; }
+
+// ---- bf16 <-> f32 on the device (round to nearest even) -------------------------------------
+__device__ __forceinline__ float bf16_to_f32(uint16_t h) { return __uint_as_float(((uint32_t)h) << 16); }
+__device__ __forceinline__ uint16_t f32_to_bf16(float f) {
+  uint32_t u = __float_as_uint(f);
+  if ((u & 0x7fffffffu) > 0x7f800000u) return 0x7fc0;  // NaN
+  u += 0x7fffu + ((u >> 16) & 1u);
+  return (uint16_t)(u >> 16);
+}
+
+// Storage-type traits: T is float or bf16_t (a 16-bit wrapper).
+struct bf16_t { uint16_t bits; };
+template <typename T> struct Elem;
+template <> struct Elem<float> {
+  static __device__ __forceinline__ float load(const float* p) { return *p; }
+  static __device__ __forceinline__ void store(float* p, float v) { *p = v; }
+};
+template <> struct Elem<bf16_t> {
+  static __device__ __forceinline__ float load(const bf16_t* p) { return bf16_to_f32(p->bits); }
+  static __device__ __forceinline__ void store(bf16_t* p, float v) { p->bits = f32_to_bf16(v); }
+};
+
+// ---- flatten plan (host) -------------------------------------------------------------------------
+struct FlattenPlan {
+  int bits_b, bits_w1, bits_w2, bits_l1, bits_l2;  // live bits of each tuple field, in sort priority
+  int key_bits;                                    // sum of the above
+  int idx_bits;                                    // bits of n-1
+  int passes;                                      // radix passes of 8 bits over the key bits
+  int64_t tiles;                                   // tiles of kTile words
+  size_t off_buf0, off_buf1, off_hist, off_frames, total;
+};
+
+constexpr int kRadixBits = 8;
+constexpr int kBins = 1 << kRadixBits;
+constexpr int kSortThreads = 256;
+constexpr int kKeysPerThread = 8;
+constexpr int kTile = kSortThreads * kKeysPerThread;
+
+int make_flatten_plan(int64_t n, const ff_geom* g, int axis, int shift, FlattenPlan* plan);
+size_t flatten_workspace_bytes(int64_t n, const ff_geom* g);
+
+int flatten_launch(const int32_t* coords, int64_t n, const ff_geom* g, int axis, int shift, int G,
+                   int32_t* perm, int32_t* group_offsets, int32_t* num_groups, uint64_t* keys_sorted,
+                   void* workspace, size_t workspace_bytes, hipStream_t stream);
+
+int rows_launch(bool scatter, const void* src, void* dst, const int32_t* perm, int64_t n, int C,
+                int dtype, hipStream_t stream);
+
+size_t layer_generic_workspace_bytes(int64_t n, const ff_layer_weights* w);
+int layer_generic_launch(const void* feats, void* out, int64_t n, const int32_t* perm,
+                         const int32_t* group_offsets, const int32_t* num_groups, int32_t max_groups,
+                         const ff_layer_weights* w, int G, int dtype, bool out_f32,
+                         void* workspace, size_t workspace_bytes, hipStream_t stream);
+
+}  // namespace ff

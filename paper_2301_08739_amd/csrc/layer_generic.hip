@@ -1,0 +1,241 @@
+// Group attention layer (paper Sec. 4.2.2, Eq. (2)), plain fp32-arithmetic kernels.
+//
+//   F'  = F  + MHSA(LN1(F)),   F'' = F' + FFN(LN2(F'))
+//
+// This is the exact-arithmetic path: storage type T (float or bf16), every product, sum,
+// exponential and erf in fp32 on the vector ALUs.  It serves dtype FF_F32 and any shape the
+// MFMA kernels do not cover.  Three kernels, intermediates in the caller's workspace:
+//   k_ln_qkv    rows of the sorted order: gather, LN1, packed QKV projection   -> qkv [n, 3C] f32
+//   k_attention one workgroup per (group, head): softmax(Q K^T / sqrt(d)) V     -> o   [n, C]  f32
+//   k_out_ffn   rows: out-proj + residual, LN2, Linear+GELU, Linear + residual, scatter
+#include "common.h"
+
+namespace ff {
+namespace {
+
+constexpr int RB = 4;  // sorted rows per workgroup in the row kernels
+
+__device__ __forceinline__ float wave_sum(float v) {
+#pragma unroll
+  for (int d = 32; d >= 1; d >>= 1) v += __shfl_xor(v, d, 64);
+  return v;
+}
+
+// LayerNorm of RB rows of width C held in LDS (src -> dst), one wavefront per row.
+__device__ __forceinline__ void ln_rows(const float* src, float* dst, int C, int rows,
+                                        const float* g_s, const float* b_s, float eps) {
+  const int lane = threadIdx.x & 63, w = threadIdx.x >> 6;
+  for (int r = w; r < rows; r += (int)(blockDim.x >> 6)) {
+    float s = 0.f;
+    for (int k = lane; k < C; k += 64) s += src[r * C + k];
+    const float mu = wave_sum(s) / (float)C;
+    float q = 0.f;
+    for (int k = lane; k < C; k += 64) { float t = src[r * C + k] - mu; q += t * t; }
+    const float rstd = 1.0f / sqrtf(wave_sum(q) / (float)C + eps);
+    for (int k = lane; k < C; k += 64) dst[r * C + k] = (src[r * C + k] - mu) * rstd * g_s[k] + b_s[k];
+  }
+}
+
+template <typename T>
+__global__ __launch_bounds__(256) void k_ln_qkv(const T* __restrict__ feats, const int32_t* __restrict__ perm,
+                                                 int64_t n, int C, const T* __restrict__ ln_g,
+                                                 const T* __restrict__ ln_b, float eps,
+                                                 const T* __restrict__ w_qkv, const T* __restrict__ b_qkv,
+                                                 float* __restrict__ qkv) {
+  extern __shared__ float lds[];
+  float* X = lds;              // [RB][C]
+  float* U = X + RB * C;       // [RB][C]
+  float* gs = U + RB * C;      // [C]
+  float* bs = gs + C;          // [C]
+  const int64_t p0 = (int64_t)blockIdx.x * RB;
+  const int rows = (int)((n - p0) < RB ? (n - p0) : RB);
+  for (int i = threadIdx.x; i < C; i += blockDim.x) { gs[i] = Elem<T>::load(ln_g + i); bs[i] = Elem<T>::load(ln_b + i); }
+  for (int i = threadIdx.x; i < rows * C; i += blockDim.x) {
+    const int r = i / C, k = i - r * C;
+    X[i] = Elem<T>::load(feats + (int64_t)perm[p0 + r] * C + k);
+  }
+  __syncthreads();
+  ln_rows(X, U, C, rows, gs, bs, eps);
+  __syncthreads();
+  for (int j = threadIdx.x; j < 3 * C; j += blockDim.x) {
+    float acc[RB];
+#pragma unroll
+    for (int r = 0; r < RB; ++r) acc[r] = 0.f;
+    const T* wrow = w_qkv + (int64_t)j * C;
+    for (int k = 0; k < C; ++k) {
+      const float wv = Elem<T>::load(wrow + k);
+#pragma unroll
+      for (int r = 0; r < RB; ++r) acc[r] = fmaf(U[r * C + k], wv, acc[r]);
+    }
+    const float bj = Elem<T>::load(b_qkv + j);
+    for (int r = 0; r < rows; ++r) qkv[(p0 + r) * 3 * (int64_t)C + j] = acc[r] + bj;
+  }
+}
+
+// One workgroup per (group, head); one thread per query row (looping when the group is larger
+// than the workgroup).  Plain two-pass softmax over the group's real members.
+template <int DMAX>
+__global__ __launch_bounds__(256) void k_attention(const float* __restrict__ qkv, const int32_t* __restrict__ group_offsets,
+                                                    const int32_t* __restrict__ num_groups, int C, int d,
+                                                    float* __restrict__ o) {
+  const int g = blockIdx.x, h = blockIdx.y;
+  if (g >= *num_groups) return;
+  const int64_t start = group_offsets[g];
+  const int m = group_offsets[g + 1] - group_offsets[g];
+  const float scale = 1.0f / sqrtf((float)d);
+  const int64_t ld = 3 * (int64_t)C;
+  for (int i = threadIdx.x; i < m; i += blockDim.x) {
+    float q[DMAX], acc[DMAX];
+    const float* qrow = qkv + (start + i) * ld + h * d;
+#pragma unroll
+    for (int c = 0; c < DMAX; ++c) { q[c] = c < d ? qrow[c] : 0.f; acc[c] = 0.f; }
+    float mx = -INFINITY;
+    for (int j = 0; j < m; ++j) {
+      const float* krow = qkv + (start + j) * ld + C + h * d;
+      float s = 0.f;
+#pragma unroll
+      for (int c = 0; c < DMAX; ++c) if (c < d) s = fmaf(q[c], krow[c], s);
+      mx = fmaxf(mx, s * scale);
+    }
+    float sum = 0.f;
+    for (int j = 0; j < m; ++j) {
+      const float* krow = qkv + (start + j) * ld + C + h * d;
+      const float* vrow = krow + C;
+      float s = 0.f;
+#pragma unroll
+      for (int c = 0; c < DMAX; ++c) if (c < d) s = fmaf(q[c], krow[c], s);
+      const float e = expf(s * scale - mx);
+      sum += e;
+#pragma unroll
+      for (int c = 0; c < DMAX; ++c) if (c < d) acc[c] = fmaf(e, vrow[c], acc[c]);
+    }
+    const float inv = 1.0f / sum;
+    float* orow = o + (start + i) * (int64_t)C + h * d;
+#pragma unroll
+    for (int c = 0; c < DMAX; ++c) if (c < d) orow[c] = acc[c] * inv;
+  }
+}
+
+template <typename T, typename TO>
+__global__ __launch_bounds__(256) void k_out_ffn(const T* __restrict__ feats, const int32_t* __restrict__ perm,
+                                                  int64_t n, int C, int F, const float* __restrict__ o,
+                                                  const T* __restrict__ w_o, const T* __restrict__ b_o,
+                                                  const T* __restrict__ ln_g, const T* __restrict__ ln_b, float eps,
+                                                  const T* __restrict__ w1, const T* __restrict__ b1,
+                                                  const T* __restrict__ w2, const T* __restrict__ b2,
+                                                  TO* __restrict__ out) {
+  extern __shared__ float lds[];
+  float* O = lds;               // [RB][C]
+  float* X1 = O + RB * C;       // [RB][C]
+  float* U = X1 + RB * C;       // [RB][C]
+  float* H = U + RB * C;        // [RB][F]
+  float* gs = H + RB * F;       // [C]
+  float* bs = gs + C;           // [C]
+  const int64_t p0 = (int64_t)blockIdx.x * RB;
+  const int rows = (int)((n - p0) < RB ? (n - p0) : RB);
+  for (int i = threadIdx.x; i < C; i += blockDim.x) { gs[i] = Elem<T>::load(ln_g + i); bs[i] = Elem<T>::load(ln_b + i); }
+  for (int i = threadIdx.x; i < RB * C; i += blockDim.x) O[i] = i < rows * C ? o[p0 * C + i] : 0.f;
+  __syncthreads();
+  for (int j = threadIdx.x; j < C; j += blockDim.x) {
+    float acc[RB];
+#pragma unroll
+    for (int r = 0; r < RB; ++r) acc[r] = 0.f;
+    const T* wrow = w_o + (int64_t)j * C;
+    for (int k = 0; k < C; ++k) {
+      const float wv = Elem<T>::load(wrow + k);
+#pragma unroll
+      for (int r = 0; r < RB; ++r) acc[r] = fmaf(O[r * C + k], wv, acc[r]);
+    }
+    const float bj = Elem<T>::load(b_o + j);
+#pragma unroll
+    for (int r = 0; r < RB; ++r) {
+      float x = r < rows ? Elem<T>::load(feats + (int64_t)perm[p0 + r] * C + j) : 0.f;
+      X1[r * C + j] = x + (acc[r] + bj);
+    }
+  }
+  __syncthreads();
+  ln_rows(X1, U, C, RB, gs, bs, eps);
+  __syncthreads();
+  for (int f = threadIdx.x; f < F; f += blockDim.x) {
+    float acc[RB];
+#pragma unroll
+    for (int r = 0; r < RB; ++r) acc[r] = 0.f;
+    const T* wrow = w1 + (int64_t)f * C;
+    for (int k = 0; k < C; ++k) {
+      const float wv = Elem<T>::load(wrow + k);
+#pragma unroll
+      for (int r = 0; r < RB; ++r) acc[r] = fmaf(U[r * C + k], wv, acc[r]);
+    }
+    const float bf = Elem<T>::load(b1 + f);
+#pragma unroll
+    for (int r = 0; r < RB; ++r) {
+      const float v = acc[r] + bf;
+      H[r * F + f] = 0.5f * v * (1.0f + erff(v * 0.70710678118654752440f));
+    }
+  }
+  __syncthreads();
+  for (int j = threadIdx.x; j < C; j += blockDim.x) {
+    float acc[RB];
+#pragma unroll
+    for (int r = 0; r < RB; ++r) acc[r] = 0.f;
+    const T* wrow = w2 + (int64_t)j * F;
+    for (int k = 0; k < F; ++k) {
+      const float wv = Elem<T>::load(wrow + k);
+#pragma unroll
+      for (int r = 0; r < RB; ++r) acc[r] = fmaf(H[r * F + k], wv, acc[r]);
+    }
+    const float bj = Elem<T>::load(b2 + j);
+    for (int r = 0; r < rows; ++r)
+      Elem<TO>::store(out + (int64_t)perm[p0 + r] * C + j, X1[r * C + j] + (acc[r] + bj));
+  }
+}
+
+template <typename T, typename TO>
+int launch_typed(const void* feats, void* out, int64_t n, const int32_t* perm, const int32_t* group_offsets,
+                 const int32_t* num_groups, int32_t max_groups, const ff_layer_weights* w, int d,
+                 float* qkv, float* o, hipStream_t stream) {
+  const int C = w->C, F = w->F;
+  const unsigned row_blocks = (unsigned)ceil_div(n, RB);
+  const size_t lds_a = (size_t)(2 * RB * C + 2 * C) * 4;
+  const size_t lds_c = (size_t)(3 * RB * C + RB * F + 2 * C) * 4;
+  hipLaunchKernelGGL((k_ln_qkv<T>), dim3(row_blocks), dim3(256), lds_a, stream, (const T*)feats, perm, n, C,
+                     (const T*)w->ln1_g, (const T*)w->ln1_b, w->ln_eps, (const T*)w->w_qkv,
+                     (const T*)w->b_qkv, qkv);
+  dim3 ga((unsigned)max_groups, (unsigned)w->heads);
+  if (d <= 16)       hipLaunchKernelGGL((k_attention<16>), ga, dim3(256), 0, stream, qkv, group_offsets, num_groups, C, d, o);
+  else if (d <= 32)  hipLaunchKernelGGL((k_attention<32>), ga, dim3(256), 0, stream, qkv, group_offsets, num_groups, C, d, o);
+  else if (d <= 64)  hipLaunchKernelGGL((k_attention<64>), ga, dim3(256), 0, stream, qkv, group_offsets, num_groups, C, d, o);
+  else               hipLaunchKernelGGL((k_attention<128>), ga, dim3(256), 0, stream, qkv, group_offsets, num_groups, C, d, o);
+  hipLaunchKernelGGL((k_out_ffn<T, TO>), dim3(row_blocks), dim3(256), lds_c, stream, (const T*)feats, perm, n, C, F, o,
+                     (const T*)w->w_o, (const T*)w->b_o, (const T*)w->ln2_g, (const T*)w->ln2_b, w->ln_eps,
+                     (const T*)w->w1, (const T*)w->b1, (const T*)w->w2, (const T*)w->b2, (TO*)out);
+  return launch_status();
+}
+
+}  // namespace
+
+size_t layer_generic_workspace_bytes(int64_t n, const ff_layer_weights* w) {
+  return align_up((size_t)n * 3 * w->C * 4, 256) + align_up((size_t)n * w->C * 4, 256);
+}
+
+int layer_generic_launch(const void* feats, void* out, int64_t n, const int32_t* perm,
+                         const int32_t* group_offsets, const int32_t* num_groups, int32_t max_groups,
+                         const ff_layer_weights* w, int G, int dtype, bool out_f32,
+                         void* workspace, size_t workspace_bytes, hipStream_t stream) {
+  (void)G;
+  const int C = w->C, F = w->F, d = C / w->heads;
+  if (d > 128) return FF_ERR_UNSUPPORTED;
+  if ((size_t)(3 * RB * C + RB * F + 2 * C) * 4 > 64 * 1024) return FF_ERR_UNSUPPORTED;
+  if (!workspace || ((uintptr_t)workspace & 255) || workspace_bytes < layer_generic_workspace_bytes(n, w))
+    return FF_ERR_WORKSPACE;
+  if (n == 0 || max_groups == 0) return FF_OK;
+  float* qkv = (float*)workspace;
+  float* o = (float*)((char*)workspace + align_up((size_t)n * 3 * C * 4, 256));
+  if (dtype == FF_F32)
+    return launch_typed<float, float>(feats, out, n, perm, group_offsets, num_groups, max_groups, w, d, qkv, o, stream);
+  if (out_f32)
+    return launch_typed<bf16_t, float>(feats, out, n, perm, group_offsets, num_groups, max_groups, w, d, qkv, o, stream);
+  return launch_typed<bf16_t, bf16_t>(feats, out, n, perm, group_offsets, num_groups, max_groups, w, d, qkv, o, stream);
+}
+
+}  // namespace ff

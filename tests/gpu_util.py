@@ -1,0 +1,36 @@
+"""Helpers shared by the GPU parity tests (not a test module)."""
+import numpy as np
+import torch
+
+import ffsynth
+import oracle
+import paper_2301_08739_amd as ff
+
+DEV = "cuda"
+
+
+def geoms(c):
+    return (ff.Geometry(c["B"], c["grid"], c["grid"], c["window"], c["window"]),
+            oracle.Geometry(c["B"], c["grid"], c["grid"], c["window"], c["window"]))
+
+
+def to_dev_feats(feats, dtype):
+    t = torch.from_numpy(np.ascontiguousarray(feats, dtype=np.float32))
+    return t.to(DEV) if dtype == ff.FF_F32 else t.to(DEV).to(torch.bfloat16)
+
+
+def to_host(t):
+    return t.detach().float().cpu().numpy().astype(np.float64)
+
+
+def dtype_of(c):
+    return ff.FF_F32 if c["dtype"] == "f32" else ff.FF_BF16
+
+
+def gpu_flatten(coords, g, axis, shift, G, want_keys=True):
+    ct = torch.from_numpy(np.ascontiguousarray(coords, dtype=np.int32)).to(DEV)
+    perm, goff, ng, keys = ff.ff_flatten(ct, g, axis, shift, G, want_keys=want_keys)
+    torch.cuda.synchronize()
+    k = int(ng.item())
+    return (perm.cpu().numpy(), goff.cpu().numpy()[:k + 1], k,
+            None if keys is None else keys.cpu().numpy().view(np.uint64), (perm, goff, ng))

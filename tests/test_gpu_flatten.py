@@ -1,0 +1,109 @@
+"""GPU parity: ff_flatten must equal the oracle bit for bit (keys, perm, group offsets)."""
+import numpy as np
+import pytest
+import torch
+
+import oracle
+import paper_2301_08739_amd as ff
+from gpu_util import geoms, gpu_flatten
+
+pytestmark = pytest.mark.gpu
+
+SORTS = [(0, 0), (1, 0), (0, 1), (1, 1)]
+
+
+def _check(coords, g, og, axis, shift, G):
+    perm, off, ng, keys, _ = gpu_flatten(coords, g, axis, shift, G)
+    wperm, woff, wkeys = oracle.flatten(coords, og, axis, shift, G)
+    assert ng == len(woff) - 1
+    assert np.array_equal(off, woff)
+    assert np.array_equal(perm, wperm)
+    assert np.array_equal(keys, wkeys)
+
+
+@pytest.mark.parametrize("i", [1, 2, 4, 5])
+def test_configs_bit_exact(cfg, i):
+    c = cfg(i)
+    g, og = geoms(c)
+    for axis, shift in SORTS:
+        print(f"flatten cfg{i} axis={axis} shift={shift} n={c['n']}", flush=True)
+        _check(c["coords"], g, og, axis, shift, c["G"])
+
+
+def _rand_coords(n, B, gx, gy, seed, unique=True):
+    rng = np.random.default_rng(seed)
+    if unique:
+        ids = rng.permutation(B * gx * gy)[:n]
+    else:
+        ids = rng.integers(0, B * gx * gy, size=n)
+    b, r = np.divmod(ids, gx * gy)
+    x, y = np.divmod(r, gy)
+    return np.stack([b, x, y], axis=1).astype(np.int32)
+
+
+@pytest.mark.parametrize("n", [0, 1, 2, 63, 64, 65, 2047, 2048, 2049, 4096, 5000])
+def test_sizes_around_tile_edges(n):
+    coords = _rand_coords(n, 3, 90, 70, seed=n, unique=True)
+    g, og = ff.Geometry(3, 90, 70, 7, 5), oracle.Geometry(3, 90, 70, 7, 5)
+    for axis, shift in [(0, 1), (1, 0)]:
+        _check(coords, g, og, axis, shift, 10)
+
+
+def test_duplicates_keep_index_order():
+    coords = _rand_coords(20000, 2, 20, 20, seed=1, unique=False)      # heavy duplication
+    g, og = ff.Geometry(2, 20, 20, 4, 4), oracle.Geometry(2, 20, 20, 4, 4)
+    for axis, shift in SORTS:
+        _check(coords, g, og, axis, shift, 33)
+    same = np.zeros((3000, 3), dtype=np.int32)                          # all keys equal
+    _check(same, ff.Geometry(1, 1, 1, 1, 1), oracle.Geometry(1, 1, 1, 1, 1), 0, 0, 7)  # zero key bits
+    _check(same, g, og, 1, 1, 7)
+
+
+def test_degenerate_windows_and_groups():
+    coords = _rand_coords(3000, 1, 300, 200, seed=2)
+    for w in (1, 256):
+        g, og = ff.Geometry(1, 300, 200, w, w), oracle.Geometry(1, 300, 200, w, w)
+        for axis, shift in [(0, 0), (1, 1)]:
+            _check(coords, g, og, axis, shift, 64)
+    g, og = ff.Geometry(1, 300, 200, 13, 9), oracle.Geometry(1, 300, 200, 13, 9)
+    for G in (1, 2999, 3000, 3001, 100000):
+        _check(coords, g, og, 0, 1, G)
+
+
+def test_many_frames_with_empty_ones():
+    B = 700
+    coords = _rand_coords(9000, B, 16, 16, seed=3)
+    coords = coords[(coords[:, 0] % 7 != 3) & (coords[:, 0] != B - 1)]  # empty frames incl. the last
+    g, og = ff.Geometry(B, 16, 16, 4, 4), oracle.Geometry(B, 16, 16, 4, 4)
+    for axis, shift in [(0, 0), (1, 1)]:
+        _check(coords, g, og, axis, shift, 5)
+
+
+def test_maximum_field_widths():
+    # 65535 frames x 65535 windows on one axis, window 256 on the other: 16+16+8(+0+0) key bits
+    rng = np.random.default_rng(4)
+    n = 4000
+    coords = np.stack([rng.integers(0, 65535, n), rng.integers(0, 65535, n), rng.integers(0, 256, n)], 1).astype(np.int32)
+    coords[0] = (65534, 65534, 255)
+    g, og = ff.Geometry(65535, 65535, 256, 1, 256), oracle.Geometry(65535, 65535, 256, 1, 256)
+    _check(coords, g, og, 0, 0, 3)
+    _check(coords, g, og, 1, 0, 3)
+
+
+def test_errors_and_determinism():
+    coords = torch.zeros((10, 3), dtype=torch.int32, device="cuda")
+    with pytest.raises(ff.FlatformerError):
+        ff.ff_flatten(coords, ff.Geometry(1, 10, 10, 0, 1), 0, 0, 4)          # window 0
+    with pytest.raises(ff.FlatformerError):
+        ff.ff_flatten(coords, ff.Geometry(1, 10, 10, 2, 2), 2, 0, 4)          # axis 2
+    with pytest.raises(ff.FlatformerError):
+        ff.ff_flatten(coords, ff.Geometry(1, 10, 10, 2, 2), 0, 0, 0)          # G 0
+    with pytest.raises(ff.FlatformerError):
+        ff.ff_flatten(coords, ff.Geometry(1, 10, 10, 2, 2), 0, 0, 4, tail=1)  # drop mode not built
+    with pytest.raises(ff.FlatformerError):                                   # 16+16+16+8+8 key bits + index
+        ff.ff_flatten(coords, ff.Geometry(65535, 65535 * 256, 65535 * 256, 256, 256), 0, 0, 4)
+    c = _rand_coords(50000, 2, 300, 300, seed=5)
+    g = ff.Geometry(2, 300, 300, 13, 13)
+    a = gpu_flatten(c, g, 0, 1, 64)
+    b = gpu_flatten(c, g, 0, 1, 64)
+    assert np.array_equal(a[0], b[0]) and np.array_equal(a[1], b[1]) and np.array_equal(a[3], b[3])
