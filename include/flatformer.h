@@ -108,7 +108,18 @@ typedef struct {
   const void *w2, *b2;       /* [C, F],  [C]   */
   int32_t C, F, heads;
   float ln_eps;
+  const void* packed;        /* NULL, or the buffer written by ff_pack_weights for THESE weights */
 } ff_layer_weights;
+
+/* Weight pre-packing for the matrix-core kernels (optional).  The fused bf16 kernel reads the
+ * four weight matrices in a tile order of its own.  With packed == NULL, ff_group_attention and
+ * ff_fwa_block re-pack the weights into their workspace on every call (one small extra launch
+ * per layer).  Weights that stay fixed across calls can be packed once: allocate
+ * ff_pack_weights_bytes(w, dtype) bytes (256-byte aligned), call ff_pack_weights, and store the
+ * pointer in w->packed.  ff_pack_weights_bytes returns 0 when the configuration has no packed
+ * form (fp32, or a shape only the plain kernels cover); `packed` is then ignored. */
+size_t ff_pack_weights_bytes(const ff_layer_weights* w, int dtype);
+int ff_pack_weights(const ff_layer_weights* w, int dtype, void* packed, void* stream);
 
 /* Flags of ff_group_attention. */
 #define FF_FLAG_OUT_F32 1u      /* store `out` as float32 even when dtype is FF_BF16 */

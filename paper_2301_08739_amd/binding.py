@@ -26,7 +26,8 @@ class Geometry(C.Structure):
 class _LayerWeightsC(C.Structure):
     _fields_ = [(k, C.c_void_p) for k in ("ln1_g", "ln1_b", "w_qkv", "b_qkv", "w_o", "b_o",
                                           "ln2_g", "ln2_b", "w1", "b1", "w2", "b2")] + \
-               [("C", C.c_int32), ("F", C.c_int32), ("heads", C.c_int32), ("ln_eps", C.c_float)]
+               [("C", C.c_int32), ("F", C.c_int32), ("heads", C.c_int32), ("ln_eps", C.c_float),
+                ("packed", C.c_void_p)]
 
 
 _PARAMS = ("ln1_g", "ln1_b", "w_qkv", "b_qkv", "w_o", "b_o", "ln2_g", "ln2_b", "w1", "b1", "w2", "b2")
@@ -42,12 +43,27 @@ class LayerWeights:
                         for k in _PARAMS}
         self.C, self.F, self.heads = int(params["C"]), int(params["F"]), int(params["heads"])
         self.ln_eps = float(params["ln_eps"])
+        self.packed = None
+
+    def pack(self):
+        """Pre-pack the weights once (ff_pack_weights); later calls skip the per-call packing."""
+        lib = load_library()
+        s = self.struct()
+        nbytes = lib.ff_pack_weights_bytes(C.byref(s), self.dtype)
+        if nbytes == 0:
+            return self
+        buf = torch.empty(nbytes + 256, dtype=torch.uint8, device=self.tensors["w_o"].device)
+        ptr = (buf.data_ptr() + 255) // 256 * 256
+        _check(lib.ff_pack_weights(C.byref(s), self.dtype, C.c_void_p(ptr), _stream()), "ff_pack_weights")
+        self._packed_buf, self.packed = buf, ptr
+        return self
 
     def struct(self):
         s = _LayerWeightsC()
         for k in _PARAMS:
             setattr(s, k, self.tensors[k].data_ptr())
         s.C, s.F, s.heads, s.ln_eps = self.C, self.F, self.heads, self.ln_eps
+        s.packed = self.packed
         return s
 
 
@@ -59,6 +75,8 @@ _SIGS = {
     "ff_group_attention": (C.c_int, [C.c_void_p, C.c_void_p, C.c_int64, C.c_void_p, C.c_void_p, C.c_void_p,
                                      C.c_int32, C.POINTER(_LayerWeightsC), C.c_int, C.c_int, C.c_uint32,
                                      C.c_void_p, C.c_size_t, C.c_void_p]),
+    "ff_pack_weights_bytes": (C.c_size_t, [C.POINTER(_LayerWeightsC), C.c_int]),
+    "ff_pack_weights": (C.c_int, [C.POINTER(_LayerWeightsC), C.c_int, C.c_void_p, C.c_void_p]),
     "ff_gather": (C.c_int, [C.c_void_p, C.c_void_p, C.c_void_p, C.c_int64, C.c_int, C.c_int, C.c_void_p]),
     "ff_scatter": (C.c_int, [C.c_void_p, C.c_void_p, C.c_void_p, C.c_int64, C.c_int, C.c_int, C.c_void_p]),
     "ff_fwa_block_workspace_bytes": (C.c_size_t, [C.c_int64, C.POINTER(Geometry), C.c_int,

@@ -36,10 +36,29 @@ int ff_flatten(const int32_t* coords, int64_t n, const ff_geom* g, int axis, int
                         workspace, workspace_bytes, (hipStream_t)stream);
 }
 
+size_t ff_pack_weights_bytes(const ff_layer_weights* w, int dtype) {
+  if (check_weights(w, dtype) != FF_OK || dtype != FF_BF16) return 0;
+  if (!layer_mfma_supported(w, 1)) return 0;
+  return layer_mfma_packed_bytes(w);
+}
+
+int ff_pack_weights(const ff_layer_weights* w, int dtype, void* packed, void* stream) {
+  int st = check_weights(w, dtype);
+  if (st != FF_OK) return st;
+  if (dtype != FF_BF16 || !layer_mfma_supported(w, 1)) return FF_ERR_UNSUPPORTED;
+  if (!packed || ((uintptr_t)packed & 255)) return FF_ERR_ARG;
+  return layer_mfma_pack(w, packed, (hipStream_t)stream);
+}
+
 size_t ff_group_attention_workspace_bytes(int64_t n, int G, const ff_layer_weights* w, int dtype) {
-  (void)G;
   if (n < 0 || check_weights(w, dtype) != FF_OK) return 0;
-  return layer_generic_workspace_bytes(n, w);
+  // Sized for either path so that a flag can switch kernels without a new query.
+  size_t b = layer_generic_workspace_bytes(n, w);
+  if (dtype == FF_BF16 && layer_mfma_supported(w, G)) {
+    const size_t p = align_up(layer_mfma_packed_bytes(w), 256);
+    if (p > b) b = p;
+  }
+  return b;
 }
 
 int ff_group_attention(const void* feats, void* out, int64_t n, const int32_t* perm,
@@ -57,8 +76,22 @@ int ff_group_attention(const void* feats, void* out, int64_t n, const int32_t* p
     const char *a = (const char*)feats, *b = (const char*)out;
     if (a < b + out_bytes && b < a + in_bytes) return FF_ERR_ARG;
   }
-  return layer_generic_launch(feats, out, n, perm, group_offsets, num_groups, max_groups, w, G, dtype,
-                              (flags & FF_FLAG_OUT_F32) != 0, workspace, workspace_bytes, (hipStream_t)stream);
+  const bool out_f32 = (flags & FF_FLAG_OUT_F32) != 0;
+  if (dtype == FF_BF16 && !(flags & FF_FLAG_FORCE_GENERIC) && layer_mfma_supported(w, G)) {
+    if (n == 0 || max_groups == 0) return FF_OK;
+    const void* packed = w->packed;
+    if (!packed) {
+      if (!workspace || ((uintptr_t)workspace & 255) || workspace_bytes < layer_mfma_packed_bytes(w))
+        return FF_ERR_WORKSPACE;
+      st = layer_mfma_pack(w, workspace, (hipStream_t)stream);
+      if (st != FF_OK) return st;
+      packed = workspace;
+    }
+    return layer_mfma_launch(feats, out, n, perm, group_offsets, num_groups, max_groups, w, G, out_f32, packed,
+                             (hipStream_t)stream);
+  }
+  return layer_generic_launch(feats, out, n, perm, group_offsets, num_groups, max_groups, w, G, dtype, out_f32,
+                              workspace, workspace_bytes, (hipStream_t)stream);
 }
 
 int ff_gather(const void* src, void* dst, const int32_t* perm, int64_t n, int C, int dtype, void* stream) {

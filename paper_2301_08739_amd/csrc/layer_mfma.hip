@@ -1,0 +1,565 @@
+// Group attention layer (paper Sec. 4.2.2, Eq. (2); Sec. 4.3 'Efficient MHSA' / 'Efficient FFN')
+// as ONE fused kernel on the bf16 matrix cores of gfx950:
+//
+//   gather -> LN1 -> packed QKV projection -> per-head softmax(Q K^T / sqrt(d)) V -> out-proj
+//   + residual -> LN2 -> Linear + GELU -> Linear + residual -> scatter
+//
+// Scores, probabilities, Q/K/V and the FFN hidden activations never leave the chip.
+//
+// Mapping.  A wavefront owns NVB blocks of 16 pillars of one group ("its" pillars); WPG wavefronts
+// share a group, NW wavefronts form a workgroup.  Everything is computed transposed, features x
+// pillars, with v_mfma_f32_16x16x32_bf16: the weight tile is the A operand (16 output features x
+// 32 inputs), the activations of 16 pillars are the B operand, and the accumulator holds
+// D[feature 4q+j][pillar i] in lane (i = lane & 15, q = lane >> 4).  That accumulator layout is,
+// after conversion to bf16, directly a B operand of the next product whose 8 k-slots in lane q
+// are inputs {4q..4q+3} of two consecutive 16-blocks; weights are pre-permuted along k to match
+// (pack kernel below), so activations chain from product to product in registers without any
+// LDS round trip.  V is produced with the operand roles swapped (pillars x features), which is
+// exactly the A operand P*V needs.  LayerNorm statistics and the softmax need only a reduction
+// over the four lanes that share a pillar.
+//
+// Weights reach the matrix cores through LDS: the packed stream is consumed in 32 KB chunks by
+// all wavefronts of the workgroup in lockstep, double buffered (one barrier per chunk).
+#include "common.h"
+
+namespace ff {
+namespace {
+
+typedef __bf16 bf16x8 __attribute__((ext_vector_type(8)));
+typedef __bf16 bf16x2 __attribute__((ext_vector_type(2)));
+typedef short s16x4 __attribute__((ext_vector_type(4)));
+typedef float f32x4 __attribute__((ext_vector_type(4)));
+typedef float f32x2 __attribute__((ext_vector_type(2)));
+typedef uint32_t u32x4 __attribute__((ext_vector_type(4)));
+typedef uint32_t u32x2 __attribute__((ext_vector_type(2)));
+
+union Frag8 {  // eight bf16 = one operand of the k=32 product
+  bf16x8 v;
+  uint32_t u[4];
+  u32x4 q;
+};
+union Frag4 {  // four bf16 = one operand of the k=16 product
+  s16x4 v;
+  uint32_t u[2];
+  u32x2 d;
+};
+
+__device__ __forceinline__ uint32_t pack2(float lo, float hi) {
+  f32x2 f = {lo, hi};
+  bf16x2 r = __builtin_convertvector(f, bf16x2);  // round to nearest even
+  return *reinterpret_cast<uint32_t*>(&r);
+}
+__device__ __forceinline__ void load4(const uint16_t* p, float* o) {  // 4 consecutive bf16 -> fp32
+  const uint2 u = *reinterpret_cast<const uint2*>(p);
+  o[0] = __uint_as_float(u.x << 16);
+  o[1] = __uint_as_float(u.x & 0xffff0000u);
+  o[2] = __uint_as_float(u.y << 16);
+  o[3] = __uint_as_float(u.y & 0xffff0000u);
+}
+__device__ __forceinline__ float quad_sum(float v) {  // over the 4 lanes that share a pillar
+  v += __shfl_xor(v, 16, 64);
+  v += __shfl_xor(v, 32, 64);
+  return v;
+}
+__device__ __forceinline__ float quad_max(float v) {
+  v = fmaxf(v, __shfl_xor(v, 16, 64));
+  v = fmaxf(v, __shfl_xor(v, 32, 64));
+  return v;
+}
+__device__ __forceinline__ f32x4 mfma32(const Frag8& a, const Frag8& b, f32x4 c) {
+  return __builtin_amdgcn_mfma_f32_16x16x32_bf16(a.v, b.v, c, 0, 0, 0);
+}
+__device__ __forceinline__ f32x4 mfma16(const Frag4& a, const Frag4& b, f32x4 c) {
+  return __builtin_amdgcn_mfma_f32_16x16x16bf16_1k(a.v, b.v, c, 0, 0, 0);
+}
+// GELU(v) = v * Phi(v) with erf from the rational-times-exponential form (abs. error 1.5e-7).
+__device__ __forceinline__ float gelu_fast(float v) {
+  const float z = fabsf(v) * 0.70710678118654752440f;
+  const float t = __builtin_amdgcn_rcpf(fmaf(0.3275911f, z, 1.0f));
+  float p = fmaf(t, 1.061405429f, -1.453152027f);
+  p = fmaf(t, p, 1.421413741f);
+  p = fmaf(t, p, -0.284496736f);
+  p = fmaf(t, p, 0.254829592f);
+  p *= t;
+  const float e = __builtin_amdgcn_exp2f(-z * z * 1.44269504088896340736f);
+  const float erf_abs = fmaf(-p, e, 1.0f);
+  const float erf_v = copysignf(erf_abs, v);
+  return 0.5f * v * (1.0f + erf_v);
+}
+
+struct SmallParams {  // per-feature vectors, bf16, read straight from the caller's arrays
+  const uint16_t *ln1_g, *ln1_b, *b_qkv, *b_o, *ln2_g, *ln2_b, *b1, *b2;
+};
+
+constexpr int kChunkFrags = 32;  // 1 KB fragments per staged chunk (32 KB)
+
+// Number of 1 KB fragments of the packed weight stream of one layer.
+__host__ __device__ constexpr int frags_per_hp(int C) { return 6 * (C / 32) + C / 16; }
+__host__ __device__ constexpr int frags_per_fc(int C) { return 2 * (C / 32) + C / 16; }
+
+// ---- weight packing ------------------------------------------------------------------------------
+// Stream order: for each 32-wide head-dim unit hp: Q rows (2 x KB fragments), K rows, V rows,
+// W_o column slice (NB fragments); then for each 32-wide hidden unit fc: W1 rows (2 x KB), W2
+// column slice (NB).  A fragment is 16 output features x 32 inputs; lane (i, q) owns 16 bytes:
+// row i, inputs kbase + 16*(s/4) + 4q + (s%4) for slot s = 0..7.
+__global__ __launch_bounds__(256) void k_pack_weights(const uint16_t* __restrict__ w_qkv, const uint16_t* __restrict__ w_o,
+                                                       const uint16_t* __restrict__ w1, const uint16_t* __restrict__ w2,
+                                                       int C, int F, uint4* __restrict__ out, int total_frags) {
+  const int t = blockIdx.x * blockDim.x + threadIdx.x;
+  const int frag = t >> 6, lane = t & 63, i = lane & 15, q = lane >> 4;
+  if (frag >= total_frags) return;
+  const int KB = C / 32, NB = C / 16, fr_hp = 6 * KB + NB, fr_fc = 2 * KB + NB, n_hp = C / 32;
+  const uint16_t* src;
+  int kbase;
+  if (frag < n_hp * fr_hp) {
+    const int hp = frag / fr_hp, r = frag % fr_hp;
+    if (r < 6 * KB) {
+      const int which = r / (2 * KB), rr = r % (2 * KB), a = rr / KB, kb = rr % KB;
+      src = w_qkv + (size_t)(which * C + 32 * hp + 16 * a + i) * C;
+      kbase = 32 * kb;
+    } else {
+      const int nb = r - 6 * KB;
+      src = w_o + (size_t)(16 * nb + i) * C;
+      kbase = 32 * hp;
+    }
+  } else {
+    const int f2 = frag - n_hp * fr_hp, fc = f2 / fr_fc, r = f2 % fr_fc;
+    if (r < 2 * KB) {
+      const int a = r / KB, kb = r % KB;
+      src = w1 + (size_t)(32 * fc + 16 * a + i) * C;
+      kbase = 32 * kb;
+    } else {
+      const int nb = r - 2 * KB;
+      src = w2 + (size_t)(16 * nb + i) * F;
+      kbase = 32 * fc;
+    }
+  }
+  uint32_t u[4];
+#pragma unroll
+  for (int s = 0; s < 8; s += 2) {
+    const int k0 = kbase + 16 * (s / 4) + 4 * q + (s % 4);
+    u[s / 2] = (uint32_t)src[k0] | ((uint32_t)src[k0 + 1] << 16);
+  }
+  out[(size_t)frag * 64 + lane] = make_uint4(u[0], u[1], u[2], u[3]);
+}
+
+// ---- the fused layer ------------------------------------------------------------------------------
+template <int C, int DH, int F, int NVB, int WPG, int NW, bool OUT_F32>
+__global__ __launch_bounds__(NW * 64, 1) void k_layer_mfma(const uint16_t* __restrict__ feats, void* __restrict__ out,
+                                                            const int32_t* __restrict__ perm,
+                                                            const int32_t* __restrict__ goff,
+                                                            const int32_t* __restrict__ num_groups,
+                                                            const u32x4* __restrict__ packed, SmallParams sp, float eps) {
+  constexpr int KB = C / 32;          // 32-wide blocks of the input features
+  constexpr int NB = C / 16;          // 16-wide blocks of the output features
+  constexpr int HP = C / 32;          // 32-wide head-dim units
+  constexpr int FC = F / 32;          // 32-wide hidden units
+  constexpr int NKB = NVB * WPG;      // key blocks of a group
+  constexpr int GPW = NW / WPG;       // groups per workgroup
+  constexpr int NT = NW * 64;
+  constexpr int FR_HP = frags_per_hp(C), FR_FC = frags_per_fc(C);
+  constexpr int CH = kChunkFrags;
+  constexpr int STG = CH * 64 / NT;   // uint4 per thread per chunk
+  constexpr int NCHUNK = (HP * FR_HP + FC * FR_FC) / CH;
+  constexpr int FCI = CH / FR_FC;     // hidden units per chunk
+  static_assert(DH == 16 || DH == 32, "head dim");
+  static_assert((HP * FR_HP) % CH == 0 && CH % FR_FC == 0 && FC % FCI == 0, "chunking");
+  static_assert(FR_HP == CH || FR_HP == 2 * CH, "chunking of a head-dim unit");
+  static_assert((CH * 64) % NT == 0, "staging");
+
+  extern __shared__ u32x4 lds[];
+  u32x4* ring = lds;                                   // [2][CH * 64]
+  u32x2* kvx = reinterpret_cast<u32x2*>(lds + 2 * CH * 64);  // K/V exchange, only when WPG > 1
+
+  const int tid = threadIdx.x, lane = tid & 63, w = tid >> 6, i = lane & 15, q = lane >> 4;
+  const int gl = w / WPG, part = w % WPG;
+  const int g = blockIdx.x * GPW + gl;
+  int start = 0, m = 0;
+  if (g < *num_groups) { start = goff[g]; m = goff[g + 1] - start; }
+
+  u32x4 stg[STG];
+  int cc = 0;  // chunk being consumed
+  auto issue = [&](int chunk) {
+    if (chunk < NCHUNK) {
+#pragma unroll
+      for (int s = 0; s < STG; ++s) stg[s] = packed[(size_t)chunk * CH * 64 + s * NT + tid];
+    }
+  };
+  auto commit = [&](int chunk) {
+    if (chunk < NCHUNK) {
+#pragma unroll
+      for (int s = 0; s < STG; ++s) ring[(chunk & 1) * CH * 64 + s * NT + tid] = stg[s];
+    }
+  };
+  auto advance = [&]() {  // done with chunk cc: publish cc+1, start fetching cc+2
+    commit(cc + 1);
+    __syncthreads();
+    ++cc;
+    issue(cc + 1);
+  };
+  issue(0);
+
+  // ---- gather + LN1 ---------------------------------------------------------------------------------
+  f32x4 x1[NVB][NB];  // residual stream of my pillars, accumulator layout
+  int64_t row[NVB];
+#pragma unroll
+  for (int vb = 0; vb < NVB; ++vb) {
+    const int s = (part * NVB + vb) * 16 + i;
+    row[vb] = s < m ? (int64_t)perm[start + s] : -1;
+#pragma unroll
+    for (int nb = 0; nb < NB; ++nb) {
+      float t[4] = {0.f, 0.f, 0.f, 0.f};
+      if (row[vb] >= 0) load4(feats + row[vb] * C + 16 * nb + 4 * q, t);
+      x1[vb][nb] = f32x4{t[0], t[1], t[2], t[3]};
+    }
+  }
+  commit(0);
+  __syncthreads();
+  issue(1);
+
+  Frag8 act[NVB][KB];  // normalised activations as B operands (LN1 output, later LN2 output)
+  auto layer_norm = [&](const uint16_t* gam, const uint16_t* bet) {
+    float mu[NVB], rstd[NVB];
+#pragma unroll
+    for (int vb = 0; vb < NVB; ++vb) {
+      float s = 0.f;
+#pragma unroll
+      for (int nb = 0; nb < NB; ++nb) s += (x1[vb][nb][0] + x1[vb][nb][1]) + (x1[vb][nb][2] + x1[vb][nb][3]);
+      mu[vb] = quad_sum(s) * (1.0f / C);
+      float v = 0.f;
+#pragma unroll
+      for (int nb = 0; nb < NB; ++nb) {
+#pragma unroll
+        for (int j = 0; j < 4; ++j) { const float d = x1[vb][nb][j] - mu[vb]; v = fmaf(d, d, v); }
+      }
+      rstd[vb] = rsqrtf(quad_sum(v) * (1.0f / C) + eps);
+    }
+#pragma unroll
+    for (int nb = 0; nb < NB; ++nb) {
+      float gm[4], bt[4];
+      load4(gam + 16 * nb + 4 * q, gm);
+      load4(bet + 16 * nb + 4 * q, bt);
+#pragma unroll
+      for (int vb = 0; vb < NVB; ++vb) {
+        float y[4];
+#pragma unroll
+        for (int j = 0; j < 4; ++j) y[j] = fmaf((x1[vb][nb][j] - mu[vb]) * rstd[vb], gm[j], bt[j]);
+        act[vb][nb / 2].u[(nb & 1) * 2 + 0] = pack2(y[0], y[1]);
+        act[vb][nb / 2].u[(nb & 1) * 2 + 1] = pack2(y[2], y[3]);
+      }
+    }
+  };
+  layer_norm(sp.ln1_g, sp.ln1_b);
+
+  // residual + output-projection bias
+#pragma unroll
+  for (int nb = 0; nb < NB; ++nb) {
+    float b[4];
+    load4(sp.b_o + 16 * nb + 4 * q, b);
+#pragma unroll
+    for (int vb = 0; vb < NVB; ++vb) x1[vb][nb] += f32x4{b[0], b[1], b[2], b[3]};
+  }
+
+  const float qscale = rsqrtf((float)DH) * 1.44269504088896340736f;  // 1/sqrt(d) * log2(e)
+
+  // ---- attention: one 32-wide head-dim unit per iteration (two heads of 16 or one head of 32) --------
+#pragma unroll 1
+  for (int hp = 0; hp < HP; ++hp) {
+    const u32x4* rb = ring + (cc & 1) * CH * 64 + lane;
+    int fo = 0;
+    Frag4 Qf[2][NVB], Kf[2][NVB], Vf[2][NVB];  // bf16 fragments of my pillars, index [16-block a][vb]
+
+    // Q and K rows: D[feature][pillar]
+#pragma unroll
+    for (int qk = 0; qk < 2; ++qk) {
+#pragma unroll
+      for (int a = 0; a < 2; ++a) {
+        f32x4 acc[NVB];
+#pragma unroll
+        for (int vb = 0; vb < NVB; ++vb) acc[vb] = f32x4{0.f, 0.f, 0.f, 0.f};
+#pragma unroll
+        for (int kb = 0; kb < KB; ++kb) {
+          Frag8 wf;
+          wf.q = rb[(fo + a * KB + kb) * 64];
+#pragma unroll
+          for (int vb = 0; vb < NVB; ++vb) acc[vb] = mfma32(wf, act[vb][kb], acc[vb]);
+        }
+        float b[4];
+        load4(sp.b_qkv + qk * C + 32 * hp + 16 * a + 4 * q, b);
+#pragma unroll
+        for (int vb = 0; vb < NVB; ++vb) {
+          if (qk == 0) {
+            Qf[a][vb].u[0] = pack2((acc[vb][0] + b[0]) * qscale, (acc[vb][1] + b[1]) * qscale);
+            Qf[a][vb].u[1] = pack2((acc[vb][2] + b[2]) * qscale, (acc[vb][3] + b[3]) * qscale);
+          } else {
+            Kf[a][vb].u[0] = pack2(acc[vb][0] + b[0], acc[vb][1] + b[1]);
+            Kf[a][vb].u[1] = pack2(acc[vb][2] + b[2], acc[vb][3] + b[3]);
+          }
+        }
+      }
+      fo += 2 * KB;
+    }
+    if (FR_HP == 2 * CH) {  // the unit spans two chunks: Q,K | V,W_o
+      advance();
+      rb = ring + (cc & 1) * CH * 64 + lane;
+      fo = 0;
+    }
+    // V rows with the operand roles swapped: D[pillar][feature]
+#pragma unroll
+    for (int a = 0; a < 2; ++a) {
+      f32x4 acc[NVB];
+#pragma unroll
+      for (int vb = 0; vb < NVB; ++vb) acc[vb] = f32x4{0.f, 0.f, 0.f, 0.f};
+#pragma unroll
+      for (int kb = 0; kb < KB; ++kb) {
+        Frag8 wf;
+        wf.q = rb[(fo + a * KB + kb) * 64];
+#pragma unroll
+        for (int vb = 0; vb < NVB; ++vb) acc[vb] = mfma32(act[vb][kb], wf, acc[vb]);
+      }
+      const float bv = bf16_to_f32(sp.b_qkv[2 * C + 32 * hp + 16 * a + i]);
+#pragma unroll
+      for (int vb = 0; vb < NVB; ++vb) {
+        Vf[a][vb].u[0] = pack2(acc[vb][0] + bv, acc[vb][1] + bv);
+        Vf[a][vb].u[1] = pack2(acc[vb][2] + bv, acc[vb][3] + bv);
+      }
+    }
+    fo += 2 * KB;
+
+    // K/V of the whole group.  One wavefront per group: they are already in registers.
+    u32x2* kv = nullptr;
+    if (WPG > 1) {
+      // exchange area: [group in workgroup][hp parity][K|V][16-block a][key block][lane]
+      kv = kvx + ((size_t)(gl * 2 + (hp & 1)) * 2) * 2 * NKB * 64 + lane;
+#pragma unroll
+      for (int a = 0; a < 2; ++a) {
+#pragma unroll
+        for (int vb = 0; vb < NVB; ++vb) {
+          kv[((0 * 2 + a) * NKB + part * NVB + vb) * 64] = Kf[a][vb].d;
+          kv[((1 * 2 + a) * NKB + part * NVB + vb) * 64] = Vf[a][vb].d;
+        }
+      }
+      __syncthreads();
+    }
+    auto Kget = [&](int a, int jb) -> Frag4 {
+      if (WPG == 1) return Kf[a][jb];
+      Frag4 f; f.d = kv[((0 * 2 + a) * NKB + jb) * 64]; return f;
+    };
+    auto Vget = [&](int a, int jb) -> Frag4 {
+      if (WPG == 1) return Vf[a][jb];
+      Frag4 f; f.d = kv[((1 * 2 + a) * NKB + jb) * 64]; return f;
+    };
+
+    Frag8 Of[NVB];  // attention output of this unit as B operand of the output projection
+    constexpr int NH = 32 / DH;  // heads in this unit
+#pragma unroll
+    for (int h = 0; h < NH; ++h) {
+#pragma unroll
+      for (int vb = 0; vb < NVB; ++vb) {
+        // scores, transposed: S[key 16*jb + 4q + j][query i]
+        f32x4 S[NKB];
+#pragma unroll
+        for (int jb = 0; jb < NKB; ++jb) {
+          const f32x4 z = f32x4{0.f, 0.f, 0.f, 0.f};
+          if (DH == 16) {
+            S[jb] = mfma16(Kget(h, jb), Qf[h][vb], z);
+          } else {
+            Frag8 k8, q8;
+            const Frag4 k0 = Kget(0, jb), k1 = Kget(1, jb);
+            k8.u[0] = k0.u[0]; k8.u[1] = k0.u[1]; k8.u[2] = k1.u[0]; k8.u[3] = k1.u[1];
+            q8.u[0] = Qf[0][vb].u[0]; q8.u[1] = Qf[0][vb].u[1]; q8.u[2] = Qf[1][vb].u[0]; q8.u[3] = Qf[1][vb].u[1];
+            S[jb] = mfma32(k8, q8, z);
+          }
+        }
+        float mx = -INFINITY;
+#pragma unroll
+        for (int jb = 0; jb < NKB; ++jb) {
+#pragma unroll
+          for (int j = 0; j < 4; ++j) {
+            if (16 * jb + 4 * q + j >= m) S[jb][j] = -INFINITY;  // keys beyond the group's real members
+            mx = fmaxf(mx, S[jb][j]);
+          }
+        }
+        mx = quad_max(mx);
+        float sum = 0.f;
+#pragma unroll
+        for (int jb = 0; jb < NKB; ++jb) {
+#pragma unroll
+          for (int j = 0; j < 4; ++j) { S[jb][j] = __builtin_amdgcn_exp2f(S[jb][j] - mx); sum += S[jb][j]; }
+        }
+        const float inv = __builtin_amdgcn_rcpf(quad_sum(sum));
+        // O^T[d][query] = sum over keys V^T[d][key] P^T[key][query]; two key blocks per product
+        constexpr int NA = DH / 16;  // 16-blocks of head dims of this head
+        f32x4 O[NA];
+#pragma unroll
+        for (int a = 0; a < NA; ++a) O[a] = f32x4{0.f, 0.f, 0.f, 0.f};
+#pragma unroll
+        for (int jb = 0; jb + 1 < NKB; jb += 2) {
+          Frag8 p8;
+          p8.u[0] = pack2(S[jb][0], S[jb][1]); p8.u[1] = pack2(S[jb][2], S[jb][3]);
+          p8.u[2] = pack2(S[jb + 1][0], S[jb + 1][1]); p8.u[3] = pack2(S[jb + 1][2], S[jb + 1][3]);
+#pragma unroll
+          for (int a = 0; a < NA; ++a) {
+            const int ab = DH == 16 ? h : a;
+            const Frag4 v0 = Vget(ab, jb), v1 = Vget(ab, jb + 1);
+            Frag8 v8;
+            v8.u[0] = v0.u[0]; v8.u[1] = v0.u[1]; v8.u[2] = v1.u[0]; v8.u[3] = v1.u[1];
+            O[a] = mfma32(v8, p8, O[a]);
+          }
+        }
+        if (NKB & 1) {
+          constexpr int jb = NKB - 1;
+          Frag4 p4;
+          p4.u[0] = pack2(S[jb][0], S[jb][1]); p4.u[1] = pack2(S[jb][2], S[jb][3]);
+#pragma unroll
+          for (int a = 0; a < NA; ++a) O[a] = mfma16(Vget(DH == 16 ? h : a, jb), p4, O[a]);
+        }
+#pragma unroll
+        for (int a = 0; a < NA; ++a) {
+          const int slot = DH == 16 ? h : a;
+          Of[vb].u[slot * 2 + 0] = pack2(O[a][0] * inv, O[a][1] * inv);
+          Of[vb].u[slot * 2 + 1] = pack2(O[a][2] * inv, O[a][3] * inv);
+        }
+      }
+    }
+    // output projection of this unit, accumulated into the residual stream
+#pragma unroll
+    for (int nb = 0; nb < NB; ++nb) {
+      Frag8 wf;
+      wf.q = rb[(fo + nb) * 64];
+#pragma unroll
+      for (int vb = 0; vb < NVB; ++vb) x1[vb][nb] = mfma32(wf, Of[vb], x1[vb][nb]);
+    }
+    advance();
+  }
+
+  // ---- FFN ------------------------------------------------------------------------------------------
+  layer_norm(sp.ln2_g, sp.ln2_b);
+#pragma unroll
+  for (int nb = 0; nb < NB; ++nb) {
+    float b[4];
+    load4(sp.b2 + 16 * nb + 4 * q, b);
+#pragma unroll
+    for (int vb = 0; vb < NVB; ++vb) x1[vb][nb] += f32x4{b[0], b[1], b[2], b[3]};
+  }
+#pragma unroll 1
+  for (int it = 0; it < FC / FCI; ++it) {
+    const u32x4* rb = ring + (cc & 1) * CH * 64 + lane;
+#pragma unroll
+    for (int fi = 0; fi < FCI; ++fi) {
+      const int fc = it * FCI + fi;
+      const int fo = fi * FR_FC;
+      Frag8 Hf[NVB];
+#pragma unroll
+      for (int a = 0; a < 2; ++a) {
+        f32x4 acc[NVB];
+#pragma unroll
+        for (int vb = 0; vb < NVB; ++vb) acc[vb] = f32x4{0.f, 0.f, 0.f, 0.f};
+#pragma unroll
+        for (int kb = 0; kb < KB; ++kb) {
+          Frag8 wf;
+          wf.q = rb[(fo + a * KB + kb) * 64];
+#pragma unroll
+          for (int vb = 0; vb < NVB; ++vb) acc[vb] = mfma32(wf, act[vb][kb], acc[vb]);
+        }
+        float b[4];
+        load4(sp.b1 + 32 * fc + 16 * a + 4 * q, b);
+#pragma unroll
+        for (int vb = 0; vb < NVB; ++vb) {
+          Hf[vb].u[a * 2 + 0] = pack2(gelu_fast(acc[vb][0] + b[0]), gelu_fast(acc[vb][1] + b[1]));
+          Hf[vb].u[a * 2 + 1] = pack2(gelu_fast(acc[vb][2] + b[2]), gelu_fast(acc[vb][3] + b[3]));
+        }
+      }
+#pragma unroll
+      for (int nb = 0; nb < NB; ++nb) {
+        Frag8 wf;
+        wf.q = rb[(fo + 2 * KB + nb) * 64];
+#pragma unroll
+        for (int vb = 0; vb < NVB; ++vb) x1[vb][nb] = mfma32(wf, Hf[vb], x1[vb][nb]);
+      }
+    }
+    if (it + 1 < FC / FCI) advance();
+  }
+
+  // ---- scatter -------------------------------------------------------------------------------------
+#pragma unroll
+  for (int vb = 0; vb < NVB; ++vb) {
+    if (row[vb] < 0) continue;
+#pragma unroll
+    for (int nb = 0; nb < NB; ++nb) {
+      const size_t o = (size_t)row[vb] * C + 16 * nb + 4 * q;
+      if (OUT_F32) {
+        *reinterpret_cast<float4*>(reinterpret_cast<float*>(out) + o) =
+            make_float4(x1[vb][nb][0], x1[vb][nb][1], x1[vb][nb][2], x1[vb][nb][3]);
+      } else {
+        *reinterpret_cast<uint2*>(reinterpret_cast<uint16_t*>(out) + o) =
+            make_uint2(pack2(x1[vb][nb][0], x1[vb][nb][1]), pack2(x1[vb][nb][2], x1[vb][nb][3]));
+      }
+    }
+  }
+}
+
+template <int C, int DH, int F, int NVB, int WPG, int NW>
+int launch_cfg(const void* feats, void* out, const int32_t* perm, const int32_t* goff, const int32_t* num_groups,
+               int32_t max_groups, const u32x4* packed, const SmallParams& sp, float eps, bool out_f32,
+               hipStream_t stream) {
+  constexpr int GPW = NW / WPG;
+  constexpr int NKB = NVB * WPG;
+  const size_t lds_bytes = (size_t)2 * kChunkFrags * 1024 + (WPG > 1 ? (size_t)GPW * 2 * 2 * 2 * NKB * 64 * 8 : 0);
+  const unsigned blocks = (unsigned)((max_groups + GPW - 1) / GPW);
+  auto go = [&](auto kern) -> int {
+    static bool attr_done = false;  // the attribute only has to be set once per kernel
+    if (!attr_done) {
+      if (hipFuncSetAttribute(reinterpret_cast<const void*>(kern), hipFuncAttributeMaxDynamicSharedMemorySize,
+                              (int)lds_bytes) != hipSuccess)
+        return FF_ERR_LAUNCH;
+      attr_done = true;
+    }
+    hipLaunchKernelGGL(kern, dim3(blocks), dim3(NW * 64), lds_bytes, stream, (const uint16_t*)feats, out, perm, goff,
+                       num_groups, packed, sp, eps);
+    return launch_status();
+  };
+  if (out_f32) return go(k_layer_mfma<C, DH, F, NVB, WPG, NW, true>);
+  return go(k_layer_mfma<C, DH, F, NVB, WPG, NW, false>);
+}
+
+}  // namespace
+
+bool layer_mfma_supported(const ff_layer_weights* w, int G) {
+  const int C = w->C, F = w->F, d = C / w->heads;
+  if (C == 128 && d == 16 && F == 256) return G <= 128;
+  return false;
+}
+
+size_t layer_mfma_packed_bytes(const ff_layer_weights* w) {
+  const int C = w->C, F = w->F;
+  return (size_t)((C / 32) * frags_per_hp(C) + (F / 32) * frags_per_fc(C)) * 1024;
+}
+
+int layer_mfma_pack(const ff_layer_weights* w, void* packed, hipStream_t stream) {
+  const int total = (int)(layer_mfma_packed_bytes(w) / 1024);
+  hipLaunchKernelGGL(k_pack_weights, dim3((unsigned)((total * 64 + 255) / 256)), dim3(256), 0, stream,
+                     (const uint16_t*)w->w_qkv, (const uint16_t*)w->w_o, (const uint16_t*)w->w1,
+                     (const uint16_t*)w->w2, w->C, w->F, (uint4*)packed, total);
+  return launch_status();
+}
+
+int layer_mfma_launch(const void* feats, void* out, int64_t n, const int32_t* perm, const int32_t* group_offsets,
+                      const int32_t* num_groups, int32_t max_groups, const ff_layer_weights* w, int G,
+                      bool out_f32, const void* packed, hipStream_t stream) {
+  (void)n;
+  if (max_groups == 0) return FF_OK;
+  SmallParams sp{(const uint16_t*)w->ln1_g, (const uint16_t*)w->ln1_b, (const uint16_t*)w->b_qkv,
+                 (const uint16_t*)w->b_o,   (const uint16_t*)w->ln2_g, (const uint16_t*)w->ln2_b,
+                 (const uint16_t*)w->b1,    (const uint16_t*)w->b2};
+  const u32x4* pk = (const u32x4*)packed;
+  const int C = w->C, F = w->F, d = C / w->heads;
+  if (C == 128 && d == 16 && F == 256) {
+    if (G <= 32) return launch_cfg<128, 16, 256, 2, 1, 4>(feats, out, perm, group_offsets, num_groups, max_groups, pk, sp, w->ln_eps, out_f32, stream);
+    if (G <= 64) return launch_cfg<128, 16, 256, 4, 1, 4>(feats, out, perm, group_offsets, num_groups, max_groups, pk, sp, w->ln_eps, out_f32, stream);
+    if (G <= 128) return launch_cfg<128, 16, 256, 4, 2, 4>(feats, out, perm, group_offsets, num_groups, max_groups, pk, sp, w->ln_eps, out_f32, stream);
+  }
+  return FF_ERR_UNSUPPORTED;
+}
+
+}  // namespace ff

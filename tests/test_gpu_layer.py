@@ -3,10 +3,12 @@
 Tolerances (max-abs, from the benchmark spec): 1e-4 for fp32, 2e-2 for bf16.  bf16 layers are
 compared teacher-forced: the GPU layer runs on the same bf16 input the oracle's layer gets.
 
-A bf16 output buffer cannot hold a value of magnitude >= 8 closer than half an ulp = 0.03125 >
-2e-2, so the bf16 bar is applied in two parts: (a) the layer's result before storage rounding
-(FF_FLAG_OUT_F32) is within 2e-2 of the oracle everywhere; (b) the bf16 buffer is exactly the
-round-to-nearest-even of (a), and is itself within 2e-2 wherever |reference| < 8."""
+A bf16 output BUFFER cannot meet 2e-2 by itself: storing a value y costs up to half an ulp,
+2^-9 |y| (0.0156 for |y| in [4,8), 0.031 beyond 8), on top of the arithmetic error.  The bf16
+bar is therefore applied as: (a) the layer's result before storage rounding (FF_FLAG_OUT_F32)
+is within 2e-2 of the oracle everywhere; (b) the bf16 buffer is bit for bit the
+round-to-nearest-even of (a); (c) the buffer itself is within 2e-2 + 2^-9 |y| everywhere, and
+within plain 2e-2 wherever |reference| < 2 (storage rounding <= 0.004 there)."""
 import numpy as np
 import pytest
 import torch
@@ -45,11 +47,13 @@ def _assert_bf16_bar(wide, narrow, want, rows=None):
     if rows is not None:
         wide, narrow, want = wide[rows], narrow[rows], want[rows]
     e_wide = np.abs(wide - want).max()
-    small = np.abs(want) < 8.0
-    e_narrow = np.abs(narrow - want)[small].max()
     assert e_wide <= 2e-2, e_wide
+    err = np.abs(narrow - want)
+    assert np.all(err <= 2e-2 + 2.0 ** -9 * np.abs(narrow))
+    small = np.abs(want) < 2.0
+    e_narrow = err[small].max()
     assert e_narrow <= 2e-2, e_narrow
-    return e_wide, e_narrow
+    return e_wide, err.max()
 
 
 def test_config1_fp32_every_layer_and_stack(cfg):
@@ -81,7 +85,7 @@ def test_bf16_layers_teacher_forced_full(cfg, i, nl):
         wide, narrow, perm, off = _run_layer_bf16_both(c, cur, c["layer_params"][l], *key)
         want = oracle.layer(cur, perm, off, c["layer_params"][l])
         ew, en = _assert_bf16_bar(wide, narrow, want)
-        print(f"cfg{i} layer {l} sort {key}: max abs err f32-store {ew:.4e} bf16-store(|ref|<8) {en:.4e}, "
+        print(f"cfg{i} layer {l} sort {key}: max abs err f32-store {ew:.4e} bf16-store {en:.4e}, "
               f"max |ref| {np.abs(want).max():.3f}", flush=True)
         cur = ffsynth.bf16_round(want)          # the next layer's input as a bf16 buffer holds it
 
@@ -132,3 +136,30 @@ def test_closed_forms_on_gpu(cfg):
     assert np.abs(gotN - oracle.group_layer(feats, p)).max() <= 1e-4
     again, _, _ = _run_layer(c, feats, p, 1, 1, G=n)
     assert np.array_equal(gotN, again)
+
+
+@pytest.mark.parametrize("G", [1, 7, 16, 32, 33, 64, 65, 100, 128])
+def test_bf16_group_sizes_and_tails(cfg, G):
+    """Every wave/group mapping of the fused bf16 kernel, full oracle comparison on a small
+    cloud whose last group is short (n = 1003)."""
+    c = dict(cfg(2, 1))
+    n = 1003
+    c["coords"], feats = c["coords"][:n], c["feats"][:n]
+    p = c["layer_params"][0]
+    g, og = geoms(c)
+    perm, off, ng, _, dev = gpu_flatten(c["coords"], g, 1, 1, G, want_keys=False)
+    want = oracle.layer(feats, perm, off, p)
+    lw = ff.LayerWeights(p, ff.FF_BF16, DEV)
+    x = to_dev_feats(feats, ff.FF_BF16)
+    wide = to_host(ff.ff_group_attention(x, dev[0], dev[1], dev[2], ng + 1, lw, G, ff.FF_BF16, ff.FF_FLAG_OUT_F32))
+    narrow = ff.ff_group_attention(x, dev[0], dev[1], dev[2], ng + 1, lw, G, ff.FF_BF16, 0)
+    plain = to_host(ff.ff_group_attention(x, dev[0], dev[1], dev[2], ng + 1, lw, G, ff.FF_BF16,
+                                          ff.FF_FLAG_OUT_F32 | ff.FF_FLAG_FORCE_GENERIC))
+    lw.pack()
+    packed = ff.ff_group_attention(x, dev[0], dev[1], dev[2], ng + 1, lw, G, ff.FF_BF16, 0)
+    torch.cuda.synchronize()
+    ew, en = _assert_bf16_bar(wide, to_host(narrow), want)
+    assert np.abs(plain - want).max() <= 2e-2
+    assert torch.equal(packed, narrow)                      # pre-packed weights change nothing
+    print(f"G={G}: fused f32-store err {ew:.3e}, bf16-store err {en:.3e}, plain kernels err "
+          f"{np.abs(plain - want).max():.3e}", flush=True)
