@@ -80,7 +80,9 @@ def main():
     ap.add_argument("--warmup", type=int, default=10)
     ap.add_argument("--config", type=int, default=2)
     ap.add_argument("--no-cpu", action="store_true")
-    ap.add_argument("--sweep", action="store_true", help="also print per-kernel lines for larger batches (stderr)")
+    ap.add_argument("--sweep", action="store_true",
+                    help="also time flatten / gather / scatter / layer on batches of frames (JSON lines on stderr)")
+    ap.add_argument("--variant", type=int, default=0, help="wave-to-group mapping of the fused layer kernel (0 = auto)")
     a = ap.parse_args()
     if a.gpus != 1:
         print("bench.py measures one GPU: this build has no multi-GPU path (run with --gpus 1)", file=sys.stderr)
@@ -120,7 +122,9 @@ def main():
     gth = torch.empty_like(feats)
     reps = max(a.steps, 20)
     ms_flat, _ = time_region(lambda: ff.ff_flatten(coords, geom, 0, 1, G, workspace=fws), reps, 5)
-    ms_layer, _ = time_region(lambda: ff.ff_group_attention(feats, perm, goff, ng, max_groups, layers[0], G, dt,
+    lpk = ff.LayerWeights(c["layer_params"][0], dt, dev).pack()       # exactly one kernel in the timed region
+    vflag = ff.FF_FLAG_VARIANT(a.variant)
+    ms_layer, _ = time_region(lambda: ff.ff_group_attention(feats, perm, goff, ng, max_groups, lpk, G, dt, vflag,
                                                             out=out, workspace=lws), reps, 5)
     ms_gather, _ = time_region(lambda: ff.ff_gather(feats, perm, dt, out=gth), reps, 5)
     ms_scatter, _ = time_region(lambda: ff.ff_scatter(gth, perm, dt, out=out), reps, 5)
@@ -165,6 +169,55 @@ def main():
     if not a.no_cpu:
         res["cpu_baseline"] = cpu_baseline(c)
     print(json.dumps(res), flush=True)
+    if a.sweep:
+        sweep(ff, torch, c, dt, dev)
+
+
+def sweep(ff, torch, c, dt, dev):
+    """Saturation sweep: B copies of the frame as a batch (frame id in column 0), same C / G."""
+    import numpy as np
+    n1, C, F, G = c["n"], c["C"], c["F"], c["G"]
+    esz = 4 if dt == ff.FF_F32 else 2
+    tdt = torch.float32 if dt == ff.FF_F32 else torch.bfloat16
+    lw = ff.LayerWeights(c["layer_params"][0], dt, dev).pack()
+    for B in (1, 8, 32, 128):
+        coords = np.tile(c["coords"], (B, 1))
+        coords[:, 0] = np.repeat(np.arange(B, dtype=np.int32), n1)
+        rng = np.random.default_rng(B)
+        coords = np.ascontiguousarray(coords[rng.permutation(coords.shape[0])])
+        n = coords.shape[0]
+        geom = ff.Geometry(B, c["grid"], c["grid"], c["window"], c["window"])
+        ct = torch.from_numpy(coords).to(dev)
+        feats = torch.randn((n, C), device=dev, dtype=torch.float32).to(tdt)
+        out = torch.empty_like(feats)
+        gth = torch.empty_like(feats)
+        fws = torch.empty(ff.ff_flatten_workspace_bytes(n, geom) + 512, dtype=torch.uint8, device=dev)
+        lws = torch.empty(ff.ff_group_attention_workspace_bytes(n, G, lw, dt) + 512, dtype=torch.uint8, device=dev)
+        perm, goff, ng, _ = ff.ff_flatten(ct, geom, 0, 1, G, workspace=fws)
+        torch.cuda.synchronize()
+        mg = -(-n // G) + B
+        reps = 20 if B <= 32 else 8
+        def bits(v):
+            return int(v - 1).bit_length() if v > 1 else 0
+        nw = -(-(c["grid"] + c["window"] // 2) // c["window"])
+        passes = -(-(bits(B) + 2 * bits(nw) + 2 * bits(c["window"])) // 8)
+        line = {"sweep_frames": B, "n": n, "radix_passes": passes}
+        ms, _ = time_region(lambda: ff.ff_flatten(ct, geom, 0, 1, G, workspace=fws), reps, 3)
+        line["flatten"] = {"ms": ms, "GBps": (28 + 24 * passes) * n / ms / 1e6, "Mvox_s": n / ms / 1e3}
+        ms, _ = time_region(lambda: ff.ff_gather(feats, perm, dt, out=gth), reps, 3)
+        line["gather"] = {"ms": ms, "GBps": (2 * C * esz + 4) * n / ms / 1e6}
+        ms, _ = time_region(lambda: ff.ff_scatter(gth, perm, dt, out=out), reps, 3)
+        line["scatter"] = {"ms": ms, "GBps": (2 * C * esz + 4) * n / ms / 1e6}
+        flops = layer_flops_per_voxel(C, F, G) * n
+        for variant in ((0,) if dt == ff.FF_F32 else (2, 3)):
+            try:
+                fl = ff.FF_FLAG_VARIANT(variant)
+                ms, _ = time_region(lambda: ff.ff_group_attention(feats, perm, goff, ng, mg, lw, G, dt, fl, out=out,
+                                                                  workspace=lws), reps, 3)
+                line[f"layer_v{variant}"] = {"ms": ms, "TFLOPs": flops / ms / 1e9, "Mvox_s": n / ms / 1e3}
+            except ff.FlatformerError as e:
+                line[f"layer_v{variant}"] = str(e)
+        print(json.dumps(line), file=sys.stderr, flush=True)
 
 
 if __name__ == "__main__":

@@ -124,6 +124,9 @@ int ff_pack_weights(const ff_layer_weights* w, int dtype, void* packed, void* st
 /* Flags of ff_group_attention. */
 #define FF_FLAG_OUT_F32 1u      /* store `out` as float32 even when dtype is FF_BF16 */
 #define FF_FLAG_FORCE_GENERIC 2u /* use the plain fp32-arithmetic kernels for any dtype */
+/* Tuning knob: bits 8..11 select one wave-to-group mapping of the fused bf16 kernel (1..15; 0 =
+ * chosen from the shape).  A mapping that cannot hold G returns FF_ERR_UNSUPPORTED. */
+#define FF_FLAG_VARIANT(v) (((uint32_t)(v) & 0xfu) << 8)
 
 size_t ff_group_attention_workspace_bytes(int64_t n, int G, const ff_layer_weights* w, int dtype);
 

@@ -6,13 +6,14 @@ used for device memory and streams.  There is no CPU fallback: calling anything 
 built library raises.
 """
 from .binding import (Geometry, LayerWeights, FF_F32, FF_BF16, FF_FLAG_OUT_F32, FF_FLAG_FORCE_GENERIC,
+                      FF_FLAG_VARIANT,
                       FlatformerError, load_library, library_path, exported_symbols,
                       ff_flatten, ff_flatten_workspace_bytes, ff_group_attention,
                       ff_group_attention_workspace_bytes, ff_gather, ff_scatter, ff_fwa_block,
                       ff_fwa_block_workspace_bytes, ff_status_string, ff_version)
 
 __all__ = [
-    "Geometry", "LayerWeights", "FF_F32", "FF_BF16", "FF_FLAG_OUT_F32", "FF_FLAG_FORCE_GENERIC",
+    "Geometry", "LayerWeights", "FF_F32", "FF_BF16", "FF_FLAG_OUT_F32", "FF_FLAG_FORCE_GENERIC", "FF_FLAG_VARIANT",
     "FlatformerError", "load_library", "library_path", "exported_symbols",
     "ff_flatten", "ff_flatten_workspace_bytes", "ff_group_attention",
     "ff_group_attention_workspace_bytes", "ff_gather", "ff_scatter", "ff_fwa_block",

@@ -13,6 +13,10 @@ FF_TAIL_MASK, FF_TAIL_DROP = 0, 1
 FF_FLAG_OUT_F32, FF_FLAG_FORCE_GENERIC = 1, 2
 
 
+def FF_FLAG_VARIANT(v):
+    return (int(v) & 0xF) << 8
+
+
 class FlatformerError(RuntimeError):
     pass
 

@@ -88,7 +88,7 @@ int ff_group_attention(const void* feats, void* out, int64_t n, const int32_t* p
       packed = workspace;
     }
     return layer_mfma_launch(feats, out, n, perm, group_offsets, num_groups, max_groups, w, G, out_f32, packed,
-                             (hipStream_t)stream);
+                             (int)((flags >> 8) & 0xf), (hipStream_t)stream);
   }
   return layer_generic_launch(feats, out, n, perm, group_offsets, num_groups, max_groups, w, G, dtype, out_f32,
                               workspace, workspace_bytes, (hipStream_t)stream);

@@ -56,15 +56,20 @@ __device__ __forceinline__ void load4(const uint16_t* p, float* o) {  // 4 conse
   o[2] = __uint_as_float(u.y << 16);
   o[3] = __uint_as_float(u.y & 0xffff0000u);
 }
-__device__ __forceinline__ float quad_sum(float v) {  // over the 4 lanes that share a pillar
-  v += __shfl_xor(v, 16, 64);
-  v += __shfl_xor(v, 32, 64);
-  return v;
+// Reductions over the 4 lanes that share a pillar (lane, lane^16, lane^32, lane^48), on the
+// vector ALU: v_permlane16_swap / v_permlane32_swap with both operands equal to v return the
+// pair (v from the even half, v from the odd half) in every lane.
+__device__ __forceinline__ float quad_sum(float v) {
+  auto a = __builtin_amdgcn_permlane16_swap(__float_as_uint(v), __float_as_uint(v), false, false);
+  v = __uint_as_float(a[0]) + __uint_as_float(a[1]);
+  auto b = __builtin_amdgcn_permlane32_swap(__float_as_uint(v), __float_as_uint(v), false, false);
+  return __uint_as_float(b[0]) + __uint_as_float(b[1]);
 }
 __device__ __forceinline__ float quad_max(float v) {
-  v = fmaxf(v, __shfl_xor(v, 16, 64));
-  v = fmaxf(v, __shfl_xor(v, 32, 64));
-  return v;
+  auto a = __builtin_amdgcn_permlane16_swap(__float_as_uint(v), __float_as_uint(v), false, false);
+  v = fmaxf(__uint_as_float(a[0]), __uint_as_float(a[1]));
+  auto b = __builtin_amdgcn_permlane32_swap(__float_as_uint(v), __float_as_uint(v), false, false);
+  return fmaxf(__uint_as_float(b[0]), __uint_as_float(b[1]));
 }
 __device__ __forceinline__ f32x4 mfma32(const Frag8& a, const Frag8& b, f32x4 c) {
   return __builtin_amdgcn_mfma_f32_16x16x32_bf16(a.v, b.v, c, 0, 0, 0);
@@ -72,26 +77,22 @@ __device__ __forceinline__ f32x4 mfma32(const Frag8& a, const Frag8& b, f32x4 c)
 __device__ __forceinline__ f32x4 mfma16(const Frag4& a, const Frag4& b, f32x4 c) {
   return __builtin_amdgcn_mfma_f32_16x16x16bf16_1k(a.v, b.v, c, 0, 0, 0);
 }
-// GELU(v) = v * Phi(v) with erf from the rational-times-exponential form (abs. error 1.5e-7).
+// GELU(v) = v * Phi(v), with Phi(v) ~ 1 / (1 + exp(-(a v + b v^3 + c v^5))): an odd quintic inside
+// a logistic, coefficients fitted to the erf form on [-8, 8] (max abs error of v * Phi(v): 2.6e-5).
+// The argument is clamped to the fitted range, where the logistic is saturated to 1e-12 anyway.
 __device__ __forceinline__ float gelu_fast(float v) {
-  const float z = fabsf(v) * 0.70710678118654752440f;
-  const float t = __builtin_amdgcn_rcpf(fmaf(0.3275911f, z, 1.0f));
-  float p = fmaf(t, 1.061405429f, -1.453152027f);
-  p = fmaf(t, p, 1.421413741f);
-  p = fmaf(t, p, -0.284496736f);
-  p = fmaf(t, p, 0.254829592f);
-  p *= t;
-  const float e = __builtin_amdgcn_exp2f(-z * z * 1.44269504088896340736f);
-  const float erf_abs = fmaf(-p, e, 1.0f);
-  const float erf_v = copysignf(erf_abs, v);
-  return 0.5f * v * (1.0f + erf_v);
+  constexpr float L2E = 1.44269504088896340736f;
+  const float x = __builtin_amdgcn_fmed3f(v, -8.0f, 8.0f);
+  const float x2 = x * x;
+  float p = fmaf(x2, 7.03033568e-04f * L2E, -7.40112920e-02f * L2E);
+  p = fmaf(x2, p, -1.59501577f * L2E);
+  const float e = __builtin_amdgcn_exp2f(p * x);
+  return v * __builtin_amdgcn_rcpf(1.0f + e);
 }
 
 struct SmallParams {  // per-feature vectors, bf16, read straight from the caller's arrays
   const uint16_t *ln1_g, *ln1_b, *b_qkv, *b_o, *ln2_g, *ln2_b, *b1, *b2;
 };
-
-constexpr int kChunkFrags = 32;  // 1 KB fragments per staged chunk (32 KB)
 
 // Number of 1 KB fragments of the packed weight stream of one layer.
 __host__ __device__ constexpr int frags_per_hp(int C) { return 6 * (C / 32) + C / 16; }
@@ -144,36 +145,40 @@ __global__ __launch_bounds__(256) void k_pack_weights(const uint16_t* __restrict
 }
 
 // ---- the fused layer ------------------------------------------------------------------------------
-template <int C, int DH, int F, int NVB, int WPG, int NW, bool OUT_F32>
-__global__ __launch_bounds__(NW * 64, 1) void k_layer_mfma(const uint16_t* __restrict__ feats, void* __restrict__ out,
-                                                            const int32_t* __restrict__ perm,
-                                                            const int32_t* __restrict__ goff,
-                                                            const int32_t* __restrict__ num_groups,
-                                                            const u32x4* __restrict__ packed, SmallParams sp, float eps) {
+// LDS map (bytes): [weight ring 2 x CH KB][small parameters as fp32: (9C + F) x 4][K/V exchange].
+template <int C, int F>
+struct ParamOff {  // float offsets inside the small-parameter area
+  static constexpr int LN1G = 0, LN1B = C, BQ = 2 * C, BK = 3 * C, BV = 4 * C, BO = 5 * C, LN2G = 6 * C,
+                       LN2B = 7 * C, B2 = 8 * C, B1 = 9 * C, TOTAL = 9 * C + F;
+};
+
+template <int C, int DH, int F, int NVB, int WPG, int NW, int MINW, bool OUT_F32>
+__global__ __launch_bounds__(NW * 64, MINW) void k_layer_mfma(const uint16_t* __restrict__ feats, void* __restrict__ out,
+                                                               const int32_t* __restrict__ perm,
+                                                               const int32_t* __restrict__ goff,
+                                                               const int32_t* __restrict__ num_groups,
+                                                               const u32x4* __restrict__ packed, SmallParams sp, float eps) {
   constexpr int KB = C / 32;          // 32-wide blocks of the input features
   constexpr int NB = C / 16;          // 16-wide blocks of the output features
   constexpr int HP = C / 32;          // 32-wide head-dim units
   constexpr int FC = F / 32;          // 32-wide hidden units
   constexpr int NKB = NVB * WPG;      // key blocks of a group
-  constexpr int GPW = NW / WPG;       // groups per workgroup
   constexpr int NT = NW * 64;
-  constexpr int FR_HP = frags_per_hp(C), FR_FC = frags_per_fc(C);
-  constexpr int CH = kChunkFrags;
-  constexpr int STG = CH * 64 / NT;   // uint4 per thread per chunk
-  constexpr int NCHUNK = (HP * FR_HP + FC * FR_FC) / CH;
-  constexpr int FCI = CH / FR_FC;     // hidden units per chunk
+  constexpr int CH = 4 * KB;          // fragments per staged chunk: {Q,K} | {V,W_o} | {W1,W2}
+  constexpr int STG = CH * 64 / NT;   // 16-byte pieces per thread per chunk
+  constexpr int NCHUNK = 2 * HP + FC;
+  using PO = ParamOff<C, F>;
   static_assert(DH == 16 || DH == 32, "head dim");
-  static_assert((HP * FR_HP) % CH == 0 && CH % FR_FC == 0 && FC % FCI == 0, "chunking");
-  static_assert(FR_HP == CH || FR_HP == 2 * CH, "chunking of a head-dim unit");
   static_assert((CH * 64) % NT == 0, "staging");
 
   extern __shared__ u32x4 lds[];
-  u32x4* ring = lds;                                   // [2][CH * 64]
-  u32x2* kvx = reinterpret_cast<u32x2*>(lds + 2 * CH * 64);  // K/V exchange, only when WPG > 1
+  u32x4* ring = lds;                                            // [2][CH * 64]
+  float* par = reinterpret_cast<float*>(lds + 2 * CH * 64);     // [PO::TOTAL]
+  u32x2* kvx = reinterpret_cast<u32x2*>(par + PO::TOTAL);       // K/V exchange, only when WPG > 1
 
   const int tid = threadIdx.x, lane = tid & 63, w = tid >> 6, i = lane & 15, q = lane >> 4;
   const int gl = w / WPG, part = w % WPG;
-  const int g = blockIdx.x * GPW + gl;
+  const int g = blockIdx.x * (NW / WPG) + gl;
   int start = 0, m = 0;
   if (g < *num_groups) { start = goff[g]; m = goff[g + 1] - start; }
 
@@ -199,6 +204,19 @@ __global__ __launch_bounds__(NW * 64, 1) void k_layer_mfma(const uint16_t* __res
   };
   issue(0);
 
+  // small parameters -> LDS as fp32
+  for (int t = tid; t < PO::TOTAL; t += NT) {
+    const uint16_t* src;
+    int o;
+    if (t < 2 * C) { src = t < C ? sp.ln1_g : sp.ln1_b; o = t < C ? t : t - C; }
+    else if (t < 5 * C) { src = sp.b_qkv; o = t - 2 * C; }
+    else if (t < 6 * C) { src = sp.b_o; o = t - 5 * C; }
+    else if (t < 8 * C) { src = t < 7 * C ? sp.ln2_g : sp.ln2_b; o = t < 7 * C ? t - 6 * C : t - 7 * C; }
+    else if (t < 9 * C) { src = sp.b2; o = t - 8 * C; }
+    else { src = sp.b1; o = t - 9 * C; }
+    par[t] = bf16_to_f32(src[o]);
+  }
+
   // ---- gather + LN1 ---------------------------------------------------------------------------------
   f32x4 x1[NVB][NB];  // residual stream of my pillars, accumulator layout
   int64_t row[NVB];
@@ -206,6 +224,9 @@ __global__ __launch_bounds__(NW * 64, 1) void k_layer_mfma(const uint16_t* __res
   for (int vb = 0; vb < NVB; ++vb) {
     const int s = (part * NVB + vb) * 16 + i;
     row[vb] = s < m ? (int64_t)perm[start + s] : -1;
+  }
+#pragma unroll
+  for (int vb = 0; vb < NVB; ++vb) {
 #pragma unroll
     for (int nb = 0; nb < NB; ++nb) {
       float t[4] = {0.f, 0.f, 0.f, 0.f};
@@ -218,7 +239,7 @@ __global__ __launch_bounds__(NW * 64, 1) void k_layer_mfma(const uint16_t* __res
   issue(1);
 
   Frag8 act[NVB][KB];  // normalised activations as B operands (LN1 output, later LN2 output)
-  auto layer_norm = [&](const uint16_t* gam, const uint16_t* bet) {
+  auto layer_norm = [&](int goff_f, int boff_f) {
     float mu[NVB], rstd[NVB];
 #pragma unroll
     for (int vb = 0; vb < NVB; ++vb) {
@@ -236,9 +257,8 @@ __global__ __launch_bounds__(NW * 64, 1) void k_layer_mfma(const uint16_t* __res
     }
 #pragma unroll
     for (int nb = 0; nb < NB; ++nb) {
-      float gm[4], bt[4];
-      load4(gam + 16 * nb + 4 * q, gm);
-      load4(bet + 16 * nb + 4 * q, bt);
+      const f32x4 gm = *reinterpret_cast<const f32x4*>(par + goff_f + 16 * nb + 4 * q);
+      const f32x4 bt = *reinterpret_cast<const f32x4*>(par + boff_f + 16 * nb + 4 * q);
 #pragma unroll
       for (int vb = 0; vb < NVB; ++vb) {
         float y[4];
@@ -249,24 +269,24 @@ __global__ __launch_bounds__(NW * 64, 1) void k_layer_mfma(const uint16_t* __res
       }
     }
   };
-  layer_norm(sp.ln1_g, sp.ln1_b);
-
-  // residual + output-projection bias
+  auto add_bias_rows = [&](int off_f) {  // x1 += per-feature vector
 #pragma unroll
-  for (int nb = 0; nb < NB; ++nb) {
-    float b[4];
-    load4(sp.b_o + 16 * nb + 4 * q, b);
+    for (int nb = 0; nb < NB; ++nb) {
+      const f32x4 b = *reinterpret_cast<const f32x4*>(par + off_f + 16 * nb + 4 * q);
 #pragma unroll
-    for (int vb = 0; vb < NVB; ++vb) x1[vb][nb] += f32x4{b[0], b[1], b[2], b[3]};
-  }
+      for (int vb = 0; vb < NVB; ++vb) x1[vb][nb] += b;
+    }
+  };
+  layer_norm(PO::LN1G, PO::LN1B);
+  add_bias_rows(PO::BO);  // residual + output-projection bias
 
   const float qscale = rsqrtf((float)DH) * 1.44269504088896340736f;  // 1/sqrt(d) * log2(e)
+  const bool short_group = m < NKB * 16;  // wave-uniform: some key slots are padding
 
   // ---- attention: one 32-wide head-dim unit per iteration (two heads of 16 or one head of 32) --------
 #pragma unroll 1
   for (int hp = 0; hp < HP; ++hp) {
     const u32x4* rb = ring + (cc & 1) * CH * 64 + lane;
-    int fo = 0;
     Frag4 Qf[2][NVB], Kf[2][NVB], Vf[2][NVB];  // bf16 fragments of my pillars, index [16-block a][vb]
 
     // Q and K rows: D[feature][pillar]
@@ -280,12 +300,11 @@ __global__ __launch_bounds__(NW * 64, 1) void k_layer_mfma(const uint16_t* __res
 #pragma unroll
         for (int kb = 0; kb < KB; ++kb) {
           Frag8 wf;
-          wf.q = rb[(fo + a * KB + kb) * 64];
+          wf.q = rb[((qk * 2 + a) * KB + kb) * 64];
 #pragma unroll
           for (int vb = 0; vb < NVB; ++vb) acc[vb] = mfma32(wf, act[vb][kb], acc[vb]);
         }
-        float b[4];
-        load4(sp.b_qkv + qk * C + 32 * hp + 16 * a + 4 * q, b);
+        const f32x4 b = *reinterpret_cast<const f32x4*>(par + (qk == 0 ? PO::BQ : PO::BK) + 32 * hp + 16 * a + 4 * q);
 #pragma unroll
         for (int vb = 0; vb < NVB; ++vb) {
           if (qk == 0) {
@@ -297,13 +316,9 @@ __global__ __launch_bounds__(NW * 64, 1) void k_layer_mfma(const uint16_t* __res
           }
         }
       }
-      fo += 2 * KB;
     }
-    if (FR_HP == 2 * CH) {  // the unit spans two chunks: Q,K | V,W_o
-      advance();
-      rb = ring + (cc & 1) * CH * 64 + lane;
-      fo = 0;
-    }
+    advance();
+    rb = ring + (cc & 1) * CH * 64 + lane;
     // V rows with the operand roles swapped: D[pillar][feature]
 #pragma unroll
     for (int a = 0; a < 2; ++a) {
@@ -313,24 +328,24 @@ __global__ __launch_bounds__(NW * 64, 1) void k_layer_mfma(const uint16_t* __res
 #pragma unroll
       for (int kb = 0; kb < KB; ++kb) {
         Frag8 wf;
-        wf.q = rb[(fo + a * KB + kb) * 64];
+        wf.q = rb[(a * KB + kb) * 64];
 #pragma unroll
         for (int vb = 0; vb < NVB; ++vb) acc[vb] = mfma32(act[vb][kb], wf, acc[vb]);
       }
-      const float bv = bf16_to_f32(sp.b_qkv[2 * C + 32 * hp + 16 * a + i]);
+      const float bv = par[PO::BV + 32 * hp + 16 * a + i];
 #pragma unroll
       for (int vb = 0; vb < NVB; ++vb) {
         Vf[a][vb].u[0] = pack2(acc[vb][0] + bv, acc[vb][1] + bv);
         Vf[a][vb].u[1] = pack2(acc[vb][2] + bv, acc[vb][3] + bv);
       }
     }
-    fo += 2 * KB;
 
     // K/V of the whole group.  One wavefront per group: they are already in registers.
+    // Otherwise through LDS: [group in workgroup][K|V][16-block a][key block][lane]; the barrier
+    // that ends every unit (advance) makes one buffer enough.
     u32x2* kv = nullptr;
     if (WPG > 1) {
-      // exchange area: [group in workgroup][hp parity][K|V][16-block a][key block][lane]
-      kv = kvx + ((size_t)(gl * 2 + (hp & 1)) * 2) * 2 * NKB * 64 + lane;
+      kv = kvx + (size_t)gl * 2 * 2 * NKB * 64 + lane;
 #pragma unroll
       for (int a = 0; a < 2; ++a) {
 #pragma unroll
@@ -371,14 +386,19 @@ __global__ __launch_bounds__(NW * 64, 1) void k_layer_mfma(const uint16_t* __res
             S[jb] = mfma32(k8, q8, z);
           }
         }
-        float mx = -INFINITY;
+        if (short_group) {  // keys beyond the group's real members
+#pragma unroll
+          for (int jb = 0; jb < NKB; ++jb) {
+#pragma unroll
+            for (int j = 0; j < 4; ++j)
+              if (16 * jb + 4 * q + j >= m) S[jb][j] = -INFINITY;
+          }
+        }
+        float mx = S[0][0];
 #pragma unroll
         for (int jb = 0; jb < NKB; ++jb) {
 #pragma unroll
-          for (int j = 0; j < 4; ++j) {
-            if (16 * jb + 4 * q + j >= m) S[jb][j] = -INFINITY;  // keys beyond the group's real members
-            mx = fmaxf(mx, S[jb][j]);
-          }
+          for (int j = 0; j < 4; ++j) mx = fmaxf(mx, S[jb][j]);
         }
         mx = quad_max(mx);
         float sum = 0.f;
@@ -426,7 +446,7 @@ __global__ __launch_bounds__(NW * 64, 1) void k_layer_mfma(const uint16_t* __res
 #pragma unroll
     for (int nb = 0; nb < NB; ++nb) {
       Frag8 wf;
-      wf.q = rb[(fo + nb) * 64];
+      wf.q = rb[(2 * KB + nb) * 64];
 #pragma unroll
       for (int vb = 0; vb < NVB; ++vb) x1[vb][nb] = mfma32(wf, Of[vb], x1[vb][nb]);
     }
@@ -434,51 +454,39 @@ __global__ __launch_bounds__(NW * 64, 1) void k_layer_mfma(const uint16_t* __res
   }
 
   // ---- FFN ------------------------------------------------------------------------------------------
-  layer_norm(sp.ln2_g, sp.ln2_b);
-#pragma unroll
-  for (int nb = 0; nb < NB; ++nb) {
-    float b[4];
-    load4(sp.b2 + 16 * nb + 4 * q, b);
-#pragma unroll
-    for (int vb = 0; vb < NVB; ++vb) x1[vb][nb] += f32x4{b[0], b[1], b[2], b[3]};
-  }
+  layer_norm(PO::LN2G, PO::LN2B);
+  add_bias_rows(PO::B2);
 #pragma unroll 1
-  for (int it = 0; it < FC / FCI; ++it) {
+  for (int fc = 0; fc < FC; ++fc) {
     const u32x4* rb = ring + (cc & 1) * CH * 64 + lane;
+    Frag8 Hf[NVB];
 #pragma unroll
-    for (int fi = 0; fi < FCI; ++fi) {
-      const int fc = it * FCI + fi;
-      const int fo = fi * FR_FC;
-      Frag8 Hf[NVB];
+    for (int a = 0; a < 2; ++a) {
+      f32x4 acc[NVB];
 #pragma unroll
-      for (int a = 0; a < 2; ++a) {
-        f32x4 acc[NVB];
+      for (int vb = 0; vb < NVB; ++vb) acc[vb] = f32x4{0.f, 0.f, 0.f, 0.f};
 #pragma unroll
-        for (int vb = 0; vb < NVB; ++vb) acc[vb] = f32x4{0.f, 0.f, 0.f, 0.f};
-#pragma unroll
-        for (int kb = 0; kb < KB; ++kb) {
-          Frag8 wf;
-          wf.q = rb[(fo + a * KB + kb) * 64];
-#pragma unroll
-          for (int vb = 0; vb < NVB; ++vb) acc[vb] = mfma32(wf, act[vb][kb], acc[vb]);
-        }
-        float b[4];
-        load4(sp.b1 + 32 * fc + 16 * a + 4 * q, b);
-#pragma unroll
-        for (int vb = 0; vb < NVB; ++vb) {
-          Hf[vb].u[a * 2 + 0] = pack2(gelu_fast(acc[vb][0] + b[0]), gelu_fast(acc[vb][1] + b[1]));
-          Hf[vb].u[a * 2 + 1] = pack2(gelu_fast(acc[vb][2] + b[2]), gelu_fast(acc[vb][3] + b[3]));
-        }
-      }
-#pragma unroll
-      for (int nb = 0; nb < NB; ++nb) {
+      for (int kb = 0; kb < KB; ++kb) {
         Frag8 wf;
-        wf.q = rb[(fo + 2 * KB + nb) * 64];
+        wf.q = rb[(a * KB + kb) * 64];
 #pragma unroll
-        for (int vb = 0; vb < NVB; ++vb) x1[vb][nb] = mfma32(wf, Hf[vb], x1[vb][nb]);
+        for (int vb = 0; vb < NVB; ++vb) acc[vb] = mfma32(wf, act[vb][kb], acc[vb]);
+      }
+      const f32x4 b = *reinterpret_cast<const f32x4*>(par + PO::B1 + 32 * fc + 16 * a + 4 * q);
+#pragma unroll
+      for (int vb = 0; vb < NVB; ++vb) {
+        Hf[vb].u[a * 2 + 0] = pack2(gelu_fast(acc[vb][0] + b[0]), gelu_fast(acc[vb][1] + b[1]));
+        Hf[vb].u[a * 2 + 1] = pack2(gelu_fast(acc[vb][2] + b[2]), gelu_fast(acc[vb][3] + b[3]));
       }
     }
-    if (it + 1 < FC / FCI) advance();
+#pragma unroll
+    for (int nb = 0; nb < NB; ++nb) {
+      Frag8 wf;
+      wf.q = rb[(2 * KB + nb) * 64];
+#pragma unroll
+      for (int vb = 0; vb < NVB; ++vb) x1[vb][nb] = mfma32(wf, Hf[vb], x1[vb][nb]);
+    }
+    if (fc + 1 < FC) advance();
   }
 
   // ---- scatter -------------------------------------------------------------------------------------
@@ -499,13 +507,15 @@ __global__ __launch_bounds__(NW * 64, 1) void k_layer_mfma(const uint16_t* __res
   }
 }
 
-template <int C, int DH, int F, int NVB, int WPG, int NW>
+template <int C, int DH, int F, int NVB, int WPG, int NW, int MINW>
 int launch_cfg(const void* feats, void* out, const int32_t* perm, const int32_t* goff, const int32_t* num_groups,
                int32_t max_groups, const u32x4* packed, const SmallParams& sp, float eps, bool out_f32,
                hipStream_t stream) {
   constexpr int GPW = NW / WPG;
   constexpr int NKB = NVB * WPG;
-  const size_t lds_bytes = (size_t)2 * kChunkFrags * 1024 + (WPG > 1 ? (size_t)GPW * 2 * 2 * 2 * NKB * 64 * 8 : 0);
+  constexpr int CH = 4 * (C / 32);
+  const size_t lds_bytes = (size_t)2 * CH * 1024 + (size_t)ParamOff<C, F>::TOTAL * 4 +
+                           (WPG > 1 ? (size_t)GPW * 2 * 2 * NKB * 64 * 8 : 0);
   const unsigned blocks = (unsigned)((max_groups + GPW - 1) / GPW);
   auto go = [&](auto kern) -> int {
     static bool attr_done = false;  // the attribute only has to be set once per kernel
@@ -519,8 +529,8 @@ int launch_cfg(const void* feats, void* out, const int32_t* perm, const int32_t*
                        num_groups, packed, sp, eps);
     return launch_status();
   };
-  if (out_f32) return go(k_layer_mfma<C, DH, F, NVB, WPG, NW, true>);
-  return go(k_layer_mfma<C, DH, F, NVB, WPG, NW, false>);
+  if (out_f32) return go(k_layer_mfma<C, DH, F, NVB, WPG, NW, MINW, true>);
+  return go(k_layer_mfma<C, DH, F, NVB, WPG, NW, MINW, false>);
 }
 
 }  // namespace
@@ -544,9 +554,10 @@ int layer_mfma_pack(const ff_layer_weights* w, void* packed, hipStream_t stream)
   return launch_status();
 }
 
+// variant: 0 = chosen from the shape; 1.. = a specific wave/group mapping (tuning and tests).
 int layer_mfma_launch(const void* feats, void* out, int64_t n, const int32_t* perm, const int32_t* group_offsets,
                       const int32_t* num_groups, int32_t max_groups, const ff_layer_weights* w, int G,
-                      bool out_f32, const void* packed, hipStream_t stream) {
+                      bool out_f32, const void* packed, int variant, hipStream_t stream) {
   (void)n;
   if (max_groups == 0) return FF_OK;
   SmallParams sp{(const uint16_t*)w->ln1_g, (const uint16_t*)w->ln1_b, (const uint16_t*)w->b_qkv,
@@ -554,11 +565,21 @@ int layer_mfma_launch(const void* feats, void* out, int64_t n, const int32_t* pe
                  (const uint16_t*)w->b1,    (const uint16_t*)w->b2};
   const u32x4* pk = (const u32x4*)packed;
   const int C = w->C, F = w->F, d = C / w->heads;
+#define FF_GO(NVB, WPG, NW, MINW) \
+  return launch_cfg<128, 16, 256, NVB, WPG, NW, MINW>(feats, out, perm, group_offsets, num_groups, max_groups, pk, sp, \
+                                                      w->ln_eps, out_f32, stream)
   if (C == 128 && d == 16 && F == 256) {
-    if (G <= 32) return launch_cfg<128, 16, 256, 2, 1, 4>(feats, out, perm, group_offsets, num_groups, max_groups, pk, sp, w->ln_eps, out_f32, stream);
-    if (G <= 64) return launch_cfg<128, 16, 256, 4, 1, 4>(feats, out, perm, group_offsets, num_groups, max_groups, pk, sp, w->ln_eps, out_f32, stream);
-    if (G <= 128) return launch_cfg<128, 16, 256, 4, 2, 4>(feats, out, perm, group_offsets, num_groups, max_groups, pk, sp, w->ln_eps, out_f32, stream);
+    if (variant == 0) variant = G <= 32 ? 1 : G <= 64 ? 2 : 4;
+    switch (variant) {
+      case 1: if (G <= 32) FF_GO(2, 1, 4, 2); break;    // 32 slots, one wave per group
+      case 2: if (G <= 64) FF_GO(2, 2, 4, 2); break;    // 64 slots, two waves per group
+      case 3: if (G <= 64) FF_GO(4, 1, 4, 1); break;    // 64 slots, one wave per group
+      case 4: if (G <= 128) FF_GO(2, 4, 4, 2); break;   // 128 slots, four waves per group
+      case 5: if (G <= 128) FF_GO(4, 2, 4, 1); break;   // 128 slots, two waves per group
+      default: break;
+    }
   }
+#undef FF_GO
   return FF_ERR_UNSUPPORTED;
 }
 

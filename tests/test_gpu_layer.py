@@ -161,5 +161,15 @@ def test_bf16_group_sizes_and_tails(cfg, G):
     ew, en = _assert_bf16_bar(wide, to_host(narrow), want)
     assert np.abs(plain - want).max() <= 2e-2
     assert torch.equal(packed, narrow)                      # pre-packed weights change nothing
+    # every wave-to-group mapping that can hold G
+    for variant, slots in [(1, 32), (2, 64), (3, 64), (4, 128), (5, 128)]:
+        fl = ff.FF_FLAG_OUT_F32 | ff.FF_FLAG_VARIANT(variant)
+        if G > slots:
+            with pytest.raises(ff.FlatformerError):
+                ff.ff_group_attention(x, dev[0], dev[1], dev[2], ng + 1, lw, G, ff.FF_BF16, fl)
+            continue
+        print(f"G={G} variant {variant}", flush=True)
+        v = to_host(ff.ff_group_attention(x, dev[0], dev[1], dev[2], ng + 1, lw, G, ff.FF_BF16, fl))
+        assert np.abs(v - want).max() <= 2e-2, (variant, np.abs(v - want).max())
     print(f"G={G}: fused f32-store err {ew:.3e}, bf16-store err {en:.3e}, plain kernels err "
           f"{np.abs(plain - want).max():.3e}", flush=True)
