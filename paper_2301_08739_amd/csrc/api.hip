@@ -24,7 +24,7 @@ size_t elem_size(int dtype) { return dtype == FF_F32 ? 4 : 2; }
 
 extern "C" {
 
-size_t ff_flatten_workspace_bytes(int64_t n, const ff_geom* g) { return flatten_workspace_bytes(n, g); }
+size_t ff_flatten_workspace_bytes(int64_t n, const ff_geom* g) { return flatten_workspace_bytes(n, g, 1); }
 
 int ff_flatten(const int32_t* coords, int64_t n, const ff_geom* g, int axis, int shift, int G, int tail,
                int32_t* perm, int32_t* group_offsets, int32_t* num_groups, uint64_t* keys_sorted,
@@ -32,7 +32,7 @@ int ff_flatten(const int32_t* coords, int64_t n, const ff_geom* g, int axis, int
   if (tail == FF_TAIL_DROP) return FF_ERR_UNSUPPORTED;
   if (tail != FF_TAIL_MASK) return FF_ERR_ARG;
   if (shift != 0 && shift != 1) return FF_ERR_ARG;
-  return flatten_launch(coords, n, g, axis, shift, G, perm, group_offsets, num_groups, keys_sorted,
+  return flatten_launch(coords, n, g, 1, &axis, &shift, G, &perm, &group_offsets, &num_groups, &keys_sorted,
                         workspace, workspace_bytes, (hipStream_t)stream);
 }
 
@@ -121,9 +121,9 @@ int make_block_plan(int64_t n, const ff_geom* g, int G, const ff_layer_weights* 
     if (st != FF_OK) return st;
     if (layers[l].C != layers[0].C) return FF_ERR_ARG;
   }
-  p->flat_bytes = flatten_workspace_bytes(n, g);
-  if (p->flat_bytes == 0) { FlattenPlan fp; int st = make_flatten_plan(n, g, 0, 1, &fp); if (st != FF_OK) return st; }
   p->sorts = num_layers < 4 ? num_layers : 4;
+  p->flat_bytes = flatten_workspace_bytes(n, g, p->sorts);
+  if (p->flat_bytes == 0) { FlattenPlan fp; int st = make_flatten_plan(n, g, 0, 1, &fp); if (st != FF_OK) return st; }
   p->max_groups = ceil_div(n, G) + g->num_frames;
   p->layer_bytes = 0;
   for (int l = 0; l < num_layers; ++l) {
@@ -162,10 +162,17 @@ int ff_fwa_block(const int32_t* coords, int64_t n, const ff_geom* g, int G, cons
   char* ws = (char*)workspace;
   const size_t perm_stride = align_up((size_t)n * 4, 256);
   const size_t goff_stride = align_up((size_t)(p.max_groups + 1) * 4, 256);
-  for (int s = 0; s < p.sorts; ++s) {
-    st = ff_flatten(coords, n, g, s % 2, (s / 2) % 2, G, FF_TAIL_MASK, (int32_t*)(ws + p.off_perm + s * perm_stride),
-                    (int32_t*)(ws + p.off_goff + s * goff_stride), (int32_t*)(ws + p.off_ng) + s, nullptr,
-                    ws + p.off_flat, p.flat_bytes, stream);
+  {  // all sort configurations of the schedule in one batched flatten
+    int axis[4], shift[4];
+    int32_t *perm[4], *goff[4], *ng[4];
+    for (int s = 0; s < p.sorts; ++s) {
+      axis[s] = s % 2; shift[s] = (s / 2) % 2;
+      perm[s] = (int32_t*)(ws + p.off_perm + s * perm_stride);
+      goff[s] = (int32_t*)(ws + p.off_goff + s * goff_stride);
+      ng[s] = (int32_t*)(ws + p.off_ng) + s;
+    }
+    st = flatten_launch(coords, n, g, p.sorts, axis, shift, G, perm, goff, ng, nullptr, ws + p.off_flat,
+                        p.flat_bytes, (hipStream_t)stream);
     if (st != FF_OK) return st;
   }
   const void* cur = feats_in;

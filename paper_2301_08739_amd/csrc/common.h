@@ -43,22 +43,20 @@ struct FlattenPlan {
   int key_bits;                                    // sum of the above
   int idx_bits;                                    // bits of n-1
   int passes;                                      // radix passes of 8 bits over the key bits
-  int64_t tiles;                                   // tiles of kTile words
-  size_t off_buf0, off_buf1, off_hist, off_frames, total;
 };
 
 constexpr int kRadixBits = 8;
 constexpr int kBins = 1 << kRadixBits;
 constexpr int kSortThreads = 256;
-constexpr int kKeysPerThread = 8;
-constexpr int kTile = kSortThreads * kKeysPerThread;
 
 int make_flatten_plan(int64_t n, const ff_geom* g, int axis, int shift, FlattenPlan* plan);
-size_t flatten_workspace_bytes(int64_t n, const ff_geom* g);
+size_t flatten_workspace_bytes(int64_t n, const ff_geom* g, int num_sorts);
 
-int flatten_launch(const int32_t* coords, int64_t n, const ff_geom* g, int axis, int shift, int G,
-                   int32_t* perm, int32_t* group_offsets, int32_t* num_groups, uint64_t* keys_sorted,
-                   void* workspace, size_t workspace_bytes, hipStream_t stream);
+// num_sorts (1..4) sort configurations of the same cloud, sorted together.
+int flatten_launch(const int32_t* coords, int64_t n, const ff_geom* g, int num_sorts, const int* axis,
+                   const int* shift, int G, int32_t* const* perm, int32_t* const* group_offsets,
+                   int32_t* const* num_groups, uint64_t* const* keys_sorted, void* workspace,
+                   size_t workspace_bytes, hipStream_t stream);
 
 int rows_launch(bool scatter, const void* src, void* dst, const int32_t* perm, int64_t n, int C,
                 int dtype, hipStream_t stream);

@@ -7,48 +7,98 @@
 // stable, so equal tuples keep ascending original index.  The word carries the index, so a pass
 // moves 8 bytes per pillar each way.
 //
-// Pass structure: per-tile digit histogram -> exclusive scan over (digit, tile) -> stable
-// rank-and-scatter.  Ranking inside a tile is done per wavefront with ballot-based digit matching
-// and LDS counters; keys are staged through LDS so global writes come out in runs.
+// Launches for one call (S sort configurations of the same cloud are sorted together, one grid
+// row each): clear control words -> key generation + digit histograms of every pass -> P
+// single-sweep passes -> outputs.  A pass ranks its tile with per-wavefront ballot matching and LDS
+// counters, learns the number of equal digits in all earlier tiles by looking back through
+// per-tile status words (aggregate / inclusive-prefix flags; tiles take their number from an atomic
+// ticket, so every tile a block waits for is already running), and scatters through an LDS
+// stage so that global writes come out in runs.  Every wait is bounded: a block that exhausts its
+// spin budget raises an error word, skips its scatter, still publishes its status, and the output
+// kernel reports num_groups = -1.
 #include "common.h"
 
 namespace ff {
 
 namespace {
 
+constexpr int kMaxSorts = 4;
+constexpr uint32_t kFlagAggregate = 1u << 30, kFlagInclusive = 2u << 30, kCountMask = (1u << 30) - 1u;
+constexpr int kSpinLimit = 1 << 20;
+
 struct KeyParams {
-  int32_t B, grid_x, grid_y, win_x, win_y;
+  int32_t B, win_x, win_y;
   int32_t sx, sy;                       // shift added to x / y
   int32_t axis;
   int32_t bits_b, bits_w1, bits_w2, bits_l1, bits_l2;
   int32_t key_bits, idx_bits;
 };
 
+struct Batch {
+  KeyParams kp[kMaxSorts];
+  int32_t* perm[kMaxSorts];
+  int32_t* group_offsets[kMaxSorts];
+  int32_t* num_groups[kMaxSorts];
+  uint64_t* keys_sorted[kMaxSorts];
+};
+
 __device__ __forceinline__ uint32_t field_mask(int bits) { return bits >= 32 ? 0xffffffffu : ((1u << bits) - 1u); }
 
-// ---- A1: coords -> sortable word ----------------------------------------------------------------
-__global__ __launch_bounds__(256) void k_keygen(const int32_t* __restrict__ coords, int64_t n,
-                                                 KeyParams kp, uint64_t* __restrict__ words) {
-  int64_t i = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
-  if (i >= n) return;
-  uint32_t b = (uint32_t)coords[3 * i + 0];
-  uint32_t X = (uint32_t)(coords[3 * i + 1] + kp.sx);
-  uint32_t Y = (uint32_t)(coords[3 * i + 2] + kp.sy);
-  uint32_t Wx = X / (uint32_t)kp.win_x, Lx = X - Wx * (uint32_t)kp.win_x;
-  uint32_t Wy = Y / (uint32_t)kp.win_y, Ly = Y - Wy * (uint32_t)kp.win_y;
-  uint32_t w1 = kp.axis == 0 ? Wx : Wy, w2 = kp.axis == 0 ? Wy : Wx;
-  uint32_t l1 = kp.axis == 0 ? Lx : Ly, l2 = kp.axis == 0 ? Ly : Lx;
-  // Fields are masked to their widths so that a coordinate outside the geometry can only
-  // disturb the order, never another field's bits or any index computed from them.
-  uint64_t k = b & field_mask(kp.bits_b);
-  k = (k << kp.bits_w1) | (w1 & field_mask(kp.bits_w1));
-  k = (k << kp.bits_w2) | (w2 & field_mask(kp.bits_w2));
-  k = (k << kp.bits_l1) | (l1 & field_mask(kp.bits_l1));
-  k = (k << kp.bits_l2) | (l2 & field_mask(kp.bits_l2));
-  words[i] = (kp.idx_bits >= 64 ? 0ull : (k << kp.idx_bits)) | (uint64_t)i;
+// digit of `word` in pass `pass` of a sort whose key occupies bits [idx_bits, idx_bits + key_bits)
+__device__ __forceinline__ uint32_t digit_of(uint64_t word, int idx_bits, int key_bits, int pass) {
+  const int lo = pass * kRadixBits;
+  const int nb = key_bits - lo < kRadixBits ? key_bits - lo : kRadixBits;
+  if (nb <= 0) return 0u;
+  return (uint32_t)(word >> (idx_bits + lo)) & ((1u << nb) - 1u);
 }
 
-// ---- block-wide exclusive scan of one uint32 per thread (256 threads) -------------------------
+__global__ __launch_bounds__(256) void k_clear(uint32_t* __restrict__ p, int64_t words) {
+  for (int64_t i = (int64_t)blockIdx.x * blockDim.x + threadIdx.x; i < words; i += (int64_t)gridDim.x * blockDim.x)
+    p[i] = 0u;
+}
+
+// ---- A1: coords -> sortable word, plus the digit histogram of every pass -------------------------------
+__global__ __launch_bounds__(256) void k_keygen_hist(const int32_t* __restrict__ coords, int64_t n, Batch bt, int P,
+                                                      uint64_t* __restrict__ words /*[S][n]*/,
+                                                      uint32_t* __restrict__ hist /*[S][P][256]*/) {
+  extern __shared__ uint32_t h[];  // [P][256]
+  const int s = blockIdx.y;
+  const KeyParams kp = bt.kp[s];
+  for (int t = threadIdx.x; t < P * kBins; t += blockDim.x) h[t] = 0u;
+  __syncthreads();
+  constexpr int PER_THREAD = 4;
+  const int64_t base = (int64_t)blockIdx.x * (256 * PER_THREAD);
+#pragma unroll
+  for (int r = 0; r < PER_THREAD; ++r) {
+    const int64_t i = base + r * 256 + threadIdx.x;
+    if (i < n) {
+      const uint32_t b = (uint32_t)coords[3 * i + 0];
+      const uint32_t X = (uint32_t)(coords[3 * i + 1] + kp.sx);
+      const uint32_t Y = (uint32_t)(coords[3 * i + 2] + kp.sy);
+      const uint32_t Wx = X / (uint32_t)kp.win_x, Lx = X - Wx * (uint32_t)kp.win_x;
+      const uint32_t Wy = Y / (uint32_t)kp.win_y, Ly = Y - Wy * (uint32_t)kp.win_y;
+      const uint32_t w1 = kp.axis == 0 ? Wx : Wy, w2 = kp.axis == 0 ? Wy : Wx;
+      const uint32_t l1 = kp.axis == 0 ? Lx : Ly, l2 = kp.axis == 0 ? Ly : Lx;
+      // Fields are masked to their widths so that a coordinate outside the geometry can only
+      // disturb the order, never another field's bits or any index computed from them.
+      uint64_t k = b & field_mask(kp.bits_b);
+      k = (k << kp.bits_w1) | (w1 & field_mask(kp.bits_w1));
+      k = (k << kp.bits_w2) | (w2 & field_mask(kp.bits_w2));
+      k = (k << kp.bits_l1) | (l1 & field_mask(kp.bits_l1));
+      k = (k << kp.bits_l2) | (l2 & field_mask(kp.bits_l2));
+      const uint64_t word = (k << kp.idx_bits) | (uint64_t)i;
+      words[(int64_t)s * n + i] = word;
+      for (int p = 0; p < P; ++p) atomicAdd(&h[p * kBins + digit_of(word, kp.idx_bits, kp.key_bits, p)], 1u);
+    }
+  }
+  __syncthreads();
+  for (int t = threadIdx.x; t < P * kBins; t += blockDim.x) {
+    const uint32_t c = h[t];
+    if (c) atomicAdd(&hist[(int64_t)s * P * kBins + t], c);
+  }
+}
+
+// ---- block-wide exclusive scan of one uint32 per thread ---------------------------------------
 __device__ __forceinline__ uint32_t wave_inclusive_scan(uint32_t v) {
   const int lane = threadIdx.x & 63;
 #pragma unroll
@@ -78,64 +128,37 @@ __device__ __forceinline__ uint32_t block_exclusive_scan(uint32_t v, uint32_t* w
   return base + inc - v;
 }
 
-// ---- A2, step 1: digit histogram of one tile ---------------------------------------------------
-__global__ __launch_bounds__(kSortThreads) void k_radix_hist(const uint64_t* __restrict__ in, int64_t n,
-                                                              int shift, uint32_t mask, int64_t tiles,
-                                                              uint32_t* __restrict__ tile_hist) {
-  __shared__ uint32_t h[kBins];
-  const int tid = threadIdx.x;
-  h[tid] = 0;
-  __syncthreads();
-  const int64_t base = (int64_t)blockIdx.x * kTile;
-#pragma unroll
-  for (int r = 0; r < kKeysPerThread; ++r) {
-    int64_t e = base + r * kSortThreads + tid;
-    if (e < n) atomicAdd(&h[(uint32_t)(in[e] >> shift) & mask], 1u);
-  }
-  __syncthreads();
-  tile_hist[(int64_t)tid * tiles + blockIdx.x] = h[tid];
-}
-
-// ---- A2, step 2: exclusive scan over the (digit-major, tile-minor) table -------------------------
-__global__ __launch_bounds__(1024) void k_scan_table(uint32_t* __restrict__ table, int64_t len) {
-  __shared__ uint32_t wave_totals[16];
-  __shared__ uint32_t carry_s;
-  if (threadIdx.x == 0) carry_s = 0;
-  __syncthreads();
-  for (int64_t base = 0; base < len; base += 1024) {
-    int64_t i = base + threadIdx.x;
-    uint32_t v = i < len ? table[i] : 0u;
-    uint32_t total;
-    uint32_t ex = block_exclusive_scan<1024>(v, wave_totals, &total);
-    uint32_t carry = carry_s;
-    if (i < len) table[i] = carry + ex;
-    __syncthreads();
-    if (threadIdx.x == 0) carry_s = carry + total;
-    __syncthreads();
-  }
-}
-
-// ---- A2, step 3: stable rank inside the tile, then scatter ----------------------------------
-__global__ __launch_bounds__(kSortThreads) void k_radix_scatter(const uint64_t* __restrict__ in,
-                                                                 uint64_t* __restrict__ out, int64_t n,
-                                                                 int shift, uint32_t mask, int64_t tiles,
-                                                                 const uint32_t* __restrict__ tile_base) {
-  constexpr int KPT = kKeysPerThread;
+// ---- A2: one radix pass in a single sweep --------------------------------------------------------
+template <int KPT>
+__global__ __launch_bounds__(kSortThreads) void k_onesweep(const uint64_t* __restrict__ in_all, uint64_t* __restrict__ out_all,
+                                                            int64_t n, Batch bt, int pass, int P, int64_t tiles,
+                                                            const uint32_t* __restrict__ hist /*[S][P][256]*/,
+                                                            uint32_t* __restrict__ status /*[S][P][tiles][256]*/,
+                                                            uint32_t* __restrict__ tickets /*[S][P]*/,
+                                                            uint32_t* __restrict__ error_word) {
   constexpr int WAVES = kSortThreads / 64;
+  constexpr int TILE = kSortThreads * KPT;
   __shared__ uint32_t wave_cnt[WAVES][kBins];
   __shared__ uint32_t digit_start[kBins];
   __shared__ uint32_t gbase[kBins];
   __shared__ uint32_t wave_totals[WAVES];
-  __shared__ uint64_t stage[kTile];
+  __shared__ uint32_t tile_s, failed_s;
+  __shared__ uint64_t stage[TILE];
 
   const int tid = threadIdx.x, lane = tid & 63, w = tid >> 6;
-  const int64_t tile_start = (int64_t)blockIdx.x * kTile;
-  const int tile_count = (int)((n - tile_start) < (int64_t)kTile ? (n - tile_start) : (int64_t)kTile);
+  const int s = blockIdx.y;
+  const int idx_bits = bt.kp[s].idx_bits, key_bits = bt.kp[s].key_bits;
+  const uint64_t* in = in_all + (int64_t)s * n;
+  uint64_t* out = out_all + (int64_t)s * n;
+  const int64_t slot = (int64_t)s * P + pass;
 
+  if (tid == 0) { tile_s = atomicAdd(&tickets[slot], 1u); failed_s = 0u; }
 #pragma unroll
   for (int i = 0; i < WAVES; ++i) wave_cnt[i][tid] = 0;
-  gbase[tid] = tile_base[(int64_t)tid * tiles + blockIdx.x];
   __syncthreads();
+  const int64_t tile = tile_s;
+  const int64_t tile_start = tile * TILE;
+  const int tile_count = (int)((n - tile_start) < (int64_t)TILE ? (n - tile_start) : (int64_t)TILE);
 
   // Element order inside the tile: wave-major, then round, then lane.  Each wave owns a
   // contiguous run of 64*KPT words, so stability only needs (wave, round, lane) order.
@@ -147,7 +170,7 @@ __global__ __launch_bounds__(kSortThreads) void k_radix_scatter(const uint64_t* 
     const int e = w * 64 * KPT + r * 64 + lane;
     const bool valid = e < tile_count;
     key[r] = valid ? in[tile_start + e] : ~0ull;
-    const uint32_t d = (uint32_t)(key[r] >> shift) & mask;
+    const uint32_t d = digit_of(key[r], idx_bits, key_bits, pass);
     uint64_t same = __ballot(valid);
 #pragma unroll
     for (int b = 0; b < kRadixBits; ++b) {
@@ -164,7 +187,7 @@ __global__ __launch_bounds__(kSortThreads) void k_radix_scatter(const uint64_t* 
   }
   __syncthreads();
 
-  // Thread d: per-wave exclusive prefix of digit d, and the tile's exclusive scan over digits.
+  // Thread d: count of digit d in this tile and its exclusive prefix over the tile's waves.
   uint32_t total = 0;
 #pragma unroll
   for (int i = 0; i < WAVES; ++i) {
@@ -172,14 +195,47 @@ __global__ __launch_bounds__(kSortThreads) void k_radix_scatter(const uint64_t* 
     wave_cnt[i][tid] = total;
     total += c;
   }
+  uint32_t* st = status + (slot * tiles + tile) * kBins;
+  __hip_atomic_store(&st[tid], total | (tile == 0 ? kFlagInclusive : kFlagAggregate), __ATOMIC_RELAXED,
+                     __HIP_MEMORY_SCOPE_AGENT);
+
+  // first output position of digit d over the whole array, and this tile's scan over digits
+  const uint32_t dbase = block_exclusive_scan<kSortThreads>(hist[slot * kBins + tid], wave_totals, nullptr);
   digit_start[tid] = block_exclusive_scan<kSortThreads>(total, wave_totals, nullptr);
+
+  // look back over earlier tiles for the number of digit-d words before this tile
+  uint32_t before = 0;
+  if (tile > 0) {
+    int64_t t = tile - 1;
+    int spins = 0;
+    while (true) {
+      const uint32_t v = __hip_atomic_load(&status[(slot * tiles + t) * kBins + tid], __ATOMIC_RELAXED,
+                                           __HIP_MEMORY_SCOPE_AGENT);
+      const uint32_t flag = v & ~kCountMask;
+      if (flag == 0u) {
+        if (++spins > kSpinLimit) { failed_s = 1u; break; }
+        __builtin_amdgcn_s_sleep(1);
+        continue;
+      }
+      before += v & kCountMask;
+      if (flag == kFlagInclusive || t == 0) break;
+      --t;
+    }
+    __hip_atomic_store(&st[tid], ((before + total) & kCountMask) | kFlagInclusive, __ATOMIC_RELAXED,
+                       __HIP_MEMORY_SCOPE_AGENT);
+  }
+  gbase[tid] = dbase + before;
   __syncthreads();
+  if (failed_s) {  // never expected; keeps every later access in bounds
+    if (tid == 0) atomicOr(error_word, 1u);
+    return;
+  }
 
 #pragma unroll
   for (int r = 0; r < KPT; ++r) {
     const int e = w * 64 * KPT + r * 64 + lane;
     if (e < tile_count) {
-      const uint32_t d = (uint32_t)(key[r] >> shift) & mask;
+      const uint32_t d = digit_of(key[r], idx_bits, key_bits, pass);
       stage[digit_start[d] + wave_cnt[w][d] + rank[r]] = key[r];
     }
   }
@@ -190,28 +246,32 @@ __global__ __launch_bounds__(kSortThreads) void k_radix_scatter(const uint64_t* 
     const int j = r * kSortThreads + tid;
     if (j < tile_count) {
       const uint64_t k = stage[j];
-      const uint32_t d = (uint32_t)(k >> shift) & mask;
-      out[(int64_t)gbase[d] + (uint32_t)(j - digit_start[d])] = k;
+      const uint32_t d = digit_of(k, idx_bits, key_bits, pass);
+      const int64_t pos = (int64_t)gbase[d] + (uint32_t)(j - digit_start[d]);
+      if (pos < n) out[pos] = k;
     }
   }
 }
 
-// ---- A3: frame boundaries and group bases (only launched when num_frames > 1) -----------------
-__global__ __launch_bounds__(256) void k_frames(const uint64_t* __restrict__ sorted, int64_t n, int B, int G,
-                                                 int frame_shift /* bit position of the frame field */,
-                                                 int32_t* __restrict__ frame_start /*[B+1]*/,
-                                                 int32_t* __restrict__ group_base /*[B+1]*/,
-                                                 int32_t* __restrict__ group_offsets,
-                                                 int32_t* __restrict__ num_groups) {
+// ---- A3: frame boundaries and group bases for many frames (num_frames > 256) ---------------------
+__global__ __launch_bounds__(256) void k_frames(const uint64_t* __restrict__ sorted_all, int64_t n, Batch bt, int G,
+                                                 int32_t* __restrict__ frame_tab /*[S][2][B+1]*/) {
   __shared__ uint32_t wave_totals[4];
   __shared__ uint32_t carry_s;
+  const int s = blockIdx.x;
+  const KeyParams kp = bt.kp[s];
+  const int B = kp.B;
+  const uint64_t* sorted = sorted_all + (int64_t)s * n;
+  int32_t* frame_start = frame_tab + (int64_t)s * 2 * (B + 1);
+  int32_t* group_base = frame_start + (B + 1);
+  const int frame_shift = kp.idx_bits + kp.key_bits - kp.bits_b;
   const int tid = threadIdx.x;
   for (int b = tid; b <= B; b += 256) {
     int64_t lo = 0, hi = n;  // first position whose frame field is >= b
     if (b == B) lo = n;
     while (lo < hi) {
-      int64_t mid = (lo + hi) >> 1;
-      uint32_t f = (uint32_t)(sorted[mid] >> frame_shift);
+      const int64_t mid = (lo + hi) >> 1;
+      const uint32_t f = (uint32_t)(sorted[mid] >> frame_shift);
       if (f < (uint32_t)b) lo = mid + 1; else hi = mid;
     }
     frame_start[b] = (int32_t)lo;
@@ -219,56 +279,104 @@ __global__ __launch_bounds__(256) void k_frames(const uint64_t* __restrict__ sor
   if (tid == 0) carry_s = 0;
   __syncthreads();
   for (int base = 0; base < B; base += 256) {
-    int b = base + tid;
+    const int b = base + tid;
     uint32_t g = 0;
     if (b < B) g = (uint32_t)((frame_start[b + 1] - frame_start[b] + G - 1) / G);
     uint32_t total;
-    uint32_t ex = block_exclusive_scan<256>(g, wave_totals, &total);
-    uint32_t carry = carry_s;
+    const uint32_t ex = block_exclusive_scan<256>(g, wave_totals, &total);
+    const uint32_t carry = carry_s;
     if (b < B) group_base[b] = (int32_t)(carry + ex);
     __syncthreads();
     if (tid == 0) carry_s = carry + total;
     __syncthreads();
   }
-  if (tid == 0) {
-    group_base[B] = (int32_t)carry_s;
-    *num_groups = (int32_t)carry_s;
-    group_offsets[carry_s] = (int32_t)n;
-  }
+  if (tid == 0) group_base[B] = (int32_t)carry_s;
 }
 
-// ---- outputs: perm, exported keys, group offsets ----------------------------------------------
-__global__ __launch_bounds__(256) void k_finalize(const uint64_t* __restrict__ sorted, int64_t n, KeyParams kp, int G,
-                                                   const int32_t* __restrict__ frame_start,
-                                                   const int32_t* __restrict__ group_base,
-                                                   int32_t* __restrict__ perm, uint64_t* __restrict__ keys_sorted,
-                                                   int32_t* __restrict__ group_offsets,
-                                                   int32_t* __restrict__ num_groups) {
-  const int64_t p = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
-  if (kp.B == 1 && p == 0) {
-    const int32_t ng = (int32_t)((n + G - 1) / G);
-    *num_groups = ng;
-    group_offsets[ng] = (int32_t)n;
+// ---- outputs: perm, exported keys, group offsets, num_groups ----------------------------------------
+// With at most 256 frames every block recomputes the frame table itself (B binary searches and
+// one block scan); otherwise it reads the table k_frames wrote.
+__global__ __launch_bounds__(256) void k_finalize(const uint64_t* __restrict__ sorted_all, int64_t n, Batch bt, int G,
+                                                   const int32_t* __restrict__ frame_tab,
+                                                   const uint32_t* __restrict__ error_word) {
+  __shared__ int32_t fstart_s[257], gbase_s[257];
+  __shared__ uint32_t wave_totals[4];
+  const int s = blockIdx.y;
+  const KeyParams kp = bt.kp[s];
+  const int B = kp.B, tid = threadIdx.x;
+  const uint64_t* sorted = sorted_all + (int64_t)s * n;
+  const int frame_shift = kp.idx_bits + kp.key_bits - kp.bits_b;
+  const int32_t* fstart = fstart_s;
+  const int32_t* gbase = gbase_s;
+  if (B == 1) {
+    if (tid == 0) { fstart_s[0] = 0; fstart_s[1] = (int32_t)n; gbase_s[0] = 0; gbase_s[1] = (int32_t)((n + G - 1) / G); }
+    __syncthreads();
+  } else if (B <= 256) {
+    if (tid == 0) fstart_s[B] = (int32_t)n;
+    if (tid < B) {
+      int64_t lo = 0, hi = n;
+      while (lo < hi) {
+        const int64_t mid = (lo + hi) >> 1;
+        const uint32_t f = (uint32_t)(sorted[mid] >> frame_shift);
+        if (f < (uint32_t)tid) lo = mid + 1; else hi = mid;
+      }
+      fstart_s[tid] = (int32_t)lo;
+    }
+    __syncthreads();
+    uint32_t g = 0;
+    if (tid < B) g = (uint32_t)((fstart_s[tid + 1] - fstart_s[tid] + G - 1) / G);
+    uint32_t total;
+    const uint32_t ex = block_exclusive_scan<256>(g, wave_totals, &total);
+    if (tid < B) gbase_s[tid] = (int32_t)ex;
+    if (tid == 0) gbase_s[B] = (int32_t)total;
+    __syncthreads();
+  } else {
+    fstart = frame_tab + (int64_t)s * 2 * (B + 1);
+    gbase = fstart + (B + 1);
+  }
+  const int64_t p = (int64_t)blockIdx.x * blockDim.x + tid;
+  if (p == 0) {
+    const int32_t ng = gbase[B];
+    *bt.num_groups[s] = *error_word ? -1 : ng;
+    bt.group_offsets[s][ng] = (int32_t)n;
   }
   if (p >= n) return;
   const uint64_t word = sorted[p];
-  const uint64_t idx_mask = kp.idx_bits >= 64 ? ~0ull : ((1ull << kp.idx_bits) - 1ull);
-  perm[p] = (int32_t)(word & idx_mask);
-  uint64_t k = kp.idx_bits >= 64 ? 0ull : (word >> kp.idx_bits);
+  const uint64_t idx_mask = (1ull << kp.idx_bits) - 1ull;
+  bt.perm[s][p] = (int32_t)(word & idx_mask);
+  uint64_t k = word >> kp.idx_bits;
   const uint64_t l2 = k & field_mask(kp.bits_l2); k >>= kp.bits_l2;
   const uint64_t l1 = k & field_mask(kp.bits_l1); k >>= kp.bits_l1;
   const uint64_t w2 = k & field_mask(kp.bits_w2); k >>= kp.bits_w2;
   const uint64_t w1 = k & field_mask(kp.bits_w1); k >>= kp.bits_w1;
   const uint64_t b = k & field_mask(kp.bits_b);
-  if (keys_sorted) keys_sorted[p] = (b << 48) | (w1 << 32) | (w2 << 16) | (l1 << 8) | l2;
-  int32_t fs = 0, gb = 0;
-  if (kp.B > 1) {
-    const int fb = b < (uint64_t)kp.B ? (int)b : kp.B - 1;
-    fs = frame_start[fb];
-    gb = group_base[fb];
-  }
-  const int32_t rel = (int32_t)p - fs;
-  if (rel % G == 0) group_offsets[gb + rel / G] = (int32_t)p;
+  if (bt.keys_sorted[s]) bt.keys_sorted[s][p] = (b << 48) | (w1 << 32) | (w2 << 16) | (l1 << 8) | l2;
+  const int fb = b < (uint64_t)B ? (int)b : B - 1;
+  const int32_t rel = (int32_t)p - fstart[fb];
+  if (rel % G == 0) bt.group_offsets[s][gbase[fb] + rel / G] = (int32_t)p;
+}
+
+struct Layout {
+  int P;            // passes (max over the batch)
+  int kpt;          // words per thread in a pass
+  int64_t tiles;
+  size_t off_words0, off_words1, off_control, control_words, off_frames, total;
+};
+
+// Workspace for S sorts of n words.  Control area (cleared by every call): error word, tickets
+// [S][P], histograms [S][P][256], tile status [S][P][tiles][256].
+void make_layout(int64_t n, int S, int P, int num_frames, Layout* L) {
+  L->P = P;
+  L->kpt = n <= (1 << 19) ? 4 : 16;
+  L->tiles = ceil_div(n > 0 ? n : 1, (int64_t)kSortThreads * L->kpt);
+  size_t off = 0;
+  L->off_words0 = off; off += align_up((size_t)S * n * 8, 256);
+  L->off_words1 = off; off += align_up((size_t)S * n * 8, 256);
+  L->off_control = off;
+  L->control_words = 64 + (size_t)S * P + (size_t)S * P * kBins + (size_t)S * P * L->tiles * kBins;
+  off += align_up(L->control_words * 4, 256);
+  L->off_frames = off; off += align_up((size_t)S * 2 * ((size_t)num_frames + 1) * 4, 256);
+  L->total = off;
 }
 
 }  // namespace
@@ -279,6 +387,7 @@ int make_flatten_plan(int64_t n, const ff_geom* g, int axis, int shift, FlattenP
   if (g->win_x < 1 || g->win_x > 256 || g->win_y < 1 || g->win_y > 256) return FF_ERR_ARG;
   if (axis != 0 && axis != 1) return FF_ERR_ARG;
   if (g->num_frames > 65535) return FF_ERR_UNSUPPORTED;
+  if (n >= (1LL << 30)) return FF_ERR_UNSUPPORTED;  // tile status words keep 30-bit counts
   const int64_t sx = shift ? g->win_x / 2 : 0, sy = shift ? g->win_y / 2 : 0;
   const int64_t nwx = ceil_div((int64_t)g->grid_x + sx, g->win_x);
   const int64_t nwy = ceil_div((int64_t)g->grid_y + sy, g->win_y);
@@ -294,72 +403,82 @@ int make_flatten_plan(int64_t n, const ff_geom* g, int axis, int shift, FlattenP
   plan->idx_bits = n > 0 ? bit_width_u64((uint64_t)n - 1) : 0;
   if (plan->key_bits + plan->idx_bits > 64) return FF_ERR_UNSUPPORTED;
   plan->passes = (plan->key_bits + kRadixBits - 1) / kRadixBits;
-  plan->tiles = ceil_div(n, kTile);
-  size_t off = 0;
-  plan->off_buf0 = off; off += align_up((size_t)n * 8, 256);
-  plan->off_buf1 = off; off += align_up((size_t)n * 8, 256);
-  plan->off_hist = off; off += align_up((size_t)kBins * (size_t)(plan->tiles > 0 ? plan->tiles : 1) * 4, 256);
-  plan->off_frames = off; off += align_up(((size_t)g->num_frames + 1) * 2 * 4, 256);
-  plan->total = off;
   return FF_OK;
 }
 
-size_t flatten_workspace_bytes(int64_t n, const ff_geom* g) {
-  // Independent of axis and shift: the shifted plan is never smaller.
+size_t flatten_workspace_bytes(int64_t n, const ff_geom* g, int num_sorts) {
+  // Independent of axis and shift: the shifted plan never has fewer key bits.
   FlattenPlan p;
+  if (num_sorts < 1 || num_sorts > kMaxSorts) return 0;
   if (make_flatten_plan(n, g, 0, 1, &p) != FF_OK) return 0;
-  return p.total;
+  Layout L;
+  make_layout(n, num_sorts, p.passes > 0 ? p.passes : 1, g->num_frames, &L);
+  return L.total;
 }
 
-int flatten_launch(const int32_t* coords, int64_t n, const ff_geom* g, int axis, int shift, int G,
-                   int32_t* perm, int32_t* group_offsets, int32_t* num_groups, uint64_t* keys_sorted,
-                   void* workspace, size_t workspace_bytes, hipStream_t stream) {
-  FlattenPlan plan;
-  int st = make_flatten_plan(n, g, axis, shift, &plan);
-  if (st != FF_OK) return st;
-  if (G < 1 || !group_offsets || !num_groups) return FF_ERR_ARG;
-  if (n > 0 && (!coords || !perm)) return FF_ERR_ARG;
-  if (!workspace || ((uintptr_t)workspace & 255) || workspace_bytes < plan.total) return FF_ERR_WORKSPACE;
+int flatten_launch(const int32_t* coords, int64_t n, const ff_geom* g, int num_sorts, const int* axis,
+                   const int* shift, int G, int32_t* const* perm, int32_t* const* group_offsets,
+                   int32_t* const* num_groups, uint64_t* const* keys_sorted, void* workspace,
+                   size_t workspace_bytes, hipStream_t stream) {
+  if (num_sorts < 1 || num_sorts > kMaxSorts || G < 1) return FF_ERR_ARG;
+  Batch bt;
+  int P = 0;
+  for (int s = 0; s < num_sorts; ++s) {
+    FlattenPlan plan;
+    const int st = make_flatten_plan(n, g, axis[s], shift[s], &plan);
+    if (st != FF_OK) return st;
+    if (!group_offsets[s] || !num_groups[s] || (n > 0 && !perm[s])) return FF_ERR_ARG;
+    KeyParams& kp = bt.kp[s];
+    kp.B = g->num_frames; kp.win_x = g->win_x; kp.win_y = g->win_y;
+    kp.sx = shift[s] ? g->win_x / 2 : 0; kp.sy = shift[s] ? g->win_y / 2 : 0;
+    kp.axis = axis[s];
+    kp.bits_b = plan.bits_b; kp.bits_w1 = plan.bits_w1; kp.bits_w2 = plan.bits_w2;
+    kp.bits_l1 = plan.bits_l1; kp.bits_l2 = plan.bits_l2;
+    kp.key_bits = plan.key_bits; kp.idx_bits = plan.idx_bits;
+    bt.perm[s] = perm[s]; bt.group_offsets[s] = group_offsets[s]; bt.num_groups[s] = num_groups[s];
+    bt.keys_sorted[s] = keys_sorted ? keys_sorted[s] : nullptr;
+    if (plan.passes > P) P = plan.passes;
+  }
+  for (int s = num_sorts; s < kMaxSorts; ++s) {
+    bt.kp[s] = bt.kp[0]; bt.perm[s] = nullptr; bt.group_offsets[s] = nullptr; bt.num_groups[s] = nullptr;
+    bt.keys_sorted[s] = nullptr;
+  }
+  if (n > 0 && !coords) return FF_ERR_ARG;
+  Layout L;
+  make_layout(n, num_sorts, P > 0 ? P : 1, g->num_frames, &L);
+  if (!workspace || ((uintptr_t)workspace & 255) || workspace_bytes < L.total) return FF_ERR_WORKSPACE;
 
   char* ws = (char*)workspace;
-  uint64_t* buf[2] = {(uint64_t*)(ws + plan.off_buf0), (uint64_t*)(ws + plan.off_buf1)};
-  uint32_t* hist = (uint32_t*)(ws + plan.off_hist);
-  int32_t* frame_start = (int32_t*)(ws + plan.off_frames);
-  int32_t* group_base = frame_start + (g->num_frames + 1);
+  uint64_t* buf[2] = {(uint64_t*)(ws + L.off_words0), (uint64_t*)(ws + L.off_words1)};
+  uint32_t* control = (uint32_t*)(ws + L.off_control);
+  uint32_t* error_word = control;
+  uint32_t* tickets = control + 64;
+  uint32_t* hist = tickets + (size_t)num_sorts * L.P;
+  uint32_t* status = hist + (size_t)num_sorts * L.P * kBins;
+  int32_t* frame_tab = (int32_t*)(ws + L.off_frames);
 
-  KeyParams kp;
-  kp.B = g->num_frames; kp.grid_x = g->grid_x; kp.grid_y = g->grid_y;
-  kp.win_x = g->win_x; kp.win_y = g->win_y;
-  kp.sx = shift ? g->win_x / 2 : 0; kp.sy = shift ? g->win_y / 2 : 0;
-  kp.axis = axis;
-  kp.bits_b = plan.bits_b; kp.bits_w1 = plan.bits_w1; kp.bits_w2 = plan.bits_w2;
-  kp.bits_l1 = plan.bits_l1; kp.bits_l2 = plan.bits_l2;
-  kp.key_bits = plan.key_bits; kp.idx_bits = plan.idx_bits;
-
-  const unsigned eblocks = (unsigned)(n > 0 ? ceil_div(n, 256) : 1);
+  int64_t cblocks = ceil_div((int64_t)L.control_words, 256 * 4);
+  if (cblocks > 1024) cblocks = 1024;
+  hipLaunchKernelGGL(k_clear, dim3((unsigned)cblocks), dim3(256), 0, stream, control, (int64_t)L.control_words);
   int cur = 0;
   if (n > 0) {
-    hipLaunchKernelGGL(k_keygen, dim3(eblocks), dim3(256), 0, stream, coords, n, kp, buf[0]);
-    for (int pass = 0; pass < plan.passes; ++pass) {
-      const int lo = pass * kRadixBits;
-      const int nb = plan.key_bits - lo < kRadixBits ? plan.key_bits - lo : kRadixBits;
-      const int sh = plan.idx_bits + lo;
-      const uint32_t mask = (1u << nb) - 1u;
-      hipLaunchKernelGGL(k_radix_hist, dim3((unsigned)plan.tiles), dim3(kSortThreads), 0, stream,
-                         buf[cur], n, sh, mask, plan.tiles, hist);
-      hipLaunchKernelGGL(k_scan_table, dim3(1), dim3(1024), 0, stream, hist, (int64_t)kBins * plan.tiles);
-      hipLaunchKernelGGL(k_radix_scatter, dim3((unsigned)plan.tiles), dim3(kSortThreads), 0, stream,
-                         buf[cur], buf[cur ^ 1], n, sh, mask, plan.tiles, hist);
+    hipLaunchKernelGGL(k_keygen_hist, dim3((unsigned)ceil_div(n, 1024), (unsigned)num_sorts), dim3(256),
+                       (size_t)L.P * kBins * 4, stream, coords, n, bt, L.P, buf[0], hist);
+    for (int pass = 0; pass < P; ++pass) {
+      const dim3 grid((unsigned)L.tiles, (unsigned)num_sorts);
+      if (L.kpt == 4)
+        hipLaunchKernelGGL(k_onesweep<4>, grid, dim3(kSortThreads), 0, stream, buf[cur], buf[cur ^ 1], n, bt, pass,
+                           L.P, L.tiles, hist, status, tickets, error_word);
+      else
+        hipLaunchKernelGGL(k_onesweep<16>, grid, dim3(kSortThreads), 0, stream, buf[cur], buf[cur ^ 1], n, bt, pass,
+                           L.P, L.tiles, hist, status, tickets, error_word);
       cur ^= 1;
     }
   }
-  if (g->num_frames > 1) {
-    hipLaunchKernelGGL(k_frames, dim3(1), dim3(256), 0, stream, buf[cur], n, g->num_frames, G,
-                       plan.idx_bits + plan.key_bits - plan.bits_b, frame_start, group_base,
-                       group_offsets, num_groups);
-  }
-  hipLaunchKernelGGL(k_finalize, dim3(eblocks), dim3(256), 0, stream, buf[cur], n, kp, G,
-                     frame_start, group_base, perm, keys_sorted, group_offsets, num_groups);
+  if (g->num_frames > 256)
+    hipLaunchKernelGGL(k_frames, dim3((unsigned)num_sorts), dim3(256), 0, stream, buf[cur], n, bt, G, frame_tab);
+  hipLaunchKernelGGL(k_finalize, dim3((unsigned)(n > 0 ? ceil_div(n, 256) : 1), (unsigned)num_sorts), dim3(256), 0,
+                     stream, buf[cur], n, bt, G, frame_tab, error_word);
   return launch_status();
 }
 
