@@ -134,7 +134,9 @@ size_t ff_group_attention_workspace_bytes(int64_t n, int G, const ff_layer_weigh
  * other groups write.  Row perm[p] of feats is member p of the sorted order; group g owns
  * sorted positions group_offsets[g] .. group_offsets[g+1]-1 (1..G of them).  num_groups is the
  * device scalar written by ff_flatten; max_groups is a host upper bound used to size the launch
- * (e.g. ceil(n/G) + num_frames).  Every row that belongs to a group is written exactly once.
+ * (e.g. ceil(n/G) + num_frames - 1) and group_offsets must hold at least max_groups + 1 readable
+ * entries (ff_flatten's buffer does for that bound).  num_groups < 0 (a failed flatten) computes
+ * nothing.  Every row that belongs to a group is written exactly once.
  * dtype FF_F32: fp32 arithmetic throughout.  FF_BF16: bf16 storage, bf16 MFMA operands, fp32
  * accumulation, statistics, softmax and GELU.
  * Limits (FF_ERR_UNSUPPORTED otherwise): C % heads == 0, C*sizeof(dtype) % 16 == 0, 1 <= G <= 1024. */

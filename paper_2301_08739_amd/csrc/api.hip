@@ -47,7 +47,7 @@ int ff_pack_weights(const ff_layer_weights* w, int dtype, void* packed, void* st
   if (st != FF_OK) return st;
   if (dtype != FF_BF16 || !layer_mfma_supported(w, 1)) return FF_ERR_UNSUPPORTED;
   if (!packed || ((uintptr_t)packed & 255)) return FF_ERR_ARG;
-  return layer_mfma_pack(w, packed, (hipStream_t)stream);
+  return layer_mfma_pack(w, 1, packed, 0, (hipStream_t)stream);
 }
 
 size_t ff_group_attention_workspace_bytes(int64_t n, int G, const ff_layer_weights* w, int dtype) {
@@ -83,7 +83,7 @@ int ff_group_attention(const void* feats, void* out, int64_t n, const int32_t* p
     if (!packed) {
       if (!workspace || ((uintptr_t)workspace & 255) || workspace_bytes < layer_mfma_packed_bytes(w))
         return FF_ERR_WORKSPACE;
-      st = layer_mfma_pack(w, workspace, (hipStream_t)stream);
+      st = layer_mfma_pack(w, 1, workspace, 0, (hipStream_t)stream);
       if (st != FF_OK) return st;
       packed = workspace;
     }
@@ -109,8 +109,8 @@ namespace {
 struct BlockPlan {
   int sorts;  // distinct sort configurations used by layers 0..L-1 (schedule order x, y, sx, sy)
   int64_t max_groups;
-  size_t off_flat, off_perm, off_goff, off_ng, off_a, off_b, off_layer, total;
-  size_t flat_bytes, layer_bytes;
+  size_t off_flat, off_perm, off_goff, off_ng, off_a, off_b, off_layer, off_packed, total;
+  size_t flat_bytes, layer_bytes, packed_stride;  // packed_stride == 0: nothing to pre-pack
 };
 
 int make_block_plan(int64_t n, const ff_geom* g, int G, const ff_layer_weights* layers, int num_layers,
@@ -139,6 +139,16 @@ int make_block_plan(int64_t n, const ff_geom* g, int G, const ff_layer_weights* 
   p->off_a = off;     off += feat_bytes;
   p->off_b = off;     off += feat_bytes;
   p->off_layer = off; off += align_up(p->layer_bytes, 256);
+  // One batched packing launch for the whole stack when every layer has the same packable shape
+  // and the caller did not pre-pack.
+  p->packed_stride = 0;
+  if (dtype == FF_BF16 && layer_mfma_supported(&layers[0], G)) {
+    bool same = true;
+    for (int l = 0; l < num_layers; ++l)
+      same = same && layers[l].F == layers[0].F && layers[l].heads == layers[0].heads && !layers[l].packed;
+    if (same) p->packed_stride = align_up(layer_mfma_packed_bytes(&layers[0]), 256);
+  }
+  p->off_packed = off; off += p->packed_stride * num_layers;
   p->total = off;
   return FF_OK;
 }
@@ -175,14 +185,20 @@ int ff_fwa_block(const int32_t* coords, int64_t n, const ff_geom* g, int G, cons
                         p.flat_bytes, (hipStream_t)stream);
     if (st != FF_OK) return st;
   }
+  if (p.packed_stride && n > 0) {
+    st = layer_mfma_pack(layers, num_layers, ws + p.off_packed, p.packed_stride, (hipStream_t)stream);
+    if (st != FF_OK) return st;
+  }
   const void* cur = feats_in;
   void* bufs[2] = {ws + p.off_a, ws + p.off_b};
   for (int l = 0; l < num_layers; ++l) {
     const int s = l % 4;
     void* dst = (l == num_layers - 1) ? feats_out : bufs[l & 1];
+    ff_layer_weights wl = layers[l];
+    if (p.packed_stride) wl.packed = ws + p.off_packed + (size_t)l * p.packed_stride;
     st = ff_group_attention(cur, dst, n, (const int32_t*)(ws + p.off_perm + s * perm_stride),
                             (const int32_t*)(ws + p.off_goff + s * goff_stride), (const int32_t*)(ws + p.off_ng) + s,
-                            (int32_t)p.max_groups, &layers[l], G, dtype, 0, ws + p.off_layer, p.layer_bytes, stream);
+                            (int32_t)p.max_groups, &wl, G, dtype, 0, ws + p.off_layer, p.layer_bytes, stream);
     if (st != FF_OK) return st;
     cur = dst;
   }

@@ -70,7 +70,7 @@ int layer_generic_launch(const void* feats, void* out, int64_t n, const int32_t*
 // Fused bf16 matrix-core layer (layer_mfma.hip)
 bool layer_mfma_supported(const ff_layer_weights* w, int G);
 size_t layer_mfma_packed_bytes(const ff_layer_weights* w);
-int layer_mfma_pack(const ff_layer_weights* w, void* packed, hipStream_t stream);
+int layer_mfma_pack(const ff_layer_weights* w, int count, void* packed, size_t stride_bytes, hipStream_t stream);
 int layer_mfma_launch(const void* feats, void* out, int64_t n, const int32_t* perm, const int32_t* group_offsets,
                       const int32_t* num_groups, int32_t max_groups, const ff_layer_weights* w, int G,
                       bool out_f32, const void* packed, int variant, hipStream_t stream);

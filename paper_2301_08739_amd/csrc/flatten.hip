@@ -134,7 +134,7 @@ __global__ __launch_bounds__(kSortThreads) void k_onesweep(const uint64_t* __res
                                                             int64_t n, Batch bt, int pass, int P, int64_t tiles,
                                                             const uint32_t* __restrict__ hist /*[S][P][256]*/,
                                                             uint32_t* __restrict__ status /*[S][P][tiles][256]*/,
-                                                            uint32_t* __restrict__ tickets /*[S][P]*/,
+                                                            uint32_t* __restrict__ tickets /*[S][P]*/, int use_tickets,
                                                             uint32_t* __restrict__ error_word) {
   constexpr int WAVES = kSortThreads / 64;
   constexpr int TILE = kSortThreads * KPT;
@@ -152,7 +152,9 @@ __global__ __launch_bounds__(kSortThreads) void k_onesweep(const uint64_t* __res
   uint64_t* out = out_all + (int64_t)s * n;
   const int64_t slot = (int64_t)s * P + pass;
 
-  if (tid == 0) { tile_s = atomicAdd(&tickets[slot], 1u); failed_s = 0u; }
+  // Tile number: the block index while the whole grid is resident at once (no block can then wait
+  // for one that has not started); otherwise an atomic ticket, so that numbers follow start order.
+  if (tid == 0) { tile_s = use_tickets ? atomicAdd(&tickets[slot], 1u) : blockIdx.x; failed_s = 0u; }
 #pragma unroll
   for (int i = 0; i < WAVES; ++i) wave_cnt[i][tid] = 0;
   __syncthreads();
@@ -203,23 +205,44 @@ __global__ __launch_bounds__(kSortThreads) void k_onesweep(const uint64_t* __res
   const uint32_t dbase = block_exclusive_scan<kSortThreads>(hist[slot * kBins + tid], wave_totals, nullptr);
   digit_start[tid] = block_exclusive_scan<kSortThreads>(total, wave_totals, nullptr);
 
-  // look back over earlier tiles for the number of digit-d words before this tile
+  // Look back over earlier tiles for the number of digit-d words before this tile, eight status
+  // words per round trip (the loads are independent, so their latencies overlap).  Walking from
+  // the nearest tile down, counts are added until a tile that already knows its inclusive prefix.
   uint32_t before = 0;
   if (tile > 0) {
-    int64_t t = tile - 1;
+    constexpr int LB = 8;
+    int64_t hi = tile - 1;
     int spins = 0;
-    while (true) {
-      const uint32_t v = __hip_atomic_load(&status[(slot * tiles + t) * kBins + tid], __ATOMIC_RELAXED,
-                                           __HIP_MEMORY_SCOPE_AGENT);
-      const uint32_t flag = v & ~kCountMask;
-      if (flag == 0u) {
+    bool done = false;
+    while (!done) {
+      uint32_t v[LB];
+      bool ready = true;
+#pragma unroll
+      for (int u = 0; u < LB; ++u) {
+        const int64_t t = hi - u;
+        v[u] = t >= 0 ? __hip_atomic_load(&status[(slot * tiles + t) * kBins + tid], __ATOMIC_RELAXED,
+                                          __HIP_MEMORY_SCOPE_AGENT)
+                      : kFlagInclusive;
+      }
+#pragma unroll
+      for (int u = 0; u < LB; ++u) {  // usable prefix of the batch: up to the first inclusive word
+        if (done) continue;
+        const uint32_t flag = v[u] & ~kCountMask;
+        if (flag == 0u) { ready = false; break; }
+        if (flag == kFlagInclusive) break;
+      }
+      if (!ready) {
         if (++spins > kSpinLimit) { failed_s = 1u; break; }
         __builtin_amdgcn_s_sleep(1);
         continue;
       }
-      before += v & kCountMask;
-      if (flag == kFlagInclusive || t == 0) break;
-      --t;
+#pragma unroll
+      for (int u = 0; u < LB; ++u) {
+        if (done) continue;
+        before += v[u] & kCountMask;
+        if ((v[u] & ~kCountMask) == kFlagInclusive) done = true;
+      }
+      hi -= LB;
     }
     __hip_atomic_store(&st[tid], ((before + total) & kCountMask) | kFlagInclusive, __ATOMIC_RELAXED,
                        __HIP_MEMORY_SCOPE_AGENT);
@@ -464,14 +487,16 @@ int flatten_launch(const int32_t* coords, int64_t n, const ff_geom* g, int num_s
   if (n > 0) {
     hipLaunchKernelGGL(k_keygen_hist, dim3((unsigned)ceil_div(n, 1024), (unsigned)num_sorts), dim3(256),
                        (size_t)L.P * kBins * 4, stream, coords, n, bt, L.P, buf[0], hist);
+    // 256 compute units hold far more than 512 of these workgroups at once
+    const int use_tickets = L.tiles * num_sorts > 512 ? 1 : 0;
     for (int pass = 0; pass < P; ++pass) {
       const dim3 grid((unsigned)L.tiles, (unsigned)num_sorts);
       if (L.kpt == 4)
         hipLaunchKernelGGL(k_onesweep<4>, grid, dim3(kSortThreads), 0, stream, buf[cur], buf[cur ^ 1], n, bt, pass,
-                           L.P, L.tiles, hist, status, tickets, error_word);
+                           L.P, L.tiles, hist, status, tickets, use_tickets, error_word);
       else
         hipLaunchKernelGGL(k_onesweep<16>, grid, dim3(kSortThreads), 0, stream, buf[cur], buf[cur ^ 1], n, bt, pass,
-                           L.P, L.tiles, hist, status, tickets, error_word);
+                           L.P, L.tiles, hist, status, tickets, use_tickets, error_word);
       cur ^= 1;
     }
   }

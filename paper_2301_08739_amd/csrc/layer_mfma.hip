@@ -22,6 +22,10 @@
 // all wavefronts of the workgroup in lockstep, double buffered (one barrier per chunk).
 #include "common.h"
 
+#ifdef FF_PROBE
+__device__ long long ff_probe_ts_global[2][64];
+#endif
+
 namespace ff {
 namespace {
 
@@ -77,18 +81,65 @@ __device__ __forceinline__ f32x4 mfma32(const Frag8& a, const Frag8& b, f32x4 c)
 __device__ __forceinline__ f32x4 mfma16(const Frag4& a, const Frag4& b, f32x4 c) {
   return __builtin_amdgcn_mfma_f32_16x16x16bf16_1k(a.v, b.v, c, 0, 0, 0);
 }
-// GELU(v) = v * Phi(v), with Phi(v) ~ 1 / (1 + exp(-(a v + b v^3 + c v^5))): an odd quintic inside
-// a logistic, coefficients fitted to the erf form on [-8, 8] (max abs error of v * Phi(v): 2.6e-5).
-// The argument is clamped to the fitted range, where the logistic is saturated to 1e-12 anyway.
+// GELU(v) = v * Phi(v) with the upper tail 1 - Phi(t) ~ 0.5 * exp(-(a t + b t^2 + c t^3)), t = |v|
+// (coefficients fitted to the erf form; all positive, so the exponent is monotone for any t):
+//   GELU(v) = max(v, 0) - 0.5 * t * exp(-(a t + b t^2 + c t^3)),   max abs error 8.6e-5.
+// One transcendental per element.
 __device__ __forceinline__ float gelu_fast(float v) {
+#ifdef FF_EXPERIMENT_NO_GELU
+  return v;
+#endif
   constexpr float L2E = 1.44269504088896340736f;
-  const float x = __builtin_amdgcn_fmed3f(v, -8.0f, 8.0f);
-  const float x2 = x * x;
-  float p = fmaf(x2, 7.03033568e-04f * L2E, -7.40112920e-02f * L2E);
-  p = fmaf(x2, p, -1.59501577f * L2E);
-  const float e = __builtin_amdgcn_exp2f(p * x);
-  return v * __builtin_amdgcn_rcpf(1.0f + e);
+  const float t = fabsf(v);
+  float p = fmaf(t, -0.01916250660946074f * L2E, -0.33840941696965965f * L2E);
+  p = fmaf(t, p, -0.7908370960657618f * L2E);
+  const float e = __builtin_amdgcn_exp2f(p * t);
+  return fmaf(-0.5f * t, e, fmaxf(v, 0.0f));
 }
+
+#ifdef FF_PROBE
+// Development aid (not part of product builds): cycle stamps of wave 0 of two workgroups, kept in
+// registers and written out when the kernel ends.
+#define ff_probe_ts ff_probe_ts_global
+#define FF_TS(k) do { ff_tsw[k] = wall_clock64(); ff_tsc[k] = clock64(); } while (0)
+#define FF_TS_DECL long long ff_tsw[24] = {0}, ff_tsc[24] = {0};
+#define FF_TS_DUMP                                                                        \
+  do {                                                                                    \
+    if ((threadIdx.x == 0) && (blockIdx.x == 0 || blockIdx.x == gridDim.x / 2)) {         \
+      for (int k = 0; k < 24; ++k) {                                                      \
+        ff_probe_ts[blockIdx.x == 0 ? 0 : 1][k] = ff_tsw[k];                              \
+        ff_probe_ts[blockIdx.x == 0 ? 0 : 1][32 + k] = ff_tsc[k];                         \
+      }                                                                                   \
+    }                                                                                     \
+  } while (0)
+#else
+#define FF_TS(k) do { } while (0)
+#define FF_TS_DECL
+#define FF_TS_DUMP do { } while (0)
+#endif
+
+// Stream N consecutive 1 KB weight fragments out of LDS with PF reads in flight: the read of
+// fragment f + PF is issued before the products that use fragment f, so the LDS latency hides
+// behind matrix-core work instead of preceding every product.
+template <int N, int PF, typename Fn>
+__device__ __forceinline__ void frag_stream(const u32x4* rb, Fn&& use) {
+  Frag8 buf[PF];
+#pragma unroll
+  for (int f = 0; f < PF && f < N; ++f) buf[f].q = rb[f * 64];
+#pragma unroll
+  for (int f = 0; f < N; ++f) {
+    const Frag8 cur = buf[f % PF];
+    __builtin_amdgcn_sched_barrier(0);
+#ifdef FF_EXPERIMENT_NO_FRAGREAD
+    if (f + PF < N) buf[f % PF].q = buf[(f + 1) % PF].q + u32x4{1, 2, 3, 4};
+#else
+    if (f + PF < N) buf[f % PF].q = rb[(f + PF) * 64];
+#endif
+    __builtin_amdgcn_sched_barrier(0);
+    use(cur, f);
+  }
+}
+constexpr int kPrefetch = 3;
 
 struct SmallParams {  // per-feature vectors, bf16, read straight from the caller's arrays
   const uint16_t *ln1_g, *ln1_b, *b_qkv, *b_o, *ln2_g, *ln2_b, *b1, *b2;
@@ -103,9 +154,17 @@ __host__ __device__ constexpr int frags_per_fc(int C) { return 2 * (C / 32) + C 
 // W_o column slice (NB fragments); then for each 32-wide hidden unit fc: W1 rows (2 x KB), W2
 // column slice (NB).  A fragment is 16 output features x 32 inputs; lane (i, q) owns 16 bytes:
 // row i, inputs kbase + 16*(s/4) + 4q + (s%4) for slot s = 0..7.
-__global__ __launch_bounds__(256) void k_pack_weights(const uint16_t* __restrict__ w_qkv, const uint16_t* __restrict__ w_o,
-                                                       const uint16_t* __restrict__ w1, const uint16_t* __restrict__ w2,
-                                                       int C, int F, uint4* __restrict__ out, int total_frags) {
+constexpr int kPackBatch = 16;
+struct PackBatch {  // up to 16 layers of identical shape packed by one launch (grid.y = layer)
+  const uint16_t *w_qkv[kPackBatch], *w_o[kPackBatch], *w1[kPackBatch], *w2[kPackBatch];
+  uint4* out[kPackBatch];
+};
+__global__ __launch_bounds__(256) void k_pack_weights(PackBatch pb, int C, int F, int total_frags) {
+  const uint16_t* __restrict__ w_qkv = pb.w_qkv[blockIdx.y];
+  const uint16_t* __restrict__ w_o = pb.w_o[blockIdx.y];
+  const uint16_t* __restrict__ w1 = pb.w1[blockIdx.y];
+  const uint16_t* __restrict__ w2 = pb.w2[blockIdx.y];
+  uint4* __restrict__ out = pb.out[blockIdx.y];
   const int t = blockIdx.x * blockDim.x + threadIdx.x;
   const int frag = t >> 6, lane = t & 63, i = lane & 15, q = lane >> 4;
   if (frag >= total_frags) return;
@@ -152,11 +211,11 @@ struct ParamOff {  // float offsets inside the small-parameter area
                        LN2B = 7 * C, B2 = 8 * C, B1 = 9 * C, TOTAL = 9 * C + F;
 };
 
-template <int C, int DH, int F, int NVB, int WPG, int NW, int MINW, bool OUT_F32>
+template <int C, int DH, int F, int NVB, int WPG, int NW, int MINW, int CHM, bool OUT_F32>
 __global__ __launch_bounds__(NW * 64, MINW) void k_layer_mfma(const uint16_t* __restrict__ feats, void* __restrict__ out,
                                                                const int32_t* __restrict__ perm,
                                                                const int32_t* __restrict__ goff,
-                                                               const int32_t* __restrict__ num_groups,
+                                                               const int32_t* __restrict__ num_groups, int max_groups,
                                                                const u32x4* __restrict__ packed, SmallParams sp, float eps) {
   constexpr int KB = C / 32;          // 32-wide blocks of the input features
   constexpr int NB = C / 16;          // 16-wide blocks of the output features
@@ -164,9 +223,11 @@ __global__ __launch_bounds__(NW * 64, MINW) void k_layer_mfma(const uint16_t* __
   constexpr int FC = F / 32;          // 32-wide hidden units
   constexpr int NKB = NVB * WPG;      // key blocks of a group
   constexpr int NT = NW * 64;
-  constexpr int CH = 4 * KB;          // fragments per staged chunk: {Q,K} | {V,W_o} | {W1,W2}
+  constexpr int CH = 4 * KB * CHM;    // fragments per staged chunk; a 4*KB piece is {Q,K} | {V,W_o} | {W1,W2}
   constexpr int STG = CH * 64 / NT;   // 16-byte pieces per thread per chunk
-  constexpr int NCHUNK = 2 * HP + FC;
+  constexpr int NCHUNK = (2 * HP + FC) / CHM;
+  static_assert(CHM == 1 || CHM == 2, "chunk multiplier");
+  static_assert((2 * HP + FC) % CHM == 0 && FC % CHM == 0, "chunking");
   using PO = ParamOff<C, F>;
   static_assert(DH == 16 || DH == 32, "head dim");
   static_assert((CH * 64) % NT == 0, "staging");
@@ -179,9 +240,14 @@ __global__ __launch_bounds__(NW * 64, MINW) void k_layer_mfma(const uint16_t* __
   const int tid = threadIdx.x, lane = tid & 63, w = tid >> 6, i = lane & 15, q = lane >> 4;
   const int gl = w / WPG, part = w % WPG;
   const int g = blockIdx.x * (NW / WPG) + gl;
+  // group_offsets has at least max_groups + 1 entries: read this group's bounds without waiting
+  // for num_groups, so that the two loads travel together.
+  const int gc = g < max_groups ? g : max_groups - 1;
+  const int off0 = goff[gc], off1 = goff[gc + 1];
   int start = 0, m = 0;
-  if (g < *num_groups) { start = goff[g]; m = goff[g + 1] - start; }
+  if (g < *num_groups) { start = off0; m = off1 - off0; }
 
+  FF_TS_DECL
   u32x4 stg[STG];
   int cc = 0;  // chunk being consumed
   auto issue = [&](int chunk) {
@@ -197,11 +263,25 @@ __global__ __launch_bounds__(NW * 64, MINW) void k_layer_mfma(const uint16_t* __
     }
   };
   auto advance = [&]() {  // done with chunk cc: publish cc+1, start fetching cc+2
+#ifdef FF_EXPERIMENT_NO_STAGING
+    return;
+#endif
+#ifdef FF_PROBE
+    if (cc == 2) FF_TS(20);
+    if (cc == 2) { asm volatile("s_waitcnt vmcnt(0)" ::: "memory"); FF_TS(21); }
+#endif
     commit(cc + 1);
+#ifdef FF_PROBE
+    if (cc == 2) FF_TS(22);
+#endif
     __syncthreads();
+#ifdef FF_PROBE
+    if (cc == 2) FF_TS(23);
+#endif
     ++cc;
     issue(cc + 1);
   };
+  FF_TS(0);
   issue(0);
 
   // small parameters -> LDS as fp32
@@ -234,26 +314,27 @@ __global__ __launch_bounds__(NW * 64, MINW) void k_layer_mfma(const uint16_t* __
       x1[vb][nb] = f32x4{t[0], t[1], t[2], t[3]};
     }
   }
+  FF_TS(1);
   commit(0);
   __syncthreads();
   issue(1);
+  FF_TS(2);
 
   Frag8 act[NVB][KB];  // normalised activations as B operands (LN1 output, later LN2 output)
   auto layer_norm = [&](int goff_f, int boff_f) {
-    float mu[NVB], rstd[NVB];
+    float sc[NVB], sh[NVB];  // y = x * sc + sh  with sc = rstd, sh = -mean * rstd
 #pragma unroll
     for (int vb = 0; vb < NVB; ++vb) {
-      float s = 0.f;
-#pragma unroll
-      for (int nb = 0; nb < NB; ++nb) s += (x1[vb][nb][0] + x1[vb][nb][1]) + (x1[vb][nb][2] + x1[vb][nb][3]);
-      mu[vb] = quad_sum(s) * (1.0f / C);
-      float v = 0.f;
+      float s = 0.f, ss = 0.f;
 #pragma unroll
       for (int nb = 0; nb < NB; ++nb) {
 #pragma unroll
-        for (int j = 0; j < 4; ++j) { const float d = x1[vb][nb][j] - mu[vb]; v = fmaf(d, d, v); }
+        for (int j = 0; j < 4; ++j) { s += x1[vb][nb][j]; ss = fmaf(x1[vb][nb][j], x1[vb][nb][j], ss); }
       }
-      rstd[vb] = rsqrtf(quad_sum(v) * (1.0f / C) + eps);
+      const float mu = quad_sum(s) * (1.0f / C);
+      const float var = fmaxf(quad_sum(ss) * (1.0f / C) - mu * mu, 0.f);
+      sc[vb] = rsqrtf(var + eps);
+      sh[vb] = -mu * sc[vb];
     }
 #pragma unroll
     for (int nb = 0; nb < NB; ++nb) {
@@ -263,7 +344,7 @@ __global__ __launch_bounds__(NW * 64, MINW) void k_layer_mfma(const uint16_t* __
       for (int vb = 0; vb < NVB; ++vb) {
         float y[4];
 #pragma unroll
-        for (int j = 0; j < 4; ++j) y[j] = fmaf((x1[vb][nb][j] - mu[vb]) * rstd[vb], gm[j], bt[j]);
+        for (int j = 0; j < 4; ++j) y[j] = fmaf(fmaf(x1[vb][nb][j], sc[vb], sh[vb]), gm[j], bt[j]);
         act[vb][nb / 2].u[(nb & 1) * 2 + 0] = pack2(y[0], y[1]);
         act[vb][nb / 2].u[(nb & 1) * 2 + 1] = pack2(y[2], y[3]);
       }
@@ -280,6 +361,7 @@ __global__ __launch_bounds__(NW * 64, MINW) void k_layer_mfma(const uint16_t* __
   layer_norm(PO::LN1G, PO::LN1B);
   add_bias_rows(PO::BO);  // residual + output-projection bias
 
+  FF_TS(3);
   const float qscale = rsqrtf((float)DH) * 1.44269504088896340736f;  // 1/sqrt(d) * log2(e)
   const bool short_group = m < NKB * 16;  // wave-uniform: some key slots are padding
 
@@ -289,55 +371,56 @@ __global__ __launch_bounds__(NW * 64, MINW) void k_layer_mfma(const uint16_t* __
     const u32x4* rb = ring + (cc & 1) * CH * 64 + lane;
     Frag4 Qf[2][NVB], Kf[2][NVB], Vf[2][NVB];  // bf16 fragments of my pillars, index [16-block a][vb]
 
-    // Q and K rows: D[feature][pillar]
+    // Q and K rows: D[feature][pillar]; fragment f = (q|k, 16-block a, k-block kb)
+    {
+      f32x4 acc[NVB];
+      frag_stream<4 * KB, kPrefetch>(rb, [&](const Frag8& wf, int f) {
+        const int qk = f / (2 * KB), a = (f / KB) & 1, kb = f % KB;
+        if (kb == 0) {  // the accumulator starts from the bias
+          const f32x4 b = *reinterpret_cast<const f32x4*>(par + (qk == 0 ? PO::BQ : PO::BK) + 32 * hp + 16 * a + 4 * q);
 #pragma unroll
-    for (int qk = 0; qk < 2; ++qk) {
-#pragma unroll
-      for (int a = 0; a < 2; ++a) {
-        f32x4 acc[NVB];
-#pragma unroll
-        for (int vb = 0; vb < NVB; ++vb) acc[vb] = f32x4{0.f, 0.f, 0.f, 0.f};
-#pragma unroll
-        for (int kb = 0; kb < KB; ++kb) {
-          Frag8 wf;
-          wf.q = rb[((qk * 2 + a) * KB + kb) * 64];
-#pragma unroll
-          for (int vb = 0; vb < NVB; ++vb) acc[vb] = mfma32(wf, act[vb][kb], acc[vb]);
+          for (int vb = 0; vb < NVB; ++vb) acc[vb] = b;
         }
-        const f32x4 b = *reinterpret_cast<const f32x4*>(par + (qk == 0 ? PO::BQ : PO::BK) + 32 * hp + 16 * a + 4 * q);
 #pragma unroll
-        for (int vb = 0; vb < NVB; ++vb) {
-          if (qk == 0) {
-            Qf[a][vb].u[0] = pack2((acc[vb][0] + b[0]) * qscale, (acc[vb][1] + b[1]) * qscale);
-            Qf[a][vb].u[1] = pack2((acc[vb][2] + b[2]) * qscale, (acc[vb][3] + b[3]) * qscale);
-          } else {
-            Kf[a][vb].u[0] = pack2(acc[vb][0] + b[0], acc[vb][1] + b[1]);
-            Kf[a][vb].u[1] = pack2(acc[vb][2] + b[2], acc[vb][3] + b[3]);
+        for (int vb = 0; vb < NVB; ++vb) acc[vb] = mfma32(wf, act[vb][kb], acc[vb]);
+        if (kb == KB - 1) {
+#pragma unroll
+          for (int vb = 0; vb < NVB; ++vb) {
+            Frag4& dst = qk == 0 ? Qf[a][vb] : Kf[a][vb];
+            dst.u[0] = pack2(acc[vb][0], acc[vb][1]);
+            dst.u[1] = pack2(acc[vb][2], acc[vb][3]);
           }
         }
-      }
+      });
     }
-    advance();
-    rb = ring + (cc & 1) * CH * 64 + lane;
+    if (hp == 0) FF_TS(4);
+    if (CHM == 1) {
+      advance();
+      rb = ring + (cc & 1) * CH * 64 + lane;
+    } else {
+      rb += 4 * KB * 64;
+    }
+    if (hp == 0) FF_TS(5);
     // V rows with the operand roles swapped: D[pillar][feature]
-#pragma unroll
-    for (int a = 0; a < 2; ++a) {
+    {
       f32x4 acc[NVB];
+      frag_stream<2 * KB, kPrefetch>(rb, [&](const Frag8& wf, int f) {
+        const int a = f / KB, kb = f % KB;
+        if (kb == 0) {
+          const float bv = par[PO::BV + 32 * hp + 16 * a + i];
 #pragma unroll
-      for (int vb = 0; vb < NVB; ++vb) acc[vb] = f32x4{0.f, 0.f, 0.f, 0.f};
-#pragma unroll
-      for (int kb = 0; kb < KB; ++kb) {
-        Frag8 wf;
-        wf.q = rb[(a * KB + kb) * 64];
+          for (int vb = 0; vb < NVB; ++vb) acc[vb] = f32x4{bv, bv, bv, bv};
+        }
 #pragma unroll
         for (int vb = 0; vb < NVB; ++vb) acc[vb] = mfma32(act[vb][kb], wf, acc[vb]);
-      }
-      const float bv = par[PO::BV + 32 * hp + 16 * a + i];
+        if (kb == KB - 1) {
 #pragma unroll
-      for (int vb = 0; vb < NVB; ++vb) {
-        Vf[a][vb].u[0] = pack2(acc[vb][0] + bv, acc[vb][1] + bv);
-        Vf[a][vb].u[1] = pack2(acc[vb][2] + bv, acc[vb][3] + bv);
-      }
+          for (int vb = 0; vb < NVB; ++vb) {
+            Vf[a][vb].u[0] = pack2(acc[vb][0], acc[vb][1]);
+            Vf[a][vb].u[1] = pack2(acc[vb][2], acc[vb][3]);
+          }
+        }
+      });
     }
 
     // K/V of the whole group.  One wavefront per group: they are already in registers.
@@ -365,129 +448,189 @@ __global__ __launch_bounds__(NW * 64, MINW) void k_layer_mfma(const uint16_t* __
       Frag4 f; f.d = kv[((1 * 2 + a) * NKB + jb) * 64]; return f;
     };
 
+    if (hp == 0) FF_TS(6);
     Frag8 Of[NVB];  // attention output of this unit as B operand of the output projection
-    constexpr int NH = 32 / DH;  // heads in this unit
+    constexpr int NH = 32 / DH;   // heads in this unit
+    constexpr int NA = DH / 16;   // 16-blocks of head dims per head
+    // The (head, pillar-block) instances are independent; they go through the softmax in
+    // lockstep stages so that the long per-instance dependency chains interleave.  HJ heads are
+    // staged jointly, limited by the registers the score tiles take.
+    constexpr int VJ = NVB * NKB <= 16 ? NVB : (16 / NKB >= 1 ? 16 / NKB : 1);
+    constexpr int HJ = (NH * VJ * NKB <= 16) ? NH : 1;
+    static_assert(NVB % VJ == 0, "pillar blocks per stage");
 #pragma unroll
-    for (int h = 0; h < NH; ++h) {
+    for (int v0 = 0; v0 < NVB; v0 += VJ)
 #pragma unroll
-      for (int vb = 0; vb < NVB; ++vb) {
-        // scores, transposed: S[key 16*jb + 4q + j][query i]
-        f32x4 S[NKB];
+    for (int h0 = 0; h0 < NH; h0 += HJ) {
+      f32x4 S[HJ][VJ][NKB];  // scores, transposed: S[key 16*jb + 4q + j][query i]
 #pragma unroll
-        for (int jb = 0; jb < NKB; ++jb) {
-          const f32x4 z = f32x4{0.f, 0.f, 0.f, 0.f};
-          if (DH == 16) {
-            S[jb] = mfma16(Kget(h, jb), Qf[h][vb], z);
-          } else {
-            Frag8 k8, q8;
-            const Frag4 k0 = Kget(0, jb), k1 = Kget(1, jb);
-            k8.u[0] = k0.u[0]; k8.u[1] = k0.u[1]; k8.u[2] = k1.u[0]; k8.u[3] = k1.u[1];
-            q8.u[0] = Qf[0][vb].u[0]; q8.u[1] = Qf[0][vb].u[1]; q8.u[2] = Qf[1][vb].u[0]; q8.u[3] = Qf[1][vb].u[1];
-            S[jb] = mfma32(k8, q8, z);
-          }
-        }
-        if (short_group) {  // keys beyond the group's real members
+      for (int hh = 0; hh < HJ; ++hh) {
+        const int h = h0 + hh;
+#pragma unroll
+        for (int vb = 0; vb < VJ; ++vb) {
 #pragma unroll
           for (int jb = 0; jb < NKB; ++jb) {
-#pragma unroll
-            for (int j = 0; j < 4; ++j)
-              if (16 * jb + 4 * q + j >= m) S[jb][j] = -INFINITY;
+            const f32x4 z = f32x4{0.f, 0.f, 0.f, 0.f};
+            if (DH == 16) {
+              S[hh][vb][jb] = mfma16(Kget(h, jb), Qf[h][v0 + vb], z);
+            } else {
+              Frag8 k8, q8;
+              const Frag4 k0 = Kget(0, jb), k1 = Kget(1, jb);
+              k8.u[0] = k0.u[0]; k8.u[1] = k0.u[1]; k8.u[2] = k1.u[0]; k8.u[3] = k1.u[1];
+              q8.u[0] = Qf[0][v0 + vb].u[0]; q8.u[1] = Qf[0][v0 + vb].u[1]; q8.u[2] = Qf[1][v0 + vb].u[0]; q8.u[3] = Qf[1][v0 + vb].u[1];
+              S[hh][vb][jb] = mfma32(k8, q8, z);
+            }
           }
         }
-        float mx = S[0][0];
+      }
+      if (short_group) {  // keys beyond the group's real members
 #pragma unroll
-        for (int jb = 0; jb < NKB; ++jb) {
+        for (int hh = 0; hh < HJ; ++hh)
 #pragma unroll
-          for (int j = 0; j < 4; ++j) mx = fmaxf(mx, S[jb][j]);
+          for (int vb = 0; vb < VJ; ++vb)
+#pragma unroll
+            for (int jb = 0; jb < NKB; ++jb)
+#pragma unroll
+              for (int j = 0; j < 4; ++j)
+                if (16 * jb + 4 * q + j >= m) S[hh][vb][jb][j] = -INFINITY;
+      }
+      float mxs[HJ][VJ];
+#pragma unroll
+      for (int hh = 0; hh < HJ; ++hh) {
+#pragma unroll
+        for (int vb = 0; vb < VJ; ++vb) {
+          float mx = S[hh][vb][0][0];
+#pragma unroll
+          for (int jb = 0; jb < NKB; ++jb)
+#pragma unroll
+            for (int j = 0; j < 4; ++j) mx = fmaxf(mx, S[hh][vb][jb][j]);
+          mxs[hh][vb] = mx;
         }
-        mx = quad_max(mx);
-        float sum = 0.f;
+      }
 #pragma unroll
-        for (int jb = 0; jb < NKB; ++jb) {
+      for (int hh = 0; hh < HJ; ++hh)
 #pragma unroll
-          for (int j = 0; j < 4; ++j) { S[jb][j] = __builtin_amdgcn_exp2f(S[jb][j] - mx); sum += S[jb][j]; }
+        for (int vb = 0; vb < VJ; ++vb) mxs[hh][vb] = -quad_max(mxs[hh][vb]) * qscale;
+      // p = 2^((s - max) * log2(e) / sqrt(d)): the score scale lives in the exponent argument
+#pragma unroll
+      for (int hh = 0; hh < HJ; ++hh)
+#pragma unroll
+        for (int vb = 0; vb < VJ; ++vb)
+#pragma unroll
+          for (int jb = 0; jb < NKB; ++jb)
+#pragma unroll
+            for (int j = 0; j < 4; ++j) {
+#ifdef FF_EXPERIMENT_NO_EXP
+              S[hh][vb][jb][j] = fmaf(S[hh][vb][jb][j], qscale, mxs[hh][vb]);
+#else
+              S[hh][vb][jb][j] = __builtin_amdgcn_exp2f(fmaf(S[hh][vb][jb][j], qscale, mxs[hh][vb]));
+#endif
+            }
+      // O^T[d][query] = sum over keys V^T[d][key] P^T[key][query], two key blocks per product.
+      // The row sums of P come from the matrix cores as well: an all-ones A operand makes every
+      // accumulator row the sum over keys of the (bf16-rounded) probabilities.
+      f32x4 O[HJ][VJ][NA], rowsum[HJ][VJ];
+#pragma unroll
+      for (int hh = 0; hh < HJ; ++hh) {
+        const int h = h0 + hh;
+#pragma unroll
+        for (int vb = 0; vb < VJ; ++vb) {
+          rowsum[hh][vb] = f32x4{0.f, 0.f, 0.f, 0.f};
+#pragma unroll
+          for (int a = 0; a < NA; ++a) O[hh][vb][a] = f32x4{0.f, 0.f, 0.f, 0.f};
+#pragma unroll
+          for (int jb = 0; jb + 1 < NKB; jb += 2) {
+            Frag8 p8;
+            p8.u[0] = pack2(S[hh][vb][jb][0], S[hh][vb][jb][1]); p8.u[1] = pack2(S[hh][vb][jb][2], S[hh][vb][jb][3]);
+            p8.u[2] = pack2(S[hh][vb][jb + 1][0], S[hh][vb][jb + 1][1]);
+            p8.u[3] = pack2(S[hh][vb][jb + 1][2], S[hh][vb][jb + 1][3]);
+#pragma unroll
+            for (int a = 0; a < NA; ++a) {
+              const int ab = DH == 16 ? h : a;
+              const Frag4 v0 = Vget(ab, jb), v1 = Vget(ab, jb + 1);
+              Frag8 v8;
+              v8.u[0] = v0.u[0]; v8.u[1] = v0.u[1]; v8.u[2] = v1.u[0]; v8.u[3] = v1.u[1];
+              O[hh][vb][a] = mfma32(v8, p8, O[hh][vb][a]);
+            }
+            Frag8 ones;
+            ones.u[0] = ones.u[1] = ones.u[2] = ones.u[3] = 0x3f803f80u;
+            rowsum[hh][vb] = mfma32(ones, p8, rowsum[hh][vb]);
+          }
+          if (NKB & 1) {
+            constexpr int jb = NKB - 1;
+            Frag4 p4, ones;
+            p4.u[0] = pack2(S[hh][vb][jb][0], S[hh][vb][jb][1]); p4.u[1] = pack2(S[hh][vb][jb][2], S[hh][vb][jb][3]);
+            ones.u[0] = ones.u[1] = 0x3f803f80u;
+#pragma unroll
+            for (int a = 0; a < NA; ++a) O[hh][vb][a] = mfma16(Vget(DH == 16 ? h : a, jb), p4, O[hh][vb][a]);
+            rowsum[hh][vb] = mfma16(ones, p4, rowsum[hh][vb]);
+          }
         }
-        const float inv = __builtin_amdgcn_rcpf(quad_sum(sum));
-        // O^T[d][query] = sum over keys V^T[d][key] P^T[key][query]; two key blocks per product
-        constexpr int NA = DH / 16;  // 16-blocks of head dims of this head
-        f32x4 O[NA];
+      }
 #pragma unroll
-        for (int a = 0; a < NA; ++a) O[a] = f32x4{0.f, 0.f, 0.f, 0.f};
+      for (int hh = 0; hh < HJ; ++hh) {
+        const int h = h0 + hh;
 #pragma unroll
-        for (int jb = 0; jb + 1 < NKB; jb += 2) {
-          Frag8 p8;
-          p8.u[0] = pack2(S[jb][0], S[jb][1]); p8.u[1] = pack2(S[jb][2], S[jb][3]);
-          p8.u[2] = pack2(S[jb + 1][0], S[jb + 1][1]); p8.u[3] = pack2(S[jb + 1][2], S[jb + 1][3]);
+        for (int vb = 0; vb < VJ; ++vb) {
+          const float inv = __builtin_amdgcn_rcpf(rowsum[hh][vb][0]);
 #pragma unroll
           for (int a = 0; a < NA; ++a) {
-            const int ab = DH == 16 ? h : a;
-            const Frag4 v0 = Vget(ab, jb), v1 = Vget(ab, jb + 1);
-            Frag8 v8;
-            v8.u[0] = v0.u[0]; v8.u[1] = v0.u[1]; v8.u[2] = v1.u[0]; v8.u[3] = v1.u[1];
-            O[a] = mfma32(v8, p8, O[a]);
+            const int slot = DH == 16 ? h : a;
+            Of[v0 + vb].u[slot * 2 + 0] = pack2(O[hh][vb][a][0] * inv, O[hh][vb][a][1] * inv);
+            Of[v0 + vb].u[slot * 2 + 1] = pack2(O[hh][vb][a][2] * inv, O[hh][vb][a][3] * inv);
           }
-        }
-        if (NKB & 1) {
-          constexpr int jb = NKB - 1;
-          Frag4 p4;
-          p4.u[0] = pack2(S[jb][0], S[jb][1]); p4.u[1] = pack2(S[jb][2], S[jb][3]);
-#pragma unroll
-          for (int a = 0; a < NA; ++a) O[a] = mfma16(Vget(DH == 16 ? h : a, jb), p4, O[a]);
-        }
-#pragma unroll
-        for (int a = 0; a < NA; ++a) {
-          const int slot = DH == 16 ? h : a;
-          Of[vb].u[slot * 2 + 0] = pack2(O[a][0] * inv, O[a][1] * inv);
-          Of[vb].u[slot * 2 + 1] = pack2(O[a][2] * inv, O[a][3] * inv);
         }
       }
     }
+    if (hp == 0) FF_TS(7);
     // output projection of this unit, accumulated into the residual stream
-#pragma unroll
-    for (int nb = 0; nb < NB; ++nb) {
-      Frag8 wf;
-      wf.q = rb[(2 * KB + nb) * 64];
+    frag_stream<NB, kPrefetch>(rb + 2 * KB * 64, [&](const Frag8& wf, int nb) {
 #pragma unroll
       for (int vb = 0; vb < NVB; ++vb) x1[vb][nb] = mfma32(wf, Of[vb], x1[vb][nb]);
-    }
+    });
+    if (hp == 0) FF_TS(8);
     advance();
+    if (hp == 0) FF_TS(9);
   }
+  FF_TS(10);
 
   // ---- FFN ------------------------------------------------------------------------------------------
   layer_norm(PO::LN2G, PO::LN2B);
   add_bias_rows(PO::B2);
+  FF_TS(11);
 #pragma unroll 1
   for (int fc = 0; fc < FC; ++fc) {
-    const u32x4* rb = ring + (cc & 1) * CH * 64 + lane;
+    const u32x4* rb = ring + (cc & 1) * CH * 64 + lane + (CHM == 2 ? (fc & 1) * 4 * KB * 64 : 0);
     Frag8 Hf[NVB];
-#pragma unroll
-    for (int a = 0; a < 2; ++a) {
+    {
       f32x4 acc[NVB];
+      frag_stream<2 * KB, kPrefetch>(rb, [&](const Frag8& wf, int f) {
+        const int a = f / KB, kb = f % KB;
+        if (kb == 0) {
+          const f32x4 b = *reinterpret_cast<const f32x4*>(par + PO::B1 + 32 * fc + 16 * a + 4 * q);
 #pragma unroll
-      for (int vb = 0; vb < NVB; ++vb) acc[vb] = f32x4{0.f, 0.f, 0.f, 0.f};
-#pragma unroll
-      for (int kb = 0; kb < KB; ++kb) {
-        Frag8 wf;
-        wf.q = rb[(a * KB + kb) * 64];
+          for (int vb = 0; vb < NVB; ++vb) acc[vb] = b;
+        }
 #pragma unroll
         for (int vb = 0; vb < NVB; ++vb) acc[vb] = mfma32(wf, act[vb][kb], acc[vb]);
-      }
-      const f32x4 b = *reinterpret_cast<const f32x4*>(par + PO::B1 + 32 * fc + 16 * a + 4 * q);
+        if (kb == KB - 1) {
 #pragma unroll
-      for (int vb = 0; vb < NVB; ++vb) {
-        Hf[vb].u[a * 2 + 0] = pack2(gelu_fast(acc[vb][0] + b[0]), gelu_fast(acc[vb][1] + b[1]));
-        Hf[vb].u[a * 2 + 1] = pack2(gelu_fast(acc[vb][2] + b[2]), gelu_fast(acc[vb][3] + b[3]));
-      }
+          for (int vb = 0; vb < NVB; ++vb) {
+            Hf[vb].u[a * 2 + 0] = pack2(gelu_fast(acc[vb][0]), gelu_fast(acc[vb][1]));
+            Hf[vb].u[a * 2 + 1] = pack2(gelu_fast(acc[vb][2]), gelu_fast(acc[vb][3]));
+          }
+        }
+      });
     }
-#pragma unroll
-    for (int nb = 0; nb < NB; ++nb) {
-      Frag8 wf;
-      wf.q = rb[(2 * KB + nb) * 64];
+    frag_stream<NB, kPrefetch>(rb + 2 * KB * 64, [&](const Frag8& wf, int nb) {
 #pragma unroll
       for (int vb = 0; vb < NVB; ++vb) x1[vb][nb] = mfma32(wf, Hf[vb], x1[vb][nb]);
-    }
-    if (fc + 1 < FC) advance();
+    });
+    if (fc == 0) FF_TS(12);
+    if (fc + 1 < FC && (CHM == 1 || (fc & 1))) advance();
+    if (fc == 0) FF_TS(13);
   }
+  FF_TS(14);
 
   // ---- scatter -------------------------------------------------------------------------------------
 #pragma unroll
@@ -505,15 +648,27 @@ __global__ __launch_bounds__(NW * 64, MINW) void k_layer_mfma(const uint16_t* __
       }
     }
   }
+  FF_TS(15);
+  FF_TS_DUMP;
 }
 
-template <int C, int DH, int F, int NVB, int WPG, int NW, int MINW>
+#ifdef FF_PROBE
+}  // namespace
+}  // namespace ff
+extern "C" int ff_debug_read_probe(long long* host_out) {
+  return (int)hipMemcpyFromSymbol(host_out, HIP_SYMBOL(ff_probe_ts_global), sizeof(long long) * 128);
+}
+namespace ff {
+namespace {
+#endif
+
+template <int C, int DH, int F, int NVB, int WPG, int NW, int MINW, int CHM>
 int launch_cfg(const void* feats, void* out, const int32_t* perm, const int32_t* goff, const int32_t* num_groups,
                int32_t max_groups, const u32x4* packed, const SmallParams& sp, float eps, bool out_f32,
                hipStream_t stream) {
   constexpr int GPW = NW / WPG;
   constexpr int NKB = NVB * WPG;
-  constexpr int CH = 4 * (C / 32);
+  constexpr int CH = 4 * (C / 32) * CHM;
   const size_t lds_bytes = (size_t)2 * CH * 1024 + (size_t)ParamOff<C, F>::TOTAL * 4 +
                            (WPG > 1 ? (size_t)GPW * 2 * 2 * NKB * 64 * 8 : 0);
   const unsigned blocks = (unsigned)((max_groups + GPW - 1) / GPW);
@@ -526,11 +681,11 @@ int launch_cfg(const void* feats, void* out, const int32_t* perm, const int32_t*
       attr_done = true;
     }
     hipLaunchKernelGGL(kern, dim3(blocks), dim3(NW * 64), lds_bytes, stream, (const uint16_t*)feats, out, perm, goff,
-                       num_groups, packed, sp, eps);
+                       num_groups, (int)max_groups, packed, sp, eps);
     return launch_status();
   };
-  if (out_f32) return go(k_layer_mfma<C, DH, F, NVB, WPG, NW, MINW, true>);
-  return go(k_layer_mfma<C, DH, F, NVB, WPG, NW, MINW, false>);
+  if (out_f32) return go(k_layer_mfma<C, DH, F, NVB, WPG, NW, MINW, CHM, true>);
+  return go(k_layer_mfma<C, DH, F, NVB, WPG, NW, MINW, CHM, false>);
 }
 
 }  // namespace
@@ -546,11 +701,21 @@ size_t layer_mfma_packed_bytes(const ff_layer_weights* w) {
   return (size_t)((C / 32) * frags_per_hp(C) + (F / 32) * frags_per_fc(C)) * 1024;
 }
 
-int layer_mfma_pack(const ff_layer_weights* w, void* packed, hipStream_t stream) {
+// Packs `count` layers of identical shape; layer l goes to packed + l * stride_bytes.
+int layer_mfma_pack(const ff_layer_weights* w, int count, void* packed, size_t stride_bytes, hipStream_t stream) {
   const int total = (int)(layer_mfma_packed_bytes(w) / 1024);
-  hipLaunchKernelGGL(k_pack_weights, dim3((unsigned)((total * 64 + 255) / 256)), dim3(256), 0, stream,
-                     (const uint16_t*)w->w_qkv, (const uint16_t*)w->w_o, (const uint16_t*)w->w1,
-                     (const uint16_t*)w->w2, w->C, w->F, (uint4*)packed, total);
+  for (int l0 = 0; l0 < count; l0 += kPackBatch) {
+    const int nl = count - l0 < kPackBatch ? count - l0 : kPackBatch;
+    PackBatch pb;
+    for (int l = 0; l < kPackBatch; ++l) {
+      const ff_layer_weights* wl = &w[l0 + (l < nl ? l : 0)];
+      pb.w_qkv[l] = (const uint16_t*)wl->w_qkv; pb.w_o[l] = (const uint16_t*)wl->w_o;
+      pb.w1[l] = (const uint16_t*)wl->w1; pb.w2[l] = (const uint16_t*)wl->w2;
+      pb.out[l] = (uint4*)((char*)packed + (size_t)(l0 + (l < nl ? l : 0)) * stride_bytes);
+    }
+    hipLaunchKernelGGL(k_pack_weights, dim3((unsigned)((total * 64 + 255) / 256), (unsigned)nl), dim3(256), 0, stream,
+                       pb, w->C, w->F, total);
+  }
   return launch_status();
 }
 
@@ -565,17 +730,23 @@ int layer_mfma_launch(const void* feats, void* out, int64_t n, const int32_t* pe
                  (const uint16_t*)w->b1,    (const uint16_t*)w->b2};
   const u32x4* pk = (const u32x4*)packed;
   const int C = w->C, F = w->F, d = C / w->heads;
-#define FF_GO(NVB, WPG, NW, MINW) \
-  return launch_cfg<128, 16, 256, NVB, WPG, NW, MINW>(feats, out, perm, group_offsets, num_groups, max_groups, pk, sp, \
-                                                      w->ln_eps, out_f32, stream)
+#define FF_GO(NVB, WPG, NW, MINW, CHM) \
+  return launch_cfg<128, 16, 256, NVB, WPG, NW, MINW, CHM>(feats, out, perm, group_offsets, num_groups, max_groups, pk, \
+                                                           sp, w->ln_eps, out_f32, stream)
   if (C == 128 && d == 16 && F == 256) {
-    if (variant == 0) variant = G <= 32 ? 1 : G <= 64 ? 2 : 4;
+    // Few groups (about one workgroup per compute unit or less): latency matters, use the big
+    // weight chunks (fewer barriers, one workgroup per CU).  Many groups: two workgroups per CU.
+    const bool few = max_groups <= 1024;
+    if (variant == 0) variant = G <= 32 ? 1 : G <= 64 ? (few ? 6 : 2) : 4;
     switch (variant) {
-      case 1: if (G <= 32) FF_GO(2, 1, 4, 2); break;    // 32 slots, one wave per group
-      case 2: if (G <= 64) FF_GO(2, 2, 4, 2); break;    // 64 slots, two waves per group
-      case 3: if (G <= 64) FF_GO(4, 1, 4, 1); break;    // 64 slots, one wave per group
-      case 4: if (G <= 128) FF_GO(2, 4, 4, 2); break;   // 128 slots, four waves per group
-      case 5: if (G <= 128) FF_GO(4, 2, 4, 1); break;   // 128 slots, two waves per group
+      case 1: if (G <= 32) FF_GO(2, 1, 4, 2, 1); break;    // 32 slots, one wave per group
+      case 2: if (G <= 64) FF_GO(2, 2, 4, 2, 1); break;    // 64 slots, two waves per group
+      case 3: if (G <= 64) FF_GO(4, 1, 4, 1, 1); break;    // 64 slots, one wave per group
+      case 4: if (G <= 128) FF_GO(2, 4, 4, 2, 1); break;   // 128 slots, four waves per group
+      case 5: if (G <= 128) FF_GO(4, 2, 4, 1, 1); break;   // 128 slots, two waves per group
+      case 6: if (G <= 64) FF_GO(2, 2, 4, 2, 2); break;    // as 2, 32 KB weight chunks
+      case 7: if (G <= 64) FF_GO(1, 4, 4, 2, 1); break;    // 64 slots, four waves per group
+      case 8: if (G <= 64) FF_GO(1, 4, 4, 2, 2); break;    // as 7, 32 KB weight chunks
       default: break;
     }
   }

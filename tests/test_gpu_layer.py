@@ -29,7 +29,7 @@ def _run_layer(c, feats, params, axis, shift, flags=0, G=None):
     dt = dtype_of(c)
     perm, off, ng, _, dev = gpu_flatten(c["coords"][:feats.shape[0]], g, axis, shift, G, want_keys=False)
     lw = ff.LayerWeights(params, dt, DEV)
-    out = ff.ff_group_attention(to_dev_feats(feats, dt), dev[0], dev[1], dev[2], len(off) - 1 + c["B"], lw, G, dt, flags)
+    out = ff.ff_group_attention(to_dev_feats(feats, dt), dev[0], dev[1], dev[2], -(-feats.shape[0] // G) + c["B"], lw, G, dt, flags)
     torch.cuda.synchronize()
     return to_host(out), perm, off
 
@@ -162,7 +162,7 @@ def test_bf16_group_sizes_and_tails(cfg, G):
     assert np.abs(plain - want).max() <= 2e-2
     assert torch.equal(packed, narrow)                      # pre-packed weights change nothing
     # every wave-to-group mapping that can hold G
-    for variant, slots in [(1, 32), (2, 64), (3, 64), (4, 128), (5, 128)]:
+    for variant, slots in [(1, 32), (2, 64), (3, 64), (4, 128), (5, 128), (6, 64), (7, 64), (8, 64)]:
         fl = ff.FF_FLAG_OUT_F32 | ff.FF_FLAG_VARIANT(variant)
         if G > slots:
             with pytest.raises(ff.FlatformerError):
