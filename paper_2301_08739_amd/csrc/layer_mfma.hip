@@ -86,9 +86,6 @@ __device__ __forceinline__ f32x4 mfma16(const Frag4& a, const Frag4& b, f32x4 c)
 //   GELU(v) = max(v, 0) - 0.5 * t * exp(-(a t + b t^2 + c t^3)),   max abs error 8.6e-5.
 // One transcendental per element.
 __device__ __forceinline__ float gelu_fast(float v) {
-#ifdef FF_EXPERIMENT_NO_GELU
-  return v;
-#endif
   constexpr float L2E = 1.44269504088896340736f;
   const float t = fabsf(v);
   float p = fmaf(t, -0.01916250660946074f * L2E, -0.33840941696965965f * L2E);
@@ -130,11 +127,7 @@ __device__ __forceinline__ void frag_stream(const u32x4* rb, Fn&& use) {
   for (int f = 0; f < N; ++f) {
     const Frag8 cur = buf[f % PF];
     __builtin_amdgcn_sched_barrier(0);
-#ifdef FF_EXPERIMENT_NO_FRAGREAD
-    if (f + PF < N) buf[f % PF].q = buf[(f + 1) % PF].q + u32x4{1, 2, 3, 4};
-#else
     if (f + PF < N) buf[f % PF].q = rb[(f + PF) * 64];
-#endif
     __builtin_amdgcn_sched_barrier(0);
     use(cur, f);
   }
@@ -211,7 +204,7 @@ struct ParamOff {  // float offsets inside the small-parameter area
                        LN2B = 7 * C, B2 = 8 * C, B1 = 9 * C, TOTAL = 9 * C + F;
 };
 
-template <int C, int DH, int F, int NVB, int WPG, int NW, int MINW, int CHM, bool OUT_F32>
+template <int C, int DH, int F, int NVB, int WPG, int NW, int MINW, bool OUT_F32>
 __global__ __launch_bounds__(NW * 64, MINW) void k_layer_mfma(const uint16_t* __restrict__ feats, void* __restrict__ out,
                                                                const int32_t* __restrict__ perm,
                                                                const int32_t* __restrict__ goff,
@@ -223,18 +216,17 @@ __global__ __launch_bounds__(NW * 64, MINW) void k_layer_mfma(const uint16_t* __
   constexpr int FC = F / 32;          // 32-wide hidden units
   constexpr int NKB = NVB * WPG;      // key blocks of a group
   constexpr int NT = NW * 64;
-  constexpr int CH = 4 * KB * CHM;    // fragments per staged chunk; a 4*KB piece is {Q,K} | {V,W_o} | {W1,W2}
-  constexpr int STG = CH * 64 / NT;   // 16-byte pieces per thread per chunk
-  constexpr int NCHUNK = (2 * HP + FC) / CHM;
-  static_assert(CHM == 1 || CHM == 2, "chunk multiplier");
-  static_assert((2 * HP + FC) % CHM == 0 && FC % CHM == 0, "chunking");
+  constexpr int CH = 4 * KB;          // fragments per staged chunk: {Q,K} | {V,W_o} | {W1,W2} of one unit
+  constexpr int RING = 3;             // LDS slots: chunks cc and cc+1 resident, cc+2 in flight
+  constexpr int FPW = CH / NW;        // fragments each wavefront copies per chunk
+  constexpr int NCHUNK = 2 * HP + FC;
+  static_assert(CH % NW == 0, "staging");
   using PO = ParamOff<C, F>;
   static_assert(DH == 16 || DH == 32, "head dim");
-  static_assert((CH * 64) % NT == 0, "staging");
 
   extern __shared__ u32x4 lds[];
-  u32x4* ring = lds;                                            // [2][CH * 64]
-  float* par = reinterpret_cast<float*>(lds + 2 * CH * 64);     // [PO::TOTAL]
+  u32x4* ring = lds;                                            // [RING][CH * 64]
+  float* par = reinterpret_cast<float*>(lds + RING * CH * 64);  // [PO::TOTAL]
   u32x2* kvx = reinterpret_cast<u32x2*>(par + PO::TOTAL);       // K/V exchange, only when WPG > 1
 
   const int tid = threadIdx.x, lane = tid & 63, w = tid >> 6, i = lane & 15, q = lane >> 4;
@@ -248,41 +240,31 @@ __global__ __launch_bounds__(NW * 64, MINW) void k_layer_mfma(const uint16_t* __
   if (g < *num_groups) { start = off0; m = off1 - off0; }
 
   FF_TS_DECL
-  u32x4 stg[STG];
   int cc = 0;  // chunk being consumed
+  const int wu = __builtin_amdgcn_readfirstlane(w);
+  // Asynchronous copy of one chunk of the packed weight stream, global memory -> LDS, 1 KB per
+  // instruction and no registers in between (lane l's 16 bytes land at slot base + 16 l).
   auto issue = [&](int chunk) {
     if (chunk < NCHUNK) {
 #pragma unroll
-      for (int s = 0; s < STG; ++s) stg[s] = packed[(size_t)chunk * CH * 64 + s * NT + tid];
+      for (int s = 0; s < FPW; ++s) {
+        const int f = s * NW + wu;
+        __builtin_amdgcn_global_load_lds(
+            (const __attribute__((address_space(1))) void*)(packed + ((size_t)chunk * CH + f) * 64 + lane),
+            (__attribute__((address_space(3))) void*)(ring + ((chunk % RING) * CH + f) * 64), 16, 0, 0);
+      }
     }
   };
-  auto commit = [&](int chunk) {
-    if (chunk < NCHUNK) {
-#pragma unroll
-      for (int s = 0; s < STG; ++s) ring[(chunk & 1) * CH * 64 + s * NT + tid] = stg[s];
-    }
-  };
-  auto advance = [&]() {  // done with chunk cc: publish cc+1, start fetching cc+2
-#ifdef FF_EXPERIMENT_NO_STAGING
-    return;
-#endif
-#ifdef FF_PROBE
-    if (cc == 2) FF_TS(20);
-    if (cc == 2) { asm volatile("s_waitcnt vmcnt(0)" ::: "memory"); FF_TS(21); }
-#endif
-    commit(cc + 1);
-#ifdef FF_PROBE
-    if (cc == 2) FF_TS(22);
-#endif
-    __syncthreads();
-#ifdef FF_PROBE
-    if (cc == 2) FF_TS(23);
-#endif
+  auto slot = [&](int chunk) -> const u32x4* { return ring + (chunk % RING) * CH * 64 + lane; };
+  auto advance = [&]() {  // done with chunk cc
+    asm volatile("s_waitcnt vmcnt(0)" ::: "memory");  // my share of chunk cc+2 has landed
+    __syncthreads();                                  // everyone's has, and everyone is done with chunk cc
     ++cc;
-    issue(cc + 1);
+    issue(cc + 2);                                    // into the slot that chunk cc-1 occupied
   };
   FF_TS(0);
   issue(0);
+  issue(1);
 
   // small parameters -> LDS as fp32
   for (int t = tid; t < PO::TOTAL; t += NT) {
@@ -315,9 +297,9 @@ __global__ __launch_bounds__(NW * 64, MINW) void k_layer_mfma(const uint16_t* __
     }
   }
   FF_TS(1);
-  commit(0);
-  __syncthreads();
-  issue(1);
+  asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
+  __syncthreads();  // chunks 0 and 1 and the small parameters are in LDS
+  issue(2);
   FF_TS(2);
 
   Frag8 act[NVB][KB];  // normalised activations as B operands (LN1 output, later LN2 output)
@@ -368,7 +350,7 @@ __global__ __launch_bounds__(NW * 64, MINW) void k_layer_mfma(const uint16_t* __
   // ---- attention: one 32-wide head-dim unit per iteration (two heads of 16 or one head of 32) --------
 #pragma unroll 1
   for (int hp = 0; hp < HP; ++hp) {
-    const u32x4* rb = ring + (cc & 1) * CH * 64 + lane;
+    const u32x4* rb = slot(cc);
     Frag4 Qf[2][NVB], Kf[2][NVB], Vf[2][NVB];  // bf16 fragments of my pillars, index [16-block a][vb]
 
     // Q and K rows: D[feature][pillar]; fragment f = (q|k, 16-block a, k-block kb)
@@ -394,12 +376,8 @@ __global__ __launch_bounds__(NW * 64, MINW) void k_layer_mfma(const uint16_t* __
       });
     }
     if (hp == 0) FF_TS(4);
-    if (CHM == 1) {
-      advance();
-      rb = ring + (cc & 1) * CH * 64 + lane;
-    } else {
-      rb += 4 * KB * 64;
-    }
+    advance();
+    rb = slot(cc);
     if (hp == 0) FF_TS(5);
     // V rows with the operand roles swapped: D[pillar][feature]
     {
@@ -520,11 +498,7 @@ __global__ __launch_bounds__(NW * 64, MINW) void k_layer_mfma(const uint16_t* __
           for (int jb = 0; jb < NKB; ++jb)
 #pragma unroll
             for (int j = 0; j < 4; ++j) {
-#ifdef FF_EXPERIMENT_NO_EXP
-              S[hh][vb][jb][j] = fmaf(S[hh][vb][jb][j], qscale, mxs[hh][vb]);
-#else
               S[hh][vb][jb][j] = __builtin_amdgcn_exp2f(fmaf(S[hh][vb][jb][j], qscale, mxs[hh][vb]));
-#endif
             }
       // O^T[d][query] = sum over keys V^T[d][key] P^T[key][query], two key blocks per product.
       // The row sums of P come from the matrix cores as well: an all-ones A operand makes every
@@ -600,7 +574,7 @@ __global__ __launch_bounds__(NW * 64, MINW) void k_layer_mfma(const uint16_t* __
   FF_TS(11);
 #pragma unroll 1
   for (int fc = 0; fc < FC; ++fc) {
-    const u32x4* rb = ring + (cc & 1) * CH * 64 + lane + (CHM == 2 ? (fc & 1) * 4 * KB * 64 : 0);
+    const u32x4* rb = slot(cc);
     Frag8 Hf[NVB];
     {
       f32x4 acc[NVB];
@@ -627,7 +601,7 @@ __global__ __launch_bounds__(NW * 64, MINW) void k_layer_mfma(const uint16_t* __
       for (int vb = 0; vb < NVB; ++vb) x1[vb][nb] = mfma32(wf, Hf[vb], x1[vb][nb]);
     });
     if (fc == 0) FF_TS(12);
-    if (fc + 1 < FC && (CHM == 1 || (fc & 1))) advance();
+    if (fc + 1 < FC) advance();
     if (fc == 0) FF_TS(13);
   }
   FF_TS(14);
@@ -662,14 +636,14 @@ namespace ff {
 namespace {
 #endif
 
-template <int C, int DH, int F, int NVB, int WPG, int NW, int MINW, int CHM>
+template <int C, int DH, int F, int NVB, int WPG, int NW, int MINW>
 int launch_cfg(const void* feats, void* out, const int32_t* perm, const int32_t* goff, const int32_t* num_groups,
                int32_t max_groups, const u32x4* packed, const SmallParams& sp, float eps, bool out_f32,
                hipStream_t stream) {
   constexpr int GPW = NW / WPG;
   constexpr int NKB = NVB * WPG;
-  constexpr int CH = 4 * (C / 32) * CHM;
-  const size_t lds_bytes = (size_t)2 * CH * 1024 + (size_t)ParamOff<C, F>::TOTAL * 4 +
+  constexpr int CH = 4 * (C / 32);
+  const size_t lds_bytes = (size_t)3 * CH * 1024 + (size_t)ParamOff<C, F>::TOTAL * 4 +
                            (WPG > 1 ? (size_t)GPW * 2 * 2 * NKB * 64 * 8 : 0);
   const unsigned blocks = (unsigned)((max_groups + GPW - 1) / GPW);
   auto go = [&](auto kern) -> int {
@@ -684,8 +658,8 @@ int launch_cfg(const void* feats, void* out, const int32_t* perm, const int32_t*
                        num_groups, (int)max_groups, packed, sp, eps);
     return launch_status();
   };
-  if (out_f32) return go(k_layer_mfma<C, DH, F, NVB, WPG, NW, MINW, CHM, true>);
-  return go(k_layer_mfma<C, DH, F, NVB, WPG, NW, MINW, CHM, false>);
+  if (out_f32) return go(k_layer_mfma<C, DH, F, NVB, WPG, NW, MINW, true>);
+  return go(k_layer_mfma<C, DH, F, NVB, WPG, NW, MINW, false>);
 }
 
 }  // namespace
@@ -730,23 +704,22 @@ int layer_mfma_launch(const void* feats, void* out, int64_t n, const int32_t* pe
                  (const uint16_t*)w->b1,    (const uint16_t*)w->b2};
   const u32x4* pk = (const u32x4*)packed;
   const int C = w->C, F = w->F, d = C / w->heads;
-#define FF_GO(NVB, WPG, NW, MINW, CHM) \
-  return launch_cfg<128, 16, 256, NVB, WPG, NW, MINW, CHM>(feats, out, perm, group_offsets, num_groups, max_groups, pk, \
-                                                           sp, w->ln_eps, out_f32, stream)
+#define FF_GO(NVB, WPG, NW, MINW) \
+  return launch_cfg<128, 16, 256, NVB, WPG, NW, MINW>(feats, out, perm, group_offsets, num_groups, max_groups, pk, sp, \
+                                                      w->ln_eps, out_f32, stream)
   if (C == 128 && d == 16 && F == 256) {
-    // Few groups (about one workgroup per compute unit or less): latency matters, use the big
-    // weight chunks (fewer barriers, one workgroup per CU).  Many groups: two workgroups per CU.
-    const bool few = max_groups <= 1024;
-    if (variant == 0) variant = G <= 32 ? 1 : G <= 64 ? (few ? 6 : 2) : 4;
+    if (variant == 0) variant = G <= 32 ? 10 : G <= 64 ? 7 : 9;
     switch (variant) {
-      case 1: if (G <= 32) FF_GO(2, 1, 4, 2, 1); break;    // 32 slots, one wave per group
-      case 2: if (G <= 64) FF_GO(2, 2, 4, 2, 1); break;    // 64 slots, two waves per group
-      case 3: if (G <= 64) FF_GO(4, 1, 4, 1, 1); break;    // 64 slots, one wave per group
-      case 4: if (G <= 128) FF_GO(2, 4, 4, 2, 1); break;   // 128 slots, four waves per group
-      case 5: if (G <= 128) FF_GO(4, 2, 4, 1, 1); break;   // 128 slots, two waves per group
-      case 6: if (G <= 64) FF_GO(2, 2, 4, 2, 2); break;    // as 2, 32 KB weight chunks
-      case 7: if (G <= 64) FF_GO(1, 4, 4, 2, 1); break;    // 64 slots, four waves per group
-      case 8: if (G <= 64) FF_GO(1, 4, 4, 2, 2); break;    // as 7, 32 KB weight chunks
+      case 1: if (G <= 32) FF_GO(2, 1, 4, 2); break;    // 32 slots, one wave per group
+      case 2: if (G <= 64) FF_GO(2, 2, 4, 2); break;    // 64 slots, two waves per group
+      case 3: if (G <= 64) FF_GO(4, 1, 4, 1); break;    // 64 slots, one wave per group
+      case 4: if (G <= 128) FF_GO(2, 4, 4, 2); break;   // 128 slots, four waves per group
+      case 5: if (G <= 128) FF_GO(4, 2, 4, 1); break;   // 128 slots, two waves per group
+      case 6: if (G <= 64) FF_GO(1, 4, 4, 2); break;    // 64 slots, four waves per group
+      case 7: if (G <= 64) FF_GO(1, 4, 8, 4); break;    // as 6, two groups per workgroup, four waves per SIMD
+      case 8: if (G <= 64) FF_GO(2, 2, 8, 2); break;    // as 2, four groups per workgroup
+      case 9: if (G <= 128) FF_GO(1, 8, 8, 4); break;   // 128 slots, eight waves per group
+      case 10: if (G <= 32) FF_GO(1, 2, 8, 4); break;   // 32 slots, two waves per group, four groups per workgroup
       default: break;
     }
   }
