@@ -218,9 +218,7 @@ __global__ __launch_bounds__(NW * 64, MINW) void k_layer_mfma(const uint16_t* __
   constexpr int NT = NW * 64;
   constexpr int CH = 4 * KB;          // fragments per staged chunk: {Q,K} | {V,W_o} | {W1,W2} of one unit
   constexpr int RING = 3;             // LDS slots: chunks cc and cc+1 resident, cc+2 in flight
-  constexpr int FPW = CH / NW;        // fragments each wavefront copies per chunk
   constexpr int NCHUNK = 2 * HP + FC;
-  static_assert(CH % NW == 0, "staging");
   using PO = ParamOff<C, F>;
   static_assert(DH == 16 || DH == 32, "head dim");
 
@@ -246,9 +244,7 @@ __global__ __launch_bounds__(NW * 64, MINW) void k_layer_mfma(const uint16_t* __
   // instruction and no registers in between (lane l's 16 bytes land at slot base + 16 l).
   auto issue = [&](int chunk) {
     if (chunk < NCHUNK) {
-#pragma unroll
-      for (int s = 0; s < FPW; ++s) {
-        const int f = s * NW + wu;
+      for (int f = wu; f < CH; f += NW) {  // wave-uniform trip count
         __builtin_amdgcn_global_load_lds(
             (const __attribute__((address_space(1))) void*)(packed + ((size_t)chunk * CH + f) * 64 + lane),
             (__attribute__((address_space(3))) void*)(ring + ((chunk % RING) * CH + f) * 64), 16, 0, 0);
@@ -664,11 +660,15 @@ int launch_cfg(const void* feats, void* out, const int32_t* perm, const int32_t*
 
 }  // namespace
 
-bool layer_mfma_supported(const ff_layer_weights* w, int G) {
+// Shapes with a fused kernel: (C, head dim, F) = (128, 16, 256) and (256, 32, 512), G <= 128.
+static int shape_id(const ff_layer_weights* w) {
   const int C = w->C, F = w->F, d = C / w->heads;
-  if (C == 128 && d == 16 && F == 256) return G <= 128;
-  return false;
+  if (C == 128 && d == 16 && F == 256) return 1;
+  if (C == 256 && d == 32 && F == 512) return 2;
+  return 0;
 }
+
+bool layer_mfma_supported(const ff_layer_weights* w, int G) { return shape_id(w) != 0 && G <= 128; }
 
 size_t layer_mfma_packed_bytes(const ff_layer_weights* w) {
   const int C = w->C, F = w->F;
@@ -703,23 +703,33 @@ int layer_mfma_launch(const void* feats, void* out, int64_t n, const int32_t* pe
                  (const uint16_t*)w->b_o,   (const uint16_t*)w->ln2_g, (const uint16_t*)w->ln2_b,
                  (const uint16_t*)w->b1,    (const uint16_t*)w->b2};
   const u32x4* pk = (const u32x4*)packed;
-  const int C = w->C, F = w->F, d = C / w->heads;
-#define FF_GO(NVB, WPG, NW, MINW) \
-  return launch_cfg<128, 16, 256, NVB, WPG, NW, MINW>(feats, out, perm, group_offsets, num_groups, max_groups, pk, sp, \
-                                                      w->ln_eps, out_f32, stream)
-  if (C == 128 && d == 16 && F == 256) {
+#define FF_GO(C, DH, F, NVB, WPG, NW, MINW) \
+  return launch_cfg<C, DH, F, NVB, WPG, NW, MINW>(feats, out, perm, group_offsets, num_groups, max_groups, pk, sp, \
+                                                  w->ln_eps, out_f32, stream)
+  const int shape = shape_id(w);
+  if (shape == 1) {
     if (variant == 0) variant = G <= 32 ? 10 : G <= 64 ? 7 : 9;
+    switch (variant) {  // (pillar blocks per wave, waves per group, waves per workgroup, min waves per SIMD)
+      case 1: if (G <= 32) FF_GO(128, 16, 256, 2, 1, 4, 2); break;
+      case 2: if (G <= 64) FF_GO(128, 16, 256, 2, 2, 4, 2); break;
+      case 3: if (G <= 64) FF_GO(128, 16, 256, 4, 1, 4, 1); break;
+      case 4: if (G <= 128) FF_GO(128, 16, 256, 2, 4, 4, 2); break;
+      case 5: if (G <= 128) FF_GO(128, 16, 256, 4, 2, 4, 1); break;
+      case 6: if (G <= 64) FF_GO(128, 16, 256, 1, 4, 4, 2); break;
+      case 7: if (G <= 64) FF_GO(128, 16, 256, 1, 4, 8, 4); break;
+      case 8: if (G <= 64) FF_GO(128, 16, 256, 2, 2, 8, 2); break;
+      case 9: if (G <= 128) FF_GO(128, 16, 256, 1, 8, 8, 4); break;
+      case 10: if (G <= 32) FF_GO(128, 16, 256, 1, 2, 8, 4); break;
+      default: break;
+    }
+  } else if (shape == 2) {
+    if (variant == 0) variant = G <= 32 ? 1 : G <= 64 ? 2 : G <= 80 ? 3 : 4;
     switch (variant) {
-      case 1: if (G <= 32) FF_GO(2, 1, 4, 2); break;    // 32 slots, one wave per group
-      case 2: if (G <= 64) FF_GO(2, 2, 4, 2); break;    // 64 slots, two waves per group
-      case 3: if (G <= 64) FF_GO(4, 1, 4, 1); break;    // 64 slots, one wave per group
-      case 4: if (G <= 128) FF_GO(2, 4, 4, 2); break;   // 128 slots, four waves per group
-      case 5: if (G <= 128) FF_GO(4, 2, 4, 1); break;   // 128 slots, two waves per group
-      case 6: if (G <= 64) FF_GO(1, 4, 4, 2); break;    // 64 slots, four waves per group
-      case 7: if (G <= 64) FF_GO(1, 4, 8, 4); break;    // as 6, two groups per workgroup, four waves per SIMD
-      case 8: if (G <= 64) FF_GO(2, 2, 8, 2); break;    // as 2, four groups per workgroup
-      case 9: if (G <= 128) FF_GO(1, 8, 8, 4); break;   // 128 slots, eight waves per group
-      case 10: if (G <= 32) FF_GO(1, 2, 8, 4); break;   // 32 slots, two waves per group, four groups per workgroup
+      case 1: if (G <= 32) FF_GO(256, 32, 512, 1, 2, 8, 2); break;
+      case 2: if (G <= 64) FF_GO(256, 32, 512, 1, 4, 8, 2); break;
+      case 3: if (G <= 80) FF_GO(256, 32, 512, 1, 5, 10, 2); break;
+      case 4: if (G <= 128) FF_GO(256, 32, 512, 1, 8, 8, 2); break;
+      case 5: if (G <= 64) FF_GO(256, 32, 512, 2, 2, 4, 1); break;
       default: break;
     }
   }

@@ -173,3 +173,32 @@ def test_bf16_group_sizes_and_tails(cfg, G):
         assert np.abs(v - want).max() <= 2e-2, (variant, np.abs(v - want).max())
     print(f"G={G}: fused f32-store err {ew:.3e}, bf16-store err {en:.3e}, plain kernels err "
           f"{np.abs(plain - want).max():.3e}", flush=True)
+
+
+@pytest.mark.parametrize("G", [5, 32, 64, 69, 80, 100, 128])
+def test_bf16_wide_layer_group_sizes(cfg, G):
+    """The C = 256, head dim 32, F = 512 instantiation (config 5's layer) on a small cloud with a
+    short last group, every mapping that can hold G, full oracle comparison."""
+    c = dict(cfg(5, 1))
+    n = 1003
+    c["coords"], feats = c["coords"][:n], c["feats"][:n]
+    p = c["layer_params"][0]
+    g, og = geoms(c)
+    perm, off, ng, _, dev = gpu_flatten(c["coords"], g, 0, 1, G, want_keys=False)
+    want = oracle.layer(feats, perm, off, p)
+    lw = ff.LayerWeights(p, ff.FF_BF16, DEV).pack()
+    x = to_dev_feats(feats, ff.FF_BF16)
+    mg = -(-n // G) + c["B"]
+    wide = to_host(ff.ff_group_attention(x, dev[0], dev[1], dev[2], mg, lw, G, ff.FF_BF16, ff.FF_FLAG_OUT_F32))
+    narrow = to_host(ff.ff_group_attention(x, dev[0], dev[1], dev[2], mg, lw, G, ff.FF_BF16, 0))
+    ew, en = _assert_bf16_bar(wide, narrow, want)
+    print(f"C=256 G={G}: f32-store err {ew:.3e}, bf16-store err {en:.3e}", flush=True)
+    for variant, slots in [(1, 32), (2, 64), (3, 80), (4, 128), (5, 64)]:
+        fl = ff.FF_FLAG_OUT_F32 | ff.FF_FLAG_VARIANT(variant)
+        if G > slots:
+            with pytest.raises(ff.FlatformerError):
+                ff.ff_group_attention(x, dev[0], dev[1], dev[2], mg, lw, G, ff.FF_BF16, fl)
+            continue
+        print(f"C=256 G={G} variant {variant}", flush=True)
+        v = to_host(ff.ff_group_attention(x, dev[0], dev[1], dev[2], mg, lw, G, ff.FF_BF16, fl))
+        assert np.abs(v - want).max() <= 2e-2, (variant, np.abs(v - want).max())
