@@ -21,6 +21,10 @@ PEAK_HBM_GBS = 8000.0          # MI355X HBM3E
 PEAK_BF16_TFLOPS = 2500.0      # dense bf16 MFMA
 PEAK_F32_TFLOPS = 157.3        # fp32 vector / MFMA
 
+# HBM bytes per launch of the fused layer kernel, from rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE scaled by
+# a plain copy of known size (profiles/fwa_layer_cfg2_hbm_counters.txt): config id -> bytes.
+MEASURED_LAYER_TRAFFIC = {2: 17355 * 1024}
+
 
 def layer_flops_per_voxel(C, F, G):
     # QKV 6C^2 + QK^T 2GC + PV 2GC + out-proj 2C^2 + FFN 4CF (multiply-add = 2 flops)
@@ -83,6 +87,8 @@ def main():
     ap.add_argument("--sweep", action="store_true",
                     help="also time flatten / gather / scatter / layer on batches of frames (JSON lines on stderr)")
     ap.add_argument("--variant", type=int, default=0, help="wave-to-group mapping of the fused layer kernel (0 = auto)")
+    ap.add_argument("--copy-calibration", action="store_true",
+                    help="also launch one plain 256 MiB device copy (reference for scaling rocprofv3 byte counters)")
     a = ap.parse_args()
     if a.gpus != 1:
         print("bench.py measures one GPU: this build has no multi-GPU path (run with --gpus 1)", file=sys.stderr)
@@ -129,9 +135,13 @@ def main():
     ms_gather, _ = time_region(lambda: ff.ff_gather(feats, perm, dt, out=gth), reps, 5)
     ms_scatter, _ = time_region(lambda: ff.ff_scatter(gth, perm, dt, out=out), reps, 5)
 
+    if a.copy_calibration:
+        src = torch.empty(256 << 20, dtype=torch.uint8, device=dev)
+        dst = torch.empty_like(src)
+        dst.copy_(src)
+        torch.cuda.synchronize()
+
     flops_layer = layer_flops_per_voxel(C, F, G) * n
-    passes = -(-max(1, sum(int(np.ceil(np.log2(max(v, 2)))) for v in (
-        c["B"] if c["B"] > 1 else 1,)) + 0) // 8)  # placeholder, replaced below
     # live key bits -> radix passes (8 bits each), shifted geometry
     def bits(v):
         return int(v - 1).bit_length() if v > 1 else 0
@@ -155,7 +165,8 @@ def main():
                                f"{len(dict.fromkeys(c['schedule']))} sorts + {L} layers per step"},
         "roofline": {"bound": "mfma", "kernel": "group attention layer (ff_group_attention, one launch)",
                      "achieved": ach_tf, "peak": peak_tf, "unit": "TFLOP/s", "frac": ach_tf / peak_tf,
-                     "traffic": None, "ms": ms_layer, "flops": flops_layer},
+                     "traffic": MEASURED_LAYER_TRAFFIC.get(a.config) if a.variant == 0 else None,
+                     "algorithmic_bytes": bytes_rows, "ms": ms_layer, "flops": flops_layer},
         "parts": {
             "flatten": {"ms": ms_flat, "bytes": bytes_flat, "GBps": bytes_flat / (ms_flat * 1e-3) / 1e9,
                         "frac_hbm": bytes_flat / (ms_flat * 1e-3) / 1e9 / PEAK_HBM_GBS, "radix_passes_credited": passes},
