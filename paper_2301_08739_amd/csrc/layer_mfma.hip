@@ -18,8 +18,12 @@
 // exactly the A operand P*V needs.  LayerNorm statistics and the softmax need only a reduction
 // over the four lanes that share a pillar.
 //
-// Weights reach the matrix cores through LDS: the packed stream is consumed in 32 KB chunks by
-// all wavefronts of the workgroup in lockstep, double buffered (one barrier per chunk).
+// Weights reach the matrix cores through LDS.  The packed stream is cut into 16 KB chunks that the
+// workgroup copies asynchronously (global memory -> LDS, no registers) into a ring of as many slots
+// as the LDS holds; slots are refilled only at workgroup barriers (one per head-dim unit, where the
+// group's K and V are exchanged anyway, and a few in the FFN).  Every wavefront reads the fragments
+// in stream order through a window of 8 fragments in registers, requested 8 products ahead of
+// their use, so that LDS latency is hidden behind the matrix cores.
 #include "common.h"
 
 #ifdef FF_PROBE
@@ -83,15 +87,16 @@ __device__ __forceinline__ f32x4 mfma16(const Frag4& a, const Frag4& b, f32x4 c)
 }
 // GELU(v) = v * Phi(v) with the upper tail 1 - Phi(t) ~ 0.5 * exp(-(a t + b t^2 + c t^3)), t = |v|
 // (coefficients fitted to the erf form; all positive, so the exponent is monotone for any t):
-//   GELU(v) = max(v, 0) - 0.5 * t * exp(-(a t + b t^2 + c t^3)),   max abs error 8.6e-5.
-// One transcendental per element.
-__device__ __forceinline__ float gelu_fast(float v) {
+//   GELU(v) = max(v, 0) - 0.5 t e = 0.5 (v + t (1 - e)),   e = exp(-(a t + b t^2 + c t^3)),
+// max abs error 8.6e-5.  This returns 2 GELU(v); the factor 0.5 is folded into the packed W2
+// (exact in bf16).  Five vector operations and one transcendental per element.
+__device__ __forceinline__ float gelu2_fast(float v) {
   constexpr float L2E = 1.44269504088896340736f;
   const float t = fabsf(v);
   float p = fmaf(t, -0.01916250660946074f * L2E, -0.33840941696965965f * L2E);
   p = fmaf(t, p, -0.7908370960657618f * L2E);
   const float e = __builtin_amdgcn_exp2f(p * t);
-  return fmaf(-0.5f * t, e, fmaxf(v, 0.0f));
+  return v + fmaf(-t, e, t);
 }
 
 #ifdef FF_PROBE
@@ -114,25 +119,6 @@ __device__ __forceinline__ float gelu_fast(float v) {
 #define FF_TS_DECL
 #define FF_TS_DUMP do { } while (0)
 #endif
-
-// Stream N consecutive 1 KB weight fragments out of LDS with PF reads in flight: the read of
-// fragment f + PF is issued before the products that use fragment f, so the LDS latency hides
-// behind matrix-core work instead of preceding every product.
-template <int N, int PF, typename Fn>
-__device__ __forceinline__ void frag_stream(const u32x4* rb, Fn&& use) {
-  Frag8 buf[PF];
-#pragma unroll
-  for (int f = 0; f < PF && f < N; ++f) buf[f].q = rb[f * 64];
-#pragma unroll
-  for (int f = 0; f < N; ++f) {
-    const Frag8 cur = buf[f % PF];
-    __builtin_amdgcn_sched_barrier(0);
-    if (f + PF < N) buf[f % PF].q = rb[(f + PF) * 64];
-    __builtin_amdgcn_sched_barrier(0);
-    use(cur, f);
-  }
-}
-constexpr int kPrefetch = 3;
 
 struct SmallParams {  // per-feature vectors, bf16, read straight from the caller's arrays
   const uint16_t *ln1_g, *ln1_b, *b_qkv, *b_o, *ln2_g, *ln2_b, *b1, *b2;
@@ -164,6 +150,7 @@ __global__ __launch_bounds__(256) void k_pack_weights(PackBatch pb, int C, int F
   const int KB = C / 32, NB = C / 16, fr_hp = 6 * KB + NB, fr_fc = 2 * KB + NB, n_hp = C / 32;
   const uint16_t* src;
   int kbase;
+  bool halve = false;  // W2 carries the 0.5 of the GELU (see gelu2_fast)
   if (frag < n_hp * fr_hp) {
     const int hp = frag / fr_hp, r = frag % fr_hp;
     if (r < 6 * KB) {
@@ -185,23 +172,44 @@ __global__ __launch_bounds__(256) void k_pack_weights(PackBatch pb, int C, int F
       const int nb = r - 2 * KB;
       src = w2 + (size_t)(16 * nb + i) * F;
       kbase = 32 * fc;
+      halve = true;
     }
   }
   uint32_t u[4];
 #pragma unroll
   for (int s = 0; s < 8; s += 2) {
     const int k0 = kbase + 16 * (s / 4) + 4 * q + (s % 4);
-    u[s / 2] = (uint32_t)src[k0] | ((uint32_t)src[k0 + 1] << 16);
+    uint16_t lo = src[k0], hi = src[k0 + 1];
+    if (halve) { lo = f32_to_bf16(0.5f * bf16_to_f32(lo)); hi = f32_to_bf16(0.5f * bf16_to_f32(hi)); }
+    u[s / 2] = (uint32_t)lo | ((uint32_t)hi << 16);
   }
   out[(size_t)frag * 64 + lane] = make_uint4(u[0], u[1], u[2], u[3]);
 }
 
 // ---- the fused layer ------------------------------------------------------------------------------
-// LDS map (bytes): [weight ring 2 x CH KB][small parameters as fp32: (9C + F) x 4][K/V exchange].
+// LDS map (bytes): [weight ring RING x 16 KB][small parameters as fp32: (9C + F) x 4][K/V exchange, 2 buffers].
 template <int C, int F>
 struct ParamOff {  // float offsets inside the small-parameter area
   static constexpr int LN1G = 0, LN1B = C, BQ = 2 * C, BK = 3 * C, BV = 4 * C, BO = 5 * C, LN2G = 6 * C,
                        LN2B = 7 * C, B2 = 8 * C, B1 = 9 * C, TOTAL = 9 * C + F;
+};
+
+constexpr int kChunkFrags = 16;        // fragments per staged chunk (16 KB)
+constexpr int kLdsBytes = 160 * 1024;  // LDS of one compute unit
+constexpr int kWindow = 8;             // weight fragments a wavefront keeps in flight (LDS -> registers)
+
+template <int C, int F, int NVB, int WPG, int NW, int MINW>
+struct LdsPlan {
+  static constexpr int NKB = NVB * WPG, GPW = NW / WPG;
+  static constexpr int WGS = (MINW * 4 / NW) > 1 ? (MINW * 4 / NW) : 1;  // workgroups meant to share a compute unit
+  static constexpr int PARAMS = ParamOff<C, F>::TOTAL * 4;
+  static constexpr int KVX_ONE = 2 * 2 * NKB * 64 * 8;                     // K and V of one group, one unit
+  static constexpr int KVX = WPG > 1 ? 2 * GPW * KVX_ONE : 0;              // double buffered
+  static constexpr int NCHUNK = ((C / 32) * (6 * (C / 32) + C / 16) + (F / 32) * (2 * (C / 32) + C / 16)) / kChunkFrags;
+  static constexpr int FIT = (kLdsBytes / WGS - PARAMS - KVX) / (kChunkFrags * 1024);
+  static constexpr int RING = FIT < NCHUNK ? FIT : NCHUNK;
+  static constexpr int TOTAL = RING * kChunkFrags * 1024 + PARAMS + KVX;
+  static_assert(RING >= 2, "weight ring");
 };
 
 template <int C, int DH, int F, int NVB, int WPG, int NW, int MINW, bool OUT_F32>
@@ -216,51 +224,84 @@ __global__ __launch_bounds__(NW * 64, MINW) void k_layer_mfma(const uint16_t* __
   constexpr int FC = F / 32;          // 32-wide hidden units
   constexpr int NKB = NVB * WPG;      // key blocks of a group
   constexpr int NT = NW * 64;
-  constexpr int CH = 4 * KB;          // fragments per staged chunk: {Q,K} | {V,W_o} | {W1,W2} of one unit
-  constexpr int RING = 3;             // LDS slots: chunks cc and cc+1 resident, cc+2 in flight
-  constexpr int NCHUNK = 2 * HP + FC;
+  constexpr int GPW = NW / WPG;       // groups per workgroup
+  constexpr int CF = kChunkFrags;
+  constexpr int FH = 6 * KB + NB;     // fragments of one head-dim unit: Q, K, V rows, W_o slice
+  constexpr int FF = 2 * KB + NB;     // fragments of one hidden unit: W1 rows, W2 slice
+  constexpr int CPH = FH / CF, CPF = FF / CF;
+  // C = 128: the unit loops are unrolled completely, which turns the ring bookkeeping into constants
+  // (about 30 KB of code).  Wider layers keep rolled loops.
+  constexpr int FULL_UNROLL = C <= 128 ? 16 : 1;
+  constexpr bool LEAN = (NW + 3) / 4 >= 3 && MINW <= 2 && C >= 256;  // three wavefronts on a SIMD: 168 registers each
+  constexpr int PF = LEAN ? 4 : kWindow;
+  using LP = LdsPlan<C, F, NVB, WPG, NW, MINW>;
+  constexpr int NCHUNK = LP::NCHUNK, RING = LP::RING;
   using PO = ParamOff<C, F>;
   static_assert(DH == 16 || DH == 32, "head dim");
+  static_assert(FH % CF == 0 && FF % CF == 0 && CF % PF == 0, "units are whole chunks");
 
   extern __shared__ u32x4 lds[];
-  u32x4* ring = lds;                                            // [RING][CH * 64]
-  float* par = reinterpret_cast<float*>(lds + RING * CH * 64);  // [PO::TOTAL]
+  u32x4* ring = lds;                                            // [RING][CF * 64]
+  float* par = reinterpret_cast<float*>(lds + RING * CF * 64);  // [PO::TOTAL]
   u32x2* kvx = reinterpret_cast<u32x2*>(par + PO::TOTAL);       // K/V exchange, only when WPG > 1
 
   const int tid = threadIdx.x, lane = tid & 63, w = tid >> 6, i = lane & 15, q = lane >> 4;
-  const int gl = w / WPG, part = w % WPG;
-  const int g = blockIdx.x * (NW / WPG) + gl;
+  const int wu = __builtin_amdgcn_readfirstlane(w);
+  const int gl = wu / WPG, part = wu % WPG;
+  const int g = blockIdx.x * GPW + gl;
   // group_offsets has at least max_groups + 1 entries: read this group's bounds without waiting
-  // for num_groups, so that the two loads travel together.
+  // for num_groups, so that the loads travel together.
   const int gc = g < max_groups ? g : max_groups - 1;
   const int off0 = goff[gc], off1 = goff[gc + 1];
   int start = 0, m = 0;
   if (g < *num_groups) { start = off0; m = off1 - off0; }
 
   FF_TS_DECL
-  int cc = 0;  // chunk being consumed
-  const int wu = __builtin_amdgcn_readfirstlane(w);
-  // Asynchronous copy of one chunk of the packed weight stream, global memory -> LDS, 1 KB per
-  // instruction and no registers in between (lane l's 16 bytes land at slot base + 16 l).
-  auto issue = [&](int chunk) {
-    if (chunk < NCHUNK) {
-      for (int f = wu; f < CH; f += NW) {  // wave-uniform trip count
+  // ---- weight stream: global memory -> LDS ring -> registers -----------------------------------------
+  // Chunk c of the packed stream lives in ring slot c % RING.  `issued` chunks have been requested,
+  // chunks below `visible` are known to have landed for every wavefront.  Both advance only at
+  // workgroup barriers that every wavefront reaches with the same values.
+  int issued = 0, visible = 0;
+  auto issue = [&](int chunk) {  // asynchronous copy, 1 KB per instruction, no registers in between
+#pragma unroll
+    for (int t = 0; t < (CF + NW - 1) / NW; ++t) {
+      const int f = wu + t * NW;
+      if ((t + 1) * NW <= CF || f < CF) {  // wave-uniform
         __builtin_amdgcn_global_load_lds(
-            (const __attribute__((address_space(1))) void*)(packed + ((size_t)chunk * CH + f) * 64 + lane),
-            (__attribute__((address_space(3))) void*)(ring + ((chunk % RING) * CH + f) * 64), 16, 0, 0);
+            (const __attribute__((address_space(1))) void*)(packed + ((size_t)chunk * CF + f) * 64 + lane),
+            (__attribute__((address_space(3))) void*)(ring + ((chunk % RING) * CF + f) * 64), 16, 0, 0);
       }
     }
   };
-  auto slot = [&](int chunk) -> const u32x4* { return ring + (chunk % RING) * CH * 64 + lane; };
-  auto advance = [&]() {  // done with chunk cc
-    asm volatile("s_waitcnt vmcnt(0)" ::: "memory");  // my share of chunk cc+2 has landed
-    __syncthreads();                                  // everyone's has, and everyone is done with chunk cc
-    ++cc;
-    issue(cc + 2);                                    // into the slot that chunk cc-1 occupied
+  // Barrier.  Every wavefront has finished with all chunks below `consumed` when it arrives.
+  auto sync = [&](int consumed) {
+    asm volatile("s_waitcnt vmcnt(0)" ::: "memory");  // my share of every issued chunk has landed
+    __syncthreads();
+    visible = issued;
+    const int lim = consumed + RING < NCHUNK ? consumed + RING : NCHUNK;
+    while (issued < lim) { issue(issued); ++issued; }
   };
+  // Before the first read of chunk cn.  voluntary: also stop when free slots could be refilled.
+  auto boundary = [&](int cn, int consumed, bool voluntary) {
+    if (cn >= NCHUNK) return;
+    if (voluntary && issued < NCHUNK && issued < consumed + RING) sync(consumed);
+    while (cn >= visible) sync(consumed);
+  };
+  // An LDS read reaches 64 KB beyond its base register through the immediate offset; the ring can be
+  // larger, so there are two bases, the second one hidden from constant folding.
+  uint32_t hi_units = 4 * CF * 64;  // slots 4.. start here (u32x4 units)
+  asm volatile("" : "+v"(hi_units));
+  const u32x4* ring_lo = ring + lane;
+  const u32x4* ring_hi = ring + hi_units + lane;
+  auto slot_ptr = [&](int chunk) -> const u32x4* {
+    const int slot = chunk % RING;
+    return slot < 4 ? ring_lo + slot * CF * 64 : ring_hi + (slot - 4) * CF * 64;
+  };
+
   FF_TS(0);
   issue(0);
   issue(1);
+  issued = 2;
 
   // small parameters -> LDS as fp32
   for (int t = tid; t < PO::TOTAL; t += NT) {
@@ -277,26 +318,34 @@ __global__ __launch_bounds__(NW * 64, MINW) void k_layer_mfma(const uint16_t* __
 
   // ---- gather + LN1 ---------------------------------------------------------------------------------
   f32x4 x1[NVB][NB];  // residual stream of my pillars, accumulator layout
-  int64_t row[NVB];
+  int32_t row[NVB];  // pillar index, -1 for padding slots
 #pragma unroll
   for (int vb = 0; vb < NVB; ++vb) {
     const int s = (part * NVB + vb) * 16 + i;
-    row[vb] = s < m ? (int64_t)perm[start + s] : -1;
+    row[vb] = s < m ? perm[start + s] : -1;
   }
 #pragma unroll
   for (int vb = 0; vb < NVB; ++vb) {
 #pragma unroll
     for (int nb = 0; nb < NB; ++nb) {
       float t[4] = {0.f, 0.f, 0.f, 0.f};
-      if (row[vb] >= 0) load4(feats + row[vb] * C + 16 * nb + 4 * q, t);
+      if (row[vb] >= 0) load4(feats + (int64_t)row[vb] * C + 16 * nb + 4 * q, t);
       x1[vb][nb] = f32x4{t[0], t[1], t[2], t[3]};
     }
   }
   FF_TS(1);
-  asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
-  __syncthreads();  // chunks 0 and 1 and the small parameters are in LDS
-  issue(2);
+  sync(0);  // chunks 0 and 1 and the small parameters are in LDS; the rest of the ring is requested
   FF_TS(2);
+
+  // The window: fragments j .. j + PF - 1 of the stream are in registers (or on their way) while
+  // fragment j is being used.
+  Frag8 win[PF];
+  {
+    const u32x4* p0 = slot_ptr(0);
+#pragma unroll
+    for (int f = 0; f < PF; ++f) win[f].q = p0[f * 64];
+  }
+  __builtin_amdgcn_sched_barrier(0);
 
   Frag8 act[NVB][KB];  // normalised activations as B operands (LN1 output, later LN2 output)
   auto layer_norm = [&](int goff_f, int boff_f) {
@@ -336,6 +385,17 @@ __global__ __launch_bounds__(NW * 64, MINW) void k_layer_mfma(const uint16_t* __
       for (int vb = 0; vb < NVB; ++vb) x1[vb][nb] += b;
     }
   };
+  // Biases of the Q, K (accumulator layout) and V (swapped roles: one feature per lane) rows of a unit.
+  f32x4 bqk[4];
+  float bvv[2];
+  auto load_unit_bias = [&](int hp) {
+#pragma unroll
+    for (int c = 0; c < 4; ++c)
+      bqk[c] = *reinterpret_cast<const f32x4*>(par + (c < 2 ? PO::BQ : PO::BK) + 32 * hp + 16 * (c & 1) + 4 * q);
+#pragma unroll
+    for (int a = 0; a < 2; ++a) bvv[a] = par[PO::BV + 32 * hp + 16 * a + i];
+  };
+  load_unit_bias(0);
   layer_norm(PO::LN1G, PO::LN1B);
   add_bias_rows(PO::BO);  // residual + output-projection bias
 
@@ -344,75 +404,64 @@ __global__ __launch_bounds__(NW * 64, MINW) void k_layer_mfma(const uint16_t* __
   const bool short_group = m < NKB * 16;  // wave-uniform: some key slots are padding
 
   // ---- attention: one 32-wide head-dim unit per iteration (two heads of 16 or one head of 32) --------
-#pragma unroll 1
+#pragma unroll FULL_UNROLL
   for (int hp = 0; hp < HP; ++hp) {
-    const u32x4* rb = slot(cc);
+    const int c0 = hp * CPH;
+    const u32x4* pb[CPH + 1];
+#pragma unroll
+    for (int k = 0; k <= CPH; ++k) pb[k] = slot_ptr(c0 + k);
+    // fragment j of this unit has been used: refill its window slot with fragment j + PF
+    auto refill = [&](int j) {
+      const int jj = j + PF, k = jj / CF;
+      __builtin_amdgcn_sched_barrier(0);
+      if (jj % CF == 0) boundary(c0 + k, c0 + (j + 1) / CF, WPG == 1);
+      win[j % PF].q = pb[k][(jj % CF) * 64];  // a hidden unit always follows: the chunk exists
+      __builtin_amdgcn_sched_barrier(0);
+    };
+    if (LEAN) load_unit_bias(hp);
     Frag4 Qf[2][NVB], Kf[2][NVB], Vf[2][NVB];  // bf16 fragments of my pillars, index [16-block a][vb]
+    u32x2* kv = kvx + (size_t)((hp & 1) * GPW + gl) * (2 * 2 * NKB * 64) + lane;  // this unit's exchange buffer
 
-    // Q and K rows: D[feature][pillar]; fragment f = (q|k, 16-block a, k-block kb)
+    // Six accumulation chains: Q a=0,1 and K a=0,1 as D[feature][pillar], V a=0,1 with the operand
+    // roles swapped as D[pillar][feature].  The conversion of a finished chain is issued after the
+    // first product of the next one.
     {
-      f32x4 acc[NVB];
-      frag_stream<4 * KB, kPrefetch>(rb, [&](const Frag8& wf, int f) {
-        const int qk = f / (2 * KB), a = (f / KB) & 1, kb = f % KB;
-        if (kb == 0) {  // the accumulator starts from the bias
-          const f32x4 b = *reinterpret_cast<const f32x4*>(par + (qk == 0 ? PO::BQ : PO::BK) + 32 * hp + 16 * a + 4 * q);
-#pragma unroll
-          for (int vb = 0; vb < NVB; ++vb) acc[vb] = b;
-        }
-#pragma unroll
-        for (int vb = 0; vb < NVB; ++vb) acc[vb] = mfma32(wf, act[vb][kb], acc[vb]);
-        if (kb == KB - 1) {
-#pragma unroll
-          for (int vb = 0; vb < NVB; ++vb) {
-            Frag4& dst = qk == 0 ? Qf[a][vb] : Kf[a][vb];
-            dst.u[0] = pack2(acc[vb][0], acc[vb][1]);
-            dst.u[1] = pack2(acc[vb][2], acc[vb][3]);
-          }
-        }
-      });
-    }
-    if (hp == 0) FF_TS(4);
-    advance();
-    rb = slot(cc);
-    if (hp == 0) FF_TS(5);
-    // V rows with the operand roles swapped: D[pillar][feature]
-    {
-      f32x4 acc[NVB];
-      frag_stream<2 * KB, kPrefetch>(rb, [&](const Frag8& wf, int f) {
-        const int a = f / KB, kb = f % KB;
-        if (kb == 0) {
-          const float bv = par[PO::BV + 32 * hp + 16 * a + i];
-#pragma unroll
-          for (int vb = 0; vb < NVB; ++vb) acc[vb] = f32x4{bv, bv, bv, bv};
-        }
-#pragma unroll
-        for (int vb = 0; vb < NVB; ++vb) acc[vb] = mfma32(act[vb][kb], wf, acc[vb]);
-        if (kb == KB - 1) {
-#pragma unroll
-          for (int vb = 0; vb < NVB; ++vb) {
-            Vf[a][vb].u[0] = pack2(acc[vb][0], acc[vb][1]);
-            Vf[a][vb].u[1] = pack2(acc[vb][2], acc[vb][3]);
-          }
-        }
-      });
-    }
-
-    // K/V of the whole group.  One wavefront per group: they are already in registers.
-    // Otherwise through LDS: [group in workgroup][K|V][16-block a][key block][lane]; the barrier
-    // that ends every unit (advance) makes one buffer enough.
-    u32x2* kv = nullptr;
-    if (WPG > 1) {
-      kv = kvx + (size_t)gl * 2 * 2 * NKB * 64 + lane;
-#pragma unroll
-      for (int a = 0; a < 2; ++a) {
+      f32x4 acc[2][NVB];
+      auto finish = [&](int ch) {
+        const int a = ch & 1;
 #pragma unroll
         for (int vb = 0; vb < NVB; ++vb) {
-          kv[((0 * 2 + a) * NKB + part * NVB + vb) * 64] = Kf[a][vb].d;
-          kv[((1 * 2 + a) * NKB + part * NVB + vb) * 64] = Vf[a][vb].d;
+          Frag4& dst = ch < 2 ? Qf[a][vb] : ch < 4 ? Kf[a][vb] : Vf[a][vb];
+          dst.u[0] = pack2(acc[ch & 1][vb][0], acc[ch & 1][vb][1]);
+          dst.u[1] = pack2(acc[ch & 1][vb][2], acc[ch & 1][vb][3]);
+          // K/V of the whole group go through LDS: [K|V][16-block a][key block][lane]
+          if (WPG > 1 && ch >= 2) kv[(((ch >= 4 ? 1 : 0) * 2 + a) * NKB + part * NVB + vb) * 64] = dst.d;
+        }
+      };
+#pragma unroll
+      for (int ch = 0; ch < 6; ++ch) {
+#pragma unroll
+        for (int kb = 0; kb < KB; ++kb) {
+          const int j = ch * KB + kb;
+          const Frag8 wf = win[j % PF];
+          if (kb == 0) {  // the accumulator starts from the bias
+#pragma unroll
+            for (int vb = 0; vb < NVB; ++vb)
+              acc[ch & 1][vb] = ch < 4 ? bqk[ch] : f32x4{bvv[ch & 1], bvv[ch & 1], bvv[ch & 1], bvv[ch & 1]};
+          }
+#pragma unroll
+          for (int vb = 0; vb < NVB; ++vb)
+            acc[ch & 1][vb] = ch < 4 ? mfma32(wf, act[vb][kb], acc[ch & 1][vb]) : mfma32(act[vb][kb], wf, acc[ch & 1][vb]);
+          if (kb == 0 && ch > 0) finish(ch - 1);
+          refill(j);
         }
       }
-      __syncthreads();
+      finish(5);
     }
+    if (hp == 0) FF_TS(4);
+    if (WPG > 1) sync(c0 + (6 * KB) / CF);  // K/V of the group are in LDS
+    if (hp == 0) FF_TS(5);
+    if (!LEAN) load_unit_bias(hp + 1 < HP ? hp + 1 : hp);
     auto Kget = [&](int a, int jb) -> Frag4 {
       if (WPG == 1) return Kf[a][jb];
       Frag4 f; f.d = kv[((0 * 2 + a) * NKB + jb) * 64]; return f;
@@ -554,51 +603,79 @@ __global__ __launch_bounds__(NW * 64, MINW) void k_layer_mfma(const uint16_t* __
     }
     if (hp == 0) FF_TS(7);
     // output projection of this unit, accumulated into the residual stream
-    frag_stream<NB, kPrefetch>(rb + 2 * KB * 64, [&](const Frag8& wf, int nb) {
+#pragma unroll
+    for (int nb = 0; nb < NB; ++nb) {
+      const int j = 6 * KB + nb;
+      const Frag8 wf = win[j % PF];
 #pragma unroll
       for (int vb = 0; vb < NVB; ++vb) x1[vb][nb] = mfma32(wf, Of[vb], x1[vb][nb]);
-    });
+      refill(j);
+    }
     if (hp == 0) FF_TS(8);
-    advance();
-    if (hp == 0) FF_TS(9);
   }
   FF_TS(10);
 
   // ---- FFN ------------------------------------------------------------------------------------------
+  f32x4 b1r[2];
+  auto load_b1 = [&](int fc) {
+#pragma unroll
+    for (int a = 0; a < 2; ++a) b1r[a] = *reinterpret_cast<const f32x4*>(par + PO::B1 + 32 * fc + 16 * a + 4 * q);
+  };
+  load_b1(0);
   layer_norm(PO::LN2G, PO::LN2B);
   add_bias_rows(PO::B2);
   FF_TS(11);
-#pragma unroll 1
+#pragma unroll FULL_UNROLL
   for (int fc = 0; fc < FC; ++fc) {
-    const u32x4* rb = slot(cc);
+    const int c0 = HP * CPH + fc * CPF;
+    const u32x4* pb[CPF + 1];
+#pragma unroll
+    for (int k = 0; k <= CPF; ++k) pb[k] = slot_ptr(c0 + k);
+    auto refill = [&](int j) {
+      const int jj = j + PF, k = jj / CF;
+      __builtin_amdgcn_sched_barrier(0);
+      if (jj % CF == 0) boundary(c0 + k, c0 + (j + 1) / CF, true);
+      if (k < CPF || fc + 1 < FC) win[j % PF].q = pb[k][(jj % CF) * 64];
+      __builtin_amdgcn_sched_barrier(0);
+    };
     Frag8 Hf[NVB];
     {
-      f32x4 acc[NVB];
-      frag_stream<2 * KB, kPrefetch>(rb, [&](const Frag8& wf, int f) {
-        const int a = f / KB, kb = f % KB;
-        if (kb == 0) {
-          const f32x4 b = *reinterpret_cast<const f32x4*>(par + PO::B1 + 32 * fc + 16 * a + 4 * q);
+      f32x4 acc[2][NVB];
+      auto finish = [&](int a) {
 #pragma unroll
-          for (int vb = 0; vb < NVB; ++vb) acc[vb] = b;
+        for (int vb = 0; vb < NVB; ++vb) {
+          Hf[vb].u[a * 2 + 0] = pack2(gelu2_fast(acc[a][vb][0]), gelu2_fast(acc[a][vb][1]));
+          Hf[vb].u[a * 2 + 1] = pack2(gelu2_fast(acc[a][vb][2]), gelu2_fast(acc[a][vb][3]));
         }
+      };
 #pragma unroll
-        for (int vb = 0; vb < NVB; ++vb) acc[vb] = mfma32(wf, act[vb][kb], acc[vb]);
-        if (kb == KB - 1) {
+      for (int a = 0; a < 2; ++a) {
 #pragma unroll
-          for (int vb = 0; vb < NVB; ++vb) {
-            Hf[vb].u[a * 2 + 0] = pack2(gelu_fast(acc[vb][0]), gelu_fast(acc[vb][1]));
-            Hf[vb].u[a * 2 + 1] = pack2(gelu_fast(acc[vb][2]), gelu_fast(acc[vb][3]));
+        for (int kb = 0; kb < KB; ++kb) {
+          const int j = a * KB + kb;
+          const Frag8 wf = win[j % PF];
+          if (kb == 0) {
+#pragma unroll
+            for (int vb = 0; vb < NVB; ++vb) acc[a][vb] = b1r[a];
           }
+#pragma unroll
+          for (int vb = 0; vb < NVB; ++vb) acc[a][vb] = mfma32(wf, act[vb][kb], acc[a][vb]);
+          if (kb == 0 && a == 1) finish(0);
+          refill(j);
         }
-      });
+      }
+      finish(1);
     }
-    frag_stream<NB, kPrefetch>(rb + 2 * KB * 64, [&](const Frag8& wf, int nb) {
+    load_b1(fc + 1 < FC ? fc + 1 : fc);
+#pragma unroll
+    for (int nb = 0; nb < NB; ++nb) {
+      const int j = 2 * KB + nb;
+      const Frag8 wf = win[j % PF];
 #pragma unroll
       for (int vb = 0; vb < NVB; ++vb) x1[vb][nb] = mfma32(wf, Hf[vb], x1[vb][nb]);
-    });
+      refill(j);
+    }
     if (fc == 0) FF_TS(12);
-    if (fc + 1 < FC) advance();
-    if (fc == 0) FF_TS(13);
   }
   FF_TS(14);
 
@@ -637,10 +714,7 @@ int launch_cfg(const void* feats, void* out, const int32_t* perm, const int32_t*
                int32_t max_groups, const u32x4* packed, const SmallParams& sp, float eps, bool out_f32,
                hipStream_t stream) {
   constexpr int GPW = NW / WPG;
-  constexpr int NKB = NVB * WPG;
-  constexpr int CH = 4 * (C / 32);
-  const size_t lds_bytes = (size_t)3 * CH * 1024 + (size_t)ParamOff<C, F>::TOTAL * 4 +
-                           (WPG > 1 ? (size_t)GPW * 2 * 2 * NKB * 64 * 8 : 0);
+  const size_t lds_bytes = LdsPlan<C, F, NVB, WPG, NW, MINW>::TOTAL;
   const unsigned blocks = (unsigned)((max_groups + GPW - 1) / GPW);
   auto go = [&](auto kern) -> int {
     static bool attr_done = false;  // the attribute only has to be set once per kernel
@@ -707,19 +781,17 @@ int layer_mfma_launch(const void* feats, void* out, int64_t n, const int32_t* pe
   return launch_cfg<C, DH, F, NVB, WPG, NW, MINW>(feats, out, perm, group_offsets, num_groups, max_groups, pk, sp, \
                                                   w->ln_eps, out_f32, stream)
   const int shape = shape_id(w);
+  // (pillar blocks per wave, waves per group, waves per workgroup, min waves per SIMD)
   if (shape == 1) {
     if (variant == 0) variant = G <= 32 ? 10 : G <= 64 ? 7 : 9;
-    switch (variant) {  // (pillar blocks per wave, waves per group, waves per workgroup, min waves per SIMD)
+    switch (variant) {
       case 1: if (G <= 32) FF_GO(128, 16, 256, 2, 1, 4, 2); break;
       case 2: if (G <= 64) FF_GO(128, 16, 256, 2, 2, 4, 2); break;
-      case 3: if (G <= 64) FF_GO(128, 16, 256, 4, 1, 4, 1); break;
-      case 4: if (G <= 128) FF_GO(128, 16, 256, 2, 4, 4, 2); break;
-      case 5: if (G <= 128) FF_GO(128, 16, 256, 4, 2, 4, 1); break;
+      case 4: if (G <= 128) FF_GO(128, 16, 256, 2, 4, 4, 1); break;
       case 6: if (G <= 64) FF_GO(128, 16, 256, 1, 4, 4, 2); break;
-      case 7: if (G <= 64) FF_GO(128, 16, 256, 1, 4, 8, 4); break;
-      case 8: if (G <= 64) FF_GO(128, 16, 256, 2, 2, 8, 2); break;
-      case 9: if (G <= 128) FF_GO(128, 16, 256, 1, 8, 8, 4); break;
-      case 10: if (G <= 32) FF_GO(128, 16, 256, 1, 2, 8, 4); break;
+      case 7: if (G <= 64) FF_GO(128, 16, 256, 1, 4, 8, 2); break;
+      case 9: if (G <= 128) FF_GO(128, 16, 256, 1, 8, 8, 2); break;
+      case 10: if (G <= 32) FF_GO(128, 16, 256, 1, 2, 8, 2); break;
       default: break;
     }
   } else if (shape == 2) {
@@ -727,7 +799,7 @@ int layer_mfma_launch(const void* feats, void* out, int64_t n, const int32_t* pe
     switch (variant) {
       case 1: if (G <= 32) FF_GO(256, 32, 512, 1, 2, 8, 2); break;
       case 2: if (G <= 64) FF_GO(256, 32, 512, 1, 4, 8, 2); break;
-      case 3: if (G <= 80) FF_GO(256, 32, 512, 1, 5, 10, 2); break;
+      case 3: if (G <= 80) FF_GO(256, 32, 512, 1, 5, 5, 1); break;
       case 4: if (G <= 128) FF_GO(256, 32, 512, 1, 8, 8, 2); break;
       case 5: if (G <= 64) FF_GO(256, 32, 512, 2, 2, 4, 1); break;
       default: break;
