@@ -18,6 +18,16 @@
 // kernel reports num_groups = -1.
 #include "common.h"
 
+#ifdef FF_PROBE
+__device__ long long ff_probe_flat[64];
+extern "C" int ff_debug_read_probe_flat(long long* host_out) {
+  return (int)hipMemcpyFromSymbol(host_out, HIP_SYMBOL(ff_probe_flat), sizeof(long long) * 64);
+}
+#define FP_TS(k) do { if (threadIdx.x == 0 && blockIdx.x == gridDim.x / 2 && blockIdx.y == 0) ff_probe_flat[(FUSE ? 32 : 0) + (k)] = wall_clock64(); } while (0)
+#else
+#define FP_TS(k) do { } while (0)
+#endif
+
 namespace ff {
 
 namespace {
@@ -276,6 +286,299 @@ __global__ __launch_bounds__(kSortThreads) void k_onesweep(const uint64_t* __res
   }
 }
 
+
+// ---- small clouds ----------------------------------------------------------------------------------
+// Up to kSmallMaxTiles tiles of 1024 words per sort: every kernel is then bound by launch and
+// memory latency, not by bandwidth.  Workgroups on different XCDs talk through memory, two
+// microseconds and more per round trip, so this path has no look-back at all and as few launches
+// as possible:
+//   * digits of up to 10 bits (two passes for the 20 key bits of one BEV frame);
+//   * a table counts[pass][tile][digit] says how many words with that digit of that pass the tile
+//     holds in the order the pass reads them.  Key generation writes the rows of the first pass
+//     (plain stores) and zeroes the others; each pass adds, for every word it places, one to the
+//     row of the tile the word lands in for the next pass.  Nothing has to be cleared beforehand;
+//   * a pass reads the whole table of its pass: column sums give the global digit starts, the
+//     rows of earlier tiles its own offsets;
+//   * the last pass writes perm, exported keys and group offsets itself.
+constexpr int kSmallKpt = 4;
+constexpr int kSmallTile = kSortThreads * kSmallKpt;  // 1024 words per tile
+constexpr int kSmallMaxTiles = 64;
+
+__device__ __forceinline__ uint32_t digit_rb(uint64_t word, int idx_bits, int key_bits, int pass, int rb) {
+  const int lo = pass * rb;
+  const int nb = key_bits - lo < rb ? key_bits - lo : rb;
+  if (nb <= 0) return 0u;
+  return (uint32_t)(word >> (idx_bits + lo)) & ((1u << nb) - 1u);
+}
+
+__device__ __forceinline__ uint64_t make_word(const int32_t* __restrict__ coords, int64_t i, const KeyParams& kp) {
+  const uint32_t b = (uint32_t)coords[3 * i + 0];
+  const uint32_t X = (uint32_t)(coords[3 * i + 1] + kp.sx);
+  const uint32_t Y = (uint32_t)(coords[3 * i + 2] + kp.sy);
+  const uint32_t Wx = X / (uint32_t)kp.win_x, Lx = X - Wx * (uint32_t)kp.win_x;
+  const uint32_t Wy = Y / (uint32_t)kp.win_y, Ly = Y - Wy * (uint32_t)kp.win_y;
+  const uint32_t w1 = kp.axis == 0 ? Wx : Wy, w2 = kp.axis == 0 ? Wy : Wx;
+  const uint32_t l1 = kp.axis == 0 ? Lx : Ly, l2 = kp.axis == 0 ? Ly : Lx;
+  // Fields are masked to their widths so that a coordinate outside the geometry can only
+  // disturb the order, never another field's bits or any index computed from them.
+  uint64_t k = b & field_mask(kp.bits_b);
+  k = (k << kp.bits_w1) | (w1 & field_mask(kp.bits_w1));
+  k = (k << kp.bits_w2) | (w2 & field_mask(kp.bits_w2));
+  k = (k << kp.bits_l1) | (l1 & field_mask(kp.bits_l1));
+  k = (k << kp.bits_l2) | (l2 & field_mask(kp.bits_l2));
+  return (k << kp.idx_bits) | (uint64_t)i;
+}
+
+__device__ __forceinline__ uint64_t exported_key(uint64_t k, const KeyParams& kp, uint32_t* frame) {
+  const uint64_t l2 = k & field_mask(kp.bits_l2); k >>= kp.bits_l2;
+  const uint64_t l1 = k & field_mask(kp.bits_l1); k >>= kp.bits_l1;
+  const uint64_t w2 = k & field_mask(kp.bits_w2); k >>= kp.bits_w2;
+  const uint64_t w1 = k & field_mask(kp.bits_w1); k >>= kp.bits_w1;
+  const uint64_t b = k & field_mask(kp.bits_b);
+  *frame = (uint32_t)b;
+  return (b << 48) | (w1 << 32) | (w2 << 16) | (l1 << 8) | l2;
+}
+
+// counts [S][P][tiles][BINS]
+template <int RB>
+__global__ __launch_bounds__(kSortThreads) void k_keygen_small(const int32_t* __restrict__ coords, int64_t n, Batch bt, int P,
+                                                                int tiles, uint64_t* __restrict__ words,
+                                                                uint32_t* __restrict__ counts, uint32_t* __restrict__ error_word) {
+  constexpr int BINS = 1 << RB;
+  __shared__ uint32_t h[BINS];
+  const int s = blockIdx.y, tile = blockIdx.x, tid = threadIdx.x;
+  const KeyParams kp = bt.kp[s];
+  for (int t = tid; t < BINS; t += kSortThreads) h[t] = 0u;
+  __syncthreads();
+#pragma unroll
+  for (int r = 0; r < kSmallKpt; ++r) {
+    const int64_t i = (int64_t)tile * kSmallTile + r * kSortThreads + tid;
+    if (i < n) {
+      const uint64_t word = make_word(coords, i, kp);
+      words[(int64_t)s * n + i] = word;
+      atomicAdd(&h[digit_rb(word, kp.idx_bits, kp.key_bits, 0, RB)], 1u);
+    }
+  }
+  __syncthreads();
+  for (int p = 0; p < P; ++p) {
+    const size_t base = (((size_t)s * P + p) * tiles + tile) * BINS;
+    for (int t = tid; t < BINS; t += kSortThreads) counts[base + t] = p == 0 ? h[t] : 0u;
+  }
+  if (tile == 0 && s == 0 && tid == 0) *error_word = 0u;
+}
+
+template <int RB, bool FUSE>
+__global__ __launch_bounds__(kSortThreads) void k_pass_small(const uint64_t* __restrict__ in_all, uint64_t* __restrict__ out_all,
+                                                              int64_t n, Batch bt, int pass, int P, int tiles, int G,
+                                                              uint32_t* __restrict__ counts) {
+  constexpr int BINS = 1 << RB, BPT = BINS / kSortThreads, WAVES = kSortThreads / 64, KPT = kSmallKpt, TILE = kSmallTile;
+  static_assert(BPT == 1 || BPT == 4, "digits of 8 or 10 bits");
+  __shared__ uint32_t wave_cnt[WAVES][BINS];  // later: frame starts and frame group bases
+  __shared__ uint32_t digit_start[BINS];      // first slot of a digit inside the tile
+  __shared__ uint32_t gbase[BINS];            // first output position of this tile's words with a digit
+  __shared__ uint32_t gdig[FUSE ? BINS : 1];  // first output position of a digit over the whole array
+  __shared__ uint32_t wave_totals[WAVES];
+  __shared__ uint64_t stage[TILE];
+
+  const int tid = threadIdx.x, lane = tid & 63, w = tid >> 6;
+  const int s = blockIdx.y, tile = blockIdx.x;
+  const KeyParams kp = bt.kp[s];
+  const int idx_bits = kp.idx_bits, key_bits = kp.key_bits;
+  const uint64_t* in = in_all + (int64_t)s * n;
+  uint64_t* out = out_all + (int64_t)s * n;
+  const uint32_t* cnt_tab = counts + ((size_t)s * P + pass) * tiles * BINS;
+  uint32_t* next_tab = counts + ((size_t)s * P + pass + 1) * tiles * BINS;
+
+  FP_TS(0);
+  const int64_t tile_start = (int64_t)tile * TILE;
+  const int tile_count = (int)((n - tile_start) < (int64_t)TILE ? (n - tile_start) : (int64_t)TILE);
+  // Element order inside the tile: wave-major, then round, then lane (see k_onesweep).
+  uint64_t key[KPT];
+  uint32_t rank[KPT];
+  const uint64_t lanes_below = (1ull << lane) - 1ull;
+#pragma unroll
+  for (int r = 0; r < KPT; ++r) {
+    const int e = w * 64 * KPT + r * 64 + lane;
+    key[r] = e < tile_count ? in[tile_start + e] : ~0ull;
+  }
+
+  // Column sums of this pass's table (thread t owns digits t * BPT ..): over all tiles and over
+  // the tiles before this one, 32 rows per memory round trip.
+  uint32_t gtot[BPT], before[BPT];
+#pragma unroll
+  for (int k = 0; k < BPT; ++k) { gtot[k] = 0; before[k] = 0; }
+  for (int t0 = 0; t0 < tiles; t0 += 32) {
+    uint32_t v[32][BPT];
+#pragma unroll
+    for (int u = 0; u < 32; ++u) {
+      const int t = t0 + u < tiles ? t0 + u : tiles - 1;
+      if (BPT == 4) {
+        const uint4 q = *reinterpret_cast<const uint4*>(cnt_tab + (size_t)t * BINS + tid * 4);
+        v[u][0] = q.x; v[u][1 % BPT] = q.y; v[u][2 % BPT] = q.z; v[u][3 % BPT] = q.w;
+      } else {
+        v[u][0] = cnt_tab[(size_t)t * BINS + tid];
+      }
+    }
+#pragma unroll
+    for (int u = 0; u < 32; ++u)
+#pragma unroll
+      for (int k = 0; k < BPT; ++k) {
+        if (t0 + u < tiles) gtot[k] += v[u][k];
+        if (t0 + u < tile) before[k] += v[u][k];
+      }
+  }
+
+  asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
+  FP_TS(1);
+#pragma unroll
+  for (int i = 0; i < WAVES; ++i)
+#pragma unroll
+    for (int k = 0; k < BPT; ++k) wave_cnt[i][tid + k * kSortThreads] = 0;
+  __syncthreads();
+#pragma unroll
+  for (int r = 0; r < KPT; ++r) {
+    const int e = w * 64 * KPT + r * 64 + lane;
+    const bool valid = e < tile_count;
+    const uint32_t d = digit_rb(key[r], idx_bits, key_bits, pass, RB);
+    uint64_t same = __ballot(valid);
+#pragma unroll
+    for (int b = 0; b < RB; ++b) {
+      const bool bit = (d >> b) & 1u;
+      const uint64_t bal = __ballot(bit);
+      same &= bit ? bal : ~bal;
+    }
+    const uint32_t below = __popcll(same & lanes_below);
+    const uint32_t cnt = __popcll(same);
+    uint32_t prev = 0;
+    if (valid) prev = wave_cnt[w][d];
+    if (valid && below == 0) wave_cnt[w][d] = prev + cnt;
+    rank[r] = prev + below;
+  }
+  __syncthreads();
+  FP_TS(2);
+
+  uint32_t total[BPT];
+  uint32_t tsum = 0, gsum = 0;
+#pragma unroll
+  for (int k = 0; k < BPT; ++k) {
+    const int d = tid * BPT + k;
+    uint32_t run = 0;
+#pragma unroll
+    for (int i = 0; i < WAVES; ++i) {
+      const uint32_t c = wave_cnt[i][d];
+      wave_cnt[i][d] = run;  // exclusive prefix over the tile's waves
+      run += c;
+    }
+    total[k] = run;
+    tsum += run;
+    gsum += gtot[k];
+  }
+  const uint32_t gex = block_exclusive_scan<kSortThreads>(gsum, wave_totals, nullptr);
+  const uint32_t tex = block_exclusive_scan<kSortThreads>(tsum, wave_totals, nullptr);
+  {
+    uint32_t grun = gex, trun = tex;
+#pragma unroll
+    for (int k = 0; k < BPT; ++k) {
+      const int d = tid * BPT + k;
+      digit_start[d] = trun;
+      gbase[d] = grun + before[k];
+      if (FUSE) gdig[d] = grun;
+      trun += total[k];
+      grun += gtot[k];
+    }
+  }
+  __syncthreads();
+#pragma unroll
+  for (int r = 0; r < KPT; ++r) {
+    const int e = w * 64 * KPT + r * 64 + lane;
+    if (e < tile_count) {
+      const uint32_t d = digit_rb(key[r], idx_bits, key_bits, pass, RB);
+      stage[digit_start[d] + wave_cnt[w][d] + rank[r]] = key[r];
+    }
+  }
+  __syncthreads();
+  FP_TS(3);
+
+  if (!FUSE) {
+#pragma unroll
+    for (int r = 0; r < KPT; ++r) {
+      const int j = r * kSortThreads + tid;
+      if (j < tile_count) {
+        const uint64_t k = stage[j];
+        const uint32_t d = digit_rb(k, idx_bits, key_bits, pass, RB);
+        const int64_t pos = (int64_t)gbase[d] + (uint32_t)(j - digit_start[d]);
+        if (pos < n) {
+          out[pos] = k;
+          if (pass + 1 < P)  // the next pass finds this word in tile pos / TILE
+            atomicAdd(&next_tab[(size_t)(pos / TILE) * BINS + digit_rb(k, idx_bits, key_bits, pass + 1, RB)], 1u);
+        }
+      }
+    }
+    FP_TS(4);
+    asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
+    FP_TS(5);
+    return;
+  }
+
+  // ---- last pass: the output position is final -------------------------------------------------------
+  // Frame b starts where the first last-pass digit of frame b starts; group bases are the running
+  // sum of ceil(frame size / G).  wave_cnt is free now: [0] = frame starts, [1] = group bases.
+  uint32_t* fstart = &wave_cnt[0][0];
+  uint32_t* fgroup = &wave_cnt[1][0];
+  const int B = kp.B;
+  const int nb_last = key_bits - pass * RB;       // bits of this digit (>= bits_b, checked by the host)
+  const int fshift = nb_last - kp.bits_b;
+  uint32_t gcount[BPT], fs[BPT], gs = 0;
+#pragma unroll
+  for (int k = 0; k < BPT; ++k) {
+    const int b = tid * BPT + k;
+    uint32_t c = 0, lo = 0;
+    if (b < B) {
+      lo = gdig[(uint32_t)b << fshift];
+      const uint32_t hi = b + 1 < B ? gdig[(uint32_t)(b + 1) << fshift] : (uint32_t)n;
+      c = (hi - lo + (uint32_t)G - 1u) / (uint32_t)G;
+    }
+    gcount[k] = c;
+    fs[k] = lo;
+    gs += c;
+  }
+  uint32_t ng_total = 0;
+  uint32_t gexcl = block_exclusive_scan<kSortThreads>(gs, wave_totals, &ng_total);
+#pragma unroll
+  for (int k = 0; k < BPT; ++k) {
+    const int b = tid * BPT + k;
+    if (b < B) { fstart[b] = fs[k]; fgroup[b] = gexcl; }
+    gexcl += gcount[k];
+  }
+  __syncthreads();
+  const uint64_t idx_mask = (1ull << idx_bits) - 1ull;
+#pragma unroll
+  for (int r = 0; r < KPT; ++r) {
+    const int j = r * kSortThreads + tid;
+    if (j < tile_count) {
+      const uint64_t word = stage[j];
+      const uint32_t d = digit_rb(word, idx_bits, key_bits, pass, RB);
+      const int64_t pos = (int64_t)gbase[d] + (uint32_t)(j - digit_start[d]);
+      if (pos < n) {
+        bt.perm[s][pos] = (int32_t)(word & idx_mask);
+        uint32_t b;
+        const uint64_t ek = exported_key(word >> idx_bits, kp, &b);
+        if (bt.keys_sorted[s]) bt.keys_sorted[s][pos] = ek;
+        const uint32_t fb = b < (uint32_t)B ? b : (uint32_t)B - 1u;
+        const uint32_t rel = (uint32_t)pos - fstart[fb];
+        if (rel % (uint32_t)G == 0u) bt.group_offsets[s][fgroup[fb] + rel / (uint32_t)G] = (int32_t)pos;
+      }
+    }
+  }
+  FP_TS(4);
+  asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
+  FP_TS(5);
+  if (tile == 0 && tid == 0) {
+    *bt.num_groups[s] = (int32_t)ng_total;
+    bt.group_offsets[s][ng_total] = (int32_t)n;
+  }
+}
+
 // ---- A3: frame boundaries and group bases for many frames (num_frames > 256) ---------------------
 __global__ __launch_bounds__(256) void k_frames(const uint64_t* __restrict__ sorted_all, int64_t n, Batch bt, int G,
                                                  int32_t* __restrict__ frame_tab /*[S][2][B+1]*/) {
@@ -383,12 +686,29 @@ struct Layout {
   int P;            // passes (max over the batch)
   int kpt;          // words per thread in a pass
   int64_t tiles;
-  size_t off_words0, off_words1, off_control, control_words, off_frames, total;
+  size_t off_words0, off_words1, off_control, control_words, off_frames, off_small, total;
 };
+
+// Small-cloud plan for keys of `key_bits` bits: passes and digit width (8 or 10 bits).
+struct SmallPlan { int passes, rb; };
+inline SmallPlan small_plan(int key_bits) {
+  SmallPlan sp;
+  sp.passes = (key_bits + 9) / 10;
+  sp.rb = (key_bits + 7) / 8 == sp.passes ? 8 : 10;
+  return sp;
+}
+inline bool small_eligible(int64_t n, int key_bits) {
+  return n > 0 && key_bits > 0 && ceil_div(n, kSmallTile) <= kSmallMaxTiles;
+}
+// words of the counts table for S sorts
+inline size_t small_table_words(int64_t n, int S, int key_bits) {
+  const SmallPlan sp = small_plan(key_bits);
+  return (size_t)S * sp.passes * (size_t)ceil_div(n, kSmallTile) * ((size_t)1 << sp.rb);
+}
 
 // Workspace for S sorts of n words.  Control area (cleared by every call): error word, tickets
 // [S][P], histograms [S][P][256], tile status [S][P][tiles][256].
-void make_layout(int64_t n, int S, int P, int num_frames, Layout* L) {
+void make_layout(int64_t n, int S, int P, int num_frames, int max_key_bits, Layout* L) {
   L->P = P;
   L->kpt = n <= (1 << 19) ? 4 : 16;
   L->tiles = ceil_div(n > 0 ? n : 1, (int64_t)kSortThreads * L->kpt);
@@ -399,6 +719,12 @@ void make_layout(int64_t n, int S, int P, int num_frames, Layout* L) {
   L->control_words = 64 + (size_t)S * P + (size_t)S * P * kBins + (size_t)S * P * L->tiles * kBins;
   off += align_up(L->control_words * 4, 256);
   L->off_frames = off; off += align_up((size_t)S * 2 * ((size_t)num_frames + 1) * 4, 256);
+  // Small-cloud tables, sized for any key width up to max_key_bits (a call may sort narrower keys
+  // than the workspace query assumed, and a narrower key can pick a wider digit).
+  size_t small_words = 0;
+  for (int kb = 1; kb <= max_key_bits; ++kb)
+    if (small_eligible(n, kb)) { const size_t w = small_table_words(n, S, kb); if (w > small_words) small_words = w; }
+  L->off_small = off; off += align_up(small_words * 4, 256);
   L->total = off;
 }
 
@@ -435,7 +761,7 @@ size_t flatten_workspace_bytes(int64_t n, const ff_geom* g, int num_sorts) {
   if (num_sorts < 1 || num_sorts > kMaxSorts) return 0;
   if (make_flatten_plan(n, g, 0, 1, &p) != FF_OK) return 0;
   Layout L;
-  make_layout(n, num_sorts, p.passes > 0 ? p.passes : 1, g->num_frames, &L);
+  make_layout(n, num_sorts, p.passes > 0 ? p.passes : 1, g->num_frames, p.key_bits, &L);
   return L.total;
 }
 
@@ -445,7 +771,7 @@ int flatten_launch(const int32_t* coords, int64_t n, const ff_geom* g, int num_s
                    size_t workspace_bytes, hipStream_t stream) {
   if (num_sorts < 1 || num_sorts > kMaxSorts || G < 1) return FF_ERR_ARG;
   Batch bt;
-  int P = 0;
+  int P = 0, max_key_bits = 0;
   for (int s = 0; s < num_sorts; ++s) {
     FlattenPlan plan;
     const int st = make_flatten_plan(n, g, axis[s], shift[s], &plan);
@@ -461,6 +787,7 @@ int flatten_launch(const int32_t* coords, int64_t n, const ff_geom* g, int num_s
     bt.perm[s] = perm[s]; bt.group_offsets[s] = group_offsets[s]; bt.num_groups[s] = num_groups[s];
     bt.keys_sorted[s] = keys_sorted ? keys_sorted[s] : nullptr;
     if (plan.passes > P) P = plan.passes;
+    if (plan.key_bits > max_key_bits) max_key_bits = plan.key_bits;
   }
   for (int s = num_sorts; s < kMaxSorts; ++s) {
     bt.kp[s] = bt.kp[0]; bt.perm[s] = nullptr; bt.group_offsets[s] = nullptr; bt.num_groups[s] = nullptr;
@@ -468,7 +795,7 @@ int flatten_launch(const int32_t* coords, int64_t n, const ff_geom* g, int num_s
   }
   if (n > 0 && !coords) return FF_ERR_ARG;
   Layout L;
-  make_layout(n, num_sorts, P > 0 ? P : 1, g->num_frames, &L);
+  make_layout(n, num_sorts, P > 0 ? P : 1, g->num_frames, max_key_bits, &L);
   if (!workspace || ((uintptr_t)workspace & 255) || workspace_bytes < L.total) return FF_ERR_WORKSPACE;
 
   char* ws = (char*)workspace;
@@ -480,11 +807,40 @@ int flatten_launch(const int32_t* coords, int64_t n, const ff_geom* g, int num_s
   uint32_t* status = hist + (size_t)num_sorts * L.P * kBins;
   int32_t* frame_tab = (int32_t*)(ws + L.off_frames);
 
-  int64_t cblocks = ceil_div((int64_t)L.control_words, 256 * 4);
-  if (cblocks > 1024) cblocks = 1024;
-  hipLaunchKernelGGL(k_clear, dim3((unsigned)cblocks), dim3(256), 0, stream, control, (int64_t)L.control_words);
   int cur = 0;
-  if (n > 0) {
+  const bool small = small_eligible(n, max_key_bits);
+  if (small) {
+    const SmallPlan sp = small_plan(max_key_bits);
+    const int tiles = (int)ceil_div(n, kSmallTile);
+    uint32_t* counts = (uint32_t*)(ws + L.off_small);
+    // The last pass can write the outputs itself when its digit contains the whole frame field.
+    bool fuse = true;
+    for (int s = 0; s < num_sorts; ++s)
+      fuse = fuse && bt.kp[s].key_bits - (sp.passes - 1) * sp.rb >= bt.kp[s].bits_b;
+    const dim3 grid((unsigned)tiles, (unsigned)num_sorts);
+#define FF_SMALL(RB)                                                                                                   \
+    do {                                                                                                               \
+      hipLaunchKernelGGL(k_keygen_small<RB>, grid, dim3(kSortThreads), 0, stream, coords, n, bt, sp.passes, tiles,    \
+                         buf[0], counts, error_word);                                                                  \
+      for (int pass = 0; pass < sp.passes; ++pass) {                                                                   \
+        if (fuse && pass == sp.passes - 1)                                                                             \
+          hipLaunchKernelGGL((k_pass_small<RB, true>), grid, dim3(kSortThreads), 0, stream, buf[cur], buf[cur ^ 1], n, \
+                             bt, pass, sp.passes, tiles, G, counts);                                                   \
+        else                                                                                                           \
+          hipLaunchKernelGGL((k_pass_small<RB, false>), grid, dim3(kSortThreads), 0, stream, buf[cur], buf[cur ^ 1],  \
+                             n, bt, pass, sp.passes, tiles, G, counts);                                                \
+        cur ^= 1;                                                                                                      \
+      }                                                                                                                \
+    } while (0)
+    if (sp.rb == 8) FF_SMALL(8); else FF_SMALL(10);
+#undef FF_SMALL
+    if (fuse) return launch_status();
+  } else {
+    int64_t cblocks = ceil_div((int64_t)L.control_words, 256 * 4);
+    if (cblocks > 1024) cblocks = 1024;
+    hipLaunchKernelGGL(k_clear, dim3((unsigned)cblocks), dim3(256), 0, stream, control, (int64_t)L.control_words);
+  }
+  if (n > 0 && !small) {
     hipLaunchKernelGGL(k_keygen_hist, dim3((unsigned)ceil_div(n, 1024), (unsigned)num_sorts), dim3(256),
                        (size_t)L.P * kBins * 4, stream, coords, n, bt, L.P, buf[0], hist);
     // 256 compute units hold far more than 512 of these workgroups at once

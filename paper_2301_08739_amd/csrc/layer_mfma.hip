@@ -28,6 +28,7 @@
 
 #ifdef FF_PROBE
 __device__ long long ff_probe_ts_global[2][64];
+__device__ long long ff_probe_blk[2][2048];  // wall-clock start and end of wave 0 of every workgroup
 #endif
 
 namespace ff {
@@ -105,8 +106,13 @@ __device__ __forceinline__ float gelu2_fast(float v) {
 #define ff_probe_ts ff_probe_ts_global
 #define FF_TS(k) do { ff_tsw[k] = wall_clock64(); ff_tsc[k] = clock64(); } while (0)
 #define FF_TS_DECL long long ff_tsw[24] = {0}, ff_tsc[24] = {0};
+#define FF_TS_WAIT(k) do { asm volatile("s_waitcnt vmcnt(0) lgkmcnt(0)" ::: "memory"); FF_TS(k); } while (0)
 #define FF_TS_DUMP                                                                        \
   do {                                                                                    \
+    if (threadIdx.x == 0 && blockIdx.x < 2048) {                                          \
+      ff_probe_blk[0][blockIdx.x] = ff_tsw[0];                                            \
+      ff_probe_blk[1][blockIdx.x] = wall_clock64();                                       \
+    }                                                                                     \
     if ((threadIdx.x == 0) && (blockIdx.x == 0 || blockIdx.x == gridDim.x / 2)) {         \
       for (int k = 0; k < 24; ++k) {                                                      \
         ff_probe_ts[blockIdx.x == 0 ? 0 : 1][k] = ff_tsw[k];                              \
@@ -116,6 +122,7 @@ __device__ __forceinline__ float gelu2_fast(float v) {
   } while (0)
 #else
 #define FF_TS(k) do { } while (0)
+#define FF_TS_WAIT(k) do { } while (0)
 #define FF_TS_DECL
 #define FF_TS_DUMP do { } while (0)
 #endif
@@ -136,8 +143,13 @@ __host__ __device__ constexpr int frags_per_fc(int C) { return 2 * (C / 32) + C 
 constexpr int kPackBatch = 16;
 struct PackBatch {  // up to 16 layers of identical shape packed by one launch (grid.y = layer)
   const uint16_t *w_qkv[kPackBatch], *w_o[kPackBatch], *w1[kPackBatch], *w2[kPackBatch];
+  const uint16_t *b_qkv[kPackBatch], *b_o[kPackBatch];
   uint4* out[kPackBatch];
 };
+// After the fragments the packed buffer holds C floats: the output-projection bias with the value
+// bias folded in.  Every softmax row sums to one, so P (V + 1 b_v^T) W_o^T = P V W_o^T + (W_o b_v)^T:
+// the value bias is a constant row added after the projection.  (The key bias shifts all scores
+// of a query by the same amount and drops out of the softmax altogether.)
 __global__ __launch_bounds__(256) void k_pack_weights(PackBatch pb, int C, int F, int total_frags) {
   const uint16_t* __restrict__ w_qkv = pb.w_qkv[blockIdx.y];
   const uint16_t* __restrict__ w_o = pb.w_o[blockIdx.y];
@@ -146,7 +158,20 @@ __global__ __launch_bounds__(256) void k_pack_weights(PackBatch pb, int C, int F
   uint4* __restrict__ out = pb.out[blockIdx.y];
   const int t = blockIdx.x * blockDim.x + threadIdx.x;
   const int frag = t >> 6, lane = t & 63, i = lane & 15, q = lane >> 4;
-  if (frag >= total_frags) return;
+  if (frag >= total_frags) {  // folded output bias: eight lanes per output feature
+    const int u = t - total_frags * 64, o = u >> 3, seg = u & 7, len = C / 8;
+    float acc = 0.f;
+    if (o < C) {
+      const uint16_t* __restrict__ bv = pb.b_qkv[blockIdx.y] + 2 * C;
+      for (int k = seg * len; k < (seg + 1) * len; ++k)
+        acc = fmaf(bf16_to_f32(w_o[(size_t)o * C + k]), bf16_to_f32(bv[k]), acc);
+    }
+    acc += __shfl_xor(acc, 1);
+    acc += __shfl_xor(acc, 2);
+    acc += __shfl_xor(acc, 4);
+    if (o < C && seg == 0) reinterpret_cast<float*>(out + (size_t)total_frags * 64)[o] = acc + bf16_to_f32(pb.b_o[blockIdx.y][o]);
+    return;
+  }
   const int KB = C / 32, NB = C / 16, fr_hp = 6 * KB + NB, fr_fc = 2 * KB + NB, n_hp = C / 32;
   const uint16_t* src;
   int kbase;
@@ -187,11 +212,11 @@ __global__ __launch_bounds__(256) void k_pack_weights(PackBatch pb, int C, int F
 }
 
 // ---- the fused layer ------------------------------------------------------------------------------
-// LDS map (bytes): [weight ring RING x 16 KB][small parameters as fp32: (9C + F) x 4][K/V exchange, 2 buffers].
+// LDS map (bytes): [weight ring RING x 16 KB][small parameters as fp32: (7C + F) x 4][K/V exchange, 2 buffers].
 template <int C, int F>
 struct ParamOff {  // float offsets inside the small-parameter area
-  static constexpr int LN1G = 0, LN1B = C, BQ = 2 * C, BK = 3 * C, BV = 4 * C, BO = 5 * C, LN2G = 6 * C,
-                       LN2B = 7 * C, B2 = 8 * C, B1 = 9 * C, TOTAL = 9 * C + F;
+  static constexpr int LN1G = 0, LN1B = C, BQ = 2 * C, BO = 3 * C, LN2G = 4 * C, LN2B = 5 * C, B2 = 6 * C,
+                       B1 = 7 * C, TOTAL = 7 * C + F;
 };
 
 constexpr int kChunkFrags = 16;        // fragments per staged chunk (16 KB)
@@ -217,7 +242,8 @@ __global__ __launch_bounds__(NW * 64, MINW) void k_layer_mfma(const uint16_t* __
                                                                const int32_t* __restrict__ perm,
                                                                const int32_t* __restrict__ goff,
                                                                const int32_t* __restrict__ num_groups, int max_groups,
-                                                               const u32x4* __restrict__ packed, SmallParams sp, float eps) {
+                                                               const u32x4* __restrict__ packed, SmallParams sp, float eps,
+                                                               int n, int G) {
   constexpr int KB = C / 32;          // 32-wide blocks of the input features
   constexpr int NB = C / 16;          // 16-wide blocks of the output features
   constexpr int HP = C / 32;          // 32-wide head-dim units
@@ -242,7 +268,11 @@ __global__ __launch_bounds__(NW * 64, MINW) void k_layer_mfma(const uint16_t* __
 
   extern __shared__ u32x4 lds[];
   u32x4* ring = lds;                                            // [RING][CF * 64]
-  float* par = reinterpret_cast<float*>(lds + RING * CF * 64);  // [PO::TOTAL]
+  // These areas lie beyond the 64 KB an LDS instruction reaches from a base register: their offset
+  // is hidden from constant folding so that each gets a base register of its own.
+  uint32_t par_units = RING * CF * 64;
+  asm volatile("" : "+v"(par_units));
+  float* par = reinterpret_cast<float*>(lds + par_units);       // [PO::TOTAL]
   u32x2* kvx = reinterpret_cast<u32x2*>(par + PO::TOTAL);       // K/V exchange, only when WPG > 1
 
   const int tid = threadIdx.x, lane = tid & 63, w = tid >> 6, i = lane & 15, q = lane >> 4;
@@ -251,12 +281,23 @@ __global__ __launch_bounds__(NW * 64, MINW) void k_layer_mfma(const uint16_t* __
   const int g = blockIdx.x * GPW + gl;
   // group_offsets has at least max_groups + 1 entries: read this group's bounds without waiting
   // for num_groups, so that the loads travel together.
+  FF_TS_DECL
+  FF_TS(0);
   const int gc = g < max_groups ? g : max_groups - 1;
   const int off0 = goff[gc], off1 = goff[gc + 1];
+  const int ngroups = *num_groups;
+  // Groups of the first (or only) frame start at g * G: fetch the pillar indices from there
+  // without waiting for the offsets, and use them if the guess turns out right.
+  int32_t guess[NVB];
+#pragma unroll
+  for (int vb = 0; vb < NVB; ++vb) {
+    const int64_t at = (int64_t)g * G + (part * NVB + vb) * 16 + i;
+    guess[vb] = perm[at < n ? at : n - 1];
+  }
+  FF_TS_WAIT(16);
   int start = 0, m = 0;
-  if (g < *num_groups) { start = off0; m = off1 - off0; }
+  if (g < ngroups) { start = off0; m = off1 - off0; }
 
-  FF_TS_DECL
   // ---- weight stream: global memory -> LDS ring -> registers -----------------------------------------
   // Chunk c of the packed stream lives in ring slot c % RING.  `issued` chunks have been requested,
   // chunks below `visible` are known to have landed for every wavefront.  Both advance only at
@@ -298,7 +339,6 @@ __global__ __launch_bounds__(NW * 64, MINW) void k_layer_mfma(const uint16_t* __
     return slot < 4 ? ring_lo + slot * CF * 64 : ring_hi + (slot - 4) * CF * 64;
   };
 
-  FF_TS(0);
   issue(0);
   issue(1);
   issued = 2;
@@ -307,12 +347,15 @@ __global__ __launch_bounds__(NW * 64, MINW) void k_layer_mfma(const uint16_t* __
   for (int t = tid; t < PO::TOTAL; t += NT) {
     const uint16_t* src;
     int o;
+    if (t >= PO::BO && t < PO::BO + C) {  // folded output bias, fp32, behind the fragments
+      par[t] = reinterpret_cast<const float*>(packed + (size_t)NCHUNK * CF * 64)[t - PO::BO];
+      continue;
+    }
     if (t < 2 * C) { src = t < C ? sp.ln1_g : sp.ln1_b; o = t < C ? t : t - C; }
-    else if (t < 5 * C) { src = sp.b_qkv; o = t - 2 * C; }
-    else if (t < 6 * C) { src = sp.b_o; o = t - 5 * C; }
-    else if (t < 8 * C) { src = t < 7 * C ? sp.ln2_g : sp.ln2_b; o = t < 7 * C ? t - 6 * C : t - 7 * C; }
-    else if (t < 9 * C) { src = sp.b2; o = t - 8 * C; }
-    else { src = sp.b1; o = t - 9 * C; }
+    else if (t < 3 * C) { src = sp.b_qkv; o = t - 2 * C; }
+    else if (t < 6 * C) { src = t < 5 * C ? sp.ln2_g : sp.ln2_b; o = t < 5 * C ? t - 4 * C : t - 5 * C; }
+    else if (t < 7 * C) { src = sp.b2; o = t - 6 * C; }
+    else { src = sp.b1; o = t - 7 * C; }
     par[t] = bf16_to_f32(src[o]);
   }
 
@@ -322,8 +365,10 @@ __global__ __launch_bounds__(NW * 64, MINW) void k_layer_mfma(const uint16_t* __
 #pragma unroll
   for (int vb = 0; vb < NVB; ++vb) {
     const int s = (part * NVB + vb) * 16 + i;
-    row[vb] = s < m ? perm[start + s] : -1;
+    if ((int64_t)g * G == start) row[vb] = s < m ? guess[vb] : -1;  // wave-uniform
+    else row[vb] = s < m ? perm[start + s] : -1;
   }
+  FF_TS_WAIT(17);
 #pragma unroll
   for (int vb = 0; vb < NVB; ++vb) {
 #pragma unroll
@@ -385,15 +430,12 @@ __global__ __launch_bounds__(NW * 64, MINW) void k_layer_mfma(const uint16_t* __
       for (int vb = 0; vb < NVB; ++vb) x1[vb][nb] += b;
     }
   };
-  // Biases of the Q, K (accumulator layout) and V (swapped roles: one feature per lane) rows of a unit.
-  f32x4 bqk[4];
-  float bvv[2];
+  // Bias of the Q rows of a unit (accumulator layout).  K and V start from zero: the key bias has no
+  // effect on the softmax and the value bias is part of the folded output bias.
+  f32x4 bqk[2];
   auto load_unit_bias = [&](int hp) {
 #pragma unroll
-    for (int c = 0; c < 4; ++c)
-      bqk[c] = *reinterpret_cast<const f32x4*>(par + (c < 2 ? PO::BQ : PO::BK) + 32 * hp + 16 * (c & 1) + 4 * q);
-#pragma unroll
-    for (int a = 0; a < 2; ++a) bvv[a] = par[PO::BV + 32 * hp + 16 * a + i];
+    for (int c = 0; c < 2; ++c) bqk[c] = *reinterpret_cast<const f32x4*>(par + PO::BQ + 32 * hp + 16 * c + 4 * q);
   };
   load_unit_bias(0);
   layer_norm(PO::LN1G, PO::LN1B);
@@ -447,7 +489,7 @@ __global__ __launch_bounds__(NW * 64, MINW) void k_layer_mfma(const uint16_t* __
           if (kb == 0) {  // the accumulator starts from the bias
 #pragma unroll
             for (int vb = 0; vb < NVB; ++vb)
-              acc[ch & 1][vb] = ch < 4 ? bqk[ch] : f32x4{bvv[ch & 1], bvv[ch & 1], bvv[ch & 1], bvv[ch & 1]};
+              acc[ch & 1][vb] = ch < 2 ? bqk[ch] : f32x4{0.f, 0.f, 0.f, 0.f};
           }
 #pragma unroll
           for (int vb = 0; vb < NVB; ++vb)
@@ -705,13 +747,16 @@ __global__ __launch_bounds__(NW * 64, MINW) void k_layer_mfma(const uint16_t* __
 extern "C" int ff_debug_read_probe(long long* host_out) {
   return (int)hipMemcpyFromSymbol(host_out, HIP_SYMBOL(ff_probe_ts_global), sizeof(long long) * 128);
 }
+extern "C" int ff_debug_read_probe_blocks(long long* host_out) {
+  return (int)hipMemcpyFromSymbol(host_out, HIP_SYMBOL(ff_probe_blk), sizeof(long long) * 4096);
+}
 namespace ff {
 namespace {
 #endif
 
 template <int C, int DH, int F, int NVB, int WPG, int NW, int MINW>
 int launch_cfg(const void* feats, void* out, const int32_t* perm, const int32_t* goff, const int32_t* num_groups,
-               int32_t max_groups, const u32x4* packed, const SmallParams& sp, float eps, bool out_f32,
+               int32_t max_groups, const u32x4* packed, const SmallParams& sp, float eps, bool out_f32, int n, int G,
                hipStream_t stream) {
   constexpr int GPW = NW / WPG;
   const size_t lds_bytes = LdsPlan<C, F, NVB, WPG, NW, MINW>::TOTAL;
@@ -725,7 +770,7 @@ int launch_cfg(const void* feats, void* out, const int32_t* perm, const int32_t*
       attr_done = true;
     }
     hipLaunchKernelGGL(kern, dim3(blocks), dim3(NW * 64), lds_bytes, stream, (const uint16_t*)feats, out, perm, goff,
-                       num_groups, (int)max_groups, packed, sp, eps);
+                       num_groups, (int)max_groups, packed, sp, eps, n, G);
     return launch_status();
   };
   if (out_f32) return go(k_layer_mfma<C, DH, F, NVB, WPG, NW, MINW, true>);
@@ -744,14 +789,19 @@ static int shape_id(const ff_layer_weights* w) {
 
 bool layer_mfma_supported(const ff_layer_weights* w, int G) { return shape_id(w) != 0 && G <= 128; }
 
+static size_t layer_mfma_frag_count(const ff_layer_weights* w) {
+  const int C = w->C, F = w->F;
+  return (size_t)((C / 32) * frags_per_hp(C) + (F / 32) * frags_per_fc(C));
+}
+
 size_t layer_mfma_packed_bytes(const ff_layer_weights* w) {
   const int C = w->C, F = w->F;
-  return (size_t)((C / 32) * frags_per_hp(C) + (F / 32) * frags_per_fc(C)) * 1024;
+  return layer_mfma_frag_count(w) * (size_t)1024 + (size_t)C * 4;
 }
 
 // Packs `count` layers of identical shape; layer l goes to packed + l * stride_bytes.
 int layer_mfma_pack(const ff_layer_weights* w, int count, void* packed, size_t stride_bytes, hipStream_t stream) {
-  const int total = (int)(layer_mfma_packed_bytes(w) / 1024);
+  const int total = (int)layer_mfma_frag_count(w);
   for (int l0 = 0; l0 < count; l0 += kPackBatch) {
     const int nl = count - l0 < kPackBatch ? count - l0 : kPackBatch;
     PackBatch pb;
@@ -759,9 +809,10 @@ int layer_mfma_pack(const ff_layer_weights* w, int count, void* packed, size_t s
       const ff_layer_weights* wl = &w[l0 + (l < nl ? l : 0)];
       pb.w_qkv[l] = (const uint16_t*)wl->w_qkv; pb.w_o[l] = (const uint16_t*)wl->w_o;
       pb.w1[l] = (const uint16_t*)wl->w1; pb.w2[l] = (const uint16_t*)wl->w2;
+      pb.b_qkv[l] = (const uint16_t*)wl->b_qkv; pb.b_o[l] = (const uint16_t*)wl->b_o;
       pb.out[l] = (uint4*)((char*)packed + (size_t)(l0 + (l < nl ? l : 0)) * stride_bytes);
     }
-    hipLaunchKernelGGL(k_pack_weights, dim3((unsigned)((total * 64 + 255) / 256), (unsigned)nl), dim3(256), 0, stream,
+    hipLaunchKernelGGL(k_pack_weights, dim3((unsigned)((total * 64 + 8 * w->C + 255) / 256), (unsigned)nl), dim3(256), 0, stream,
                        pb, w->C, w->F, total);
   }
   return launch_status();
@@ -771,22 +822,21 @@ int layer_mfma_pack(const ff_layer_weights* w, int count, void* packed, size_t s
 int layer_mfma_launch(const void* feats, void* out, int64_t n, const int32_t* perm, const int32_t* group_offsets,
                       const int32_t* num_groups, int32_t max_groups, const ff_layer_weights* w, int G,
                       bool out_f32, const void* packed, int variant, hipStream_t stream) {
-  (void)n;
-  if (max_groups == 0) return FF_OK;
+  if (max_groups == 0 || n == 0) return FF_OK;
   SmallParams sp{(const uint16_t*)w->ln1_g, (const uint16_t*)w->ln1_b, (const uint16_t*)w->b_qkv,
                  (const uint16_t*)w->b_o,   (const uint16_t*)w->ln2_g, (const uint16_t*)w->ln2_b,
                  (const uint16_t*)w->b1,    (const uint16_t*)w->b2};
   const u32x4* pk = (const u32x4*)packed;
 #define FF_GO(C, DH, F, NVB, WPG, NW, MINW) \
   return launch_cfg<C, DH, F, NVB, WPG, NW, MINW>(feats, out, perm, group_offsets, num_groups, max_groups, pk, sp, \
-                                                  w->ln_eps, out_f32, stream)
+                                                  w->ln_eps, out_f32, (int)n, G, stream)
   const int shape = shape_id(w);
   // (pillar blocks per wave, waves per group, waves per workgroup, min waves per SIMD)
   if (shape == 1) {
     if (variant == 0) variant = G <= 32 ? 10 : G <= 64 ? 7 : 9;
     switch (variant) {
       case 1: if (G <= 32) FF_GO(128, 16, 256, 2, 1, 4, 2); break;
-      case 2: if (G <= 64) FF_GO(128, 16, 256, 2, 2, 4, 2); break;
+      case 2: if (G <= 64) FF_GO(128, 16, 256, 2, 2, 4, 1); break;  // 512 registers
       case 4: if (G <= 128) FF_GO(128, 16, 256, 2, 4, 4, 1); break;
       case 6: if (G <= 64) FF_GO(128, 16, 256, 1, 4, 4, 2); break;
       case 7: if (G <= 64) FF_GO(128, 16, 256, 1, 4, 8, 2); break;

@@ -41,10 +41,11 @@ def _rand_coords(n, B, gx, gy, seed, unique=True):
     return np.stack([b, x, y], axis=1).astype(np.int32)
 
 
-@pytest.mark.parametrize("n", [0, 1, 2, 63, 64, 65, 2047, 2048, 2049, 4096, 5000])
+@pytest.mark.parametrize("n", [0, 1, 2, 63, 64, 65, 2047, 2048, 2049, 4095, 4096, 4097, 5000, 12288, 65536, 65537])
 def test_sizes_around_tile_edges(n):
-    coords = _rand_coords(n, 3, 90, 70, seed=n, unique=True)
-    g, og = ff.Geometry(3, 90, 70, 7, 5), oracle.Geometry(3, 90, 70, 7, 5)
+    gx, gy = (90, 70) if n <= 3 * 90 * 70 else (300, 200)
+    coords = _rand_coords(n, 3, gx, gy, seed=n, unique=True)
+    g, og = ff.Geometry(3, gx, gy, 7, 5), oracle.Geometry(3, gx, gy, 7, 5)
     for axis, shift in [(0, 1), (1, 0)]:
         _check(coords, g, og, axis, shift, 10)
 
