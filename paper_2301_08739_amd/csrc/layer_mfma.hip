@@ -385,11 +385,12 @@ __global__ __launch_bounds__(NW * 64, MINW) void k_layer_mfma(const uint16_t* __
   // The window: fragments j .. j + PF - 1 of the stream are in registers (or on their way) while
   // fragment j is being used.
   Frag8 win[PF];
-  {
+  auto fill_window = [&]() {
     const u32x4* p0 = slot_ptr(0);
 #pragma unroll
     for (int f = 0; f < PF; ++f) win[f].q = p0[f * 64];
-  }
+  };
+  if (!LEAN) fill_window();  // early, so that the reads overlap the LayerNorm arithmetic
   __builtin_amdgcn_sched_barrier(0);
 
   Frag8 act[NVB][KB];  // normalised activations as B operands (LN1 output, later LN2 output)
@@ -437,9 +438,10 @@ __global__ __launch_bounds__(NW * 64, MINW) void k_layer_mfma(const uint16_t* __
 #pragma unroll
     for (int c = 0; c < 2; ++c) bqk[c] = *reinterpret_cast<const f32x4*>(par + PO::BQ + 32 * hp + 16 * c + 4 * q);
   };
-  load_unit_bias(0);
+  if (!LEAN) load_unit_bias(0);
   layer_norm(PO::LN1G, PO::LN1B);
   add_bias_rows(PO::BO);  // residual + output-projection bias
+  if (LEAN) { __builtin_amdgcn_sched_barrier(0); fill_window(); }
 
   FF_TS(3);
   const float qscale = rsqrtf((float)DH) * 1.44269504088896340736f;  // 1/sqrt(d) * log2(e)
@@ -663,7 +665,7 @@ __global__ __launch_bounds__(NW * 64, MINW) void k_layer_mfma(const uint16_t* __
 #pragma unroll
     for (int a = 0; a < 2; ++a) b1r[a] = *reinterpret_cast<const f32x4*>(par + PO::B1 + 32 * fc + 16 * a + 4 * q);
   };
-  load_b1(0);
+  if (!LEAN) load_b1(0);
   layer_norm(PO::LN2G, PO::LN2B);
   add_bias_rows(PO::B2);
   FF_TS(11);
@@ -681,6 +683,7 @@ __global__ __launch_bounds__(NW * 64, MINW) void k_layer_mfma(const uint16_t* __
       __builtin_amdgcn_sched_barrier(0);
     };
     Frag8 Hf[NVB];
+    if (LEAN) load_b1(fc);
     {
       f32x4 acc[2][NVB];
       auto finish = [&](int a) {
@@ -708,7 +711,7 @@ __global__ __launch_bounds__(NW * 64, MINW) void k_layer_mfma(const uint16_t* __
       }
       finish(1);
     }
-    load_b1(fc + 1 < FC ? fc + 1 : fc);
+    if (!LEAN) load_b1(fc + 1 < FC ? fc + 1 : fc);
 #pragma unroll
     for (int nb = 0; nb < NB; ++nb) {
       const int j = 2 * KB + nb;
@@ -849,9 +852,10 @@ int layer_mfma_launch(const void* feats, void* out, int64_t n, const int32_t* pe
     switch (variant) {
       case 1: if (G <= 32) FF_GO(256, 32, 512, 1, 2, 8, 2); break;
       case 2: if (G <= 64) FF_GO(256, 32, 512, 1, 4, 8, 2); break;
-      case 3: if (G <= 80) FF_GO(256, 32, 512, 1, 5, 5, 1); break;
+      case 3: if (G <= 80) FF_GO(256, 32, 512, 1, 5, 10, 2); break;  // lean: 168 registers, no scratch
       case 4: if (G <= 128) FF_GO(256, 32, 512, 1, 8, 8, 2); break;
       case 5: if (G <= 64) FF_GO(256, 32, 512, 2, 2, 4, 1); break;
+      case 6: if (G <= 80) FF_GO(256, 32, 512, 1, 5, 5, 1); break;
       default: break;
     }
   }

@@ -193,7 +193,7 @@ def test_bf16_wide_layer_group_sizes(cfg, G):
     narrow = to_host(ff.ff_group_attention(x, dev[0], dev[1], dev[2], mg, lw, G, ff.FF_BF16, 0))
     ew, en = _assert_bf16_bar(wide, narrow, want)
     print(f"C=256 G={G}: f32-store err {ew:.3e}, bf16-store err {en:.3e}", flush=True)
-    for variant, slots in [(1, 32), (2, 64), (3, 80), (4, 128), (5, 64)]:
+    for variant, slots in [(1, 32), (2, 64), (3, 80), (4, 128), (5, 64), (6, 80)]:
         fl = ff.FF_FLAG_OUT_F32 | ff.FF_FLAG_VARIANT(variant)
         if G > slots:
             with pytest.raises(ff.FlatformerError):
