@@ -428,7 +428,6 @@ __global__ __launch_bounds__(kSortThreads) void k_pass_small(const uint64_t* __r
       }
   }
 
-  asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
   FP_TS(1);
 #pragma unroll
   for (int i = 0; i < WAVES; ++i)
@@ -515,8 +514,6 @@ __global__ __launch_bounds__(kSortThreads) void k_pass_small(const uint64_t* __r
       }
     }
     FP_TS(4);
-    asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
-    FP_TS(5);
     return;
   }
 
@@ -571,8 +568,6 @@ __global__ __launch_bounds__(kSortThreads) void k_pass_small(const uint64_t* __r
     }
   }
   FP_TS(4);
-  asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
-  FP_TS(5);
   if (tile == 0 && tid == 0) {
     *bt.num_groups[s] = (int32_t)ng_total;
     bt.group_offsets[s][ng_total] = (int32_t)n;

@@ -200,13 +200,21 @@ __global__ __launch_bounds__(256) void k_pack_weights(PackBatch pb, int C, int F
       halve = true;
     }
   }
+  // slots 0..3 are inputs kbase + 4q .. + 3, slots 4..7 the same plus 16: two 8-byte loads
   uint32_t u[4];
 #pragma unroll
-  for (int s = 0; s < 8; s += 2) {
-    const int k0 = kbase + 16 * (s / 4) + 4 * q + (s % 4);
-    uint16_t lo = src[k0], hi = src[k0 + 1];
-    if (halve) { lo = f32_to_bf16(0.5f * bf16_to_f32(lo)); hi = f32_to_bf16(0.5f * bf16_to_f32(hi)); }
-    u[s / 2] = (uint32_t)lo | ((uint32_t)hi << 16);
+  for (int h = 0; h < 2; ++h) {
+    const uint2 v = *reinterpret_cast<const uint2*>(src + kbase + 16 * h + 4 * q);
+    u[2 * h] = v.x;
+    u[2 * h + 1] = v.y;
+  }
+  if (halve) {
+#pragma unroll
+    for (int s = 0; s < 4; ++s) {
+      const uint32_t lo = f32_to_bf16(0.5f * bf16_to_f32((uint16_t)(u[s] & 0xffffu)));
+      const uint32_t hi = f32_to_bf16(0.5f * bf16_to_f32((uint16_t)(u[s] >> 16)));
+      u[s] = lo | (hi << 16);
+    }
   }
   out[(size_t)frag * 64 + lane] = make_uint4(u[0], u[1], u[2], u[3]);
 }
