@@ -3,19 +3,28 @@
 //
 // Each pillar becomes ONE 64-bit word  (compact_key << idx_bits) | original_index, where the
 // compact key packs the tuple fields (b, W_major, W_minor, L_major, L_minor) using only as many
-// bits as the geometry needs.  An LSD radix sort over the compact-key bits, 8 bits per pass, is
-// stable, so equal tuples keep ascending original index.  The word carries the index, so a pass
-// moves 8 bytes per pillar each way.
+// bits as the geometry needs.  An LSD radix sort over the compact-key bits is stable, so equal
+// tuples keep ascending original index.  The word carries the index, so a pass moves 8 bytes per
+// pillar each way.
 //
-// Launches for one call (S sort configurations of the same cloud are sorted together, one grid
-// row each): clear control words -> key generation + digit histograms of every pass -> P
-// single-sweep passes -> outputs.  A pass ranks its tile with per-wavefront ballot matching and LDS
-// counters, learns the number of equal digits in all earlier tiles by looking back through
-// per-tile status words (aggregate / inclusive-prefix flags; tiles take their number from an atomic
-// ticket, so every tile a block waits for is already running), and scatters through an LDS
-// stage so that global writes come out in runs.  Every wait is bounded: a block that exhausts its
-// spin budget raises an error word, skips its scatter, still publishes its status, and the output
-// kernel reports num_groups = -1.
+// S sort configurations of the same cloud are sorted together, one grid row each.  Workgroups on
+// different XCDs of this chip talk through memory (two microseconds and more per flag round trip),
+// so no kernel waits for another workgroup: everything a pass needs is in memory when it starts.
+//   * A table counts[pass][tile][digit] says how many words with that digit of that pass the tile
+//     holds in the order the pass reads them.  Key generation writes the rows of the first pass
+//     (plain stores) and zeroes the others; each pass adds, for every word it places, one to the
+//     row of the tile the word lands in for the next pass.  Nothing has to be cleared beforehand.
+//   * Small clouds (at most 64 tiles of 1024 words: launch and latency bound): digits of up to 10
+//     bits, and a pass reads the whole table of its pass itself (column sums = global digit
+//     starts, rows of earlier tiles = its own offsets): key generation + one launch per pass.
+//   * Larger clouds (tiles of 4096 words, 8-bit digits: bandwidth bound): per-word atomics would
+//     dominate, so passes after the first count their tiles in a kernel of their own, and a small
+//     scan kernel turns the table of a pass into exclusive prefixes over the tiles plus per-digit
+//     totals.
+//   * A tile ranks its words with per-wavefront ballot matching and LDS counters and scatters
+//     through an LDS stage so that global writes come out in runs.
+//   * The last pass writes perm, exported keys and group offsets itself when its digit contains
+//     the whole frame field; otherwise two small output kernels run.
 #include "common.h"
 
 #ifdef FF_PROBE
@@ -33,8 +42,9 @@ namespace ff {
 namespace {
 
 constexpr int kMaxSorts = 4;
-constexpr uint32_t kFlagAggregate = 1u << 30, kFlagInclusive = 2u << 30, kCountMask = (1u << 30) - 1u;
-constexpr int kSpinLimit = 1 << 20;
+constexpr int kSmallKpt = 4, kSmallMaxTiles = 64;   // small clouds: tiles of 1024 words
+constexpr int kLargeKpt = 16;                       // larger clouds: tiles of 4096 words
+constexpr int kScanThreads = 1024;
 
 struct KeyParams {
   int32_t B, win_x, win_y;
@@ -53,60 +63,6 @@ struct Batch {
 };
 
 __device__ __forceinline__ uint32_t field_mask(int bits) { return bits >= 32 ? 0xffffffffu : ((1u << bits) - 1u); }
-
-// digit of `word` in pass `pass` of a sort whose key occupies bits [idx_bits, idx_bits + key_bits)
-__device__ __forceinline__ uint32_t digit_of(uint64_t word, int idx_bits, int key_bits, int pass) {
-  const int lo = pass * kRadixBits;
-  const int nb = key_bits - lo < kRadixBits ? key_bits - lo : kRadixBits;
-  if (nb <= 0) return 0u;
-  return (uint32_t)(word >> (idx_bits + lo)) & ((1u << nb) - 1u);
-}
-
-__global__ __launch_bounds__(256) void k_clear(uint32_t* __restrict__ p, int64_t words) {
-  for (int64_t i = (int64_t)blockIdx.x * blockDim.x + threadIdx.x; i < words; i += (int64_t)gridDim.x * blockDim.x)
-    p[i] = 0u;
-}
-
-// ---- A1: coords -> sortable word, plus the digit histogram of every pass -------------------------------
-__global__ __launch_bounds__(256) void k_keygen_hist(const int32_t* __restrict__ coords, int64_t n, Batch bt, int P,
-                                                      uint64_t* __restrict__ words /*[S][n]*/,
-                                                      uint32_t* __restrict__ hist /*[S][P][256]*/) {
-  extern __shared__ uint32_t h[];  // [P][256]
-  const int s = blockIdx.y;
-  const KeyParams kp = bt.kp[s];
-  for (int t = threadIdx.x; t < P * kBins; t += blockDim.x) h[t] = 0u;
-  __syncthreads();
-  constexpr int PER_THREAD = 4;
-  const int64_t base = (int64_t)blockIdx.x * (256 * PER_THREAD);
-#pragma unroll
-  for (int r = 0; r < PER_THREAD; ++r) {
-    const int64_t i = base + r * 256 + threadIdx.x;
-    if (i < n) {
-      const uint32_t b = (uint32_t)coords[3 * i + 0];
-      const uint32_t X = (uint32_t)(coords[3 * i + 1] + kp.sx);
-      const uint32_t Y = (uint32_t)(coords[3 * i + 2] + kp.sy);
-      const uint32_t Wx = X / (uint32_t)kp.win_x, Lx = X - Wx * (uint32_t)kp.win_x;
-      const uint32_t Wy = Y / (uint32_t)kp.win_y, Ly = Y - Wy * (uint32_t)kp.win_y;
-      const uint32_t w1 = kp.axis == 0 ? Wx : Wy, w2 = kp.axis == 0 ? Wy : Wx;
-      const uint32_t l1 = kp.axis == 0 ? Lx : Ly, l2 = kp.axis == 0 ? Ly : Lx;
-      // Fields are masked to their widths so that a coordinate outside the geometry can only
-      // disturb the order, never another field's bits or any index computed from them.
-      uint64_t k = b & field_mask(kp.bits_b);
-      k = (k << kp.bits_w1) | (w1 & field_mask(kp.bits_w1));
-      k = (k << kp.bits_w2) | (w2 & field_mask(kp.bits_w2));
-      k = (k << kp.bits_l1) | (l1 & field_mask(kp.bits_l1));
-      k = (k << kp.bits_l2) | (l2 & field_mask(kp.bits_l2));
-      const uint64_t word = (k << kp.idx_bits) | (uint64_t)i;
-      words[(int64_t)s * n + i] = word;
-      for (int p = 0; p < P; ++p) atomicAdd(&h[p * kBins + digit_of(word, kp.idx_bits, kp.key_bits, p)], 1u);
-    }
-  }
-  __syncthreads();
-  for (int t = threadIdx.x; t < P * kBins; t += blockDim.x) {
-    const uint32_t c = h[t];
-    if (c) atomicAdd(&hist[(int64_t)s * P * kBins + t], c);
-  }
-}
 
 // ---- block-wide exclusive scan of one uint32 per thread ---------------------------------------
 __device__ __forceinline__ uint32_t wave_inclusive_scan(uint32_t v) {
@@ -137,172 +93,6 @@ __device__ __forceinline__ uint32_t block_exclusive_scan(uint32_t v, uint32_t* w
   __syncthreads();
   return base + inc - v;
 }
-
-// ---- A2: one radix pass in a single sweep --------------------------------------------------------
-template <int KPT>
-__global__ __launch_bounds__(kSortThreads) void k_onesweep(const uint64_t* __restrict__ in_all, uint64_t* __restrict__ out_all,
-                                                            int64_t n, Batch bt, int pass, int P, int64_t tiles,
-                                                            const uint32_t* __restrict__ hist /*[S][P][256]*/,
-                                                            uint32_t* __restrict__ status /*[S][P][tiles][256]*/,
-                                                            uint32_t* __restrict__ tickets /*[S][P]*/, int use_tickets,
-                                                            uint32_t* __restrict__ error_word) {
-  constexpr int WAVES = kSortThreads / 64;
-  constexpr int TILE = kSortThreads * KPT;
-  __shared__ uint32_t wave_cnt[WAVES][kBins];
-  __shared__ uint32_t digit_start[kBins];
-  __shared__ uint32_t gbase[kBins];
-  __shared__ uint32_t wave_totals[WAVES];
-  __shared__ uint32_t tile_s, failed_s;
-  __shared__ uint64_t stage[TILE];
-
-  const int tid = threadIdx.x, lane = tid & 63, w = tid >> 6;
-  const int s = blockIdx.y;
-  const int idx_bits = bt.kp[s].idx_bits, key_bits = bt.kp[s].key_bits;
-  const uint64_t* in = in_all + (int64_t)s * n;
-  uint64_t* out = out_all + (int64_t)s * n;
-  const int64_t slot = (int64_t)s * P + pass;
-
-  // Tile number: the block index while the whole grid is resident at once (no block can then wait
-  // for one that has not started); otherwise an atomic ticket, so that numbers follow start order.
-  if (tid == 0) { tile_s = use_tickets ? atomicAdd(&tickets[slot], 1u) : blockIdx.x; failed_s = 0u; }
-#pragma unroll
-  for (int i = 0; i < WAVES; ++i) wave_cnt[i][tid] = 0;
-  __syncthreads();
-  const int64_t tile = tile_s;
-  const int64_t tile_start = tile * TILE;
-  const int tile_count = (int)((n - tile_start) < (int64_t)TILE ? (n - tile_start) : (int64_t)TILE);
-
-  // Element order inside the tile: wave-major, then round, then lane.  Each wave owns a
-  // contiguous run of 64*KPT words, so stability only needs (wave, round, lane) order.
-  uint64_t key[KPT];
-  uint32_t rank[KPT];
-  const uint64_t lanes_below = (1ull << lane) - 1ull;
-#pragma unroll
-  for (int r = 0; r < KPT; ++r) {
-    const int e = w * 64 * KPT + r * 64 + lane;
-    const bool valid = e < tile_count;
-    key[r] = valid ? in[tile_start + e] : ~0ull;
-    const uint32_t d = digit_of(key[r], idx_bits, key_bits, pass);
-    uint64_t same = __ballot(valid);
-#pragma unroll
-    for (int b = 0; b < kRadixBits; ++b) {
-      const bool bit = (d >> b) & 1u;
-      const uint64_t bal = __ballot(bit);
-      same &= bit ? bal : ~bal;
-    }
-    const uint32_t below = __popcll(same & lanes_below);
-    const uint32_t cnt = __popcll(same);
-    uint32_t prev = 0;
-    if (valid) prev = wave_cnt[w][d];
-    if (valid && below == 0) wave_cnt[w][d] = prev + cnt;
-    rank[r] = prev + below;
-  }
-  __syncthreads();
-
-  // Thread d: count of digit d in this tile and its exclusive prefix over the tile's waves.
-  uint32_t total = 0;
-#pragma unroll
-  for (int i = 0; i < WAVES; ++i) {
-    uint32_t c = wave_cnt[i][tid];
-    wave_cnt[i][tid] = total;
-    total += c;
-  }
-  uint32_t* st = status + (slot * tiles + tile) * kBins;
-  __hip_atomic_store(&st[tid], total | (tile == 0 ? kFlagInclusive : kFlagAggregate), __ATOMIC_RELAXED,
-                     __HIP_MEMORY_SCOPE_AGENT);
-
-  // first output position of digit d over the whole array, and this tile's scan over digits
-  const uint32_t dbase = block_exclusive_scan<kSortThreads>(hist[slot * kBins + tid], wave_totals, nullptr);
-  digit_start[tid] = block_exclusive_scan<kSortThreads>(total, wave_totals, nullptr);
-
-  // Look back over earlier tiles for the number of digit-d words before this tile, eight status
-  // words per round trip (the loads are independent, so their latencies overlap).  Walking from
-  // the nearest tile down, counts are added until a tile that already knows its inclusive prefix.
-  uint32_t before = 0;
-  if (tile > 0) {
-    constexpr int LB = 8;
-    int64_t hi = tile - 1;
-    int spins = 0;
-    bool done = false;
-    while (!done) {
-      uint32_t v[LB];
-      bool ready = true;
-#pragma unroll
-      for (int u = 0; u < LB; ++u) {
-        const int64_t t = hi - u;
-        v[u] = t >= 0 ? __hip_atomic_load(&status[(slot * tiles + t) * kBins + tid], __ATOMIC_RELAXED,
-                                          __HIP_MEMORY_SCOPE_AGENT)
-                      : kFlagInclusive;
-      }
-#pragma unroll
-      for (int u = 0; u < LB; ++u) {  // usable prefix of the batch: up to the first inclusive word
-        if (done) continue;
-        const uint32_t flag = v[u] & ~kCountMask;
-        if (flag == 0u) { ready = false; break; }
-        if (flag == kFlagInclusive) break;
-      }
-      if (!ready) {
-        if (++spins > kSpinLimit) { failed_s = 1u; break; }
-        __builtin_amdgcn_s_sleep(1);
-        continue;
-      }
-#pragma unroll
-      for (int u = 0; u < LB; ++u) {
-        if (done) continue;
-        before += v[u] & kCountMask;
-        if ((v[u] & ~kCountMask) == kFlagInclusive) done = true;
-      }
-      hi -= LB;
-    }
-    __hip_atomic_store(&st[tid], ((before + total) & kCountMask) | kFlagInclusive, __ATOMIC_RELAXED,
-                       __HIP_MEMORY_SCOPE_AGENT);
-  }
-  gbase[tid] = dbase + before;
-  __syncthreads();
-  if (failed_s) {  // never expected; keeps every later access in bounds
-    if (tid == 0) atomicOr(error_word, 1u);
-    return;
-  }
-
-#pragma unroll
-  for (int r = 0; r < KPT; ++r) {
-    const int e = w * 64 * KPT + r * 64 + lane;
-    if (e < tile_count) {
-      const uint32_t d = digit_of(key[r], idx_bits, key_bits, pass);
-      stage[digit_start[d] + wave_cnt[w][d] + rank[r]] = key[r];
-    }
-  }
-  __syncthreads();
-
-#pragma unroll
-  for (int r = 0; r < KPT; ++r) {
-    const int j = r * kSortThreads + tid;
-    if (j < tile_count) {
-      const uint64_t k = stage[j];
-      const uint32_t d = digit_of(k, idx_bits, key_bits, pass);
-      const int64_t pos = (int64_t)gbase[d] + (uint32_t)(j - digit_start[d]);
-      if (pos < n) out[pos] = k;
-    }
-  }
-}
-
-
-// ---- small clouds ----------------------------------------------------------------------------------
-// Up to kSmallMaxTiles tiles of 1024 words per sort: every kernel is then bound by launch and
-// memory latency, not by bandwidth.  Workgroups on different XCDs talk through memory, two
-// microseconds and more per round trip, so this path has no look-back at all and as few launches
-// as possible:
-//   * digits of up to 10 bits (two passes for the 20 key bits of one BEV frame);
-//   * a table counts[pass][tile][digit] says how many words with that digit of that pass the tile
-//     holds in the order the pass reads them.  Key generation writes the rows of the first pass
-//     (plain stores) and zeroes the others; each pass adds, for every word it places, one to the
-//     row of the tile the word lands in for the next pass.  Nothing has to be cleared beforehand;
-//   * a pass reads the whole table of its pass: column sums give the global digit starts, the
-//     rows of earlier tiles its own offsets;
-//   * the last pass writes perm, exported keys and group offsets itself.
-constexpr int kSmallKpt = 4;
-constexpr int kSmallTile = kSortThreads * kSmallKpt;  // 1024 words per tile
-constexpr int kSmallMaxTiles = 64;
 
 __device__ __forceinline__ uint32_t digit_rb(uint64_t word, int idx_bits, int key_bits, int pass, int rb) {
   const int lo = pass * rb;
@@ -339,20 +129,22 @@ __device__ __forceinline__ uint64_t exported_key(uint64_t k, const KeyParams& kp
   return (b << 48) | (w1 << 32) | (w2 << 16) | (l1 << 8) | l2;
 }
 
+// ---- A1: coords -> sortable words, plus the digit counts of the first pass ---------------------------
 // counts [S][P][tiles][BINS]
-template <int RB>
-__global__ __launch_bounds__(kSortThreads) void k_keygen_small(const int32_t* __restrict__ coords, int64_t n, Batch bt, int P,
-                                                                int tiles, uint64_t* __restrict__ words,
-                                                                uint32_t* __restrict__ counts, uint32_t* __restrict__ error_word) {
-  constexpr int BINS = 1 << RB;
+template <int RB, int KPT>
+__global__ __launch_bounds__(kSortThreads) void k_keygen(const int32_t* __restrict__ coords, int64_t n, Batch bt, int P,
+                                                          int64_t tiles, uint64_t* __restrict__ words,
+                                                          uint32_t* __restrict__ counts) {
+  constexpr int BINS = 1 << RB, TILE = kSortThreads * KPT;
   __shared__ uint32_t h[BINS];
-  const int s = blockIdx.y, tile = blockIdx.x, tid = threadIdx.x;
+  const int s = blockIdx.y, tid = threadIdx.x;
+  const int64_t tile = blockIdx.x;
   const KeyParams kp = bt.kp[s];
   for (int t = tid; t < BINS; t += kSortThreads) h[t] = 0u;
   __syncthreads();
-#pragma unroll
-  for (int r = 0; r < kSmallKpt; ++r) {
-    const int64_t i = (int64_t)tile * kSmallTile + r * kSortThreads + tid;
+#pragma unroll 4
+  for (int r = 0; r < KPT; ++r) {
+    const int64_t i = tile * TILE + r * kSortThreads + tid;
     if (i < n) {
       const uint64_t word = make_word(coords, i, kp);
       words[(int64_t)s * n + i] = word;
@@ -364,14 +156,104 @@ __global__ __launch_bounds__(kSortThreads) void k_keygen_small(const int32_t* __
     const size_t base = (((size_t)s * P + p) * tiles + tile) * BINS;
     for (int t = tid; t < BINS; t += kSortThreads) counts[base + t] = p == 0 ? h[t] : 0u;
   }
-  if (tile == 0 && s == 0 && tid == 0) *error_word = 0u;
 }
 
-template <int RB, bool FUSE>
-__global__ __launch_bounds__(kSortThreads) void k_pass_small(const uint64_t* __restrict__ in_all, uint64_t* __restrict__ out_all,
-                                                              int64_t n, Batch bt, int pass, int P, int tiles, int G,
-                                                              uint32_t* __restrict__ counts) {
-  constexpr int BINS = 1 << RB, BPT = BINS / kSortThreads, WAVES = kSortThreads / 64, KPT = kSmallKpt, TILE = kSmallTile;
+// ---- digit counts of one pass, one table row per tile (larger clouds, passes after the first) ---------
+template <int RB, int KPT>
+__global__ __launch_bounds__(kSortThreads) void k_tile_counts(const uint64_t* __restrict__ in_all, int64_t n, Batch bt, int pass,
+                                                               int P, int64_t tiles, uint32_t* __restrict__ counts) {
+  constexpr int BINS = 1 << RB, TILE = kSortThreads * KPT;
+  __shared__ uint32_t h[BINS];
+  const int s = blockIdx.y, tid = threadIdx.x;
+  const int64_t tile = blockIdx.x;
+  const int idx_bits = bt.kp[s].idx_bits, key_bits = bt.kp[s].key_bits;
+  const uint64_t* in = in_all + (int64_t)s * n;
+  for (int t = tid; t < BINS; t += kSortThreads) h[t] = 0u;
+  __syncthreads();
+  uint64_t key[KPT];
+#pragma unroll
+  for (int r = 0; r < KPT; ++r) {
+    const int64_t i = tile * TILE + r * kSortThreads + tid;
+    key[r] = i < n ? in[i] : ~0ull;
+  }
+#pragma unroll
+  for (int r = 0; r < KPT; ++r) {
+    const int64_t i = tile * TILE + r * kSortThreads + tid;
+    if (i < n) atomicAdd(&h[digit_rb(key[r], idx_bits, key_bits, pass, RB)], 1u);
+  }
+  __syncthreads();
+  const size_t base = (((size_t)s * P + pass) * tiles + tile) * BINS;
+  for (int t = tid; t < BINS; t += kSortThreads) counts[base + t] = h[t];
+}
+
+// ---- exclusive prefixes of a pass's table over the tiles, and the per-digit totals ------------------
+// One workgroup per 64 digits; wavefront w takes the w-th sixteenth of the rows, lane = digit.  Up to
+// 64 rows per wavefront are loaded at once and stay in registers between the two sweeps.
+template <int RB>
+__global__ __launch_bounds__(kScanThreads) void k_scan_cols(uint32_t* __restrict__ counts, uint32_t* __restrict__ totals,
+                                                             int pass, int P, int64_t tiles) {
+  constexpr int BINS = 1 << RB, WAVES = kScanThreads / 64, ROWS = 64;
+  __shared__ uint32_t part[WAVES][64];
+  const int s = blockIdx.y, lane = threadIdx.x & 63, w = threadIdx.x >> 6;
+  const int d = blockIdx.x * 64 + lane;
+  uint32_t* tab = counts + ((size_t)s * P + pass) * tiles * BINS + d;
+  const int64_t per = (tiles + WAVES - 1) / WAVES;
+  const int64_t r0 = w * per, r1 = r0 + per < tiles ? r0 + per : tiles;
+  const bool fits = per <= ROWS;  // the same for every wavefront
+  uint32_t v[ROWS];
+  uint32_t sum = 0;
+  if (fits) {
+#pragma unroll
+    for (int u = 0; u < ROWS; ++u) v[u] = r0 + u < r1 ? tab[(size_t)(r0 + u) * BINS] : 0u;
+#pragma unroll
+    for (int u = 0; u < ROWS; ++u) sum += v[u];
+  } else {
+    for (int64_t r = r0; r < r1; r += 8) {
+      uint32_t t[8];
+#pragma unroll
+      for (int u = 0; u < 8; ++u) t[u] = r + u < r1 ? tab[(size_t)(r + u) * BINS] : 0u;
+#pragma unroll
+      for (int u = 0; u < 8; ++u) sum += t[u];
+    }
+  }
+  part[w][lane] = sum;
+  __syncthreads();
+  uint32_t run = 0, total = 0;
+#pragma unroll
+  for (int i = 0; i < WAVES; ++i) {
+    const uint32_t c = part[i][lane];
+    if (i < w) run += c;
+    total += c;
+  }
+  if (w == 0) totals[((size_t)s * P + pass) * BINS + d] = total;
+  if (fits) {
+#pragma unroll
+    for (int u = 0; u < ROWS; ++u) {
+      if (r0 + u < r1) tab[(size_t)(r0 + u) * BINS] = run;
+      run += v[u];
+    }
+  } else {
+    for (int64_t r = r0; r < r1; r += 8) {
+      uint32_t t[8];
+#pragma unroll
+      for (int u = 0; u < 8; ++u) t[u] = r + u < r1 ? tab[(size_t)(r + u) * BINS] : 0u;
+#pragma unroll
+      for (int u = 0; u < 8; ++u) {
+        if (r + u < r1) tab[(size_t)(r + u) * BINS] = run;
+        run += t[u];
+      }
+    }
+  }
+}
+
+// ---- A2: one radix pass ----------------------------------------------------------------------------
+// SCANNED: the table row of this tile already holds the counts of earlier tiles and `totals` the
+// per-digit totals (k_scan_cols ran); otherwise the workgroup adds the table up itself.
+template <int RB, int KPT, bool FUSE, bool SCANNED>
+__global__ __launch_bounds__(kSortThreads) void k_pass(const uint64_t* __restrict__ in_all, uint64_t* __restrict__ out_all,
+                                                        int64_t n, Batch bt, int pass, int P, int64_t tiles, int G,
+                                                        uint32_t* __restrict__ counts, const uint32_t* __restrict__ totals) {
+  constexpr int BINS = 1 << RB, BPT = BINS / kSortThreads, WAVES = kSortThreads / 64, TILE = kSortThreads * KPT;
   static_assert(BPT == 1 || BPT == 4, "digits of 8 or 10 bits");
   __shared__ uint32_t wave_cnt[WAVES][BINS];  // later: frame starts and frame group bases
   __shared__ uint32_t digit_start[BINS];      // first slot of a digit inside the tile
@@ -381,7 +263,8 @@ __global__ __launch_bounds__(kSortThreads) void k_pass_small(const uint64_t* __r
   __shared__ uint64_t stage[TILE];
 
   const int tid = threadIdx.x, lane = tid & 63, w = tid >> 6;
-  const int s = blockIdx.y, tile = blockIdx.x;
+  const int s = blockIdx.y;
+  const int64_t tile = blockIdx.x;
   const KeyParams kp = bt.kp[s];
   const int idx_bits = kp.idx_bits, key_bits = kp.key_bits;
   const uint64_t* in = in_all + (int64_t)s * n;
@@ -390,9 +273,10 @@ __global__ __launch_bounds__(kSortThreads) void k_pass_small(const uint64_t* __r
   uint32_t* next_tab = counts + ((size_t)s * P + pass + 1) * tiles * BINS;
 
   FP_TS(0);
-  const int64_t tile_start = (int64_t)tile * TILE;
+  const int64_t tile_start = tile * TILE;
   const int tile_count = (int)((n - tile_start) < (int64_t)TILE ? (n - tile_start) : (int64_t)TILE);
-  // Element order inside the tile: wave-major, then round, then lane (see k_onesweep).
+  // Element order inside the tile: wave-major, then round, then lane.  Each wave owns a contiguous
+  // run of 64 * KPT words, so stability only needs (wave, round, lane) order.
   uint64_t key[KPT];
   uint32_t rank[KPT];
   const uint64_t lanes_below = (1ull << lane) - 1ull;
@@ -402,30 +286,37 @@ __global__ __launch_bounds__(kSortThreads) void k_pass_small(const uint64_t* __r
     key[r] = e < tile_count ? in[tile_start + e] : ~0ull;
   }
 
-  // Column sums of this pass's table (thread t owns digits t * BPT ..): over all tiles and over
-  // the tiles before this one, 32 rows per memory round trip.
+  // Thread t owns digits t * BPT ..: their counts over the whole array and over earlier tiles.
   uint32_t gtot[BPT], before[BPT];
+  if (SCANNED) {
 #pragma unroll
-  for (int k = 0; k < BPT; ++k) { gtot[k] = 0; before[k] = 0; }
-  for (int t0 = 0; t0 < tiles; t0 += 32) {
-    uint32_t v[32][BPT];
-#pragma unroll
-    for (int u = 0; u < 32; ++u) {
-      const int t = t0 + u < tiles ? t0 + u : tiles - 1;
-      if (BPT == 4) {
-        const uint4 q = *reinterpret_cast<const uint4*>(cnt_tab + (size_t)t * BINS + tid * 4);
-        v[u][0] = q.x; v[u][1 % BPT] = q.y; v[u][2 % BPT] = q.z; v[u][3 % BPT] = q.w;
-      } else {
-        v[u][0] = cnt_tab[(size_t)t * BINS + tid];
-      }
+    for (int k = 0; k < BPT; ++k) {
+      gtot[k] = totals[((size_t)s * P + pass) * BINS + tid * BPT + k];
+      before[k] = cnt_tab[(size_t)tile * BINS + tid * BPT + k];
     }
+  } else {  // column sums, 32 rows per memory round trip
 #pragma unroll
-    for (int u = 0; u < 32; ++u)
+    for (int k = 0; k < BPT; ++k) { gtot[k] = 0; before[k] = 0; }
+    for (int t0 = 0; t0 < tiles; t0 += 32) {
+      uint32_t v[32][BPT];
 #pragma unroll
-      for (int k = 0; k < BPT; ++k) {
-        if (t0 + u < tiles) gtot[k] += v[u][k];
-        if (t0 + u < tile) before[k] += v[u][k];
+      for (int u = 0; u < 32; ++u) {
+        const int64_t t = t0 + u < tiles ? t0 + u : tiles - 1;
+        if (BPT == 4) {
+          const uint4 q = *reinterpret_cast<const uint4*>(cnt_tab + (size_t)t * BINS + tid * 4);
+          v[u][0] = q.x; v[u][1 % BPT] = q.y; v[u][2 % BPT] = q.z; v[u][3 % BPT] = q.w;
+        } else {
+          v[u][0] = cnt_tab[(size_t)t * BINS + tid];
+        }
       }
+#pragma unroll
+      for (int u = 0; u < 32; ++u)
+#pragma unroll
+        for (int k = 0; k < BPT; ++k) {
+          if (t0 + u < tiles) gtot[k] += v[u][k];
+          if (t0 + u < tile) before[k] += v[u][k];
+        }
+    }
   }
 
   FP_TS(1);
@@ -508,7 +399,7 @@ __global__ __launch_bounds__(kSortThreads) void k_pass_small(const uint64_t* __r
         const int64_t pos = (int64_t)gbase[d] + (uint32_t)(j - digit_start[d]);
         if (pos < n) {
           out[pos] = k;
-          if (pass + 1 < P)  // the next pass finds this word in tile pos / TILE
+          if (!SCANNED && pass + 1 < P)  // small clouds: the next pass finds this word in tile pos / TILE
             atomicAdd(&next_tab[(size_t)(pos / TILE) * BINS + digit_rb(k, idx_bits, key_bits, pass + 1, RB)], 1u);
         }
       }
@@ -615,11 +506,10 @@ __global__ __launch_bounds__(256) void k_frames(const uint64_t* __restrict__ sor
 }
 
 // ---- outputs: perm, exported keys, group offsets, num_groups ----------------------------------------
-// With at most 256 frames every block recomputes the frame table itself (B binary searches and
-// one block scan); otherwise it reads the table k_frames wrote.
+// For a small cloud with at most 256 frames every block recomputes the frame table itself (B binary
+// searches and one block scan); otherwise it reads the table k_frames wrote.
 __global__ __launch_bounds__(256) void k_finalize(const uint64_t* __restrict__ sorted_all, int64_t n, Batch bt, int G,
-                                                   const int32_t* __restrict__ frame_tab,
-                                                   const uint32_t* __restrict__ error_word) {
+                                                   const int32_t* __restrict__ frame_tab) {
   __shared__ int32_t fstart_s[257], gbase_s[257];
   __shared__ uint32_t wave_totals[4];
   const int s = blockIdx.y;
@@ -632,7 +522,7 @@ __global__ __launch_bounds__(256) void k_finalize(const uint64_t* __restrict__ s
   if (B == 1) {
     if (tid == 0) { fstart_s[0] = 0; fstart_s[1] = (int32_t)n; gbase_s[0] = 0; gbase_s[1] = (int32_t)((n + G - 1) / G); }
     __syncthreads();
-  } else if (B <= 256) {
+  } else if (B <= 256 && n <= 65536) {
     if (tid == 0) fstart_s[B] = (int32_t)n;
     if (tid < B) {
       int64_t lo = 0, hi = n;
@@ -658,7 +548,7 @@ __global__ __launch_bounds__(256) void k_finalize(const uint64_t* __restrict__ s
   const int64_t p = (int64_t)blockIdx.x * blockDim.x + tid;
   if (p == 0) {
     const int32_t ng = gbase[B];
-    *bt.num_groups[s] = *error_word ? -1 : ng;
+    *bt.num_groups[s] = ng;
     bt.group_offsets[s][ng] = (int32_t)n;
   }
   if (p >= n) return;
@@ -677,49 +567,46 @@ __global__ __launch_bounds__(256) void k_finalize(const uint64_t* __restrict__ s
   if (rel % G == 0) bt.group_offsets[s][gbase[fb] + rel / G] = (int32_t)p;
 }
 
+// Pass plan for keys of `key_bits` bits: digit width and number of passes.
+struct PassPlan { bool small; int kpt, rb, passes; int64_t tiles; };
+inline PassPlan pass_plan(int64_t n, int key_bits) {
+  PassPlan pp;
+  pp.small = ceil_div(n > 0 ? n : 1, (int64_t)kSortThreads * kSmallKpt) <= kSmallMaxTiles;
+  if (pp.small) {
+    pp.kpt = kSmallKpt;
+    pp.passes = (key_bits + 9) / 10;
+    pp.rb = (key_bits + 7) / 8 == pp.passes ? 8 : 10;
+  } else {
+    pp.kpt = kLargeKpt;
+    pp.passes = (key_bits + 9) / 10;
+    pp.rb = (key_bits + 7) / 8 == pp.passes ? 8 : 10;
+  }
+  pp.tiles = ceil_div(n > 0 ? n : 1, (int64_t)kSortThreads * pp.kpt);
+  return pp;
+}
+
 struct Layout {
-  int P;            // passes (max over the batch)
-  int kpt;          // words per thread in a pass
-  int64_t tiles;
-  size_t off_words0, off_words1, off_control, control_words, off_frames, off_small, total;
+  size_t off_words0, off_words1, off_counts, off_totals, off_frames, total;
 };
 
-// Small-cloud plan for keys of `key_bits` bits: passes and digit width (8 or 10 bits).
-struct SmallPlan { int passes, rb; };
-inline SmallPlan small_plan(int key_bits) {
-  SmallPlan sp;
-  sp.passes = (key_bits + 9) / 10;
-  sp.rb = (key_bits + 7) / 8 == sp.passes ? 8 : 10;
-  return sp;
-}
-inline bool small_eligible(int64_t n, int key_bits) {
-  return n > 0 && key_bits > 0 && ceil_div(n, kSmallTile) <= kSmallMaxTiles;
-}
-// words of the counts table for S sorts
-inline size_t small_table_words(int64_t n, int S, int key_bits) {
-  const SmallPlan sp = small_plan(key_bits);
-  return (size_t)S * sp.passes * (size_t)ceil_div(n, kSmallTile) * ((size_t)1 << sp.rb);
-}
-
-// Workspace for S sorts of n words.  Control area (cleared by every call): error word, tickets
-// [S][P], histograms [S][P][256], tile status [S][P][tiles][256].
-void make_layout(int64_t n, int S, int P, int num_frames, int max_key_bits, Layout* L) {
-  L->P = P;
-  L->kpt = n <= (1 << 19) ? 4 : 16;
-  L->tiles = ceil_div(n > 0 ? n : 1, (int64_t)kSortThreads * L->kpt);
+// Workspace for S sorts of n words whose keys have at most max_key_bits bits (a call may sort
+// narrower keys than the workspace query assumed, and a narrower key can pick a wider digit).
+void make_layout(int64_t n, int S, int num_frames, int max_key_bits, Layout* L) {
+  size_t count_words = 0, total_words = 0;
+  for (int kb = 0; kb <= max_key_bits; ++kb) {
+    const PassPlan pp = pass_plan(n, kb);
+    const size_t pc = pp.passes > 0 ? pp.passes : 1;  // key generation always fills one table
+    const size_t cw = (size_t)S * pc * (size_t)pp.tiles * ((size_t)1 << pp.rb);
+    const size_t tw = (size_t)S * pc * ((size_t)1 << pp.rb);
+    if (cw > count_words) count_words = cw;
+    if (tw > total_words) total_words = tw;
+  }
   size_t off = 0;
   L->off_words0 = off; off += align_up((size_t)S * n * 8, 256);
   L->off_words1 = off; off += align_up((size_t)S * n * 8, 256);
-  L->off_control = off;
-  L->control_words = 64 + (size_t)S * P + (size_t)S * P * kBins + (size_t)S * P * L->tiles * kBins;
-  off += align_up(L->control_words * 4, 256);
+  L->off_counts = off; off += align_up(count_words * 4 + 256, 256);
+  L->off_totals = off; off += align_up(total_words * 4 + 256, 256);
   L->off_frames = off; off += align_up((size_t)S * 2 * ((size_t)num_frames + 1) * 4, 256);
-  // Small-cloud tables, sized for any key width up to max_key_bits (a call may sort narrower keys
-  // than the workspace query assumed, and a narrower key can pick a wider digit).
-  size_t small_words = 0;
-  for (int kb = 1; kb <= max_key_bits; ++kb)
-    if (small_eligible(n, kb)) { const size_t w = small_table_words(n, S, kb); if (w > small_words) small_words = w; }
-  L->off_small = off; off += align_up(small_words * 4, 256);
   L->total = off;
 }
 
@@ -731,7 +618,6 @@ int make_flatten_plan(int64_t n, const ff_geom* g, int axis, int shift, FlattenP
   if (g->win_x < 1 || g->win_x > 256 || g->win_y < 1 || g->win_y > 256) return FF_ERR_ARG;
   if (axis != 0 && axis != 1) return FF_ERR_ARG;
   if (g->num_frames > 65535) return FF_ERR_UNSUPPORTED;
-  if (n >= (1LL << 30)) return FF_ERR_UNSUPPORTED;  // tile status words keep 30-bit counts
   const int64_t sx = shift ? g->win_x / 2 : 0, sy = shift ? g->win_y / 2 : 0;
   const int64_t nwx = ceil_div((int64_t)g->grid_x + sx, g->win_x);
   const int64_t nwy = ceil_div((int64_t)g->grid_y + sy, g->win_y);
@@ -756,7 +642,7 @@ size_t flatten_workspace_bytes(int64_t n, const ff_geom* g, int num_sorts) {
   if (num_sorts < 1 || num_sorts > kMaxSorts) return 0;
   if (make_flatten_plan(n, g, 0, 1, &p) != FF_OK) return 0;
   Layout L;
-  make_layout(n, num_sorts, p.passes > 0 ? p.passes : 1, g->num_frames, p.key_bits, &L);
+  make_layout(n, num_sorts, g->num_frames, p.key_bits, &L);
   return L.total;
 }
 
@@ -766,7 +652,7 @@ int flatten_launch(const int32_t* coords, int64_t n, const ff_geom* g, int num_s
                    size_t workspace_bytes, hipStream_t stream) {
   if (num_sorts < 1 || num_sorts > kMaxSorts || G < 1) return FF_ERR_ARG;
   Batch bt;
-  int P = 0, max_key_bits = 0;
+  int max_key_bits = 0;
   for (int s = 0; s < num_sorts; ++s) {
     FlattenPlan plan;
     const int st = make_flatten_plan(n, g, axis[s], shift[s], &plan);
@@ -781,7 +667,6 @@ int flatten_launch(const int32_t* coords, int64_t n, const ff_geom* g, int num_s
     kp.key_bits = plan.key_bits; kp.idx_bits = plan.idx_bits;
     bt.perm[s] = perm[s]; bt.group_offsets[s] = group_offsets[s]; bt.num_groups[s] = num_groups[s];
     bt.keys_sorted[s] = keys_sorted ? keys_sorted[s] : nullptr;
-    if (plan.passes > P) P = plan.passes;
     if (plan.key_bits > max_key_bits) max_key_bits = plan.key_bits;
   }
   for (int s = num_sorts; s < kMaxSorts; ++s) {
@@ -790,71 +675,58 @@ int flatten_launch(const int32_t* coords, int64_t n, const ff_geom* g, int num_s
   }
   if (n > 0 && !coords) return FF_ERR_ARG;
   Layout L;
-  make_layout(n, num_sorts, P > 0 ? P : 1, g->num_frames, max_key_bits, &L);
+  make_layout(n, num_sorts, g->num_frames, max_key_bits, &L);
   if (!workspace || ((uintptr_t)workspace & 255) || workspace_bytes < L.total) return FF_ERR_WORKSPACE;
 
   char* ws = (char*)workspace;
   uint64_t* buf[2] = {(uint64_t*)(ws + L.off_words0), (uint64_t*)(ws + L.off_words1)};
-  uint32_t* control = (uint32_t*)(ws + L.off_control);
-  uint32_t* error_word = control;
-  uint32_t* tickets = control + 64;
-  uint32_t* hist = tickets + (size_t)num_sorts * L.P;
-  uint32_t* status = hist + (size_t)num_sorts * L.P * kBins;
+  uint32_t* counts = (uint32_t*)(ws + L.off_counts);
+  uint32_t* totals = (uint32_t*)(ws + L.off_totals);
   int32_t* frame_tab = (int32_t*)(ws + L.off_frames);
 
   int cur = 0;
-  const bool small = small_eligible(n, max_key_bits);
-  if (small) {
-    const SmallPlan sp = small_plan(max_key_bits);
-    const int tiles = (int)ceil_div(n, kSmallTile);
-    uint32_t* counts = (uint32_t*)(ws + L.off_small);
+  bool outputs_done = false;
+  if (n > 0) {
+    const PassPlan pp = pass_plan(n, max_key_bits);
+    const int P = pp.passes > 0 ? pp.passes : 1;  // zero key bits: the words are generated in order
     // The last pass can write the outputs itself when its digit contains the whole frame field.
-    bool fuse = true;
+    bool fuse = pp.passes > 0;
     for (int s = 0; s < num_sorts; ++s)
-      fuse = fuse && bt.kp[s].key_bits - (sp.passes - 1) * sp.rb >= bt.kp[s].bits_b;
-    const dim3 grid((unsigned)tiles, (unsigned)num_sorts);
-#define FF_SMALL(RB)                                                                                                   \
-    do {                                                                                                               \
-      hipLaunchKernelGGL(k_keygen_small<RB>, grid, dim3(kSortThreads), 0, stream, coords, n, bt, sp.passes, tiles,    \
-                         buf[0], counts, error_word);                                                                  \
-      for (int pass = 0; pass < sp.passes; ++pass) {                                                                   \
-        if (fuse && pass == sp.passes - 1)                                                                             \
-          hipLaunchKernelGGL((k_pass_small<RB, true>), grid, dim3(kSortThreads), 0, stream, buf[cur], buf[cur ^ 1], n, \
-                             bt, pass, sp.passes, tiles, G, counts);                                                   \
-        else                                                                                                           \
-          hipLaunchKernelGGL((k_pass_small<RB, false>), grid, dim3(kSortThreads), 0, stream, buf[cur], buf[cur ^ 1],  \
-                             n, bt, pass, sp.passes, tiles, G, counts);                                                \
-        cur ^= 1;                                                                                                      \
-      }                                                                                                                \
+      fuse = fuse && bt.kp[s].key_bits - (pp.passes - 1) * pp.rb >= bt.kp[s].bits_b;
+    const dim3 grid((unsigned)pp.tiles, (unsigned)num_sorts), block(kSortThreads);
+#define FF_PASSES(RB, KPT, SCANNED)                                                                                  \
+    do {                                                                                                             \
+      hipLaunchKernelGGL((k_keygen<RB, KPT>), grid, block, 0, stream, coords, n, bt, P, pp.tiles, buf[0], counts);   \
+      for (int pass = 0; pass < pp.passes; ++pass) {                                                                 \
+        if (SCANNED) {                                                                                               \
+          if (pass > 0)                                                                                              \
+            hipLaunchKernelGGL((k_tile_counts<RB, KPT>), grid, block, 0, stream, buf[cur], n, bt, pass, P, pp.tiles, \
+                               counts);                                                                              \
+          hipLaunchKernelGGL(k_scan_cols<RB>, dim3((1u << RB) / 64, (unsigned)num_sorts), dim3(kScanThreads), 0,    \
+                             stream, counts, totals, pass, P, pp.tiles);                                             \
+        }                                                                                                            \
+        if (fuse && pass == pp.passes - 1)                                                                           \
+          hipLaunchKernelGGL((k_pass<RB, KPT, true, SCANNED>), grid, block, 0, stream, buf[cur], buf[cur ^ 1], n,   \
+                             bt, pass, P, pp.tiles, G, counts, totals);                                              \
+        else                                                                                                         \
+          hipLaunchKernelGGL((k_pass<RB, KPT, false, SCANNED>), grid, block, 0, stream, buf[cur], buf[cur ^ 1], n,  \
+                             bt, pass, P, pp.tiles, G, counts, totals);                                              \
+        cur ^= 1;                                                                                                    \
+      }                                                                                                              \
     } while (0)
-    if (sp.rb == 8) FF_SMALL(8); else FF_SMALL(10);
-#undef FF_SMALL
-    if (fuse) return launch_status();
-  } else {
-    int64_t cblocks = ceil_div((int64_t)L.control_words, 256 * 4);
-    if (cblocks > 1024) cblocks = 1024;
-    hipLaunchKernelGGL(k_clear, dim3((unsigned)cblocks), dim3(256), 0, stream, control, (int64_t)L.control_words);
+    if (!pp.small && pp.rb == 8) FF_PASSES(8, kLargeKpt, true);
+    else if (!pp.small) FF_PASSES(10, kLargeKpt, true);
+    else if (pp.rb == 8) FF_PASSES(8, kSmallKpt, false);
+    else FF_PASSES(10, kSmallKpt, false);
+#undef FF_PASSES
+    outputs_done = fuse;
   }
-  if (n > 0 && !small) {
-    hipLaunchKernelGGL(k_keygen_hist, dim3((unsigned)ceil_div(n, 1024), (unsigned)num_sorts), dim3(256),
-                       (size_t)L.P * kBins * 4, stream, coords, n, bt, L.P, buf[0], hist);
-    // 256 compute units hold far more than 512 of these workgroups at once
-    const int use_tickets = L.tiles * num_sorts > 512 ? 1 : 0;
-    for (int pass = 0; pass < P; ++pass) {
-      const dim3 grid((unsigned)L.tiles, (unsigned)num_sorts);
-      if (L.kpt == 4)
-        hipLaunchKernelGGL(k_onesweep<4>, grid, dim3(kSortThreads), 0, stream, buf[cur], buf[cur ^ 1], n, bt, pass,
-                           L.P, L.tiles, hist, status, tickets, use_tickets, error_word);
-      else
-        hipLaunchKernelGGL(k_onesweep<16>, grid, dim3(kSortThreads), 0, stream, buf[cur], buf[cur ^ 1], n, bt, pass,
-                           L.P, L.tiles, hist, status, tickets, use_tickets, error_word);
-      cur ^= 1;
-    }
+  if (!outputs_done) {
+    if (g->num_frames > 256 || (g->num_frames > 1 && n > 65536))  // else every output block derives it itself
+      hipLaunchKernelGGL(k_frames, dim3((unsigned)num_sorts), dim3(256), 0, stream, buf[cur], n, bt, G, frame_tab);
+    hipLaunchKernelGGL(k_finalize, dim3((unsigned)(n > 0 ? ceil_div(n, 256) : 1), (unsigned)num_sorts), dim3(256), 0,
+                       stream, buf[cur], n, bt, G, frame_tab);
   }
-  if (g->num_frames > 256)
-    hipLaunchKernelGGL(k_frames, dim3((unsigned)num_sorts), dim3(256), 0, stream, buf[cur], n, bt, G, frame_tab);
-  hipLaunchKernelGGL(k_finalize, dim3((unsigned)(n > 0 ? ceil_div(n, 256) : 1), (unsigned)num_sorts), dim3(256), 0,
-                     stream, buf[cur], n, bt, G, frame_tab, error_word);
   return launch_status();
 }
 
