@@ -256,11 +256,11 @@ __global__ __launch_bounds__(kSortThreads) void k_pass(const uint64_t* __restric
   constexpr int BINS = 1 << RB, BPT = BINS / kSortThreads, WAVES = kSortThreads / 64, TILE = kSortThreads * KPT;
   static_assert(BPT == 1 || BPT == 4, "digits of 8 or 10 bits");
   __shared__ uint32_t wave_cnt[WAVES][BINS];  // later: frame starts and frame group bases
-  __shared__ uint32_t digit_start[BINS];      // first slot of a digit inside the tile
-  __shared__ uint32_t gbase[BINS];            // first output position of this tile's words with a digit
+  __shared__ uint32_t gbase[BINS];            // output position of a word = gbase[digit] + its stage slot
   __shared__ uint32_t gdig[FUSE ? BINS : 1];  // first output position of a digit over the whole array
   __shared__ uint32_t wave_totals[WAVES];
-  __shared__ uint64_t stage[TILE];
+  // first the per-wavefront match tables (one 64-bit lane mask per digit), then the output stage
+  __shared__ uint64_t stage[TILE > WAVES * BINS ? TILE : WAVES * BINS];
 
   const int tid = threadIdx.x, lane = tid & 63, w = tid >> 6;
   const int s = blockIdx.y;
@@ -323,25 +323,25 @@ __global__ __launch_bounds__(kSortThreads) void k_pass(const uint64_t* __restric
 #pragma unroll
   for (int i = 0; i < WAVES; ++i)
 #pragma unroll
-    for (int k = 0; k < BPT; ++k) wave_cnt[i][tid + k * kSortThreads] = 0;
+    for (int k = 0; k < BPT; ++k) { wave_cnt[i][tid + k * kSortThreads] = 0; stage[i * BINS + tid + k * kSortThreads] = 0ull; }
   __syncthreads();
+  // Rank inside the wavefront's run: lanes with the same digit find each other through the match
+  // table (every lane ORs its bit into the digit's entry; LDS instructions of a wavefront execute in
+  // order, so the read that follows sees all of them), the first of them adds the count to the
+  // wavefront's running digit counter and clears the entry for the next round.
+  unsigned long long* match = reinterpret_cast<unsigned long long*>(stage) + w * BINS;
 #pragma unroll
   for (int r = 0; r < KPT; ++r) {
     const int e = w * 64 * KPT + r * 64 + lane;
     const bool valid = e < tile_count;
     const uint32_t d = digit_rb(key[r], idx_bits, key_bits, pass, RB);
-    uint64_t same = __ballot(valid);
-#pragma unroll
-    for (int b = 0; b < RB; ++b) {
-      const bool bit = (d >> b) & 1u;
-      const uint64_t bal = __ballot(bit);
-      same &= bit ? bal : ~bal;
-    }
+    unsigned long long same = 0ull;
+    uint32_t prev = 0;
+    if (valid) atomicOr(&match[d], 1ull << lane);
+    if (valid) { same = match[d]; prev = wave_cnt[w][d]; }
     const uint32_t below = __popcll(same & lanes_below);
     const uint32_t cnt = __popcll(same);
-    uint32_t prev = 0;
-    if (valid) prev = wave_cnt[w][d];
-    if (valid && below == 0) wave_cnt[w][d] = prev + cnt;
+    if (valid && below == 0) { wave_cnt[w][d] = prev + cnt; match[d] = 0ull; }
     rank[r] = prev + below;
   }
   __syncthreads();
@@ -370,9 +370,10 @@ __global__ __launch_bounds__(kSortThreads) void k_pass(const uint64_t* __restric
 #pragma unroll
     for (int k = 0; k < BPT; ++k) {
       const int d = tid * BPT + k;
-      digit_start[d] = trun;
-      gbase[d] = grun + before[k];
+      gbase[d] = grun + before[k] - trun;  // output position = gbase[digit] + slot in the stage
       if (FUSE) gdig[d] = grun;
+#pragma unroll
+      for (int i = 0; i < WAVES; ++i) wave_cnt[i][d] += trun;  // first stage slot of (wave, digit)
       trun += total[k];
       grun += gtot[k];
     }
@@ -383,7 +384,7 @@ __global__ __launch_bounds__(kSortThreads) void k_pass(const uint64_t* __restric
     const int e = w * 64 * KPT + r * 64 + lane;
     if (e < tile_count) {
       const uint32_t d = digit_rb(key[r], idx_bits, key_bits, pass, RB);
-      stage[digit_start[d] + wave_cnt[w][d] + rank[r]] = key[r];
+      stage[wave_cnt[w][d] + rank[r]] = key[r];
     }
   }
   __syncthreads();
@@ -396,7 +397,7 @@ __global__ __launch_bounds__(kSortThreads) void k_pass(const uint64_t* __restric
       if (j < tile_count) {
         const uint64_t k = stage[j];
         const uint32_t d = digit_rb(k, idx_bits, key_bits, pass, RB);
-        const int64_t pos = (int64_t)gbase[d] + (uint32_t)(j - digit_start[d]);
+        const int64_t pos = (int64_t)(gbase[d] + (uint32_t)j);
         if (pos < n) {
           out[pos] = k;
           if (!SCANNED && pass + 1 < P)  // small clouds: the next pass finds this word in tile pos / TILE
@@ -446,7 +447,7 @@ __global__ __launch_bounds__(kSortThreads) void k_pass(const uint64_t* __restric
     if (j < tile_count) {
       const uint64_t word = stage[j];
       const uint32_t d = digit_rb(word, idx_bits, key_bits, pass, RB);
-      const int64_t pos = (int64_t)gbase[d] + (uint32_t)(j - digit_start[d]);
+      const int64_t pos = (int64_t)(gbase[d] + (uint32_t)j);
       if (pos < n) {
         bt.perm[s][pos] = (int32_t)(word & idx_mask);
         uint32_t b;
