@@ -220,7 +220,7 @@ def sweep(ff, torch, c, dt, dev):
         ms, _ = time_region(lambda: ff.ff_scatter(gth, perm, dt, out=out), reps, 3)
         line["scatter"] = {"ms": ms, "GBps": (2 * C * esz + 4) * n / ms / 1e6}
         flops = layer_flops_per_voxel(C, F, G) * n
-        for variant in ((0,) if dt == ff.FF_F32 else (2, 3, 6, 7, 8)):
+        for variant in ((0,) if dt == ff.FF_F32 else (6, 7, 11)):
             try:
                 fl = ff.FF_FLAG_VARIANT(variant)
                 ms, _ = time_region(lambda: ff.ff_group_attention(feats, perm, goff, ng, mg, lw, G, dt, fl, out=out,

@@ -265,7 +265,7 @@ __global__ __launch_bounds__(NW * 64, MINW) void k_layer_mfma(const uint16_t* __
   constexpr int CPH = FH / CF, CPF = FF / CF;
   // C = 128: the unit loops are unrolled completely, which turns the ring bookkeeping into constants
   // (about 30 KB of code).  Wider layers keep rolled loops.
-  constexpr int FULL_UNROLL = C <= 128 ? 16 : 1;
+  constexpr int FULL_UNROLL = C <= 128 && NW <= 8 ? 16 : 1;  // more waves per SIMD leave too few registers for it
   constexpr bool LEAN = (NW + 3) / 4 >= 3 && MINW <= 2 && C >= 256;  // three wavefronts on a SIMD: 168 registers each
   constexpr int PF = LEAN ? 4 : kWindow;
   using LP = LdsPlan<C, F, NVB, WPG, NW, MINW>;
@@ -844,7 +844,9 @@ int layer_mfma_launch(const void* feats, void* out, int64_t n, const int32_t* pe
   const int shape = shape_id(w);
   // (pillar blocks per wave, waves per group, waves per workgroup, min waves per SIMD)
   if (shape == 1) {
-    if (variant == 0) variant = G <= 32 ? 10 : G <= 64 ? 7 : 9;
+    // many groups: three groups per workgroup (three waves per SIMD) hide more latency than the unrolled
+    // two-group mapping gains from constant folding
+    if (variant == 0) variant = G <= 32 ? 10 : G <= 64 ? (max_groups >= 1500 ? 11 : 7) : 9;
     switch (variant) {
       case 1: if (G <= 32) FF_GO(128, 16, 256, 2, 1, 4, 2); break;
       case 2: if (G <= 64) FF_GO(128, 16, 256, 2, 2, 4, 1); break;  // 512 registers
@@ -853,6 +855,7 @@ int layer_mfma_launch(const void* feats, void* out, int64_t n, const int32_t* pe
       case 7: if (G <= 64) FF_GO(128, 16, 256, 1, 4, 8, 2); break;
       case 9: if (G <= 128) FF_GO(128, 16, 256, 1, 8, 8, 2); break;
       case 10: if (G <= 32) FF_GO(128, 16, 256, 1, 2, 8, 2); break;
+      case 11: if (G <= 64) FF_GO(128, 16, 256, 1, 4, 12, 3); break;  // three groups, three waves per SIMD
       default: break;
     }
   } else if (shape == 2) {

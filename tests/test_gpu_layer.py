@@ -162,7 +162,7 @@ def test_bf16_group_sizes_and_tails(cfg, G):
     assert np.abs(plain - want).max() <= 2e-2
     assert torch.equal(packed, narrow)                      # pre-packed weights change nothing
     # every wave-to-group mapping that can hold G
-    for variant, slots in [(1, 32), (2, 64), (4, 128), (6, 64), (7, 64), (9, 128), (10, 32)]:
+    for variant, slots in [(1, 32), (2, 64), (4, 128), (6, 64), (7, 64), (9, 128), (10, 32), (11, 64)]:
         fl = ff.FF_FLAG_OUT_F32 | ff.FF_FLAG_VARIANT(variant)
         if G > slots:
             with pytest.raises(ff.FlatformerError):
