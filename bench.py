@@ -6,7 +6,7 @@ One "step" = one pass of the whole hot path over one synthetic frame: the sorts 
 layer stack (gather, LayerNorm, QKV, softmax attention, out-proj, FFN, scatter per layer).
 Inputs are resident in HBM before the timed region.  Prints ONE JSON line.
 
-    python bench.py [--gpus 1] [--steps K] [--warmup W] [--config 2] [--no-cpu] [--sweep]
+    python bench.py [--gpus 1] [--steps K] [--warmup W] [--config 2] [--tail mask|drop] [--no-cpu] [--sweep]
 """
 import argparse
 import json
@@ -87,6 +87,8 @@ def main():
     ap.add_argument("--sweep", action="store_true",
                     help="also time flatten / gather / scatter / layer on batches of frames (JSON lines on stderr)")
     ap.add_argument("--variant", type=int, default=0, help="wave-to-group mapping of the fused layer kernel (0 = auto)")
+    ap.add_argument("--tail", choices=("mask", "drop"), default="mask",
+                    help="short last groups attend over their members (mask) or skip the layer (drop, Sec. 4.3)")
     ap.add_argument("--copy-calibration", action="store_true",
                     help="also launch one plain 256 MiB device copy (reference for scaling rocprofv3 byte counters)")
     a = ap.parse_args()
@@ -114,22 +116,24 @@ def main():
     out = torch.empty_like(feats)
     ws = torch.empty(ff.ff_fwa_block_workspace_bytes(n, geom, G, layers, dt) + 512, dtype=torch.uint8, device=dev)
 
+    tail = ff.FF_TAIL_DROP if a.tail == "drop" else ff.FF_TAIL_MASK
+
     def step():
-        ff.ff_fwa_block(coords, geom, G, layers, dt, feats, out=out, workspace=ws)
+        ff.ff_fwa_block(coords, geom, G, layers, dt, feats, out=out, workspace=ws, tail=tail)
 
     ms, wall_ms = time_region(step, a.steps, a.warmup)
 
     # ---- per-part timings, same launch configuration as inside the block ----
-    perm, goff, ng, _ = ff.ff_flatten(coords, geom, 0, 0, G)
+    perm, goff, ng, _ = ff.ff_flatten(coords, geom, 0, 0, G, tail=tail)
     torch.cuda.synchronize()
     max_groups = -(-n // G) + c["B"]
     fws = torch.empty(ff.ff_flatten_workspace_bytes(n, geom) + 512, dtype=torch.uint8, device=dev)
     lws = torch.empty(ff.ff_group_attention_workspace_bytes(n, G, layers[0], dt) + 512, dtype=torch.uint8, device=dev)
     gth = torch.empty_like(feats)
     reps = max(a.steps, 20)
-    ms_flat, _ = time_region(lambda: ff.ff_flatten(coords, geom, 0, 1, G, workspace=fws), reps, 5)
+    ms_flat, _ = time_region(lambda: ff.ff_flatten(coords, geom, 0, 1, G, tail=tail, workspace=fws), reps, 5)
     lpk = ff.LayerWeights(c["layer_params"][0], dt, dev).pack()       # exactly one kernel in the timed region
-    vflag = ff.FF_FLAG_VARIANT(a.variant)
+    vflag = ff.FF_FLAG_VARIANT(a.variant) | (ff.FF_FLAG_TAIL_DROP if a.tail == "drop" else 0)
     ms_layer, _ = time_region(lambda: ff.ff_group_attention(feats, perm, goff, ng, max_groups, lpk, G, dt, vflag,
                                                             out=out, workspace=lws), reps, 5)
     ms_gather, _ = time_region(lambda: ff.ff_gather(feats, perm, dt, out=gth), reps, 5)
@@ -162,7 +166,8 @@ def main():
         "config": {"workload": f"config {a.config} ({c['name']}): {n} pillars on {c['grid']}x{c['grid']}, "
                                f"B={c['B']}, window {c['window']}x{c['window']}, G={G}, C={C}, heads={c['heads']}, "
                                f"F={F}, {L} layers (x, y, shifted x, shifted y ...), "
-                               f"{len(dict.fromkeys(c['schedule']))} sorts + {L} layers per step"},
+                               f"{len(dict.fromkeys(c['schedule']))} sorts + {L} layers per step"
+                               + (", short groups dropped" if a.tail == "drop" else "")},
         "roofline": {"bound": "mfma", "kernel": "group attention layer (ff_group_attention, one launch)",
                      "achieved": ach_tf, "peak": peak_tf, "unit": "TFLOP/s", "frac": ach_tf / peak_tf,
                      "traffic": MEASURED_LAYER_TRAFFIC.get(a.config) if a.variant == 0 else None,

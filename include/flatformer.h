@@ -44,7 +44,8 @@ typedef enum { FF_F32 = 0, FF_BF16 = 1 } ff_dtype;
 
 typedef enum {
   FF_TAIL_MASK = 0, /* a frame's last group may be short; it attends over its real members only */
-  FF_TAIL_DROP = 1  /* short groups are left out ('Drop Residual', Sec. 4.3); not built yet      */
+  FF_TAIL_DROP = 1  /* short groups are left out of the list ('Drop Residual', Sec. 4.3): every   */
+                    /* listed group has exactly G members, the others' pillars skip the layer    */
 } ff_tail;
 
 /* Geometry of the BEV grid.  coords[:,0] in [0,num_frames), coords[:,1] in
@@ -70,11 +71,14 @@ typedef struct {
  *   group_offsets    start of every group in the sorted order, then n             [>= ceil(n/G)+num_frames+1]
  *                    (only the first *num_groups + 1 entries are written)
  *   num_groups       number of groups = sum over frames of ceil(n_b / G)          [1]
+ *                    (FF_TAIL_DROP: of floor(n_b / G))
  *   keys_sorted      exported key of every sorted position, or NULL               [n]
  *
  * Groups never cross frames; within a frame they are consecutive runs of G sorted pillars,
- * the last one possibly shorter ('Equal-Size Grouping').  n == 0 is legal (num_groups = 0,
- * group_offsets[0] = 0).  Duplicate coordinates are legal.  Coordinates outside the geometry
+ * the last one possibly shorter ('Equal-Size Grouping').  With FF_TAIL_DROP that shorter group
+ * is not listed: group_offsets holds the starts of the full groups only, then n, so that group g
+ * is positions group_offsets[g] .. group_offsets[g]+G-1 and group_offsets[g+1] may lie beyond its
+ * end.  n == 0 is legal (num_groups = 0, group_offsets[0] = 0).  Duplicate coordinates are legal.  Coordinates outside the geometry
  * give an unspecified (but still bijective) perm; no memory outside the buffers is touched.
  *
  * Limit: bits(key fields actually used) + bits(n-1) must not exceed 64 (FF_ERR_UNSUPPORTED
@@ -124,6 +128,7 @@ int ff_pack_weights(const ff_layer_weights* w, int dtype, void* packed, void* st
 /* Flags of ff_group_attention. */
 #define FF_FLAG_OUT_F32 1u      /* store `out` as float32 even when dtype is FF_BF16 */
 #define FF_FLAG_FORCE_GENERIC 2u /* use the plain fp32-arithmetic kernels for any dtype */
+#define FF_FLAG_TAIL_DROP 4u     /* the group list was made with FF_TAIL_DROP: rows of no group are copied through */
 /* Tuning knob: bits 8..11 select one wave-to-group mapping of the fused bf16 kernel (1..15; 0 =
  * chosen from the shape).  A mapping that cannot hold G returns FF_ERR_UNSUPPORTED. */
 #define FF_FLAG_VARIANT(v) (((uint32_t)(v) & 0xfu) << 8)
@@ -132,11 +137,16 @@ size_t ff_group_attention_workspace_bytes(int64_t n, int G, const ff_layer_weigh
 
 /* feats [n,C] and out [n,C] are in pillar order and must not overlap: a group reads rows that
  * other groups write.  Row perm[p] of feats is member p of the sorted order; group g owns
- * sorted positions group_offsets[g] .. group_offsets[g+1]-1 (1..G of them).  num_groups is the
+ * sorted positions group_offsets[g] .. min(group_offsets[g+1], group_offsets[g]+G)-1 (1..G of
+ * them; the clamp only matters for a list made with FF_TAIL_DROP).  num_groups is the
  * device scalar written by ff_flatten; max_groups is a host upper bound used to size the launch
  * (e.g. ceil(n/G) + num_frames - 1) and group_offsets must hold at least max_groups + 1 readable
  * entries (ff_flatten's buffer does for that bound).  num_groups < 0 (a failed flatten) computes
- * nothing.  Every row that belongs to a group is written exactly once.
+ * nothing.  Every row that belongs to a group is written exactly once.  Rows of sorted positions
+ * that no group covers are left untouched in `out`, unless FF_FLAG_TAIL_DROP is set: then each
+ * such row of `out` receives the row of `feats` (converted when the storage types differ), which
+ * is what skipping the layer means for a residual layer; max_groups may then be as small as
+ * floor(n/G), and 0 copies everything.
  * dtype FF_F32: fp32 arithmetic throughout.  FF_BF16: bf16 storage, bf16 MFMA operands, fp32
  * accumulation, statistics, softmax and GELU.
  * Limits (FF_ERR_UNSUPPORTED otherwise): C % heads == 0, C*sizeof(dtype) % 16 == 0, 1 <= G <= 1024. */
@@ -156,11 +166,13 @@ int ff_scatter(const void* src, void* dst, const int32_t* perm, int64_t n, int C
  * Layer l sorts along axis l % 2 with the shift on when (l / 2) % 2 == 1 (x, y, shifted x,
  * shifted y, x, ...); each distinct (axis, shift) pair is flattened once and reused by every
  * layer that needs it ('Reuse Sorting', Sec. 4.3).  layers: host array of num_layers structs.
+ * tail (ff_tail) is handed to the sorts; with FF_TAIL_DROP the pillars of a layer's short groups
+ * skip that layer (they can still be grouped by another layer's sort).
  * feats_in / feats_out: [n, C] in pillar order, must not overlap. */
 size_t ff_fwa_block_workspace_bytes(int64_t n, const ff_geom* g, int G,
                                     const ff_layer_weights* layers, int num_layers, int dtype);
 
-int ff_fwa_block(const int32_t* coords, int64_t n, const ff_geom* g, int G,
+int ff_fwa_block(const int32_t* coords, int64_t n, const ff_geom* g, int G, int tail,
                  const ff_layer_weights* layers, int num_layers, int dtype,
                  const void* feats_in, void* feats_out,
                  void* workspace, size_t workspace_bytes, void* stream);

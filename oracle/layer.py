@@ -59,27 +59,35 @@ def group_layer(X, p):
     return X1 + H @ _f64(p, "w2").T + _f64(p, "b2")
 
 
-def layer(feats, perm, group_offsets, p, groups=None, dropped_passthrough=True):
+def layer(feats, perm, group_offsets, p, groups=None, dropped_passthrough=True, group_size=None):
     """Gather each group's rows, apply `group_layer`, scatter back.
 
     feats [n, C] in pillar order; perm / group_offsets from `flatten`.  With
     `groups` (an iterable of group indices) only those groups are computed; all
     other rows of the result are NaN.  Rows that belong to no group (dropped
     tails) pass through unchanged when every group is computed.
+    With `group_size` given, `group_offsets` is the list of group starts that
+    `flatten(..., tail="drop")` returns ('Drop Residual', Sec. 4.3): no closing
+    entry, every group has exactly `group_size` members.
     Returns float64 [n, C].
     """
     feats = np.asarray(feats, dtype=np.float64)
     n = feats.shape[0]
     perm = np.asarray(perm)
     off = np.asarray(group_offsets)
-    num_groups = len(off) - 1
+    if group_size is None:
+        num_groups = len(off) - 1
+        ends = off[1:]
+    else:
+        num_groups = len(off)
+        ends = off + int(group_size)
     if groups is None:
         out = feats.copy() if dropped_passthrough else np.full_like(feats, np.nan)
         groups = range(num_groups)
     else:
         out = np.full_like(feats, np.nan)
     for g in groups:
-        rows = perm[int(off[g]):int(off[g + 1])]
+        rows = perm[int(off[g]):int(ends[g])]
         out[rows] = group_layer(feats[rows], p)
     return out
 

@@ -6,6 +6,7 @@ used for device memory and streams.  There is no CPU fallback: calling anything 
 built library raises.
 """
 from .binding import (Geometry, LayerWeights, FF_F32, FF_BF16, FF_FLAG_OUT_F32, FF_FLAG_FORCE_GENERIC,
+                      FF_FLAG_TAIL_DROP, FF_TAIL_MASK, FF_TAIL_DROP,
                       FF_FLAG_VARIANT,
                       FlatformerError, load_library, library_path, exported_symbols,
                       ff_flatten, ff_flatten_workspace_bytes, ff_group_attention,
@@ -14,6 +15,7 @@ from .binding import (Geometry, LayerWeights, FF_F32, FF_BF16, FF_FLAG_OUT_F32, 
 
 __all__ = [
     "Geometry", "LayerWeights", "FF_F32", "FF_BF16", "FF_FLAG_OUT_F32", "FF_FLAG_FORCE_GENERIC", "FF_FLAG_VARIANT",
+    "FF_FLAG_TAIL_DROP", "FF_TAIL_MASK", "FF_TAIL_DROP",
     "FlatformerError", "load_library", "library_path", "exported_symbols",
     "ff_flatten", "ff_flatten_workspace_bytes", "ff_group_attention",
     "ff_group_attention_workspace_bytes", "ff_gather", "ff_scatter", "ff_fwa_block",

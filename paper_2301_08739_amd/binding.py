@@ -10,7 +10,7 @@ _lib = None
 
 FF_F32, FF_BF16 = 0, 1
 FF_TAIL_MASK, FF_TAIL_DROP = 0, 1
-FF_FLAG_OUT_F32, FF_FLAG_FORCE_GENERIC = 1, 2
+FF_FLAG_OUT_F32, FF_FLAG_FORCE_GENERIC, FF_FLAG_TAIL_DROP = 1, 2, 4
 
 
 def FF_FLAG_VARIANT(v):
@@ -85,7 +85,7 @@ _SIGS = {
     "ff_scatter": (C.c_int, [C.c_void_p, C.c_void_p, C.c_void_p, C.c_int64, C.c_int, C.c_int, C.c_void_p]),
     "ff_fwa_block_workspace_bytes": (C.c_size_t, [C.c_int64, C.POINTER(Geometry), C.c_int,
                                                    C.POINTER(_LayerWeightsC), C.c_int, C.c_int]),
-    "ff_fwa_block": (C.c_int, [C.c_void_p, C.c_int64, C.POINTER(Geometry), C.c_int, C.POINTER(_LayerWeightsC),
+    "ff_fwa_block": (C.c_int, [C.c_void_p, C.c_int64, C.POINTER(Geometry), C.c_int, C.c_int, C.POINTER(_LayerWeightsC),
                                C.c_int, C.c_int, C.c_void_p, C.c_void_p, C.c_void_p, C.c_size_t, C.c_void_p]),
     "ff_status_string": (C.c_char_p, [C.c_int]),
     "ff_version": (C.c_int, []),
@@ -222,7 +222,7 @@ def ff_fwa_block_workspace_bytes(n, geom, G, layers, dtype):
     return load_library().ff_fwa_block_workspace_bytes(int(n), C.byref(geom), G, arr, len(layers), dtype)
 
 
-def ff_fwa_block(coords, geom, G, layers, dtype, feats_in, out=None, workspace=None):
+def ff_fwa_block(coords, geom, G, layers, dtype, feats_in, out=None, workspace=None, tail=FF_TAIL_MASK):
     lib = load_library()
     n = coords.shape[0]
     arr = _layer_array(layers)
@@ -230,7 +230,7 @@ def ff_fwa_block(coords, geom, G, layers, dtype, feats_in, out=None, workspace=N
         out = torch.empty_like(feats_in)
     need = lib.ff_fwa_block_workspace_bytes(n, C.byref(geom), G, arr, len(layers), dtype)
     ws = workspace if workspace is not None else _workspace(need, coords.device)
-    st = lib.ff_fwa_block(_ptr(coords), n, C.byref(geom), G, arr, len(layers), dtype, _ptr(feats_in), _ptr(out),
+    st = lib.ff_fwa_block(_ptr(coords), n, C.byref(geom), G, tail, arr, len(layers), dtype, _ptr(feats_in), _ptr(out),
                           C.c_void_p(_aligned_ptr(ws)), ws.numel() - 256, _stream())
     _check(st, "ff_fwa_block")
     return out

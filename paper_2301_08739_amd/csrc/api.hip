@@ -29,10 +29,9 @@ size_t ff_flatten_workspace_bytes(int64_t n, const ff_geom* g) { return flatten_
 int ff_flatten(const int32_t* coords, int64_t n, const ff_geom* g, int axis, int shift, int G, int tail,
                int32_t* perm, int32_t* group_offsets, int32_t* num_groups, uint64_t* keys_sorted,
                void* workspace, size_t workspace_bytes, void* stream) {
-  if (tail == FF_TAIL_DROP) return FF_ERR_UNSUPPORTED;
-  if (tail != FF_TAIL_MASK) return FF_ERR_ARG;
+  if (tail != FF_TAIL_MASK && tail != FF_TAIL_DROP) return FF_ERR_ARG;
   if (shift != 0 && shift != 1) return FF_ERR_ARG;
-  return flatten_launch(coords, n, g, 1, &axis, &shift, G, &perm, &group_offsets, &num_groups, &keys_sorted,
+  return flatten_launch(coords, n, g, 1, &axis, &shift, G, tail == FF_TAIL_DROP, &perm, &group_offsets, &num_groups, &keys_sorted,
                         workspace, workspace_bytes, (hipStream_t)stream);
 }
 
@@ -77,6 +76,10 @@ int ff_group_attention(const void* feats, void* out, int64_t n, const int32_t* p
     if (a < b + out_bytes && b < a + in_bytes) return FF_ERR_ARG;
   }
   const bool out_f32 = (flags & FF_FLAG_OUT_F32) != 0;
+  const bool drop = (flags & FF_FLAG_TAIL_DROP) != 0;
+  if (drop && n > 0 && max_groups == 0)  // no group can exist: every row skips the layer
+    return rows_copy_ungrouped_launch(feats, out, n, perm, group_offsets, num_groups, 0, w->C, G, dtype, out_f32,
+                                      (hipStream_t)stream);
   if (dtype == FF_BF16 && !(flags & FF_FLAG_FORCE_GENERIC) && layer_mfma_supported(w, G)) {
     if (n == 0 || max_groups == 0) return FF_OK;
     const void* packed = w->packed;
@@ -87,11 +90,15 @@ int ff_group_attention(const void* feats, void* out, int64_t n, const int32_t* p
       if (st != FF_OK) return st;
       packed = workspace;
     }
-    return layer_mfma_launch(feats, out, n, perm, group_offsets, num_groups, max_groups, w, G, out_f32, packed,
-                             (int)((flags >> 8) & 0xf), (hipStream_t)stream);
+    return layer_mfma_launch(feats, out, n, perm, group_offsets, num_groups, max_groups, w, G, out_f32, drop,
+                             packed, (int)((flags >> 8) & 0xf), (hipStream_t)stream);
   }
-  return layer_generic_launch(feats, out, n, perm, group_offsets, num_groups, max_groups, w, G, dtype, out_f32,
-                              workspace, workspace_bytes, (hipStream_t)stream);
+  st = layer_generic_launch(feats, out, n, perm, group_offsets, num_groups, max_groups, w, G, dtype, out_f32,
+                            workspace, workspace_bytes, (hipStream_t)stream);
+  if (st != FF_OK || !drop || n == 0) return st;
+  // The row kernels above wrote every row; the rows of no group get the input back.
+  return rows_copy_ungrouped_launch(feats, out, n, perm, group_offsets, num_groups, max_groups, w->C, G, dtype,
+                                    out_f32, (hipStream_t)stream);
 }
 
 int ff_gather(const void* src, void* dst, const int32_t* perm, int64_t n, int C, int dtype, void* stream) {
@@ -161,9 +168,11 @@ size_t ff_fwa_block_workspace_bytes(int64_t n, const ff_geom* g, int G, const ff
   return p.total;
 }
 
-int ff_fwa_block(const int32_t* coords, int64_t n, const ff_geom* g, int G, const ff_layer_weights* layers,
-                 int num_layers, int dtype, const void* feats_in, void* feats_out, void* workspace,
-                 size_t workspace_bytes, void* stream) {
+int ff_fwa_block(const int32_t* coords, int64_t n, const ff_geom* g, int G, int tail,
+                 const ff_layer_weights* layers, int num_layers, int dtype, const void* feats_in, void* feats_out,
+                 void* workspace, size_t workspace_bytes, void* stream) {
+  if (tail != FF_TAIL_MASK && tail != FF_TAIL_DROP) return FF_ERR_ARG;
+  const bool drop = tail == FF_TAIL_DROP;
   BlockPlan p;
   int st = make_block_plan(n, g, G, layers, num_layers, dtype, &p);
   if (st != FF_OK) return st;
@@ -181,7 +190,7 @@ int ff_fwa_block(const int32_t* coords, int64_t n, const ff_geom* g, int G, cons
       goff[s] = (int32_t*)(ws + p.off_goff + s * goff_stride);
       ng[s] = (int32_t*)(ws + p.off_ng) + s;
     }
-    st = flatten_launch(coords, n, g, p.sorts, axis, shift, G, perm, goff, ng, nullptr, ws + p.off_flat,
+    st = flatten_launch(coords, n, g, p.sorts, axis, shift, G, drop, perm, goff, ng, nullptr, ws + p.off_flat,
                         p.flat_bytes, (hipStream_t)stream);
     if (st != FF_OK) return st;
   }
@@ -198,7 +207,8 @@ int ff_fwa_block(const int32_t* coords, int64_t n, const ff_geom* g, int G, cons
     if (p.packed_stride) wl.packed = ws + p.off_packed + (size_t)l * p.packed_stride;
     st = ff_group_attention(cur, dst, n, (const int32_t*)(ws + p.off_perm + s * perm_stride),
                             (const int32_t*)(ws + p.off_goff + s * goff_stride), (const int32_t*)(ws + p.off_ng) + s,
-                            (int32_t)p.max_groups, &wl, G, dtype, 0, ws + p.off_layer, p.layer_bytes, stream);
+                            (int32_t)p.max_groups, &wl, G, dtype, drop ? FF_FLAG_TAIL_DROP : 0u, ws + p.off_layer,
+                            p.layer_bytes, stream);
     if (st != FF_OK) return st;
     cur = dst;
   }

@@ -54,12 +54,17 @@ size_t flatten_workspace_bytes(int64_t n, const ff_geom* g, int num_sorts);
 
 // num_sorts (1..4) sort configurations of the same cloud, sorted together.
 int flatten_launch(const int32_t* coords, int64_t n, const ff_geom* g, int num_sorts, const int* axis,
-                   const int* shift, int G, int32_t* const* perm, int32_t* const* group_offsets,
+                   const int* shift, int G, int drop, int32_t* const* perm, int32_t* const* group_offsets,
                    int32_t* const* num_groups, uint64_t* const* keys_sorted, void* workspace,
                    size_t workspace_bytes, hipStream_t stream);
 
 int rows_launch(bool scatter, const void* src, void* dst, const int32_t* perm, int64_t n, int C,
                 int dtype, hipStream_t stream);
+// out[perm[p], :] = feats[perm[p], :] for every sorted position p outside all groups, a group being
+// G positions from its start.  max_groups == 0: no group exists, every row is copied.
+int rows_copy_ungrouped_launch(const void* feats, void* out, int64_t n, const int32_t* perm,
+                               const int32_t* group_offsets, const int32_t* num_groups, int32_t max_groups, int C,
+                               int G, int dtype, bool out_f32, hipStream_t stream);
 
 size_t layer_generic_workspace_bytes(int64_t n, const ff_layer_weights* w);
 int layer_generic_launch(const void* feats, void* out, int64_t n, const int32_t* perm,
@@ -73,6 +78,6 @@ size_t layer_mfma_packed_bytes(const ff_layer_weights* w);
 int layer_mfma_pack(const ff_layer_weights* w, int count, void* packed, size_t stride_bytes, hipStream_t stream);
 int layer_mfma_launch(const void* feats, void* out, int64_t n, const int32_t* perm, const int32_t* group_offsets,
                       const int32_t* num_groups, int32_t max_groups, const ff_layer_weights* w, int G,
-                      bool out_f32, const void* packed, int variant, hipStream_t stream);
+                      bool out_f32, bool drop, const void* packed, int variant, hipStream_t stream);
 
 }  // namespace ff

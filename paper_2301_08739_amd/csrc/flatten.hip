@@ -252,7 +252,8 @@ __global__ __launch_bounds__(kScanThreads) void k_scan_cols(uint32_t* __restrict
 template <int RB, int KPT, bool FUSE, bool SCANNED>
 __global__ __launch_bounds__(kSortThreads) void k_pass(const uint64_t* __restrict__ in_all, uint64_t* __restrict__ out_all,
                                                         int64_t n, Batch bt, int pass, int P, int64_t tiles, int G,
-                                                        uint32_t* __restrict__ counts, const uint32_t* __restrict__ totals) {
+                                                        int drop, uint32_t* __restrict__ counts,
+                                                        const uint32_t* __restrict__ totals) {
   constexpr int BINS = 1 << RB, BPT = BINS / kSortThreads, WAVES = kSortThreads / 64, TILE = kSortThreads * KPT;
   static_assert(BPT == 1 || BPT == 4, "digits of 8 or 10 bits");
   __shared__ uint32_t wave_cnt[WAVES][BINS];  // later: frame starts and frame group bases
@@ -411,9 +412,11 @@ __global__ __launch_bounds__(kSortThreads) void k_pass(const uint64_t* __restric
 
   // ---- last pass: the output position is final -------------------------------------------------------
   // Frame b starts where the first last-pass digit of frame b starts; group bases are the running
-  // sum of ceil(frame size / G).  wave_cnt is free now: [0] = frame starts, [1] = group bases.
+  // sum of the frames' group counts, ceil(frame size / G), or floor when short groups are dropped.
+  // wave_cnt is free now: [0] = frame starts, [1] = group bases, [2] = group counts.
   uint32_t* fstart = &wave_cnt[0][0];
   uint32_t* fgroup = &wave_cnt[1][0];
+  uint32_t* fcount = &wave_cnt[2][0];
   const int B = kp.B;
   const int nb_last = key_bits - pass * RB;       // bits of this digit (>= bits_b, checked by the host)
   const int fshift = nb_last - kp.bits_b;
@@ -425,7 +428,7 @@ __global__ __launch_bounds__(kSortThreads) void k_pass(const uint64_t* __restric
     if (b < B) {
       lo = gdig[(uint32_t)b << fshift];
       const uint32_t hi = b + 1 < B ? gdig[(uint32_t)(b + 1) << fshift] : (uint32_t)n;
-      c = (hi - lo + (uint32_t)G - 1u) / (uint32_t)G;
+      c = (hi - lo + (drop ? 0u : (uint32_t)G - 1u)) / (uint32_t)G;
     }
     gcount[k] = c;
     fs[k] = lo;
@@ -436,7 +439,7 @@ __global__ __launch_bounds__(kSortThreads) void k_pass(const uint64_t* __restric
 #pragma unroll
   for (int k = 0; k < BPT; ++k) {
     const int b = tid * BPT + k;
-    if (b < B) { fstart[b] = fs[k]; fgroup[b] = gexcl; }
+    if (b < B) { fstart[b] = fs[k]; fgroup[b] = gexcl; fcount[b] = gcount[k]; }
     gexcl += gcount[k];
   }
   __syncthreads();
@@ -454,8 +457,8 @@ __global__ __launch_bounds__(kSortThreads) void k_pass(const uint64_t* __restric
         const uint64_t ek = exported_key(word >> idx_bits, kp, &b);
         if (bt.keys_sorted[s]) bt.keys_sorted[s][pos] = ek;
         const uint32_t fb = b < (uint32_t)B ? b : (uint32_t)B - 1u;
-        const uint32_t rel = (uint32_t)pos - fstart[fb];
-        if (rel % (uint32_t)G == 0u) bt.group_offsets[s][fgroup[fb] + rel / (uint32_t)G] = (int32_t)pos;
+        const uint32_t rel = (uint32_t)pos - fstart[fb], k = rel / (uint32_t)G;
+        if (rel == k * (uint32_t)G && k < fcount[fb]) bt.group_offsets[s][fgroup[fb] + k] = (int32_t)pos;
       }
     }
   }
@@ -468,7 +471,7 @@ __global__ __launch_bounds__(kSortThreads) void k_pass(const uint64_t* __restric
 
 // ---- A3: frame boundaries and group bases for many frames (num_frames > 256) ---------------------
 __global__ __launch_bounds__(256) void k_frames(const uint64_t* __restrict__ sorted_all, int64_t n, Batch bt, int G,
-                                                 int32_t* __restrict__ frame_tab /*[S][2][B+1]*/) {
+                                                 int drop, int32_t* __restrict__ frame_tab /*[S][2][B+1]*/) {
   __shared__ uint32_t wave_totals[4];
   __shared__ uint32_t carry_s;
   const int s = blockIdx.x;
@@ -494,7 +497,7 @@ __global__ __launch_bounds__(256) void k_frames(const uint64_t* __restrict__ sor
   for (int base = 0; base < B; base += 256) {
     const int b = base + tid;
     uint32_t g = 0;
-    if (b < B) g = (uint32_t)((frame_start[b + 1] - frame_start[b] + G - 1) / G);
+    if (b < B) g = (uint32_t)((frame_start[b + 1] - frame_start[b] + (drop ? 0 : G - 1)) / G);
     uint32_t total;
     const uint32_t ex = block_exclusive_scan<256>(g, wave_totals, &total);
     const uint32_t carry = carry_s;
@@ -510,7 +513,7 @@ __global__ __launch_bounds__(256) void k_frames(const uint64_t* __restrict__ sor
 // For a small cloud with at most 256 frames every block recomputes the frame table itself (B binary
 // searches and one block scan); otherwise it reads the table k_frames wrote.
 __global__ __launch_bounds__(256) void k_finalize(const uint64_t* __restrict__ sorted_all, int64_t n, Batch bt, int G,
-                                                   const int32_t* __restrict__ frame_tab) {
+                                                   int drop, const int32_t* __restrict__ frame_tab) {
   __shared__ int32_t fstart_s[257], gbase_s[257];
   __shared__ uint32_t wave_totals[4];
   const int s = blockIdx.y;
@@ -521,7 +524,7 @@ __global__ __launch_bounds__(256) void k_finalize(const uint64_t* __restrict__ s
   const int32_t* fstart = fstart_s;
   const int32_t* gbase = gbase_s;
   if (B == 1) {
-    if (tid == 0) { fstart_s[0] = 0; fstart_s[1] = (int32_t)n; gbase_s[0] = 0; gbase_s[1] = (int32_t)((n + G - 1) / G); }
+    if (tid == 0) { fstart_s[0] = 0; fstart_s[1] = (int32_t)n; gbase_s[0] = 0; gbase_s[1] = (int32_t)((n + (drop ? 0 : G - 1)) / G); }
     __syncthreads();
   } else if (B <= 256 && n <= 65536) {
     if (tid == 0) fstart_s[B] = (int32_t)n;
@@ -536,7 +539,7 @@ __global__ __launch_bounds__(256) void k_finalize(const uint64_t* __restrict__ s
     }
     __syncthreads();
     uint32_t g = 0;
-    if (tid < B) g = (uint32_t)((fstart_s[tid + 1] - fstart_s[tid] + G - 1) / G);
+    if (tid < B) g = (uint32_t)((fstart_s[tid + 1] - fstart_s[tid] + (drop ? 0 : G - 1)) / G);
     uint32_t total;
     const uint32_t ex = block_exclusive_scan<256>(g, wave_totals, &total);
     if (tid < B) gbase_s[tid] = (int32_t)ex;
@@ -564,8 +567,8 @@ __global__ __launch_bounds__(256) void k_finalize(const uint64_t* __restrict__ s
   const uint64_t b = k & field_mask(kp.bits_b);
   if (bt.keys_sorted[s]) bt.keys_sorted[s][p] = (b << 48) | (w1 << 32) | (w2 << 16) | (l1 << 8) | l2;
   const int fb = b < (uint64_t)B ? (int)b : B - 1;
-  const int32_t rel = (int32_t)p - fstart[fb];
-  if (rel % G == 0) bt.group_offsets[s][gbase[fb] + rel / G] = (int32_t)p;
+  const int32_t rel = (int32_t)p - fstart[fb], gi = rel / G;
+  if (rel == gi * G && gi < gbase[fb + 1] - gbase[fb]) bt.group_offsets[s][gbase[fb] + gi] = (int32_t)p;
 }
 
 // Pass plan for keys of `key_bits` bits: digit width and number of passes.
@@ -648,7 +651,7 @@ size_t flatten_workspace_bytes(int64_t n, const ff_geom* g, int num_sorts) {
 }
 
 int flatten_launch(const int32_t* coords, int64_t n, const ff_geom* g, int num_sorts, const int* axis,
-                   const int* shift, int G, int32_t* const* perm, int32_t* const* group_offsets,
+                   const int* shift, int G, int drop, int32_t* const* perm, int32_t* const* group_offsets,
                    int32_t* const* num_groups, uint64_t* const* keys_sorted, void* workspace,
                    size_t workspace_bytes, hipStream_t stream) {
   if (num_sorts < 1 || num_sorts > kMaxSorts || G < 1) return FF_ERR_ARG;
@@ -708,10 +711,10 @@ int flatten_launch(const int32_t* coords, int64_t n, const ff_geom* g, int num_s
         }                                                                                                            \
         if (fuse && pass == pp.passes - 1)                                                                           \
           hipLaunchKernelGGL((k_pass<RB, KPT, true, SCANNED>), grid, block, 0, stream, buf[cur], buf[cur ^ 1], n,   \
-                             bt, pass, P, pp.tiles, G, counts, totals);                                              \
+                             bt, pass, P, pp.tiles, G, drop, counts, totals);                                        \
         else                                                                                                         \
           hipLaunchKernelGGL((k_pass<RB, KPT, false, SCANNED>), grid, block, 0, stream, buf[cur], buf[cur ^ 1], n,  \
-                             bt, pass, P, pp.tiles, G, counts, totals);                                              \
+                             bt, pass, P, pp.tiles, G, drop, counts, totals);                                        \
         cur ^= 1;                                                                                                    \
       }                                                                                                              \
     } while (0)
@@ -724,9 +727,9 @@ int flatten_launch(const int32_t* coords, int64_t n, const ff_geom* g, int num_s
   }
   if (!outputs_done) {
     if (g->num_frames > 256 || (g->num_frames > 1 && n > 65536))  // else every output block derives it itself
-      hipLaunchKernelGGL(k_frames, dim3((unsigned)num_sorts), dim3(256), 0, stream, buf[cur], n, bt, G, frame_tab);
+      hipLaunchKernelGGL(k_frames, dim3((unsigned)num_sorts), dim3(256), 0, stream, buf[cur], n, bt, G, drop, frame_tab);
     hipLaunchKernelGGL(k_finalize, dim3((unsigned)(n > 0 ? ceil_div(n, 256) : 1), (unsigned)num_sorts), dim3(256), 0,
-                       stream, buf[cur], n, bt, G, frame_tab);
+                       stream, buf[cur], n, bt, G, drop, frame_tab);
   }
   return launch_status();
 }

@@ -76,12 +76,13 @@ __global__ __launch_bounds__(256) void k_ln_qkv(const T* __restrict__ feats, con
 // than the workgroup).  Plain two-pass softmax over the group's real members.
 template <int DMAX>
 __global__ __launch_bounds__(256) void k_attention(const float* __restrict__ qkv, const int32_t* __restrict__ group_offsets,
-                                                    const int32_t* __restrict__ num_groups, int C, int d,
+                                                    const int32_t* __restrict__ num_groups, int C, int d, int G,
                                                     float* __restrict__ o) {
   const int g = blockIdx.x, h = blockIdx.y;
   if (g >= *num_groups) return;
   const int64_t start = group_offsets[g];
-  const int m = group_offsets[g + 1] - group_offsets[g];
+  int m = group_offsets[g + 1] - group_offsets[g];
+  m = m < G ? m : G;  // a list of full groups only: the next start may lie beyond this group's end
   const float scale = 1.0f / sqrtf((float)d);
   const int64_t ld = 3 * (int64_t)C;
   for (int i = threadIdx.x; i < m; i += blockDim.x) {
@@ -192,7 +193,7 @@ __global__ __launch_bounds__(256) void k_out_ffn(const T* __restrict__ feats, co
 
 template <typename T, typename TO>
 int launch_typed(const void* feats, void* out, int64_t n, const int32_t* perm, const int32_t* group_offsets,
-                 const int32_t* num_groups, int32_t max_groups, const ff_layer_weights* w, int d,
+                 const int32_t* num_groups, int32_t max_groups, const ff_layer_weights* w, int d, int G,
                  float* qkv, float* o, hipStream_t stream) {
   const int C = w->C, F = w->F;
   const unsigned row_blocks = (unsigned)ceil_div(n, RB);
@@ -202,10 +203,10 @@ int launch_typed(const void* feats, void* out, int64_t n, const int32_t* perm, c
                      (const T*)w->ln1_g, (const T*)w->ln1_b, w->ln_eps, (const T*)w->w_qkv,
                      (const T*)w->b_qkv, qkv);
   dim3 ga((unsigned)max_groups, (unsigned)w->heads);
-  if (d <= 16)       hipLaunchKernelGGL((k_attention<16>), ga, dim3(256), 0, stream, qkv, group_offsets, num_groups, C, d, o);
-  else if (d <= 32)  hipLaunchKernelGGL((k_attention<32>), ga, dim3(256), 0, stream, qkv, group_offsets, num_groups, C, d, o);
-  else if (d <= 64)  hipLaunchKernelGGL((k_attention<64>), ga, dim3(256), 0, stream, qkv, group_offsets, num_groups, C, d, o);
-  else               hipLaunchKernelGGL((k_attention<128>), ga, dim3(256), 0, stream, qkv, group_offsets, num_groups, C, d, o);
+  if (d <= 16)       hipLaunchKernelGGL((k_attention<16>), ga, dim3(256), 0, stream, qkv, group_offsets, num_groups, C, d, G, o);
+  else if (d <= 32)  hipLaunchKernelGGL((k_attention<32>), ga, dim3(256), 0, stream, qkv, group_offsets, num_groups, C, d, G, o);
+  else if (d <= 64)  hipLaunchKernelGGL((k_attention<64>), ga, dim3(256), 0, stream, qkv, group_offsets, num_groups, C, d, G, o);
+  else               hipLaunchKernelGGL((k_attention<128>), ga, dim3(256), 0, stream, qkv, group_offsets, num_groups, C, d, G, o);
   hipLaunchKernelGGL((k_out_ffn<T, TO>), dim3(row_blocks), dim3(256), lds_c, stream, (const T*)feats, perm, n, C, F, o,
                      (const T*)w->w_o, (const T*)w->b_o, (const T*)w->ln2_g, (const T*)w->ln2_b, w->ln_eps,
                      (const T*)w->w1, (const T*)w->b1, (const T*)w->w2, (const T*)w->b2, (TO*)out);
@@ -222,7 +223,6 @@ int layer_generic_launch(const void* feats, void* out, int64_t n, const int32_t*
                          const int32_t* group_offsets, const int32_t* num_groups, int32_t max_groups,
                          const ff_layer_weights* w, int G, int dtype, bool out_f32,
                          void* workspace, size_t workspace_bytes, hipStream_t stream) {
-  (void)G;
   const int C = w->C, F = w->F, d = C / w->heads;
   if (d > 128) return FF_ERR_UNSUPPORTED;
   if ((size_t)(3 * RB * C + RB * F + 2 * C) * 4 > 64 * 1024) return FF_ERR_UNSUPPORTED;
@@ -232,10 +232,10 @@ int layer_generic_launch(const void* feats, void* out, int64_t n, const int32_t*
   float* qkv = (float*)workspace;
   float* o = (float*)((char*)workspace + align_up((size_t)n * 3 * C * 4, 256));
   if (dtype == FF_F32)
-    return launch_typed<float, float>(feats, out, n, perm, group_offsets, num_groups, max_groups, w, d, qkv, o, stream);
+    return launch_typed<float, float>(feats, out, n, perm, group_offsets, num_groups, max_groups, w, d, G, qkv, o, stream);
   if (out_f32)
-    return launch_typed<bf16_t, float>(feats, out, n, perm, group_offsets, num_groups, max_groups, w, d, qkv, o, stream);
-  return launch_typed<bf16_t, bf16_t>(feats, out, n, perm, group_offsets, num_groups, max_groups, w, d, qkv, o, stream);
+    return launch_typed<bf16_t, float>(feats, out, n, perm, group_offsets, num_groups, max_groups, w, d, G, qkv, o, stream);
+  return launch_typed<bf16_t, bf16_t>(feats, out, n, perm, group_offsets, num_groups, max_groups, w, d, G, qkv, o, stream);
 }
 
 }  // namespace ff

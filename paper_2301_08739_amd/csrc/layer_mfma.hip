@@ -25,6 +25,7 @@
 // in stream order through a window of 8 fragments in registers, requested 8 products ahead of
 // their use, so that LDS latency is hidden behind the matrix cores.
 #include "common.h"
+#include <atomic>
 
 #ifdef FF_PROBE
 __device__ long long ff_probe_ts_global[2][64];
@@ -251,7 +252,7 @@ __global__ __launch_bounds__(NW * 64, MINW) void k_layer_mfma(const uint16_t* __
                                                                const int32_t* __restrict__ goff,
                                                                const int32_t* __restrict__ num_groups, int max_groups,
                                                                const u32x4* __restrict__ packed, SmallParams sp, float eps,
-                                                               int n, int G) {
+                                                               int n, int G, int drop) {
   constexpr int KB = C / 32;          // 32-wide blocks of the input features
   constexpr int NB = C / 16;          // 16-wide blocks of the output features
   constexpr int HP = C / 32;          // 32-wide head-dim units
@@ -304,7 +305,8 @@ __global__ __launch_bounds__(NW * 64, MINW) void k_layer_mfma(const uint16_t* __
   }
   FF_TS_WAIT(16);
   int start = 0, m = 0;
-  if (g < ngroups) { start = off0; m = off1 - off0; }
+  // A list of full groups only ('Drop Residual') has the next start beyond this group's end.
+  if (g < ngroups) { start = off0; m = off1 - off0 < G ? off1 - off0 : G; }
 
   // ---- weight stream: global memory -> LDS ring -> registers -----------------------------------------
   // Chunk c of the packed stream lives in ring slot c % RING.  `issued` chunks have been requested,
@@ -387,6 +389,32 @@ __global__ __launch_bounds__(NW * 64, MINW) void k_layer_mfma(const uint16_t* __
     }
   }
   FF_TS(1);
+  if (drop) {
+    // Pillars of no group skip the layer: their rows are copied.  The wavefronts of group g take the
+    // sorted positions between its end and the next group's start, those of group index 0 also the
+    // positions before the first start (every position when the list is empty).
+    auto copy_rows = [&](int lo, int hi) {
+      constexpr int LPR = C / 8, RPW = 64 / LPR;  // 16 bytes per lane, several rows per wavefront
+      const int sub = lane / LPR, col = (lane % LPR) * 8;
+      hi = hi < n ? hi : n;
+      for (int p = lo + part * RPW + sub; p < hi; p += WPG * RPW) {
+        const int64_t at = (int64_t)perm[p] * C + col;
+        const u32x4 v = *reinterpret_cast<const u32x4*>(feats + at);
+        if constexpr (OUT_F32) {
+          float* dst = reinterpret_cast<float*>(out) + at;
+#pragma unroll
+          for (int e = 0; e < 4; ++e) {
+            dst[2 * e] = __uint_as_float(v[e] << 16);
+            dst[2 * e + 1] = __uint_as_float(v[e] & 0xffff0000u);
+          }
+        } else {
+          *reinterpret_cast<u32x4*>(reinterpret_cast<uint16_t*>(out) + at) = v;
+        }
+      }
+    };
+    if (g == 0) copy_rows(0, ngroups > 0 ? off0 : n);
+    if (g < ngroups) copy_rows(start + m, off1);
+  }
   sync(0);  // chunks 0 and 1 and the small parameters are in LDS; the rest of the ring is requested
   FF_TS(2);
 
@@ -768,24 +796,29 @@ namespace {
 template <int C, int DH, int F, int NVB, int WPG, int NW, int MINW>
 int launch_cfg(const void* feats, void* out, const int32_t* perm, const int32_t* goff, const int32_t* num_groups,
                int32_t max_groups, const u32x4* packed, const SmallParams& sp, float eps, bool out_f32, int n, int G,
-               hipStream_t stream) {
+               int drop, hipStream_t stream) {
   constexpr int GPW = NW / WPG;
   const size_t lds_bytes = LdsPlan<C, F, NVB, WPG, NW, MINW>::TOTAL;
   const unsigned blocks = (unsigned)((max_groups + GPW - 1) / GPW);
-  auto go = [&](auto kern) -> int {
-    static bool attr_done = false;  // the attribute only has to be set once per kernel
-    if (!attr_done) {
+  // The dynamic LDS size has to be allowed once per kernel and device (both output types are
+  // separate kernels).
+  static std::atomic<uint64_t> allowed[2] = {{0}, {0}};  // bit d: done on device d
+  auto go = [&](auto kern, int which) -> int {
+    int dev = 0;
+    if (hipGetDevice(&dev) != hipSuccess) return FF_ERR_LAUNCH;
+    const uint64_t bit = 1ull << (dev & 63);
+    if (!(allowed[which].load(std::memory_order_acquire) & bit)) {
       if (hipFuncSetAttribute(reinterpret_cast<const void*>(kern), hipFuncAttributeMaxDynamicSharedMemorySize,
                               (int)lds_bytes) != hipSuccess)
         return FF_ERR_LAUNCH;
-      attr_done = true;
+      allowed[which].fetch_or(bit, std::memory_order_release);
     }
     hipLaunchKernelGGL(kern, dim3(blocks), dim3(NW * 64), lds_bytes, stream, (const uint16_t*)feats, out, perm, goff,
-                       num_groups, (int)max_groups, packed, sp, eps, n, G);
+                       num_groups, (int)max_groups, packed, sp, eps, n, G, drop);
     return launch_status();
   };
-  if (out_f32) return go(k_layer_mfma<C, DH, F, NVB, WPG, NW, MINW, true>);
-  return go(k_layer_mfma<C, DH, F, NVB, WPG, NW, MINW, false>);
+  if (out_f32) return go(k_layer_mfma<C, DH, F, NVB, WPG, NW, MINW, true>, 1);
+  return go(k_layer_mfma<C, DH, F, NVB, WPG, NW, MINW, false>, 0);
 }
 
 }  // namespace
@@ -832,7 +865,7 @@ int layer_mfma_pack(const ff_layer_weights* w, int count, void* packed, size_t s
 // variant: 0 = chosen from the shape; 1.. = a specific wave/group mapping (tuning and tests).
 int layer_mfma_launch(const void* feats, void* out, int64_t n, const int32_t* perm, const int32_t* group_offsets,
                       const int32_t* num_groups, int32_t max_groups, const ff_layer_weights* w, int G,
-                      bool out_f32, const void* packed, int variant, hipStream_t stream) {
+                      bool out_f32, bool drop, const void* packed, int variant, hipStream_t stream) {
   if (max_groups == 0 || n == 0) return FF_OK;
   SmallParams sp{(const uint16_t*)w->ln1_g, (const uint16_t*)w->ln1_b, (const uint16_t*)w->b_qkv,
                  (const uint16_t*)w->b_o,   (const uint16_t*)w->ln2_g, (const uint16_t*)w->ln2_b,
@@ -840,7 +873,7 @@ int layer_mfma_launch(const void* feats, void* out, int64_t n, const int32_t* pe
   const u32x4* pk = (const u32x4*)packed;
 #define FF_GO(C, DH, F, NVB, WPG, NW, MINW) \
   return launch_cfg<C, DH, F, NVB, WPG, NW, MINW>(feats, out, perm, group_offsets, num_groups, max_groups, pk, sp, \
-                                                  w->ln_eps, out_f32, (int)n, G, stream)
+                                                  w->ln_eps, out_f32, (int)n, G, drop ? 1 : 0, stream)
   const int shape = shape_id(w);
   // (pillar blocks per wave, waves per group, waves per workgroup, min waves per SIMD)
   if (shape == 1) {

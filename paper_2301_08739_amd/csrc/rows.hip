@@ -20,7 +20,61 @@ __global__ __launch_bounds__(256) void k_rows(const uint4* __restrict__ src, uin
   }
 }
 
+// Rows of sorted positions outside every group skip the layer ('Drop Residual', Sec. 4.3): for a
+// residual layer that means out = feats.  A workgroup looks at 64 consecutive sorted positions; a
+// position p is grouped when the last group start at or before p lies less than G before it.
+template <typename T, typename TO>
+__global__ __launch_bounds__(256) void k_copy_ungrouped(const T* __restrict__ feats, TO* __restrict__ out,
+                                                         const int32_t* __restrict__ perm,
+                                                         const int32_t* __restrict__ group_offsets,
+                                                         const int32_t* __restrict__ num_groups, int max_groups,
+                                                         int64_t n, int C, int G) {
+  __shared__ int32_t row_of[64];
+  const int64_t p0 = (int64_t)blockIdx.x * 64;
+  if (threadIdx.x < 64) {
+    const int64_t p = p0 + threadIdx.x;
+    int32_t row = -1;
+    if (p < n) {
+      int ng = max_groups > 0 ? *num_groups : 0;
+      ng = ng < 0 ? 0 : (ng > max_groups ? max_groups : ng);
+      int lo = 0, hi = ng;  // first group start beyond p
+      while (lo < hi) {
+        const int mid = (lo + hi) >> 1;
+        if (group_offsets[mid] <= p) lo = mid + 1; else hi = mid;
+      }
+      if (lo == 0 || p >= (int64_t)group_offsets[lo - 1] + G) row = perm[p];
+    }
+    row_of[threadIdx.x] = row;
+  }
+  __syncthreads();
+  for (int r = 0; r < 64; ++r) {
+    const int32_t row = row_of[r];
+    if (row < 0) continue;
+    for (int k = threadIdx.x; k < C; k += blockDim.x)
+      Elem<TO>::store(out + (int64_t)row * C + k, Elem<T>::load(feats + (int64_t)row * C + k));
+  }
+}
+
 }  // namespace
+
+int rows_copy_ungrouped_launch(const void* feats, void* out, int64_t n, const int32_t* perm,
+                               const int32_t* group_offsets, const int32_t* num_groups, int32_t max_groups, int C,
+                               int G, int dtype, bool out_f32, hipStream_t stream) {
+  if (n < 0 || C < 1 || G < 1 || max_groups < 0 || (dtype != FF_F32 && dtype != FF_BF16)) return FF_ERR_ARG;
+  if (n == 0) return FF_OK;
+  if (!feats || !out || !perm || (max_groups > 0 && (!group_offsets || !num_groups))) return FF_ERR_ARG;
+  const dim3 grid((unsigned)ceil_div(n, 64)), block(256);
+  if (dtype == FF_F32)
+    hipLaunchKernelGGL((k_copy_ungrouped<float, float>), grid, block, 0, stream, (const float*)feats, (float*)out,
+                       perm, group_offsets, num_groups, (int)max_groups, n, C, G);
+  else if (out_f32)
+    hipLaunchKernelGGL((k_copy_ungrouped<bf16_t, float>), grid, block, 0, stream, (const bf16_t*)feats, (float*)out,
+                       perm, group_offsets, num_groups, (int)max_groups, n, C, G);
+  else
+    hipLaunchKernelGGL((k_copy_ungrouped<bf16_t, bf16_t>), grid, block, 0, stream, (const bf16_t*)feats,
+                       (bf16_t*)out, perm, group_offsets, num_groups, (int)max_groups, n, C, G);
+  return launch_status();
+}
 
 int rows_launch(bool scatter, const void* src, void* dst, const int32_t* perm, int64_t n, int C,
                 int dtype, hipStream_t stream) {

@@ -27,9 +27,10 @@ def dtype_of(c):
     return ff.FF_F32 if c["dtype"] == "f32" else ff.FF_BF16
 
 
-def gpu_flatten(coords, g, axis, shift, G, want_keys=True):
+def gpu_flatten(coords, g, axis, shift, G, want_keys=True, tail=ff.FF_TAIL_MASK):
+    """(perm, group_offsets[:num_groups + 1], num_groups, keys, device tensors), on the host."""
     ct = torch.from_numpy(np.ascontiguousarray(coords, dtype=np.int32)).to(DEV)
-    perm, goff, ng, keys = ff.ff_flatten(ct, g, axis, shift, G, want_keys=want_keys)
+    perm, goff, ng, keys = ff.ff_flatten(ct, g, axis, shift, G, tail=tail, want_keys=want_keys)
     torch.cuda.synchronize()
     k = int(ng.item())
     return (perm.cpu().numpy(), goff.cpu().numpy()[:k + 1], k,

@@ -100,7 +100,7 @@ def test_errors_and_determinism():
     with pytest.raises(ff.FlatformerError):
         ff.ff_flatten(coords, ff.Geometry(1, 10, 10, 2, 2), 0, 0, 0)          # G 0
     with pytest.raises(ff.FlatformerError):
-        ff.ff_flatten(coords, ff.Geometry(1, 10, 10, 2, 2), 0, 0, 4, tail=1)  # drop mode not built
+        ff.ff_flatten(coords, ff.Geometry(1, 10, 10, 2, 2), 0, 0, 4, tail=2)  # no such tail mode
     with pytest.raises(ff.FlatformerError):                                   # 16+16+16+8+8 key bits + index
         ff.ff_flatten(coords, ff.Geometry(65535, 65535 * 256, 65535 * 256, 256, 256), 0, 0, 4)
     c = _rand_coords(50000, 2, 300, 300, seed=5)

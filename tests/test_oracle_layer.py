@@ -213,3 +213,35 @@ def test_stack_uses_four_sorts_and_drop_passthrough(cfg):
     out = oracle.layer(feats, pr, off_full, c["layer_params"][0])
     tail_rows = pr[off_full[-1]:]
     assert len(tail_rows) == 16 and np.array_equal(out[tail_rows], feats[tail_rows].astype(np.float64))
+
+
+def test_drop_residual_with_several_frames(cfg):
+    """'Drop Residual' (Sec. 4.3) over four frames, one of them shorter than a group: the listed
+    groups are exactly the full runs of G inside each frame, their rows equal the group layer of
+    those rows, and every other row is the input row."""
+    c = cfg(1, 1)
+    rng = np.random.default_rng(5)
+    counts = [70, 9, 64, 45]                                # frame sizes: 2+0+2+1 full groups of 32
+    coords = np.concatenate([np.column_stack([np.full(k, b), rng.permutation(40 * 40)[:k] // 40,
+                                              rng.permutation(40 * 40)[:k] % 40])
+                             for b, k in enumerate(counts)]).astype(np.int32)
+    coords = coords[rng.permutation(len(coords))]
+    n, G = len(coords), 32
+    feats = c["feats"][:n]
+    g = Geometry(4, 40, 40, 8, 8)
+    perm, starts, _ = oracle.flatten(coords, g, 1, 1, G, tail="drop")
+    frame_start = np.concatenate([[0], np.cumsum(counts)])
+    want = [int(frame_start[b]) + k * G for b in range(4) for k in range(counts[b] // G)]
+    assert starts.tolist() == want                          # brute force from the frame sizes
+    out = oracle.layer(feats, perm, starts, c["layer_params"][0], group_size=G)
+    grouped = np.zeros(n, bool)
+    for s0 in want:
+        rows = perm[s0:s0 + G]
+        assert len(set(coords[rows, 0])) == 1               # a group never spans two frames
+        assert np.array_equal(out[rows], oracle.group_layer(feats[rows].astype(np.float64), c["layer_params"][0]))
+        grouped[rows] = True
+    assert grouped.sum() == G * len(want) and (~grouped).sum() == 6 + 9 + 0 + 13
+    assert np.array_equal(out[~grouped], feats[~grouped].astype(np.float64))
+    # the masked list restricted to its full groups is the same list
+    _, off, _ = oracle.flatten(coords, g, 1, 1, G)
+    assert [int(a) for a, b in zip(off[:-1], off[1:]) if b - a == G] == want
