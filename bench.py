@@ -190,7 +190,8 @@ def main():
 
 
 def sweep(ff, torch, c, dt, dev):
-    """Saturation sweep: B copies of the frame as a batch (frame id in column 0), same C / G."""
+    """Saturation sweep: a batch of B frames (the frame of the configuration, cyclically shifted by a
+    random offset per frame; frame id in column 0), same C / G."""
     import numpy as np
     n1, C, F, G = c["n"], c["C"], c["F"], c["G"]
     esz = 4 if dt == ff.FF_F32 else 2
@@ -200,6 +201,11 @@ def sweep(ff, torch, c, dt, dev):
         coords = np.tile(c["coords"], (B, 1))
         coords[:, 0] = np.repeat(np.arange(B, dtype=np.int32), n1)
         rng = np.random.default_rng(B)
+        # every frame gets its own cyclic offset: identical frames would give every window the same
+        # population in every frame, a regularity real batches do not have
+        off = rng.integers(0, c["grid"], size=(B, 2))
+        off[0] = 0
+        coords[:, 1:] = (coords[:, 1:] + np.repeat(off, n1, axis=0)) % c["grid"]
         coords = np.ascontiguousarray(coords[rng.permutation(coords.shape[0])])
         n = coords.shape[0]
         geom = ff.Geometry(B, c["grid"], c["grid"], c["window"], c["window"])

@@ -45,6 +45,7 @@ constexpr int kMaxSorts = 4;
 constexpr int kSmallKpt = 4, kSmallMaxTiles = 64;   // small clouds: tiles of 1024 words
 constexpr int kLargeKpt = 16;                       // larger clouds: tiles of 4096 words
 constexpr int kScanThreads = 1024;
+constexpr int kScanStrip = 64;  // digits per workgroup of the column scan (narrower strips were no faster)
 
 struct KeyParams {
   int32_t B, win_x, win_y;
@@ -187,19 +188,20 @@ __global__ __launch_bounds__(kSortThreads) void k_tile_counts(const uint64_t* __
 }
 
 // ---- exclusive prefixes of a pass's table over the tiles, and the per-digit totals ------------------
-// One workgroup per 64 digits; wavefront w takes the w-th sixteenth of the rows, lane = digit.  Up to
-// 64 rows per wavefront are loaded at once and stay in registers between the two sweeps.
-template <int RB>
+// One workgroup per W digits (a strip of the table, W * 4 bytes of every row).  The rows are cut into
+// 1024 / W runs, W lanes take one run.  Up to 64 rows per run are loaded at once and stay in registers
+// between the two sweeps.
+template <int RB, int W>
 __global__ __launch_bounds__(kScanThreads) void k_scan_cols(uint32_t* __restrict__ counts, uint32_t* __restrict__ totals,
                                                              int pass, int P, int64_t tiles) {
-  constexpr int BINS = 1 << RB, WAVES = kScanThreads / 64, ROWS = 64;
-  __shared__ uint32_t part[WAVES][64];
-  const int s = blockIdx.y, lane = threadIdx.x & 63, w = threadIdx.x >> 6;
-  const int d = blockIdx.x * 64 + lane;
+  constexpr int BINS = 1 << RB, RUNS = kScanThreads / W, ROWS = 64;
+  __shared__ uint32_t part[RUNS][W];
+  const int s = blockIdx.y, dl = threadIdx.x % W, c = threadIdx.x / W;
+  const int d = blockIdx.x * W + dl;
   uint32_t* tab = counts + ((size_t)s * P + pass) * tiles * BINS + d;
-  const int64_t per = (tiles + WAVES - 1) / WAVES;
-  const int64_t r0 = w * per, r1 = r0 + per < tiles ? r0 + per : tiles;
-  const bool fits = per <= ROWS;  // the same for every wavefront
+  const int64_t per = (tiles + RUNS - 1) / RUNS;
+  const int64_t r0 = c * per, r1 = r0 + per < tiles ? r0 + per : tiles;
+  const bool fits = per <= ROWS;  // the same for every thread
   uint32_t v[ROWS];
   uint32_t sum = 0;
   if (fits) {
@@ -216,16 +218,16 @@ __global__ __launch_bounds__(kScanThreads) void k_scan_cols(uint32_t* __restrict
       for (int u = 0; u < 8; ++u) sum += t[u];
     }
   }
-  part[w][lane] = sum;
+  part[c][dl] = sum;
   __syncthreads();
   uint32_t run = 0, total = 0;
-#pragma unroll
-  for (int i = 0; i < WAVES; ++i) {
-    const uint32_t c = part[i][lane];
-    if (i < w) run += c;
-    total += c;
+#pragma unroll 8
+  for (int i = 0; i < RUNS; ++i) {
+    const uint32_t t = part[i][dl];
+    if (i < c) run += t;
+    total += t;
   }
-  if (w == 0) totals[((size_t)s * P + pass) * BINS + d] = total;
+  if (c == 0) totals[((size_t)s * P + pass) * BINS + d] = total;
   if (fits) {
 #pragma unroll
     for (int u = 0; u < ROWS; ++u) {
@@ -255,13 +257,19 @@ __global__ __launch_bounds__(kSortThreads) void k_pass(const uint64_t* __restric
                                                         int drop, uint32_t* __restrict__ counts,
                                                         const uint32_t* __restrict__ totals) {
   constexpr int BINS = 1 << RB, BPT = BINS / kSortThreads, WAVES = kSortThreads / 64, TILE = kSortThreads * KPT;
-  static_assert(BPT == 1 || BPT == 4, "digits of 8 or 10 bits");
-  __shared__ uint32_t wave_cnt[WAVES][BINS];  // later: frame starts and frame group bases
-  __shared__ uint32_t gbase[BINS];            // output position of a word = gbase[digit] + its stage slot
-  __shared__ uint32_t gdig[FUSE ? BINS : 1];  // first output position of a digit over the whole array
-  __shared__ uint32_t wave_totals[WAVES];
-  // first the per-wavefront match tables (one 64-bit lane mask per digit), then the output stage
+  static_assert(BPT == 1 || BPT == 2 || BPT == 4, "digits of 8, 9 or 10 bits");
+  // LDS is what limits the workgroups per compute unit (4 with 9-bit digits and 4096 words: 40 KB), so
+  // the two arrays are reused: wave_cnt holds the per-wavefront digit counters until the words are
+  // staged, then the output tables (row 0: gbase, output position of a word = gbase[digit] + its stage
+  // slot; row 1: gdig, first output position of a digit over the whole array; rows 2 and 3: the frame
+  // table of the last pass).  stage holds the per-wavefront match tables (one 64-bit lane mask per
+  // digit), then the scratch of the block scans, then the words in output order.
+  __shared__ uint32_t wave_cnt[WAVES][BINS];
   __shared__ uint64_t stage[TILE > WAVES * BINS ? TILE : WAVES * BINS];
+  static_assert(WAVES >= 4, "rows of wave_cnt are reused for four tables");
+  uint32_t* wave_totals = reinterpret_cast<uint32_t*>(stage);
+  uint32_t* gbase = &wave_cnt[0][0];
+  uint32_t* gdig = &wave_cnt[1][0];
 
   const int tid = threadIdx.x, lane = tid & 63, w = tid >> 6;
   const int s = blockIdx.y;
@@ -306,6 +314,9 @@ __global__ __launch_bounds__(kSortThreads) void k_pass(const uint64_t* __restric
         if (BPT == 4) {
           const uint4 q = *reinterpret_cast<const uint4*>(cnt_tab + (size_t)t * BINS + tid * 4);
           v[u][0] = q.x; v[u][1 % BPT] = q.y; v[u][2 % BPT] = q.z; v[u][3 % BPT] = q.w;
+        } else if (BPT == 2) {
+          const uint2 q = *reinterpret_cast<const uint2*>(cnt_tab + (size_t)t * BINS + tid * 2);
+          v[u][0] = q.x; v[u][1 % BPT] = q.y;
         } else {
           v[u][0] = cnt_tab[(size_t)t * BINS + tid];
         }
@@ -366,13 +377,14 @@ __global__ __launch_bounds__(kSortThreads) void k_pass(const uint64_t* __restric
   }
   const uint32_t gex = block_exclusive_scan<kSortThreads>(gsum, wave_totals, nullptr);
   const uint32_t tex = block_exclusive_scan<kSortThreads>(tsum, wave_totals, nullptr);
+  uint32_t gb[BPT], gd[BPT];
   {
     uint32_t grun = gex, trun = tex;
 #pragma unroll
     for (int k = 0; k < BPT; ++k) {
       const int d = tid * BPT + k;
-      gbase[d] = grun + before[k] - trun;  // output position = gbase[digit] + slot in the stage
-      if (FUSE) gdig[d] = grun;
+      gb[k] = grun + before[k] - trun;
+      gd[k] = grun;
 #pragma unroll
       for (int i = 0; i < WAVES; ++i) wave_cnt[i][d] += trun;  // first stage slot of (wave, digit)
       trun += total[k];
@@ -387,6 +399,12 @@ __global__ __launch_bounds__(kSortThreads) void k_pass(const uint64_t* __restric
       const uint32_t d = digit_rb(key[r], idx_bits, key_bits, pass, RB);
       stage[wave_cnt[w][d] + rank[r]] = key[r];
     }
+  }
+  __syncthreads();
+#pragma unroll
+  for (int k = 0; k < BPT; ++k) {
+    gbase[tid * BPT + k] = gb[k];
+    if (FUSE) gdig[tid * BPT + k] = gd[k];
   }
   __syncthreads();
   FP_TS(3);
@@ -411,12 +429,38 @@ __global__ __launch_bounds__(kSortThreads) void k_pass(const uint64_t* __restric
   }
 
   // ---- last pass: the output position is final -------------------------------------------------------
+  int32_t* __restrict__ const perm_s = bt.perm[s];  // read once: the stores below must not wait for them
+  uint64_t* __restrict__ const keys_s = bt.keys_sorted[s];
+  int32_t* __restrict__ const goff_s = bt.group_offsets[s];
+  const uint32_t idx_mask = idx_bits >= 32 ? ~0u : (1u << idx_bits) - 1u;  // n < 2^31
+  uint32_t pos_r[KPT], idx_r[KPT];
+#pragma unroll
+  for (int r = 0; r < KPT; ++r) {
+    const int j = r * kSortThreads + tid;
+    const uint64_t word = stage[j < tile_count ? j : 0];
+    const uint32_t d = digit_rb(word, idx_bits, key_bits, pass, RB);
+    pos_r[r] = j < tile_count ? gbase[d] + (uint32_t)j : 0xffffffffu;
+    idx_r[r] = (uint32_t)word & idx_mask;
+  }
+#pragma unroll
+  for (int r = 0; r < KPT; ++r)
+    if ((int64_t)pos_r[r] < n) perm_s[pos_r[r]] = (int32_t)idx_r[r];
+  if (keys_s) {  // the same for the whole workgroup
+#pragma unroll
+    for (int r = 0; r < KPT; ++r) {
+      if ((int64_t)pos_r[r] < n) {
+        uint32_t b;
+        keys_s[pos_r[r]] = exported_key(stage[r * kSortThreads + tid] >> idx_bits, kp, &b);
+      }
+    }
+  }
   // Frame b starts where the first last-pass digit of frame b starts; group bases are the running
   // sum of the frames' group counts, ceil(frame size / G), or floor when short groups are dropped.
-  // wave_cnt is free now: [0] = frame starts, [1] = group bases, [2] = group counts.
-  uint32_t* fstart = &wave_cnt[0][0];
-  uint32_t* fgroup = &wave_cnt[1][0];
-  uint32_t* fcount = &wave_cnt[2][0];
+  // The group list follows from that table alone: every workgroup builds the table and writes its
+  // share of the list.
+  __syncthreads();  // the stage has been read: its memory serves the block scan again
+  uint32_t* fstart = &wave_cnt[2][0];
+  uint32_t* fgroup = &wave_cnt[3][0];
   const int B = kp.B;
   const int nb_last = key_bits - pass * RB;       // bits of this digit (>= bits_b, checked by the host)
   const int fshift = nb_last - kp.bits_b;
@@ -439,33 +483,22 @@ __global__ __launch_bounds__(kSortThreads) void k_pass(const uint64_t* __restric
 #pragma unroll
   for (int k = 0; k < BPT; ++k) {
     const int b = tid * BPT + k;
-    if (b < B) { fstart[b] = fs[k]; fgroup[b] = gexcl; fcount[b] = gcount[k]; }
+    if (b < B) { fstart[b] = fs[k]; fgroup[b] = gexcl; }
     gexcl += gcount[k];
   }
   __syncthreads();
-  const uint64_t idx_mask = (1ull << idx_bits) - 1ull;
-#pragma unroll
-  for (int r = 0; r < KPT; ++r) {
-    const int j = r * kSortThreads + tid;
-    if (j < tile_count) {
-      const uint64_t word = stage[j];
-      const uint32_t d = digit_rb(word, idx_bits, key_bits, pass, RB);
-      const int64_t pos = (int64_t)(gbase[d] + (uint32_t)j);
-      if (pos < n) {
-        bt.perm[s][pos] = (int32_t)(word & idx_mask);
-        uint32_t b;
-        const uint64_t ek = exported_key(word >> idx_bits, kp, &b);
-        if (bt.keys_sorted[s]) bt.keys_sorted[s][pos] = ek;
-        const uint32_t fb = b < (uint32_t)B ? b : (uint32_t)B - 1u;
-        const uint32_t rel = (uint32_t)pos - fstart[fb], k = rel / (uint32_t)G;
-        if (rel == k * (uint32_t)G && k < fcount[fb]) bt.group_offsets[s][fgroup[fb] + k] = (int32_t)pos;
-      }
+  for (int64_t gi = tile * kSortThreads + tid; gi < (int64_t)ng_total; gi += tiles * kSortThreads) {
+    int lo = 0, hi = B;  // the last frame whose group base is at or below gi (empty frames share a base)
+    while (hi - lo > 1) {
+      const int mid = (lo + hi) >> 1;
+      if (fgroup[mid] <= (uint32_t)gi) lo = mid; else hi = mid;
     }
+    goff_s[gi] = (int32_t)(fstart[lo] + ((uint32_t)gi - fgroup[lo]) * (uint32_t)G);
   }
   FP_TS(4);
   if (tile == 0 && tid == 0) {
     *bt.num_groups[s] = (int32_t)ng_total;
-    bt.group_offsets[s][ng_total] = (int32_t)n;
+    goff_s[ng_total] = (int32_t)n;
   }
 }
 
@@ -576,15 +609,10 @@ struct PassPlan { bool small; int kpt, rb, passes; int64_t tiles; };
 inline PassPlan pass_plan(int64_t n, int key_bits) {
   PassPlan pp;
   pp.small = ceil_div(n > 0 ? n : 1, (int64_t)kSortThreads * kSmallKpt) <= kSmallMaxTiles;
-  if (pp.small) {
-    pp.kpt = kSmallKpt;
-    pp.passes = (key_bits + 9) / 10;
-    pp.rb = (key_bits + 7) / 8 == pp.passes ? 8 : 10;
-  } else {
-    pp.kpt = kLargeKpt;
-    pp.passes = (key_bits + 9) / 10;
-    pp.rb = (key_bits + 7) / 8 == pp.passes ? 8 : 10;
-  }
+  pp.kpt = pp.small ? kSmallKpt : kLargeKpt;
+  pp.passes = (key_bits + 9) / 10;
+  // the narrowest digit that still needs no extra pass: smaller tables, longer runs per digit
+  pp.rb = 8 * pp.passes >= key_bits ? 8 : 9 * pp.passes >= key_bits ? 9 : 10;
   pp.tiles = ceil_div(n > 0 ? n : 1, (int64_t)kSortThreads * pp.kpt);
   return pp;
 }
@@ -706,7 +734,7 @@ int flatten_launch(const int32_t* coords, int64_t n, const ff_geom* g, int num_s
           if (pass > 0)                                                                                              \
             hipLaunchKernelGGL((k_tile_counts<RB, KPT>), grid, block, 0, stream, buf[cur], n, bt, pass, P, pp.tiles, \
                                counts);                                                                              \
-          hipLaunchKernelGGL(k_scan_cols<RB>, dim3((1u << RB) / 64, (unsigned)num_sorts), dim3(kScanThreads), 0,    \
+          hipLaunchKernelGGL((k_scan_cols<RB, kScanStrip>), dim3((1u << RB) / kScanStrip, (unsigned)num_sorts), dim3(kScanThreads), 0,    \
                              stream, counts, totals, pass, P, pp.tiles);                                             \
         }                                                                                                            \
         if (fuse && pass == pp.passes - 1)                                                                           \
@@ -719,8 +747,10 @@ int flatten_launch(const int32_t* coords, int64_t n, const ff_geom* g, int num_s
       }                                                                                                              \
     } while (0)
     if (!pp.small && pp.rb == 8) FF_PASSES(8, kLargeKpt, true);
+    else if (!pp.small && pp.rb == 9) FF_PASSES(9, kLargeKpt, true);
     else if (!pp.small) FF_PASSES(10, kLargeKpt, true);
     else if (pp.rb == 8) FF_PASSES(8, kSmallKpt, false);
+    else if (pp.rb == 9) FF_PASSES(9, kSmallKpt, false);
     else FF_PASSES(10, kSmallKpt, false);
 #undef FF_PASSES
     outputs_done = fuse;
