@@ -245,3 +245,43 @@ def test_drop_residual_with_several_frames(cfg):
     # the masked list restricted to its full groups is the same list
     _, off, _ = oracle.flatten(coords, g, 1, 1, G)
     assert [int(a) for a, b in zip(off[:-1], off[1:]) if b - a == G] == want
+
+
+@pytest.mark.parametrize("C,F,heads,m", [(32, 48, 4, 11), (128, 256, 8, 64)])
+def test_positional_embedding_against_library_attention(C, F, heads, m):
+    """PE(C) of Eq. (2) as read here: queries and keys from LN(F) + PE, values from LN(F).  The
+    library's attention module takes the three inputs separately."""
+    p = ffsynth.layer_params(C, F, heads, seed=6)
+    rng = np.random.default_rng(2)
+    X, pe = rng.standard_normal((m, C)), 0.5 * rng.standard_normal((m, C))
+    enc = _torch_encoder_layer(p)
+    with torch.no_grad():
+        x = torch.tensor(X)[None]
+        u = enc.norm1(x)
+        qk = u + torch.tensor(pe)[None]
+        x1 = x + enc.self_attn(qk, qk, u, need_weights=False)[0]
+        want = (x1 + enc.linear2(torch.nn.functional.gelu(enc.linear1(enc.norm2(x1)))))[0].numpy()
+    got = oracle.group_layer(X, p, pe)
+    assert np.abs(got - want).max() < 1e-12
+    assert np.abs(got - oracle.group_layer(X, p)).max() > 1e-3          # the embedding matters
+    assert np.array_equal(oracle.group_layer(X, p, np.zeros((m, C))), oracle.group_layer(X, p))
+    # with no query and key projection the embedding cannot reach the output
+    p0 = dict(p)
+    p0["w_qkv"] = np.array(p["w_qkv"], dtype=np.float64)
+    p0["w_qkv"][:2 * C] = 0.0
+    assert np.array_equal(oracle.group_layer(X, p0, pe), oracle.group_layer(X, p0))
+
+
+def test_positional_embedding_rows_follow_the_pillars(cfg):
+    """layer() hands each group the embedding rows of its own members (pillar order, like feats)."""
+    c = cfg(1, 1)
+    n = 200
+    feats, coords, p = c["feats"][:n], c["coords"][:n], c["layer_params"][0]
+    pe = np.random.default_rng(3).standard_normal(feats.shape)
+    perm, off, _ = oracle.flatten(coords, Geometry(1, 64, 64, 8, 8), 1, 0, 32)
+    out = oracle.layer(feats, perm, off, p, pos_embed=pe)
+    for g in range(len(off) - 1):
+        rows = perm[off[g]:off[g + 1]]
+        assert np.array_equal(out[rows], oracle.group_layer(feats[rows].astype(np.float64), p, pe[rows]))
+    tr = oracle.stack(feats, {(1, 0): perm}, {(1, 0): off}, [p], [(1, 0)], pos_embed=pe)
+    assert np.array_equal(tr[-1], out)
