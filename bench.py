@@ -6,7 +6,7 @@ One "step" = one pass of the whole hot path over one synthetic frame: the sorts 
 layer stack (gather, LayerNorm, QKV, softmax attention, out-proj, FFN, scatter per layer).
 Inputs are resident in HBM before the timed region.  Prints ONE JSON line.
 
-    python bench.py [--gpus 1] [--steps K] [--warmup W] [--config 2] [--tail mask|drop] [--no-cpu] [--sweep]
+    python bench.py [--gpus 1] [--steps K] [--warmup W] [--config 2] [--tail mask|drop] [--pos-embed] [--no-cpu] [--sweep]
 """
 import argparse
 import json
@@ -89,6 +89,8 @@ def main():
     ap.add_argument("--variant", type=int, default=0, help="wave-to-group mapping of the fused layer kernel (0 = auto)")
     ap.add_argument("--tail", choices=("mask", "drop"), default="mask",
                     help="short last groups attend over their members (mask) or skip the layer (drop, Sec. 4.3)")
+    ap.add_argument("--pos-embed", action="store_true",
+                    help="hand every layer a positional embedding [n, C] (second argument of the attention in Eq. (2))")
     ap.add_argument("--copy-calibration", action="store_true",
                     help="also launch one plain 256 MiB device copy (reference for scaling rocprofv3 byte counters)")
     a = ap.parse_args()
@@ -117,9 +119,10 @@ def main():
     ws = torch.empty(ff.ff_fwa_block_workspace_bytes(n, geom, G, layers, dt) + 512, dtype=torch.uint8, device=dev)
 
     tail = ff.FF_TAIL_DROP if a.tail == "drop" else ff.FF_TAIL_MASK
+    pe = (0.5 * torch.randn_like(feats, dtype=torch.float32)).to(tdt) if a.pos_embed else None
 
     def step():
-        ff.ff_fwa_block(coords, geom, G, layers, dt, feats, out=out, workspace=ws, tail=tail)
+        ff.ff_fwa_block(coords, geom, G, layers, dt, feats, out=out, workspace=ws, tail=tail, pos_embed=pe)
 
     ms, wall_ms = time_region(step, a.steps, a.warmup)
 
@@ -135,7 +138,7 @@ def main():
     lpk = ff.LayerWeights(c["layer_params"][0], dt, dev).pack()       # exactly one kernel in the timed region
     vflag = ff.FF_FLAG_VARIANT(a.variant) | (ff.FF_FLAG_TAIL_DROP if a.tail == "drop" else 0)
     ms_layer, _ = time_region(lambda: ff.ff_group_attention(feats, perm, goff, ng, max_groups, lpk, G, dt, vflag,
-                                                            out=out, workspace=lws), reps, 5)
+                                                            out=out, workspace=lws, pos_embed=pe), reps, 5)
     ms_gather, _ = time_region(lambda: ff.ff_gather(feats, perm, dt, out=gth), reps, 5)
     ms_scatter, _ = time_region(lambda: ff.ff_scatter(gth, perm, dt, out=out), reps, 5)
 
@@ -167,7 +170,8 @@ def main():
                                f"B={c['B']}, window {c['window']}x{c['window']}, G={G}, C={C}, heads={c['heads']}, "
                                f"F={F}, {L} layers (x, y, shifted x, shifted y ...), "
                                f"{len(dict.fromkeys(c['schedule']))} sorts + {L} layers per step"
-                               + (", short groups dropped" if a.tail == "drop" else "")},
+                               + (", short groups dropped" if a.tail == "drop" else "")
+                               + (", with positional embedding" if a.pos_embed else "")},
         "roofline": {"bound": "mfma", "kernel": "group attention layer (ff_group_attention, one launch)",
                      "achieved": ach_tf, "peak": peak_tf, "unit": "TFLOP/s", "frac": ach_tf / peak_tf,
                      "traffic": MEASURED_LAYER_TRAFFIC.get(a.config) if a.variant == 0 else None,

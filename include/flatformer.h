@@ -101,7 +101,11 @@ int ff_flatten(const int32_t* coords /* [n,3] (b,x,y) */, int64_t n, const ff_ge
  * All parameter arrays have the element type `dtype` of the call.  LayerNorm uses the
  * biased variance and ln_eps.  w_qkv rows [0,C) are the query projection, [C,2C) key,
  * [2C,3C) value; head h owns rows h*d..(h+1)*d-1 of each third, d = C / heads.
- * The positional-embedding term of Eq. (2) is not part of this entry point.
+ *
+ * PE(C), the second argument of MHSA in Eq. (2), is a global absolute positional embedding the
+ * paper gives no formula for.  It enters as pos_embed: NULL, or a device array [n, C] of the
+ * call's dtype in pillar order (row i belongs to pillar i, like feats), computed by the caller.
+ * When given, queries and keys are projected from LN(F) + PE and values from LN(F).
  */
 typedef struct {
   const void *ln1_g, *ln1_b; /* [C]            */
@@ -113,6 +117,7 @@ typedef struct {
   int32_t C, F, heads;
   float ln_eps;
   const void* packed;        /* NULL, or the buffer written by ff_pack_weights for THESE weights */
+  const void* pos_embed;     /* NULL, or [n, C] per-call input (see above); not a weight, never packed */
 } ff_layer_weights;
 
 /* Weight pre-packing for the matrix-core kernels (optional).  The fused bf16 kernel reads the

@@ -31,7 +31,7 @@ class _LayerWeightsC(C.Structure):
     _fields_ = [(k, C.c_void_p) for k in ("ln1_g", "ln1_b", "w_qkv", "b_qkv", "w_o", "b_o",
                                           "ln2_g", "ln2_b", "w1", "b1", "w2", "b2")] + \
                [("C", C.c_int32), ("F", C.c_int32), ("heads", C.c_int32), ("ln_eps", C.c_float),
-                ("packed", C.c_void_p)]
+                ("packed", C.c_void_p), ("pos_embed", C.c_void_p)]
 
 
 _PARAMS = ("ln1_g", "ln1_b", "w_qkv", "b_qkv", "w_o", "b_o", "ln2_g", "ln2_b", "w1", "b1", "w2", "b2")
@@ -62,12 +62,13 @@ class LayerWeights:
         self._packed_buf, self.packed = buf, ptr
         return self
 
-    def struct(self):
+    def struct(self, pos_embed=None):
         s = _LayerWeightsC()
         for k in _PARAMS:
             setattr(s, k, self.tensors[k].data_ptr())
         s.C, s.F, s.heads, s.ln_eps = self.C, self.F, self.heads, self.ln_eps
         s.packed = self.packed
+        s.pos_embed = None if pos_embed is None else pos_embed.data_ptr()
         return s
 
 
@@ -174,15 +175,18 @@ def ff_group_attention_workspace_bytes(n, G, weights, dtype):
 
 
 def ff_group_attention(feats, perm, group_offsets, num_groups, max_groups, weights, G, dtype,
-                       flags=0, out=None, workspace=None):
-    """feats [n,C] (float32 or bfloat16 per dtype) -> out [n,C] in pillar order."""
+                       flags=0, out=None, workspace=None, pos_embed=None):
+    """feats [n,C] (float32 or bfloat16 per dtype) -> out [n,C] in pillar order.  pos_embed: None or a
+    tensor like feats (the positional embedding of every pillar)."""
     lib = load_library()
     assert feats.is_cuda and feats.is_contiguous()
     n = feats.shape[0]
     if out is None:
         odt = torch.float32 if (dtype == FF_F32 or (flags & FF_FLAG_OUT_F32)) else torch.bfloat16
         out = torch.empty((n, weights.C), dtype=odt, device=feats.device)
-    s = weights.struct()
+    if pos_embed is not None:
+        assert pos_embed.shape == feats.shape and pos_embed.dtype == feats.dtype and pos_embed.is_contiguous()
+    s = weights.struct(pos_embed)
     need = lib.ff_group_attention_workspace_bytes(n, G, C.byref(s), dtype)
     ws = workspace if workspace is not None else _workspace(need, feats.device)
     st = lib.ff_group_attention(_ptr(feats), _ptr(out), n, _ptr(perm), _ptr(group_offsets), _ptr(num_groups),
@@ -210,10 +214,10 @@ def ff_scatter(src, perm, dtype, out=None):
     return _rows("ff_scatter", src, perm, dtype, out)
 
 
-def _layer_array(layers):
+def _layer_array(layers, pos_embed=None):
     arr = (_LayerWeightsC * len(layers))()
     for i, l in enumerate(layers):
-        arr[i] = l.struct()
+        arr[i] = l.struct(pos_embed)
     return arr
 
 
@@ -222,10 +226,14 @@ def ff_fwa_block_workspace_bytes(n, geom, G, layers, dtype):
     return load_library().ff_fwa_block_workspace_bytes(int(n), C.byref(geom), G, arr, len(layers), dtype)
 
 
-def ff_fwa_block(coords, geom, G, layers, dtype, feats_in, out=None, workspace=None, tail=FF_TAIL_MASK):
+def ff_fwa_block(coords, geom, G, layers, dtype, feats_in, out=None, workspace=None, tail=FF_TAIL_MASK,
+                 pos_embed=None):
+    """pos_embed: None or a tensor like feats_in, handed to every layer of the block."""
     lib = load_library()
     n = coords.shape[0]
-    arr = _layer_array(layers)
+    if pos_embed is not None:
+        assert pos_embed.shape == feats_in.shape and pos_embed.dtype == feats_in.dtype and pos_embed.is_contiguous()
+    arr = _layer_array(layers, pos_embed)
     if out is None:
         out = torch.empty_like(feats_in)
     need = lib.ff_fwa_block_workspace_bytes(n, C.byref(geom), G, arr, len(layers), dtype)

@@ -69,6 +69,7 @@ int ff_group_attention(const void* feats, void* out, int64_t n, const int32_t* p
   if (n < 0 || n > 0x7fffffffLL || max_groups < 0 || G < 1) return FF_ERR_ARG;
   if (G > 1024) return FF_ERR_UNSUPPORTED;
   if (n > 0 && (!feats || !out || !perm || !group_offsets || !num_groups)) return FF_ERR_ARG;
+  if ((uintptr_t)w->pos_embed & 15) return FF_ERR_ARG;
   if (n > 0) {  // overlap of the two [n, C] buffers
     const size_t in_bytes = (size_t)n * w->C * elem_size(dtype);
     const size_t out_bytes = (size_t)n * w->C * ((flags & FF_FLAG_OUT_F32) ? 4 : elem_size(dtype));

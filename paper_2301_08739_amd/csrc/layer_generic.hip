@@ -41,7 +41,7 @@ __global__ __launch_bounds__(256) void k_ln_qkv(const T* __restrict__ feats, con
                                                  int64_t n, int C, const T* __restrict__ ln_g,
                                                  const T* __restrict__ ln_b, float eps,
                                                  const T* __restrict__ w_qkv, const T* __restrict__ b_qkv,
-                                                 float* __restrict__ qkv) {
+                                                 const T* __restrict__ pos_embed, float* __restrict__ qkv) {
   extern __shared__ float lds[];
   float* X = lds;              // [RB][C]
   float* U = X + RB * C;       // [RB][C]
@@ -57,15 +57,23 @@ __global__ __launch_bounds__(256) void k_ln_qkv(const T* __restrict__ feats, con
   __syncthreads();
   ln_rows(X, U, C, rows, gs, bs, eps);
   __syncthreads();
+  if (pos_embed) {  // queries and keys are projected from LN(F) + PE (kept in X), values from LN(F)
+    for (int i = threadIdx.x; i < RB * C; i += blockDim.x) {
+      const int r = i / C, k = i - r * C;
+      X[i] = r < rows ? U[i] + Elem<T>::load(pos_embed + (int64_t)perm[p0 + r] * C + k) : 0.f;
+    }
+    __syncthreads();
+  }
   for (int j = threadIdx.x; j < 3 * C; j += blockDim.x) {
     float acc[RB];
 #pragma unroll
     for (int r = 0; r < RB; ++r) acc[r] = 0.f;
     const T* wrow = w_qkv + (int64_t)j * C;
+    const float* in = pos_embed && j < 2 * C ? X : U;
     for (int k = 0; k < C; ++k) {
       const float wv = Elem<T>::load(wrow + k);
 #pragma unroll
-      for (int r = 0; r < RB; ++r) acc[r] = fmaf(U[r * C + k], wv, acc[r]);
+      for (int r = 0; r < RB; ++r) acc[r] = fmaf(in[r * C + k], wv, acc[r]);
     }
     const float bj = Elem<T>::load(b_qkv + j);
     for (int r = 0; r < rows; ++r) qkv[(p0 + r) * 3 * (int64_t)C + j] = acc[r] + bj;
@@ -201,7 +209,7 @@ int launch_typed(const void* feats, void* out, int64_t n, const int32_t* perm, c
   const size_t lds_c = (size_t)(3 * RB * C + RB * F + 2 * C) * 4;
   hipLaunchKernelGGL((k_ln_qkv<T>), dim3(row_blocks), dim3(256), lds_a, stream, (const T*)feats, perm, n, C,
                      (const T*)w->ln1_g, (const T*)w->ln1_b, w->ln_eps, (const T*)w->w_qkv,
-                     (const T*)w->b_qkv, qkv);
+                     (const T*)w->b_qkv, (const T*)w->pos_embed, qkv);
   dim3 ga((unsigned)max_groups, (unsigned)w->heads);
   if (d <= 16)       hipLaunchKernelGGL((k_attention<16>), ga, dim3(256), 0, stream, qkv, group_offsets, num_groups, C, d, G, o);
   else if (d <= 32)  hipLaunchKernelGGL((k_attention<32>), ga, dim3(256), 0, stream, qkv, group_offsets, num_groups, C, d, G, o);

@@ -246,8 +246,9 @@ struct LdsPlan {
   static_assert(RING >= 2, "weight ring");
 };
 
-template <int C, int DH, int F, int NVB, int WPG, int NW, int MINW, bool OUT_F32>
+template <int C, int DH, int F, int NVB, int WPG, int NW, int MINW, bool OUT_F32, bool PE>
 __global__ __launch_bounds__(NW * 64, MINW) void k_layer_mfma(const uint16_t* __restrict__ feats, void* __restrict__ out,
+                                                               const uint16_t* __restrict__ pos_embed,
                                                                const int32_t* __restrict__ perm,
                                                                const int32_t* __restrict__ goff,
                                                                const int32_t* __restrict__ num_groups, int max_groups,
@@ -388,6 +389,20 @@ __global__ __launch_bounds__(NW * 64, MINW) void k_layer_mfma(const uint16_t* __
       x1[vb][nb] = f32x4{t[0], t[1], t[2], t[3]};
     }
   }
+  // Positional embedding of my pillars, still bf16, in the layout of `act` (Eq. (2), second argument
+  // of the attention): it is added to the LayerNorm output on the way to the query and key products.
+  Frag8 pef[PE ? NVB : 1][PE ? KB : 1];
+  if constexpr (PE) {
+#pragma unroll
+    for (int vb = 0; vb < NVB; ++vb)
+#pragma unroll
+      for (int nb = 0; nb < NB; ++nb) {
+        uint2 u = make_uint2(0u, 0u);
+        if (row[vb] >= 0) u = *reinterpret_cast<const uint2*>(pos_embed + (int64_t)row[vb] * C + 16 * nb + 4 * q);
+        pef[vb][nb / 2].u[(nb & 1) * 2 + 0] = u.x;
+        pef[vb][nb / 2].u[(nb & 1) * 2 + 1] = u.y;
+      }
+  }
   FF_TS(1);
   if (drop) {
     // Pillars of no group skip the layer: their rows are copied.  The wavefronts of group g take the
@@ -430,7 +445,8 @@ __global__ __launch_bounds__(NW * 64, MINW) void k_layer_mfma(const uint16_t* __
   __builtin_amdgcn_sched_barrier(0);
 
   Frag8 act[NVB][KB];  // normalised activations as B operands (LN1 output, later LN2 output)
-  auto layer_norm = [&](int goff_f, int boff_f) {
+  Frag8 actqk[PE ? NVB : 1][PE ? KB : 1];  // LN1 output plus the positional embedding: input of Q and K
+  auto layer_norm = [&](int goff_f, int boff_f, bool first) {
     float sc[NVB], sh[NVB];  // y = x * sc + sh  with sc = rstd, sh = -mean * rstd
 #pragma unroll
     for (int vb = 0; vb < NVB; ++vb) {
@@ -456,6 +472,15 @@ __global__ __launch_bounds__(NW * 64, MINW) void k_layer_mfma(const uint16_t* __
         for (int j = 0; j < 4; ++j) y[j] = fmaf(fmaf(x1[vb][nb][j], sc[vb], sh[vb]), gm[j], bt[j]);
         act[vb][nb / 2].u[(nb & 1) * 2 + 0] = pack2(y[0], y[1]);
         act[vb][nb / 2].u[(nb & 1) * 2 + 1] = pack2(y[2], y[3]);
+        if constexpr (PE) {
+          if (first) {
+            const uint32_t p01 = pef[vb][nb / 2].u[(nb & 1) * 2 + 0], p23 = pef[vb][nb / 2].u[(nb & 1) * 2 + 1];
+            actqk[vb][nb / 2].u[(nb & 1) * 2 + 0] =
+                pack2(y[0] + __uint_as_float(p01 << 16), y[1] + __uint_as_float(p01 & 0xffff0000u));
+            actqk[vb][nb / 2].u[(nb & 1) * 2 + 1] =
+                pack2(y[2] + __uint_as_float(p23 << 16), y[3] + __uint_as_float(p23 & 0xffff0000u));
+          }
+        }
       }
     }
   };
@@ -475,7 +500,7 @@ __global__ __launch_bounds__(NW * 64, MINW) void k_layer_mfma(const uint16_t* __
     for (int c = 0; c < 2; ++c) bqk[c] = *reinterpret_cast<const f32x4*>(par + PO::BQ + 32 * hp + 16 * c + 4 * q);
   };
   if (!LEAN) load_unit_bias(0);
-  layer_norm(PO::LN1G, PO::LN1B);
+  layer_norm(PO::LN1G, PO::LN1B, true);
   add_bias_rows(PO::BO);  // residual + output-projection bias
   if (LEAN) { __builtin_amdgcn_sched_barrier(0); fill_window(); }
 
@@ -531,7 +556,8 @@ __global__ __launch_bounds__(NW * 64, MINW) void k_layer_mfma(const uint16_t* __
           }
 #pragma unroll
           for (int vb = 0; vb < NVB; ++vb)
-            acc[ch & 1][vb] = ch < 4 ? mfma32(wf, act[vb][kb], acc[ch & 1][vb]) : mfma32(act[vb][kb], wf, acc[ch & 1][vb]);
+            acc[ch & 1][vb] = ch < 4 ? mfma32(wf, PE ? actqk[PE ? vb : 0][PE ? kb : 0] : act[vb][kb], acc[ch & 1][vb])
+                                     : mfma32(act[vb][kb], wf, acc[ch & 1][vb]);
           if (kb == 0 && ch > 0) finish(ch - 1);
           refill(j);
         }
@@ -702,7 +728,7 @@ __global__ __launch_bounds__(NW * 64, MINW) void k_layer_mfma(const uint16_t* __
     for (int a = 0; a < 2; ++a) b1r[a] = *reinterpret_cast<const f32x4*>(par + PO::B1 + 32 * fc + 16 * a + 4 * q);
   };
   if (!LEAN) load_b1(0);
-  layer_norm(PO::LN2G, PO::LN2B);
+  layer_norm(PO::LN2G, PO::LN2B, false);
   add_bias_rows(PO::B2);
   FF_TS(11);
 #pragma unroll FULL_UNROLL
@@ -794,15 +820,16 @@ namespace {
 #endif
 
 template <int C, int DH, int F, int NVB, int WPG, int NW, int MINW>
-int launch_cfg(const void* feats, void* out, const int32_t* perm, const int32_t* goff, const int32_t* num_groups,
+int launch_cfg(const void* feats, void* out, const void* pos_embed, const int32_t* perm, const int32_t* goff,
+               const int32_t* num_groups,
                int32_t max_groups, const u32x4* packed, const SmallParams& sp, float eps, bool out_f32, int n, int G,
                int drop, hipStream_t stream) {
   constexpr int GPW = NW / WPG;
   const size_t lds_bytes = LdsPlan<C, F, NVB, WPG, NW, MINW>::TOTAL;
   const unsigned blocks = (unsigned)((max_groups + GPW - 1) / GPW);
-  // The dynamic LDS size has to be allowed once per kernel and device (both output types are
-  // separate kernels).
-  static std::atomic<uint64_t> allowed[2] = {{0}, {0}};  // bit d: done on device d
+  // The dynamic LDS size has to be allowed once per kernel and device (output type and positional
+  // embedding make four kernels of a mapping).
+  static std::atomic<uint64_t> allowed[4] = {{0}, {0}, {0}, {0}};  // bit d: done on device d
   auto go = [&](auto kern, int which) -> int {
     int dev = 0;
     if (hipGetDevice(&dev) != hipSuccess) return FF_ERR_LAUNCH;
@@ -813,12 +840,24 @@ int launch_cfg(const void* feats, void* out, const int32_t* perm, const int32_t*
         return FF_ERR_LAUNCH;
       allowed[which].fetch_or(bit, std::memory_order_release);
     }
-    hipLaunchKernelGGL(kern, dim3(blocks), dim3(NW * 64), lds_bytes, stream, (const uint16_t*)feats, out, perm, goff,
+    hipLaunchKernelGGL(kern, dim3(blocks), dim3(NW * 64), lds_bytes, stream, (const uint16_t*)feats, out,
+                       (const uint16_t*)pos_embed, perm, goff,
                        num_groups, (int)max_groups, packed, sp, eps, n, G, drop);
     return launch_status();
   };
-  if (out_f32) return go(k_layer_mfma<C, DH, F, NVB, WPG, NW, MINW, true>, 1);
-  return go(k_layer_mfma<C, DH, F, NVB, WPG, NW, MINW, false>, 0);
+  if (pos_embed) {
+    // Two mappings have no registers left for the second operand set (they would spill, which no
+    // shipped mapping may): they are not built with a positional embedding.
+    constexpr bool kFits = !(C == 128 && NVB == 2 && WPG == 1) && !(C == 256 && NW == 10);
+    if constexpr (kFits) {
+      if (out_f32) return go(k_layer_mfma<C, DH, F, NVB, WPG, NW, MINW, true, true>, 3);
+      return go(k_layer_mfma<C, DH, F, NVB, WPG, NW, MINW, false, true>, 2);
+    } else {
+      return FF_ERR_UNSUPPORTED;
+    }
+  }
+  if (out_f32) return go(k_layer_mfma<C, DH, F, NVB, WPG, NW, MINW, true, false>, 1);
+  return go(k_layer_mfma<C, DH, F, NVB, WPG, NW, MINW, false, false>, 0);
 }
 
 }  // namespace
@@ -872,7 +911,7 @@ int layer_mfma_launch(const void* feats, void* out, int64_t n, const int32_t* pe
                  (const uint16_t*)w->b1,    (const uint16_t*)w->b2};
   const u32x4* pk = (const u32x4*)packed;
 #define FF_GO(C, DH, F, NVB, WPG, NW, MINW) \
-  return launch_cfg<C, DH, F, NVB, WPG, NW, MINW>(feats, out, perm, group_offsets, num_groups, max_groups, pk, sp, \
+  return launch_cfg<C, DH, F, NVB, WPG, NW, MINW>(feats, out, w->pos_embed, perm, group_offsets, num_groups, max_groups, pk, sp, \
                                                   w->ln_eps, out_f32, (int)n, G, drop ? 1 : 0, stream)
   const int shape = shape_id(w);
   // (pillar blocks per wave, waves per group, waves per workgroup, min waves per SIMD)
@@ -892,7 +931,8 @@ int layer_mfma_launch(const void* feats, void* out, int64_t n, const int32_t* pe
       default: break;
     }
   } else if (shape == 2) {
-    if (variant == 0) variant = G <= 32 ? 1 : G <= 64 ? 2 : G <= 80 ? 3 : 4;
+    // with a positional embedding the ten-wave mapping has no registers to spare: one group per workgroup instead
+    if (variant == 0) variant = G <= 32 ? 1 : G <= 64 ? 2 : G <= 80 ? (w->pos_embed ? 6 : 3) : 4;
     switch (variant) {
       case 1: if (G <= 32) FF_GO(256, 32, 512, 1, 2, 8, 2); break;
       case 2: if (G <= 64) FF_GO(256, 32, 512, 1, 4, 8, 2); break;
