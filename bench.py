@@ -23,7 +23,7 @@ PEAK_F32_TFLOPS = 157.3        # fp32 vector / MFMA
 
 # HBM bytes per launch of the fused layer kernel, from rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE scaled by
 # a plain copy of known size (profiles/fwa_layer_cfg2_hbm_counters.txt): config id -> bytes.
-MEASURED_LAYER_TRAFFIC = {2: 17945007}
+MEASURED_LAYER_TRAFFIC = {2: 17959895}
 
 
 def layer_flops_per_voxel(C, F, G):
@@ -174,7 +174,7 @@ def main():
                                + (", with positional embedding" if a.pos_embed else "")},
         "roofline": {"bound": "mfma", "kernel": "group attention layer (ff_group_attention, one launch)",
                      "achieved": ach_tf, "peak": peak_tf, "unit": "TFLOP/s", "frac": ach_tf / peak_tf,
-                     "traffic": MEASURED_LAYER_TRAFFIC.get(a.config) if a.variant == 0 else None,
+                     "traffic": MEASURED_LAYER_TRAFFIC.get(a.config) if a.variant == 0 and a.tail == "mask" and not a.pos_embed else None,
                      "algorithmic_bytes": bytes_rows, "ms": ms_layer, "flops": flops_layer},
         "parts": {
             "flatten": {"ms": ms_flat, "bytes": bytes_flat, "GBps": bytes_flat / (ms_flat * 1e-3) / 1e9,
