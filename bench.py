@@ -6,7 +6,7 @@ One "step" = one pass of the whole hot path over one synthetic frame: the sorts 
 layer stack (gather, LayerNorm, QKV, softmax attention, out-proj, FFN, scatter per layer).
 Inputs are resident in HBM before the timed region.  Prints ONE JSON line.
 
-    python bench.py [--gpus 1] [--steps K] [--warmup W] [--config 2] [--tail mask|drop] [--pos-embed] [--no-cpu] [--sweep]
+    python bench.py [--gpus 1] [--steps K] [--warmup W] [--config 2] [--tail mask|drop] [--pos-embed] [--f16] [--no-cpu] [--sweep]
 """
 import argparse
 import json
@@ -89,6 +89,8 @@ def main():
     ap.add_argument("--variant", type=int, default=0, help="wave-to-group mapping of the fused layer kernel (0 = auto)")
     ap.add_argument("--tail", choices=("mask", "drop"), default="mask",
                     help="short last groups attend over their members (mask) or skip the layer (drop, Sec. 4.3)")
+    ap.add_argument("--f16", action="store_true",
+                    help="IEEE half storage and operands instead of the configuration's bf16 (the paper's precision)")
     ap.add_argument("--pos-embed", action="store_true",
                     help="hand every layer a positional embedding [n, C] (second argument of the attention in Eq. (2))")
     ap.add_argument("--copy-calibration", action="store_true",
@@ -108,8 +110,8 @@ def main():
     dev = torch.device("cuda:0")
     c = ffsynth.make_config(a.config)
     n, C, F, G, L = c["n"], c["C"], c["F"], c["G"], len(c["schedule"])
-    dt = ff.FF_F32 if c["dtype"] == "f32" else ff.FF_BF16
-    tdt = torch.float32 if dt == ff.FF_F32 else torch.bfloat16
+    dt = ff.FF_F32 if c["dtype"] == "f32" else (ff.FF_F16 if a.f16 else ff.FF_BF16)
+    tdt = {ff.FF_F32: torch.float32, ff.FF_BF16: torch.bfloat16, ff.FF_F16: torch.float16}[dt]
     esz = 4 if dt == ff.FF_F32 else 2
     geom = ff.Geometry(c["B"], c["grid"], c["grid"], c["window"], c["window"])
     coords = torch.from_numpy(c["coords"]).to(dev)
@@ -165,7 +167,7 @@ def main():
         "metric": "FWA block voxels/sec at 30k pillars C=128 G=64; %HBM BW sort, %MFMA attn",
         "value": n / (ms * 1e-3), "unit": "voxels/s", "n_gpus": 1, "steps": a.steps, "warmup": a.warmup,
         "ms_per_step": ms, "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
-        "dtype": "f32" if dt == ff.FF_F32 else "bf16", "data": "synthetic",
+        "dtype": {ff.FF_F32: "f32", ff.FF_BF16: "bf16", ff.FF_F16: "f16"}[dt], "data": "synthetic",
         "config": {"workload": f"config {a.config} ({c['name']}): {n} pillars on {c['grid']}x{c['grid']}, "
                                f"B={c['B']}, window {c['window']}x{c['window']}, G={G}, C={C}, heads={c['heads']}, "
                                f"F={F}, {L} layers (x, y, shifted x, shifted y ...), "
@@ -174,7 +176,7 @@ def main():
                                + (", with positional embedding" if a.pos_embed else "")},
         "roofline": {"bound": "mfma", "kernel": "group attention layer (ff_group_attention, one launch)",
                      "achieved": ach_tf, "peak": peak_tf, "unit": "TFLOP/s", "frac": ach_tf / peak_tf,
-                     "traffic": MEASURED_LAYER_TRAFFIC.get(a.config) if a.variant == 0 and a.tail == "mask" and not a.pos_embed else None,
+                     "traffic": MEASURED_LAYER_TRAFFIC.get(a.config) if a.variant == 0 and a.tail == "mask" and not a.pos_embed and not a.f16 else None,
                      "algorithmic_bytes": bytes_rows, "ms": ms_layer, "flops": flops_layer},
         "parts": {
             "flatten": {"ms": ms_flat, "bytes": bytes_flat, "GBps": bytes_flat / (ms_flat * 1e-3) / 1e9,
@@ -199,7 +201,7 @@ def sweep(ff, torch, c, dt, dev):
     import numpy as np
     n1, C, F, G = c["n"], c["C"], c["F"], c["G"]
     esz = 4 if dt == ff.FF_F32 else 2
-    tdt = torch.float32 if dt == ff.FF_F32 else torch.bfloat16
+    tdt = {ff.FF_F32: torch.float32, ff.FF_BF16: torch.bfloat16, ff.FF_F16: torch.float16}[dt]
     lw = ff.LayerWeights(c["layer_params"][0], dt, dev).pack()
     for B in (1, 8, 32, 128):
         coords = np.tile(c["coords"], (B, 1))

@@ -28,3 +28,9 @@ def bf16_bits_to_f32(b):
 def bf16_round(a):
     """float array -> float32 array whose every value is bf16-representable."""
     return bf16_bits_to_f32(f32_to_bf16_bits(np.asarray(a, dtype=np.float32)))
+
+
+def f16_round(a):
+    """float array -> float32 array whose every value is representable in IEEE half precision
+    (numpy's float16 conversion rounds to nearest, ties to even)."""
+    return np.asarray(a, dtype=np.float32).astype(np.float16).astype(np.float32)

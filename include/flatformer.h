@@ -40,7 +40,7 @@ typedef enum {
   FF_ERR_LAUNCH = -4       /* the HIP runtime refused a launch                  */
 } ff_status;
 
-typedef enum { FF_F32 = 0, FF_BF16 = 1 } ff_dtype;
+typedef enum { FF_F32 = 0, FF_BF16 = 1, FF_F16 = 2 /* IEEE half, the paper's inference precision */ } ff_dtype;
 
 typedef enum {
   FF_TAIL_MASK = 0, /* a frame's last group may be short; it attends over its real members only */
@@ -126,12 +126,13 @@ typedef struct {
  * per layer).  Weights that stay fixed across calls can be packed once: allocate
  * ff_pack_weights_bytes(w, dtype) bytes (256-byte aligned), call ff_pack_weights, and store the
  * pointer in w->packed.  ff_pack_weights_bytes returns 0 when the configuration has no packed
- * form (fp32, or a shape only the plain kernels cover); `packed` is then ignored. */
+ * form (fp32, or a shape only the plain kernels cover); `packed` is then ignored.  A packed
+ * buffer is specific to the dtype it was packed for. */
 size_t ff_pack_weights_bytes(const ff_layer_weights* w, int dtype);
 int ff_pack_weights(const ff_layer_weights* w, int dtype, void* packed, void* stream);
 
 /* Flags of ff_group_attention. */
-#define FF_FLAG_OUT_F32 1u      /* store `out` as float32 even when dtype is FF_BF16 */
+#define FF_FLAG_OUT_F32 1u      /* store `out` as float32 even when dtype is a 16-bit type */
 #define FF_FLAG_FORCE_GENERIC 2u /* use the plain fp32-arithmetic kernels for any dtype */
 #define FF_FLAG_TAIL_DROP 4u     /* the group list was made with FF_TAIL_DROP: rows of no group are copied through */
 /* Tuning knob: bits 8..11 select one wave-to-group mapping of the fused bf16 kernel (1..15; 0 =
@@ -152,8 +153,8 @@ size_t ff_group_attention_workspace_bytes(int64_t n, int G, const ff_layer_weigh
  * such row of `out` receives the row of `feats` (converted when the storage types differ), which
  * is what skipping the layer means for a residual layer; max_groups may then be as small as
  * floor(n/G), and 0 copies everything.
- * dtype FF_F32: fp32 arithmetic throughout.  FF_BF16: bf16 storage, bf16 MFMA operands, fp32
- * accumulation, statistics, softmax and GELU.
+ * dtype FF_F32: fp32 arithmetic throughout.  FF_BF16 / FF_F16: 16-bit storage, matrix-core operands
+ * of that type, fp32 accumulation, statistics, softmax and GELU.
  * Limits (FF_ERR_UNSUPPORTED otherwise): C % heads == 0, C*sizeof(dtype) % 16 == 0, 1 <= G <= 1024. */
 int ff_group_attention(const void* feats, void* out, int64_t n,
                        const int32_t* perm, const int32_t* group_offsets,

@@ -8,7 +8,8 @@ HERE = os.path.dirname(os.path.abspath(__file__))
 _LIB_PATH = os.path.join(HERE, "libflatformer.so")
 _lib = None
 
-FF_F32, FF_BF16 = 0, 1
+FF_F32, FF_BF16, FF_F16 = 0, 1, 2
+_TORCH_DTYPE = {FF_F32: torch.float32, FF_BF16: torch.bfloat16, FF_F16: torch.float16}
 FF_TAIL_MASK, FF_TAIL_DROP = 0, 1
 FF_FLAG_OUT_F32, FF_FLAG_FORCE_GENERIC, FF_FLAG_TAIL_DROP = 1, 2, 4
 
@@ -41,7 +42,7 @@ class LayerWeights:
     """Device tensors of one layer plus the ff_layer_weights struct that points at them."""
 
     def __init__(self, params, dtype, device="cuda"):
-        tdt = torch.float32 if dtype == FF_F32 else torch.bfloat16
+        tdt = _TORCH_DTYPE[dtype]
         self.dtype = dtype
         self.tensors = {k: torch.as_tensor(params[k], dtype=torch.float32).to(device=device, dtype=tdt).contiguous()
                         for k in _PARAMS}
@@ -176,13 +177,13 @@ def ff_group_attention_workspace_bytes(n, G, weights, dtype):
 
 def ff_group_attention(feats, perm, group_offsets, num_groups, max_groups, weights, G, dtype,
                        flags=0, out=None, workspace=None, pos_embed=None):
-    """feats [n,C] (float32 or bfloat16 per dtype) -> out [n,C] in pillar order.  pos_embed: None or a
+    """feats [n,C] (float32, bfloat16 or float16 per dtype) -> out [n,C] in pillar order.  pos_embed: None or a
     tensor like feats (the positional embedding of every pillar)."""
     lib = load_library()
     assert feats.is_cuda and feats.is_contiguous()
     n = feats.shape[0]
     if out is None:
-        odt = torch.float32 if (dtype == FF_F32 or (flags & FF_FLAG_OUT_F32)) else torch.bfloat16
+        odt = torch.float32 if (flags & FF_FLAG_OUT_F32) else _TORCH_DTYPE[dtype]
         out = torch.empty((n, weights.C), dtype=odt, device=feats.device)
     if pos_embed is not None:
         assert pos_embed.shape == feats.shape and pos_embed.dtype == feats.dtype and pos_embed.is_contiguous()

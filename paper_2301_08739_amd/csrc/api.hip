@@ -8,7 +8,7 @@ namespace {
 
 int check_weights(const ff_layer_weights* w, int dtype) {
   if (!w) return FF_ERR_ARG;
-  if (dtype != FF_F32 && dtype != FF_BF16) return FF_ERR_ARG;
+  if (dtype != FF_F32 && dtype != FF_BF16 && dtype != FF_F16) return FF_ERR_ARG;
   if (w->C < 1 || w->F < 1 || w->heads < 1) return FF_ERR_ARG;
   if (!w->ln1_g || !w->ln1_b || !w->w_qkv || !w->b_qkv || !w->w_o || !w->b_o || !w->ln2_g || !w->ln2_b ||
       !w->w1 || !w->b1 || !w->w2 || !w->b2)
@@ -19,6 +19,7 @@ int check_weights(const ff_layer_weights* w, int dtype) {
 }
 
 size_t elem_size(int dtype) { return dtype == FF_F32 ? 4 : 2; }
+bool is_16bit(int dtype) { return dtype == FF_BF16 || dtype == FF_F16; }  // the types with a fused matrix-core kernel
 
 }  // namespace
 
@@ -36,7 +37,7 @@ int ff_flatten(const int32_t* coords, int64_t n, const ff_geom* g, int axis, int
 }
 
 size_t ff_pack_weights_bytes(const ff_layer_weights* w, int dtype) {
-  if (check_weights(w, dtype) != FF_OK || dtype != FF_BF16) return 0;
+  if (check_weights(w, dtype) != FF_OK || !is_16bit(dtype)) return 0;
   if (!layer_mfma_supported(w, 1)) return 0;
   return layer_mfma_packed_bytes(w);
 }
@@ -44,16 +45,17 @@ size_t ff_pack_weights_bytes(const ff_layer_weights* w, int dtype) {
 int ff_pack_weights(const ff_layer_weights* w, int dtype, void* packed, void* stream) {
   int st = check_weights(w, dtype);
   if (st != FF_OK) return st;
-  if (dtype != FF_BF16 || !layer_mfma_supported(w, 1)) return FF_ERR_UNSUPPORTED;
+  if (!is_16bit(dtype) || !layer_mfma_supported(w, 1)) return FF_ERR_UNSUPPORTED;
   if (!packed || ((uintptr_t)packed & 255)) return FF_ERR_ARG;
-  return layer_mfma_pack(w, 1, packed, 0, (hipStream_t)stream);
+  return dtype == FF_F16 ? layer_mfma_pack_f16(w, 1, packed, 0, (hipStream_t)stream)
+                         : layer_mfma_pack(w, 1, packed, 0, (hipStream_t)stream);
 }
 
 size_t ff_group_attention_workspace_bytes(int64_t n, int G, const ff_layer_weights* w, int dtype) {
   if (n < 0 || check_weights(w, dtype) != FF_OK) return 0;
   // Sized for either path so that a flag can switch kernels without a new query.
   size_t b = layer_generic_workspace_bytes(n, w);
-  if (dtype == FF_BF16 && layer_mfma_supported(w, G)) {
+  if (is_16bit(dtype) && layer_mfma_supported(w, G)) {
     const size_t p = align_up(layer_mfma_packed_bytes(w), 256);
     if (p > b) b = p;
   }
@@ -81,18 +83,23 @@ int ff_group_attention(const void* feats, void* out, int64_t n, const int32_t* p
   if (drop && n > 0 && max_groups == 0)  // no group can exist: every row skips the layer
     return rows_copy_ungrouped_launch(feats, out, n, perm, group_offsets, num_groups, 0, w->C, G, dtype, out_f32,
                                       (hipStream_t)stream);
-  if (dtype == FF_BF16 && !(flags & FF_FLAG_FORCE_GENERIC) && layer_mfma_supported(w, G)) {
+  if (is_16bit(dtype) && !(flags & FF_FLAG_FORCE_GENERIC) && layer_mfma_supported(w, G)) {
     if (n == 0 || max_groups == 0) return FF_OK;
     const void* packed = w->packed;
     if (!packed) {
       if (!workspace || ((uintptr_t)workspace & 255) || workspace_bytes < layer_mfma_packed_bytes(w))
         return FF_ERR_WORKSPACE;
-      st = layer_mfma_pack(w, 1, workspace, 0, (hipStream_t)stream);
+      st = dtype == FF_F16 ? layer_mfma_pack_f16(w, 1, workspace, 0, (hipStream_t)stream)
+                           : layer_mfma_pack(w, 1, workspace, 0, (hipStream_t)stream);
       if (st != FF_OK) return st;
       packed = workspace;
     }
+    const int variant = (int)((flags >> 8) & 0xf);
+    if (dtype == FF_F16)
+      return layer_mfma_launch_f16(feats, out, n, perm, group_offsets, num_groups, max_groups, w, G, out_f32, drop,
+                                   packed, variant, (hipStream_t)stream);
     return layer_mfma_launch(feats, out, n, perm, group_offsets, num_groups, max_groups, w, G, out_f32, drop,
-                             packed, (int)((flags >> 8) & 0xf), (hipStream_t)stream);
+                             packed, variant, (hipStream_t)stream);
   }
   st = layer_generic_launch(feats, out, n, perm, group_offsets, num_groups, max_groups, w, G, dtype, out_f32,
                             workspace, workspace_bytes, (hipStream_t)stream);
@@ -150,7 +157,7 @@ int make_block_plan(int64_t n, const ff_geom* g, int G, const ff_layer_weights* 
   // One batched packing launch for the whole stack when every layer has the same packable shape
   // and the caller did not pre-pack.
   p->packed_stride = 0;
-  if (dtype == FF_BF16 && layer_mfma_supported(&layers[0], G)) {
+  if (is_16bit(dtype) && layer_mfma_supported(&layers[0], G)) {
     bool same = true;
     for (int l = 0; l < num_layers; ++l)
       same = same && layers[l].F == layers[0].F && layers[l].heads == layers[0].heads && !layers[l].packed;
@@ -196,7 +203,8 @@ int ff_fwa_block(const int32_t* coords, int64_t n, const ff_geom* g, int G, int 
     if (st != FF_OK) return st;
   }
   if (p.packed_stride && n > 0) {
-    st = layer_mfma_pack(layers, num_layers, ws + p.off_packed, p.packed_stride, (hipStream_t)stream);
+    st = dtype == FF_F16 ? layer_mfma_pack_f16(layers, num_layers, ws + p.off_packed, p.packed_stride, (hipStream_t)stream)
+                         : layer_mfma_pack(layers, num_layers, ws + p.off_packed, p.packed_stride, (hipStream_t)stream);
     if (st != FF_OK) return st;
   }
   const void* cur = feats_in;

@@ -25,8 +25,9 @@ __device__ __forceinline__ uint16_t f32_to_bf16(float f) {
   return (uint16_t)(u >> 16);
 }
 
-// Storage-type traits: T is float or bf16_t (a 16-bit wrapper).
+// Storage-type traits: T is float, bf16_t or f16_t (16-bit wrappers).
 struct bf16_t { uint16_t bits; };
+struct f16_t { uint16_t bits; };
 template <typename T> struct Elem;
 template <> struct Elem<float> {
   static __device__ __forceinline__ float load(const float* p) { return *p; }
@@ -35,6 +36,10 @@ template <> struct Elem<float> {
 template <> struct Elem<bf16_t> {
   static __device__ __forceinline__ float load(const bf16_t* p) { return bf16_to_f32(p->bits); }
   static __device__ __forceinline__ void store(bf16_t* p, float v) { p->bits = f32_to_bf16(v); }
+};
+template <> struct Elem<f16_t> {  // IEEE half, round to nearest even
+  static __device__ __forceinline__ float load(const f16_t* p) { return (float)__builtin_bit_cast(_Float16, p->bits); }
+  static __device__ __forceinline__ void store(f16_t* p, float v) { p->bits = __builtin_bit_cast(uint16_t, (_Float16)v); }
 };
 
 // ---- flatten plan (host) -------------------------------------------------------------------------
@@ -79,5 +84,10 @@ int layer_mfma_pack(const ff_layer_weights* w, int count, void* packed, size_t s
 int layer_mfma_launch(const void* feats, void* out, int64_t n, const int32_t* perm, const int32_t* group_offsets,
                       const int32_t* num_groups, int32_t max_groups, const ff_layer_weights* w, int G,
                       bool out_f32, bool drop, const void* packed, int variant, hipStream_t stream);
+// the same two for IEEE half storage (layer_mfma_f16.hip); shapes and packed size do not differ
+int layer_mfma_pack_f16(const ff_layer_weights* w, int count, void* packed, size_t stride_bytes, hipStream_t stream);
+int layer_mfma_launch_f16(const void* feats, void* out, int64_t n, const int32_t* perm, const int32_t* group_offsets,
+                          const int32_t* num_groups, int32_t max_groups, const ff_layer_weights* w, int G,
+                          bool out_f32, bool drop, const void* packed, int variant, hipStream_t stream);
 
 }  // namespace ff

@@ -241,6 +241,11 @@ int layer_generic_launch(const void* feats, void* out, int64_t n, const int32_t*
   float* o = (float*)((char*)workspace + align_up((size_t)n * 3 * C * 4, 256));
   if (dtype == FF_F32)
     return launch_typed<float, float>(feats, out, n, perm, group_offsets, num_groups, max_groups, w, d, G, qkv, o, stream);
+  if (dtype == FF_F16) {
+    if (out_f32)
+      return launch_typed<f16_t, float>(feats, out, n, perm, group_offsets, num_groups, max_groups, w, d, G, qkv, o, stream);
+    return launch_typed<f16_t, f16_t>(feats, out, n, perm, group_offsets, num_groups, max_groups, w, d, G, qkv, o, stream);
+  }
   if (out_f32)
     return launch_typed<bf16_t, float>(feats, out, n, perm, group_offsets, num_groups, max_groups, w, d, G, qkv, o, stream);
   return launch_typed<bf16_t, bf16_t>(feats, out, n, perm, group_offsets, num_groups, max_groups, w, d, G, qkv, o, stream);

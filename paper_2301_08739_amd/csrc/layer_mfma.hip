@@ -35,36 +35,57 @@ __device__ long long ff_probe_blk[2][2048];  // wall-clock start and end of wave
 namespace ff {
 namespace {
 
-typedef __bf16 bf16x8 __attribute__((ext_vector_type(8)));
-typedef __bf16 bf16x2 __attribute__((ext_vector_type(2)));
-typedef short s16x4 __attribute__((ext_vector_type(4)));
+// ---- number format of the 16-bit storage and of the matrix-core operands --------------------------------
+// This source builds the bfloat16 kernels; layer_mfma_f16.hip defines FF_LAYER_F16 and includes it
+// to build the IEEE half kernels (the precision the paper runs in, Sec. 5.1) from the same code.
+#ifdef FF_LAYER_F16
+typedef _Float16 el8 __attribute__((ext_vector_type(8)));
+typedef _Float16 el4 __attribute__((ext_vector_type(4)));
+typedef _Float16 el2 __attribute__((ext_vector_type(2)));
+constexpr uint32_t kOnePair = 0x3c003c00u;  // two ones
+__device__ __forceinline__ float el_to_f32(uint16_t h) { return (float)__builtin_bit_cast(_Float16, h); }
+__device__ __forceinline__ uint16_t f32_to_el(float f) { return __builtin_bit_cast(uint16_t, (_Float16)f); }
+__device__ __forceinline__ float el_lo(uint32_t u) { return el_to_f32((uint16_t)(u & 0xffffu)); }
+__device__ __forceinline__ float el_hi(uint32_t u) { return el_to_f32((uint16_t)(u >> 16)); }
+#define FF_LAYER_SYM(name) name##_f16
+#else
+typedef __bf16 el8 __attribute__((ext_vector_type(8)));
+typedef short el4 __attribute__((ext_vector_type(4)));
+typedef __bf16 el2 __attribute__((ext_vector_type(2)));
+constexpr uint32_t kOnePair = 0x3f803f80u;  // two ones
+__device__ __forceinline__ float el_to_f32(uint16_t h) { return bf16_to_f32(h); }
+__device__ __forceinline__ uint16_t f32_to_el(float f) { return f32_to_bf16(f); }
+__device__ __forceinline__ float el_lo(uint32_t u) { return __uint_as_float(u << 16); }
+__device__ __forceinline__ float el_hi(uint32_t u) { return __uint_as_float(u & 0xffff0000u); }
+#define FF_LAYER_SYM(name) name
+#endif
 typedef float f32x4 __attribute__((ext_vector_type(4)));
 typedef float f32x2 __attribute__((ext_vector_type(2)));
 typedef uint32_t u32x4 __attribute__((ext_vector_type(4)));
 typedef uint32_t u32x2 __attribute__((ext_vector_type(2)));
 
-union Frag8 {  // eight bf16 = one operand of the k=32 product
-  bf16x8 v;
+union Frag8 {  // eight 16-bit elements = one operand of the k=32 product
+  el8 v;
   uint32_t u[4];
   u32x4 q;
 };
-union Frag4 {  // four bf16 = one operand of the k=16 product
-  s16x4 v;
+union Frag4 {  // four 16-bit elements = one operand of the k=16 product
+  el4 v;
   uint32_t u[2];
   u32x2 d;
 };
 
 __device__ __forceinline__ uint32_t pack2(float lo, float hi) {
   f32x2 f = {lo, hi};
-  bf16x2 r = __builtin_convertvector(f, bf16x2);  // round to nearest even
+  el2 r = __builtin_convertvector(f, el2);  // round to nearest even
   return *reinterpret_cast<uint32_t*>(&r);
 }
-__device__ __forceinline__ void load4(const uint16_t* p, float* o) {  // 4 consecutive bf16 -> fp32
+__device__ __forceinline__ void load4(const uint16_t* p, float* o) {  // 4 consecutive elements -> fp32
   const uint2 u = *reinterpret_cast<const uint2*>(p);
-  o[0] = __uint_as_float(u.x << 16);
-  o[1] = __uint_as_float(u.x & 0xffff0000u);
-  o[2] = __uint_as_float(u.y << 16);
-  o[3] = __uint_as_float(u.y & 0xffff0000u);
+  o[0] = el_lo(u.x);
+  o[1] = el_hi(u.x);
+  o[2] = el_lo(u.y);
+  o[3] = el_hi(u.y);
 }
 // Reductions over the 4 lanes that share a pillar (lane, lane^16, lane^32, lane^48), on the
 // vector ALU: v_permlane16_swap / v_permlane32_swap with both operands equal to v return the
@@ -82,10 +103,18 @@ __device__ __forceinline__ float quad_max(float v) {
   return fmaxf(__uint_as_float(b[0]), __uint_as_float(b[1]));
 }
 __device__ __forceinline__ f32x4 mfma32(const Frag8& a, const Frag8& b, f32x4 c) {
+#ifdef FF_LAYER_F16
+  return __builtin_amdgcn_mfma_f32_16x16x32_f16(a.v, b.v, c, 0, 0, 0);
+#else
   return __builtin_amdgcn_mfma_f32_16x16x32_bf16(a.v, b.v, c, 0, 0, 0);
+#endif
 }
 __device__ __forceinline__ f32x4 mfma16(const Frag4& a, const Frag4& b, f32x4 c) {
+#ifdef FF_LAYER_F16
+  return __builtin_amdgcn_mfma_f32_16x16x16f16(a.v, b.v, c, 0, 0, 0);
+#else
   return __builtin_amdgcn_mfma_f32_16x16x16bf16_1k(a.v, b.v, c, 0, 0, 0);
+#endif
 }
 // GELU(v) = v * Phi(v) with the upper tail 1 - Phi(t) ~ 0.5 * exp(-(a t + b t^2 + c t^3)), t = |v|
 // (coefficients fitted to the erf form; all positive, so the exponent is monotone for any t):
@@ -165,12 +194,12 @@ __global__ __launch_bounds__(256) void k_pack_weights(PackBatch pb, int C, int F
     if (o < C) {
       const uint16_t* __restrict__ bv = pb.b_qkv[blockIdx.y] + 2 * C;
       for (int k = seg * len; k < (seg + 1) * len; ++k)
-        acc = fmaf(bf16_to_f32(w_o[(size_t)o * C + k]), bf16_to_f32(bv[k]), acc);
+        acc = fmaf(el_to_f32(w_o[(size_t)o * C + k]), el_to_f32(bv[k]), acc);
     }
     acc += __shfl_xor(acc, 1);
     acc += __shfl_xor(acc, 2);
     acc += __shfl_xor(acc, 4);
-    if (o < C && seg == 0) reinterpret_cast<float*>(out + (size_t)total_frags * 64)[o] = acc + bf16_to_f32(pb.b_o[blockIdx.y][o]);
+    if (o < C && seg == 0) reinterpret_cast<float*>(out + (size_t)total_frags * 64)[o] = acc + el_to_f32(pb.b_o[blockIdx.y][o]);
     return;
   }
   const int KB = C / 32, NB = C / 16, fr_hp = 6 * KB + NB, fr_fc = 2 * KB + NB, n_hp = C / 32;
@@ -212,8 +241,8 @@ __global__ __launch_bounds__(256) void k_pack_weights(PackBatch pb, int C, int F
   if (halve) {
 #pragma unroll
     for (int s = 0; s < 4; ++s) {
-      const uint32_t lo = f32_to_bf16(0.5f * bf16_to_f32((uint16_t)(u[s] & 0xffffu)));
-      const uint32_t hi = f32_to_bf16(0.5f * bf16_to_f32((uint16_t)(u[s] >> 16)));
+      const uint32_t lo = f32_to_el(0.5f * el_lo(u[s]));
+      const uint32_t hi = f32_to_el(0.5f * el_hi(u[s]));
       u[s] = lo | (hi << 16);
     }
   }
@@ -367,7 +396,7 @@ __global__ __launch_bounds__(NW * 64, MINW) void k_layer_mfma(const uint16_t* __
     else if (t < 6 * C) { src = t < 5 * C ? sp.ln2_g : sp.ln2_b; o = t < 5 * C ? t - 4 * C : t - 5 * C; }
     else if (t < 7 * C) { src = sp.b2; o = t - 6 * C; }
     else { src = sp.b1; o = t - 7 * C; }
-    par[t] = bf16_to_f32(src[o]);
+    par[t] = el_to_f32(src[o]);
   }
 
   // ---- gather + LN1 ---------------------------------------------------------------------------------
@@ -419,8 +448,8 @@ __global__ __launch_bounds__(NW * 64, MINW) void k_layer_mfma(const uint16_t* __
           float* dst = reinterpret_cast<float*>(out) + at;
 #pragma unroll
           for (int e = 0; e < 4; ++e) {
-            dst[2 * e] = __uint_as_float(v[e] << 16);
-            dst[2 * e + 1] = __uint_as_float(v[e] & 0xffff0000u);
+            dst[2 * e] = el_lo(v[e]);
+            dst[2 * e + 1] = el_hi(v[e]);
           }
         } else {
           *reinterpret_cast<u32x4*>(reinterpret_cast<uint16_t*>(out) + at) = v;
@@ -476,9 +505,9 @@ __global__ __launch_bounds__(NW * 64, MINW) void k_layer_mfma(const uint16_t* __
           if (first) {
             const uint32_t p01 = pef[vb][nb / 2].u[(nb & 1) * 2 + 0], p23 = pef[vb][nb / 2].u[(nb & 1) * 2 + 1];
             actqk[vb][nb / 2].u[(nb & 1) * 2 + 0] =
-                pack2(y[0] + __uint_as_float(p01 << 16), y[1] + __uint_as_float(p01 & 0xffff0000u));
+                pack2(y[0] + el_lo(p01), y[1] + el_hi(p01));
             actqk[vb][nb / 2].u[(nb & 1) * 2 + 1] =
-                pack2(y[2] + __uint_as_float(p23 << 16), y[3] + __uint_as_float(p23 & 0xffff0000u));
+                pack2(y[2] + el_lo(p23), y[3] + el_hi(p23));
           }
         }
       }
@@ -678,14 +707,14 @@ __global__ __launch_bounds__(NW * 64, MINW) void k_layer_mfma(const uint16_t* __
               O[hh][vb][a] = mfma32(v8, p8, O[hh][vb][a]);
             }
             Frag8 ones;
-            ones.u[0] = ones.u[1] = ones.u[2] = ones.u[3] = 0x3f803f80u;
+            ones.u[0] = ones.u[1] = ones.u[2] = ones.u[3] = kOnePair;
             rowsum[hh][vb] = mfma32(ones, p8, rowsum[hh][vb]);
           }
           if (NKB & 1) {
             constexpr int jb = NKB - 1;
             Frag4 p4, ones;
             p4.u[0] = pack2(S[hh][vb][jb][0], S[hh][vb][jb][1]); p4.u[1] = pack2(S[hh][vb][jb][2], S[hh][vb][jb][3]);
-            ones.u[0] = ones.u[1] = 0x3f803f80u;
+            ones.u[0] = ones.u[1] = kOnePair;
 #pragma unroll
             for (int a = 0; a < NA; ++a) O[hh][vb][a] = mfma16(Vget(DH == 16 ? h : a, jb), p4, O[hh][vb][a]);
             rowsum[hh][vb] = mfma16(ones, p4, rowsum[hh][vb]);
@@ -870,20 +899,25 @@ static int shape_id(const ff_layer_weights* w) {
   return 0;
 }
 
+#ifndef FF_LAYER_F16  // the same for both formats
 bool layer_mfma_supported(const ff_layer_weights* w, int G) { return shape_id(w) != 0 && G <= 128; }
+#endif
 
 static size_t layer_mfma_frag_count(const ff_layer_weights* w) {
   const int C = w->C, F = w->F;
   return (size_t)((C / 32) * frags_per_hp(C) + (F / 32) * frags_per_fc(C));
 }
 
+#ifndef FF_LAYER_F16
 size_t layer_mfma_packed_bytes(const ff_layer_weights* w) {
   const int C = w->C, F = w->F;
   return layer_mfma_frag_count(w) * (size_t)1024 + (size_t)C * 4;
 }
+#endif
 
 // Packs `count` layers of identical shape; layer l goes to packed + l * stride_bytes.
-int layer_mfma_pack(const ff_layer_weights* w, int count, void* packed, size_t stride_bytes, hipStream_t stream) {
+int FF_LAYER_SYM(layer_mfma_pack)(const ff_layer_weights* w, int count, void* packed, size_t stride_bytes,
+                                  hipStream_t stream) {
   const int total = (int)layer_mfma_frag_count(w);
   for (int l0 = 0; l0 < count; l0 += kPackBatch) {
     const int nl = count - l0 < kPackBatch ? count - l0 : kPackBatch;
@@ -902,7 +936,7 @@ int layer_mfma_pack(const ff_layer_weights* w, int count, void* packed, size_t s
 }
 
 // variant: 0 = chosen from the shape; 1.. = a specific wave/group mapping (tuning and tests).
-int layer_mfma_launch(const void* feats, void* out, int64_t n, const int32_t* perm, const int32_t* group_offsets,
+int FF_LAYER_SYM(layer_mfma_launch)(const void* feats, void* out, int64_t n, const int32_t* perm, const int32_t* group_offsets,
                       const int32_t* num_groups, int32_t max_groups, const ff_layer_weights* w, int G,
                       bool out_f32, bool drop, const void* packed, int variant, hipStream_t stream) {
   if (max_groups == 0 || n == 0) return FF_OK;

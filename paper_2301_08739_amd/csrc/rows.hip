@@ -60,17 +60,20 @@ __global__ __launch_bounds__(256) void k_copy_ungrouped(const T* __restrict__ fe
 int rows_copy_ungrouped_launch(const void* feats, void* out, int64_t n, const int32_t* perm,
                                const int32_t* group_offsets, const int32_t* num_groups, int32_t max_groups, int C,
                                int G, int dtype, bool out_f32, hipStream_t stream) {
-  if (n < 0 || C < 1 || G < 1 || max_groups < 0 || (dtype != FF_F32 && dtype != FF_BF16)) return FF_ERR_ARG;
+  if (n < 0 || C < 1 || G < 1 || max_groups < 0 || (dtype != FF_F32 && dtype != FF_BF16 && dtype != FF_F16)) return FF_ERR_ARG;
   if (n == 0) return FF_OK;
   if (!feats || !out || !perm || (max_groups > 0 && (!group_offsets || !num_groups))) return FF_ERR_ARG;
   const dim3 grid((unsigned)ceil_div(n, 64)), block(256);
   if (dtype == FF_F32)
     hipLaunchKernelGGL((k_copy_ungrouped<float, float>), grid, block, 0, stream, (const float*)feats, (float*)out,
                        perm, group_offsets, num_groups, (int)max_groups, n, C, G);
+  else if (out_f32 && dtype == FF_F16)
+    hipLaunchKernelGGL((k_copy_ungrouped<f16_t, float>), grid, block, 0, stream, (const f16_t*)feats, (float*)out,
+                       perm, group_offsets, num_groups, (int)max_groups, n, C, G);
   else if (out_f32)
     hipLaunchKernelGGL((k_copy_ungrouped<bf16_t, float>), grid, block, 0, stream, (const bf16_t*)feats, (float*)out,
                        perm, group_offsets, num_groups, (int)max_groups, n, C, G);
-  else
+  else  // 16 bits to the same 16 bits: a bit copy for either format
     hipLaunchKernelGGL((k_copy_ungrouped<bf16_t, bf16_t>), grid, block, 0, stream, (const bf16_t*)feats,
                        (bf16_t*)out, perm, group_offsets, num_groups, (int)max_groups, n, C, G);
   return launch_status();
@@ -78,7 +81,7 @@ int rows_copy_ungrouped_launch(const void* feats, void* out, int64_t n, const in
 
 int rows_launch(bool scatter, const void* src, void* dst, const int32_t* perm, int64_t n, int C,
                 int dtype, hipStream_t stream) {
-  if (n < 0 || C < 1 || (dtype != FF_F32 && dtype != FF_BF16)) return FF_ERR_ARG;
+  if (n < 0 || C < 1 || (dtype != FF_F32 && dtype != FF_BF16 && dtype != FF_F16)) return FF_ERR_ARG;
   const size_t row_bytes = (size_t)C * (dtype == FF_F32 ? 4 : 2);
   if (row_bytes % 16) return FF_ERR_UNSUPPORTED;
   if (n == 0) return FF_OK;

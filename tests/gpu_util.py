@@ -16,7 +16,7 @@ def geoms(c):
 
 def to_dev_feats(feats, dtype):
     t = torch.from_numpy(np.ascontiguousarray(feats, dtype=np.float32))
-    return t.to(DEV) if dtype == ff.FF_F32 else t.to(DEV).to(torch.bfloat16)
+    return t.to(DEV).to({ff.FF_F32: torch.float32, ff.FF_BF16: torch.bfloat16, ff.FF_F16: torch.float16}[dtype])
 
 
 def to_host(t):
