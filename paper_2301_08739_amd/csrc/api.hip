@@ -1,6 +1,7 @@
 // extern "C" entry points: argument checks, workspace carving and launch order.  No kernel lives
 // here; see flatten.hip, rows.hip, layer_generic.hip, layer_mfma.hip.
 #include "common.h"
+#include "pack_weights.h"
 
 using namespace ff;
 
@@ -33,7 +34,7 @@ int ff_flatten(const int32_t* coords, int64_t n, const ff_geom* g, int axis, int
   if (tail != FF_TAIL_MASK && tail != FF_TAIL_DROP) return FF_ERR_ARG;
   if (shift != 0 && shift != 1) return FF_ERR_ARG;
   return flatten_launch(coords, n, g, 1, &axis, &shift, G, tail == FF_TAIL_DROP, &perm, &group_offsets, &num_groups, &keys_sorted,
-                        workspace, workspace_bytes, (hipStream_t)stream);
+                        workspace, workspace_bytes, nullptr, (hipStream_t)stream);
 }
 
 size_t ff_pack_weights_bytes(const ff_layer_weights* w, int dtype) {
@@ -198,14 +199,20 @@ int ff_fwa_block(const int32_t* coords, int64_t n, const ff_geom* g, int G, int 
       goff[s] = (int32_t*)(ws + p.off_goff + s * goff_stride);
       ng[s] = (int32_t*)(ws + p.off_ng) + s;
     }
+    // The layers' weights are re-tiled by extra workgroups of the first sort kernel when one launch can
+    // take them all; otherwise by a launch of their own.
+    PackJob job;
+    const bool ride = p.packed_stride && n > 0 && num_layers <= kPackBatch;
+    if (ride) make_pack_job(layers, num_layers, ws + p.off_packed, p.packed_stride, dtype == FF_F16, &job);
     st = flatten_launch(coords, n, g, p.sorts, axis, shift, G, drop, perm, goff, ng, nullptr, ws + p.off_flat,
-                        p.flat_bytes, (hipStream_t)stream);
+                        p.flat_bytes, ride ? &job : nullptr, (hipStream_t)stream);
     if (st != FF_OK) return st;
-  }
-  if (p.packed_stride && n > 0) {
-    st = dtype == FF_F16 ? layer_mfma_pack_f16(layers, num_layers, ws + p.off_packed, p.packed_stride, (hipStream_t)stream)
-                         : layer_mfma_pack(layers, num_layers, ws + p.off_packed, p.packed_stride, (hipStream_t)stream);
-    if (st != FF_OK) return st;
+    if (p.packed_stride && n > 0 && !ride) {
+      st = dtype == FF_F16
+               ? layer_mfma_pack_f16(layers, num_layers, ws + p.off_packed, p.packed_stride, (hipStream_t)stream)
+               : layer_mfma_pack(layers, num_layers, ws + p.off_packed, p.packed_stride, (hipStream_t)stream);
+      if (st != FF_OK) return st;
+    }
   }
   const void* cur = feats_in;
   void* bufs[2] = {ws + p.off_a, ws + p.off_b};

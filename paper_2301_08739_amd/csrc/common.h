@@ -57,11 +57,13 @@ constexpr int kSortThreads = 256;
 int make_flatten_plan(int64_t n, const ff_geom* g, int axis, int shift, FlattenPlan* plan);
 size_t flatten_workspace_bytes(int64_t n, const ff_geom* g, int num_sorts);
 
-// num_sorts (1..4) sort configurations of the same cloud, sorted together.
+// num_sorts (1..4) sort configurations of the same cloud, sorted together.  pack: nullptr, or layer
+// weights to re-tile in extra workgroups of the first kernel (n > 0 only; see pack_weights.h).
+struct PackJob;
 int flatten_launch(const int32_t* coords, int64_t n, const ff_geom* g, int num_sorts, const int* axis,
                    const int* shift, int G, int drop, int32_t* const* perm, int32_t* const* group_offsets,
                    int32_t* const* num_groups, uint64_t* const* keys_sorted, void* workspace,
-                   size_t workspace_bytes, hipStream_t stream);
+                   size_t workspace_bytes, const PackJob* pack, hipStream_t stream);
 
 int rows_launch(bool scatter, const void* src, void* dst, const int32_t* perm, int64_t n, int C,
                 int dtype, hipStream_t stream);

@@ -26,6 +26,7 @@
 //   * The last pass writes perm, exported keys and group offsets itself when its digit contains
 //     the whole frame field; otherwise two small output kernels run.
 #include "common.h"
+#include "pack_weights.h"
 
 #ifdef FF_PROBE
 __device__ long long ff_probe_flat[64];
@@ -132,14 +133,31 @@ __device__ __forceinline__ uint64_t exported_key(uint64_t k, const KeyParams& kp
 
 // ---- A1: coords -> sortable words, plus the digit counts of the first pass ---------------------------
 // counts [S][P][tiles][BINS]
+// A sort kernel can take workgroups along that do not sort: they re-tile layer weights for the fused
+// attention kernels (pack_weights.h), work that does not depend on the sort and would otherwise cost
+// a launch of its own in front of the first layer.  Such a launch has a wider grid; the workgroups
+// are numbered in dispatch order, the first tiles * sorts of them sort, the rest pack.
+__device__ __forceinline__ void pack_tail(const PackJob& pack, int id) {
+  const int layer = id / pack.blocks, blk = id - layer * pack.blocks;
+  if (layer >= pack.layers) return;
+  if (pack.half) pack_weights_block<true>(pack.pb, layer, blk, pack.C, pack.F, pack.total_frags);
+  else pack_weights_block<false>(pack.pb, layer, blk, pack.C, pack.F, pack.total_frags);
+}
+
 template <int RB, int KPT>
 __global__ __launch_bounds__(kSortThreads) void k_keygen(const int32_t* __restrict__ coords, int64_t n, Batch bt, int P,
                                                           int64_t tiles, uint64_t* __restrict__ words,
-                                                          uint32_t* __restrict__ counts) {
+                                                          uint32_t* __restrict__ counts, PackJob pack) {
   constexpr int BINS = 1 << RB, TILE = kSortThreads * KPT;
+  static_assert(kSortThreads == 256, "pack_weights_block works in workgroups of 256 threads");
+  const int64_t wg = (int64_t)blockIdx.y * gridDim.x + blockIdx.x;  // dispatch order
+  if (wg >= tiles * gridDim.y) {  // the same for the whole workgroup
+    pack_tail(pack, (int)(wg - tiles * gridDim.y));
+    return;
+  }
   __shared__ uint32_t h[BINS];
-  const int s = blockIdx.y, tid = threadIdx.x;
-  const int64_t tile = blockIdx.x;
+  const int s = (int)(wg / tiles), tid = threadIdx.x;
+  const int64_t tile = wg % tiles;
   const KeyParams kp = bt.kp[s];
   for (int t = tid; t < BINS; t += kSortThreads) h[t] = 0u;
   __syncthreads();
@@ -255,7 +273,7 @@ template <int RB, int KPT, bool FUSE, bool SCANNED>
 __global__ __launch_bounds__(kSortThreads) void k_pass(const uint64_t* __restrict__ in_all, uint64_t* __restrict__ out_all,
                                                         int64_t n, Batch bt, int pass, int P, int64_t tiles, int G,
                                                         int drop, uint32_t* __restrict__ counts,
-                                                        const uint32_t* __restrict__ totals) {
+                                                        const uint32_t* __restrict__ totals, PackJob pack) {
   constexpr int BINS = 1 << RB, BPT = BINS / kSortThreads, WAVES = kSortThreads / 64, TILE = kSortThreads * KPT;
   static_assert(BPT == 1 || BPT == 2 || BPT == 4, "digits of 8, 9 or 10 bits");
   // LDS is what limits the workgroups per compute unit (4 with 9-bit digits and 4096 words: 40 KB), so
@@ -272,8 +290,13 @@ __global__ __launch_bounds__(kSortThreads) void k_pass(const uint64_t* __restric
   uint32_t* gdig = &wave_cnt[1][0];
 
   const int tid = threadIdx.x, lane = tid & 63, w = tid >> 6;
-  const int s = blockIdx.y;
-  const int64_t tile = blockIdx.x;
+  const int64_t wg = (int64_t)blockIdx.y * gridDim.x + blockIdx.x;  // dispatch order
+  if (wg >= tiles * gridDim.y) {  // the same for the whole workgroup
+    pack_tail(pack, (int)(wg - tiles * gridDim.y));
+    return;
+  }
+  const int s = (int)(wg / tiles);
+  const int64_t tile = wg % tiles;
   const KeyParams kp = bt.kp[s];
   const int idx_bits = kp.idx_bits, key_bits = kp.key_bits;
   const uint64_t* in = in_all + (int64_t)s * n;
@@ -681,7 +704,7 @@ size_t flatten_workspace_bytes(int64_t n, const ff_geom* g, int num_sorts) {
 int flatten_launch(const int32_t* coords, int64_t n, const ff_geom* g, int num_sorts, const int* axis,
                    const int* shift, int G, int drop, int32_t* const* perm, int32_t* const* group_offsets,
                    int32_t* const* num_groups, uint64_t* const* keys_sorted, void* workspace,
-                   size_t workspace_bytes, hipStream_t stream) {
+                   size_t workspace_bytes, const PackJob* pack, hipStream_t stream) {
   if (num_sorts < 1 || num_sorts > kMaxSorts || G < 1) return FF_ERR_ARG;
   Batch bt;
   int max_key_bits = 0;
@@ -726,9 +749,16 @@ int flatten_launch(const int32_t* coords, int64_t n, const ff_geom* g, int num_s
     for (int s = 0; s < num_sorts; ++s)
       fuse = fuse && bt.kp[s].key_bits - (pp.passes - 1) * pp.rb >= bt.kp[s].bits_b;
     const dim3 grid((unsigned)pp.tiles, (unsigned)num_sorts), block(kSortThreads);
+    // The first radix pass takes the weight-packing workgroups along (key generation when there is no
+    // pass): that launch is bound by the latency of a few sort workgroups and leaves most of the chip idle.
+    PackJob no_job = PackJob();
+    no_job.layers = 0; no_job.blocks = 1;
+    const PackJob job = pack ? *pack : no_job;
+    const dim3 grid_pack((unsigned)(pp.tiles + ceil_div((int64_t)job.layers * job.blocks, num_sorts)), (unsigned)num_sorts);
 #define FF_PASSES(RB, KPT, SCANNED)                                                                                  \
     do {                                                                                                             \
-      hipLaunchKernelGGL((k_keygen<RB, KPT>), grid, block, 0, stream, coords, n, bt, P, pp.tiles, buf[0], counts);   \
+      hipLaunchKernelGGL((k_keygen<RB, KPT>), pp.passes > 0 ? grid : grid_pack, block, 0, stream, coords, n, bt, P,  \
+                         pp.tiles, buf[0], counts, pp.passes > 0 ? no_job : job);                                     \
       for (int pass = 0; pass < pp.passes; ++pass) {                                                                 \
         if (SCANNED) {                                                                                               \
           if (pass > 0)                                                                                              \
@@ -738,11 +768,13 @@ int flatten_launch(const int32_t* coords, int64_t n, const ff_geom* g, int num_s
                              stream, counts, totals, pass, P, pp.tiles);                                             \
         }                                                                                                            \
         if (fuse && pass == pp.passes - 1)                                                                           \
-          hipLaunchKernelGGL((k_pass<RB, KPT, true, SCANNED>), grid, block, 0, stream, buf[cur], buf[cur ^ 1], n,   \
-                             bt, pass, P, pp.tiles, G, drop, counts, totals);                                        \
+          hipLaunchKernelGGL((k_pass<RB, KPT, true, SCANNED>), pass == 0 ? grid_pack : grid, block, 0, stream,      \
+                             buf[cur], buf[cur ^ 1], n, bt, pass, P, pp.tiles, G, drop, counts, totals,              \
+                             pass == 0 ? job : no_job);                                                              \
         else                                                                                                         \
-          hipLaunchKernelGGL((k_pass<RB, KPT, false, SCANNED>), grid, block, 0, stream, buf[cur], buf[cur ^ 1], n,  \
-                             bt, pass, P, pp.tiles, G, drop, counts, totals);                                        \
+          hipLaunchKernelGGL((k_pass<RB, KPT, false, SCANNED>), pass == 0 ? grid_pack : grid, block, 0, stream,     \
+                             buf[cur], buf[cur ^ 1], n, bt, pass, P, pp.tiles, G, drop, counts, totals,              \
+                             pass == 0 ? job : no_job);                                                              \
         cur ^= 1;                                                                                                    \
       }                                                                                                              \
     } while (0)

@@ -25,6 +25,7 @@
 // in stream order through a window of 8 fragments in registers, requested 8 products ahead of
 // their use, so that LDS latency is hidden behind the matrix cores.
 #include "common.h"
+#include "pack_weights.h"
 #include <atomic>
 
 #ifdef FF_PROBE
@@ -165,88 +166,14 @@ struct SmallParams {  // per-feature vectors, bf16, read straight from the calle
 __host__ __device__ constexpr int frags_per_hp(int C) { return 6 * (C / 32) + C / 16; }
 __host__ __device__ constexpr int frags_per_fc(int C) { return 2 * (C / 32) + C / 16; }
 
-// ---- weight packing ------------------------------------------------------------------------------
-// Stream order: for each 32-wide head-dim unit hp: Q rows (2 x KB fragments), K rows, V rows,
-// W_o column slice (NB fragments); then for each 32-wide hidden unit fc: W1 rows (2 x KB), W2
-// column slice (NB).  A fragment is 16 output features x 32 inputs; lane (i, q) owns 16 bytes:
-// row i, inputs kbase + 16*(s/4) + 4q + (s%4) for slot s = 0..7.
-constexpr int kPackBatch = 16;
-struct PackBatch {  // up to 16 layers of identical shape packed by one launch (grid.y = layer)
-  const uint16_t *w_qkv[kPackBatch], *w_o[kPackBatch], *w1[kPackBatch], *w2[kPackBatch];
-  const uint16_t *b_qkv[kPackBatch], *b_o[kPackBatch];
-  uint4* out[kPackBatch];
-};
-// After the fragments the packed buffer holds C floats: the output-projection bias with the value
-// bias folded in.  Every softmax row sums to one, so P (V + 1 b_v^T) W_o^T = P V W_o^T + (W_o b_v)^T:
-// the value bias is a constant row added after the projection.  (The key bias shifts all scores
-// of a query by the same amount and drops out of the softmax altogether.)
+// ---- weight packing (pack_weights.h) as a kernel of its own: grid (blocks per layer, layers) -----------
+#ifdef FF_LAYER_F16
+constexpr bool kHalf = true;
+#else
+constexpr bool kHalf = false;
+#endif
 __global__ __launch_bounds__(256) void k_pack_weights(PackBatch pb, int C, int F, int total_frags) {
-  const uint16_t* __restrict__ w_qkv = pb.w_qkv[blockIdx.y];
-  const uint16_t* __restrict__ w_o = pb.w_o[blockIdx.y];
-  const uint16_t* __restrict__ w1 = pb.w1[blockIdx.y];
-  const uint16_t* __restrict__ w2 = pb.w2[blockIdx.y];
-  uint4* __restrict__ out = pb.out[blockIdx.y];
-  const int t = blockIdx.x * blockDim.x + threadIdx.x;
-  const int frag = t >> 6, lane = t & 63, i = lane & 15, q = lane >> 4;
-  if (frag >= total_frags) {  // folded output bias: eight lanes per output feature
-    const int u = t - total_frags * 64, o = u >> 3, seg = u & 7, len = C / 8;
-    float acc = 0.f;
-    if (o < C) {
-      const uint16_t* __restrict__ bv = pb.b_qkv[blockIdx.y] + 2 * C;
-      for (int k = seg * len; k < (seg + 1) * len; ++k)
-        acc = fmaf(el_to_f32(w_o[(size_t)o * C + k]), el_to_f32(bv[k]), acc);
-    }
-    acc += __shfl_xor(acc, 1);
-    acc += __shfl_xor(acc, 2);
-    acc += __shfl_xor(acc, 4);
-    if (o < C && seg == 0) reinterpret_cast<float*>(out + (size_t)total_frags * 64)[o] = acc + el_to_f32(pb.b_o[blockIdx.y][o]);
-    return;
-  }
-  const int KB = C / 32, NB = C / 16, fr_hp = 6 * KB + NB, fr_fc = 2 * KB + NB, n_hp = C / 32;
-  const uint16_t* src;
-  int kbase;
-  bool halve = false;  // W2 carries the 0.5 of the GELU (see gelu2_fast)
-  if (frag < n_hp * fr_hp) {
-    const int hp = frag / fr_hp, r = frag % fr_hp;
-    if (r < 6 * KB) {
-      const int which = r / (2 * KB), rr = r % (2 * KB), a = rr / KB, kb = rr % KB;
-      src = w_qkv + (size_t)(which * C + 32 * hp + 16 * a + i) * C;
-      kbase = 32 * kb;
-    } else {
-      const int nb = r - 6 * KB;
-      src = w_o + (size_t)(16 * nb + i) * C;
-      kbase = 32 * hp;
-    }
-  } else {
-    const int f2 = frag - n_hp * fr_hp, fc = f2 / fr_fc, r = f2 % fr_fc;
-    if (r < 2 * KB) {
-      const int a = r / KB, kb = r % KB;
-      src = w1 + (size_t)(32 * fc + 16 * a + i) * C;
-      kbase = 32 * kb;
-    } else {
-      const int nb = r - 2 * KB;
-      src = w2 + (size_t)(16 * nb + i) * F;
-      kbase = 32 * fc;
-      halve = true;
-    }
-  }
-  // slots 0..3 are inputs kbase + 4q .. + 3, slots 4..7 the same plus 16: two 8-byte loads
-  uint32_t u[4];
-#pragma unroll
-  for (int h = 0; h < 2; ++h) {
-    const uint2 v = *reinterpret_cast<const uint2*>(src + kbase + 16 * h + 4 * q);
-    u[2 * h] = v.x;
-    u[2 * h + 1] = v.y;
-  }
-  if (halve) {
-#pragma unroll
-    for (int s = 0; s < 4; ++s) {
-      const uint32_t lo = f32_to_el(0.5f * el_lo(u[s]));
-      const uint32_t hi = f32_to_el(0.5f * el_hi(u[s]));
-      u[s] = lo | (hi << 16);
-    }
-  }
-  out[(size_t)frag * 64 + lane] = make_uint4(u[0], u[1], u[2], u[3]);
+  pack_weights_block<kHalf>(pb, blockIdx.y, blockIdx.x, C, F, total_frags);
 }
 
 // ---- the fused layer ------------------------------------------------------------------------------
@@ -918,19 +845,12 @@ size_t layer_mfma_packed_bytes(const ff_layer_weights* w) {
 // Packs `count` layers of identical shape; layer l goes to packed + l * stride_bytes.
 int FF_LAYER_SYM(layer_mfma_pack)(const ff_layer_weights* w, int count, void* packed, size_t stride_bytes,
                                   hipStream_t stream) {
-  const int total = (int)layer_mfma_frag_count(w);
   for (int l0 = 0; l0 < count; l0 += kPackBatch) {
     const int nl = count - l0 < kPackBatch ? count - l0 : kPackBatch;
-    PackBatch pb;
-    for (int l = 0; l < kPackBatch; ++l) {
-      const ff_layer_weights* wl = &w[l0 + (l < nl ? l : 0)];
-      pb.w_qkv[l] = (const uint16_t*)wl->w_qkv; pb.w_o[l] = (const uint16_t*)wl->w_o;
-      pb.w1[l] = (const uint16_t*)wl->w1; pb.w2[l] = (const uint16_t*)wl->w2;
-      pb.b_qkv[l] = (const uint16_t*)wl->b_qkv; pb.b_o[l] = (const uint16_t*)wl->b_o;
-      pb.out[l] = (uint4*)((char*)packed + (size_t)(l0 + (l < nl ? l : 0)) * stride_bytes);
-    }
-    hipLaunchKernelGGL(k_pack_weights, dim3((unsigned)((total * 64 + 8 * w->C + 255) / 256), (unsigned)nl), dim3(256), 0, stream,
-                       pb, w->C, w->F, total);
+    PackJob job;
+    make_pack_job(w + l0, nl, (char*)packed + (size_t)l0 * stride_bytes, stride_bytes, kHalf, &job);
+    hipLaunchKernelGGL(k_pack_weights, dim3((unsigned)job.blocks, (unsigned)nl), dim3(256), 0, stream, job.pb, job.C,
+                       job.F, job.total_frags);
   }
   return launch_status();
 }

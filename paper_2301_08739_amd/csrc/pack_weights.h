@@ -1,0 +1,129 @@
+// Weight packing for the fused group attention kernels: the re-tiling of one layer's four weight
+// matrices into the fragment stream the kernel reads, as a device function, so that it can run as
+// a kernel of its own (layer_mfma.hip) or as extra workgroups of the first sort kernel (flatten.hip),
+// where it costs no launch.
+#pragma once
+#include "common.h"
+
+namespace ff {
+
+// Stream order: for each 32-wide head-dim unit hp: Q rows (2 x KB fragments), K rows, V rows,
+// W_o column slice (NB fragments); then for each 32-wide hidden unit fc: W1 rows (2 x KB), W2
+// column slice (NB).  A fragment is 16 output features x 32 inputs; lane (i, q) owns 16 bytes:
+// row i, inputs kbase + 16*(s/4) + 4q + (s%4) for slot s = 0..7.
+constexpr int kPackBatch = 16;
+struct PackBatch {  // up to 16 layers of identical shape packed by one launch
+  const uint16_t *w_qkv[kPackBatch], *w_o[kPackBatch], *w1[kPackBatch], *w2[kPackBatch];
+  const uint16_t *b_qkv[kPackBatch], *b_o[kPackBatch];
+  uint4* out[kPackBatch];
+};
+// What a launch needs to know to pack `layers` layers: `blocks` workgroups of 256 threads per layer.
+struct PackJob {
+  PackBatch pb;
+  int layers, C, F, total_frags, blocks, half;  // half: IEEE half elements instead of bfloat16
+};
+
+inline int pack_frag_count(int C, int F) { return (C / 32) * (6 * (C / 32) + C / 16) + (F / 32) * (2 * (C / 32) + C / 16); }
+
+// Layers w[0..count) (count <= kPackBatch) to packed + l * stride_bytes.
+inline void make_pack_job(const ff_layer_weights* w, int count, void* packed, size_t stride_bytes, bool half,
+                          PackJob* job) {
+  job->layers = count; job->C = w->C; job->F = w->F; job->half = half ? 1 : 0;
+  job->total_frags = pack_frag_count(w->C, w->F);
+  job->blocks = (job->total_frags * 64 + 8 * w->C + 255) / 256;
+  for (int l = 0; l < kPackBatch; ++l) {
+    const ff_layer_weights* wl = &w[l < count ? l : 0];
+    job->pb.w_qkv[l] = (const uint16_t*)wl->w_qkv; job->pb.w_o[l] = (const uint16_t*)wl->w_o;
+    job->pb.w1[l] = (const uint16_t*)wl->w1; job->pb.w2[l] = (const uint16_t*)wl->w2;
+    job->pb.b_qkv[l] = (const uint16_t*)wl->b_qkv; job->pb.b_o[l] = (const uint16_t*)wl->b_o;
+    job->pb.out[l] = (uint4*)((char*)packed + (size_t)(l < count ? l : 0) * stride_bytes);
+  }
+}
+
+template <bool HALF> __device__ __forceinline__ float pack_el_to_f32(uint16_t h) {
+  if constexpr (HALF) return (float)__builtin_bit_cast(_Float16, h);
+  else return bf16_to_f32(h);
+}
+template <bool HALF> __device__ __forceinline__ uint16_t pack_f32_to_el(float f) {
+  if constexpr (HALF) return __builtin_bit_cast(uint16_t, (_Float16)f);
+  else return f32_to_bf16(f);
+}
+
+// After the fragments the packed buffer holds C floats: the output-projection bias with the value
+// bias folded in.  Every softmax row sums to one, so P (V + 1 b_v^T) W_o^T = P V W_o^T + (W_o b_v)^T:
+// the value bias is a constant row added after the projection.  (The key bias shifts all scores
+// of a query by the same amount and drops out of the softmax altogether.)
+// Work of workgroup `block` (256 threads) of layer `layer`.
+template <bool HALF>
+__device__ __forceinline__ void pack_weights_block(const PackBatch& pb, int layer, int block, int C, int F,
+                                                   int total_frags) {
+  const uint16_t* __restrict__ w_qkv = pb.w_qkv[layer];
+  const uint16_t* __restrict__ w_o = pb.w_o[layer];
+  const uint16_t* __restrict__ w1 = pb.w1[layer];
+  const uint16_t* __restrict__ w2 = pb.w2[layer];
+  uint4* __restrict__ out = pb.out[layer];
+  const int t = block * 256 + (int)threadIdx.x;
+  const int frag = t >> 6, lane = t & 63, i = lane & 15, q = lane >> 4;
+  if (frag >= total_frags) {  // folded output bias: eight lanes per output feature
+    const int u = t - total_frags * 64, o = u >> 3, seg = u & 7, len = C / 8;
+    float acc = 0.f;
+    if (o < C) {
+      const uint16_t* __restrict__ bv = pb.b_qkv[layer] + 2 * C;
+      for (int k = seg * len; k < (seg + 1) * len; ++k)
+        acc = fmaf(pack_el_to_f32<HALF>(w_o[(size_t)o * C + k]), pack_el_to_f32<HALF>(bv[k]), acc);
+    }
+    acc += __shfl_xor(acc, 1);
+    acc += __shfl_xor(acc, 2);
+    acc += __shfl_xor(acc, 4);
+    if (o < C && seg == 0)
+      reinterpret_cast<float*>(out + (size_t)total_frags * 64)[o] = acc + pack_el_to_f32<HALF>(pb.b_o[layer][o]);
+    return;
+  }
+  const int KB = C / 32, NB = C / 16, fr_hp = 6 * KB + NB, fr_fc = 2 * KB + NB, n_hp = C / 32;
+  const uint16_t* src;
+  int kbase;
+  bool halve = false;  // W2 carries the 0.5 of the GELU (the kernel computes twice the GELU)
+  if (frag < n_hp * fr_hp) {
+    const int hp = frag / fr_hp, r = frag % fr_hp;
+    if (r < 6 * KB) {
+      const int which = r / (2 * KB), rr = r % (2 * KB), a = rr / KB, kb = rr % KB;
+      src = w_qkv + (size_t)(which * C + 32 * hp + 16 * a + i) * C;
+      kbase = 32 * kb;
+    } else {
+      const int nb = r - 6 * KB;
+      src = w_o + (size_t)(16 * nb + i) * C;
+      kbase = 32 * hp;
+    }
+  } else {
+    const int f2 = frag - n_hp * fr_hp, fc = f2 / fr_fc, r = f2 % fr_fc;
+    if (r < 2 * KB) {
+      const int a = r / KB, kb = r % KB;
+      src = w1 + (size_t)(32 * fc + 16 * a + i) * C;
+      kbase = 32 * kb;
+    } else {
+      const int nb = r - 2 * KB;
+      src = w2 + (size_t)(16 * nb + i) * F;
+      kbase = 32 * fc;
+      halve = true;
+    }
+  }
+  // slots 0..3 are inputs kbase + 4q .. + 3, slots 4..7 the same plus 16: two 8-byte loads
+  uint32_t u[4];
+#pragma unroll
+  for (int h = 0; h < 2; ++h) {
+    const uint2 v = *reinterpret_cast<const uint2*>(src + kbase + 16 * h + 4 * q);
+    u[2 * h] = v.x;
+    u[2 * h + 1] = v.y;
+  }
+  if (halve) {
+#pragma unroll
+    for (int s = 0; s < 4; ++s) {
+      const uint32_t lo = pack_f32_to_el<HALF>(0.5f * pack_el_to_f32<HALF>((uint16_t)(u[s] & 0xffffu)));
+      const uint32_t hi = pack_f32_to_el<HALF>(0.5f * pack_el_to_f32<HALF>((uint16_t)(u[s] >> 16)));
+      u[s] = lo | (hi << 16);
+    }
+  }
+  out[(size_t)frag * 64 + lane] = make_uint4(u[0], u[1], u[2], u[3]);
+}
+
+}  // namespace ff
