@@ -33,7 +33,7 @@ int ff_flatten(const int32_t* coords, int64_t n, const ff_geom* g, int axis, int
                void* workspace, size_t workspace_bytes, void* stream) {
   if (tail != FF_TAIL_MASK && tail != FF_TAIL_DROP) return FF_ERR_ARG;
   if (shift != 0 && shift != 1) return FF_ERR_ARG;
-  return flatten_launch(coords, n, g, 1, &axis, &shift, G, tail == FF_TAIL_DROP, &perm, &group_offsets, &num_groups, &keys_sorted,
+  return flatten_launch(coords, n, g, 1, &axis, &shift, G, tail == FF_TAIL_DROP, &perm, nullptr, &group_offsets, &num_groups, &keys_sorted,
                         workspace, workspace_bytes, nullptr, (hipStream_t)stream);
 }
 
@@ -63,10 +63,20 @@ size_t ff_group_attention_workspace_bytes(int64_t n, int G, const ff_layer_weigh
   return b;
 }
 
-int ff_group_attention(const void* feats, void* out, int64_t n, const int32_t* perm,
-                       const int32_t* group_offsets, const int32_t* num_groups, int32_t max_groups,
-                       const ff_layer_weights* w, int G, int dtype, uint32_t flags,
-                       void* workspace, size_t workspace_bytes, void* stream) {
+}  // extern "C"
+
+namespace {
+// Does this call run on the fused matrix-core kernel?
+bool takes_fused_path(const ff_layer_weights* w, int G, int dtype, uint32_t flags) {
+  return is_16bit(dtype) && !(flags & FF_FLAG_FORCE_GENERIC) && layer_mfma_supported(w, G);
+}
+
+// ff_group_attention plus the two internal options of the fused kernel that ff_fwa_block uses to hand
+// features from layer to layer in sorted order (see layer_mfma_launch); they need the fused path.
+int group_attention(const void* feats, void* out, int64_t n, const int32_t* perm,
+                    const int32_t* group_offsets, const int32_t* num_groups, int32_t max_groups,
+                    const ff_layer_weights* w, int G, int dtype, uint32_t flags, void* workspace,
+                    size_t workspace_bytes, const int32_t* out_index, int in_sorted, void* stream) {
   int st = check_weights(w, dtype);
   if (st != FF_OK) return st;
   if (n < 0 || n > 0x7fffffffLL || max_groups < 0 || G < 1) return FF_ERR_ARG;
@@ -84,7 +94,7 @@ int ff_group_attention(const void* feats, void* out, int64_t n, const int32_t* p
   if (drop && n > 0 && max_groups == 0)  // no group can exist: every row skips the layer
     return rows_copy_ungrouped_launch(feats, out, n, perm, group_offsets, num_groups, 0, w->C, G, dtype, out_f32,
                                       (hipStream_t)stream);
-  if (is_16bit(dtype) && !(flags & FF_FLAG_FORCE_GENERIC) && layer_mfma_supported(w, G)) {
+  if (takes_fused_path(w, G, dtype, flags)) {
     if (n == 0 || max_groups == 0) return FF_OK;
     const void* packed = w->packed;
     if (!packed) {
@@ -98,16 +108,28 @@ int ff_group_attention(const void* feats, void* out, int64_t n, const int32_t* p
     const int variant = (int)((flags >> 8) & 0xf);
     if (dtype == FF_F16)
       return layer_mfma_launch_f16(feats, out, n, perm, group_offsets, num_groups, max_groups, w, G, out_f32, drop,
-                                   packed, variant, (hipStream_t)stream);
+                                   packed, variant, out_index, in_sorted, (hipStream_t)stream);
     return layer_mfma_launch(feats, out, n, perm, group_offsets, num_groups, max_groups, w, G, out_f32, drop,
-                             packed, variant, (hipStream_t)stream);
+                             packed, variant, out_index, in_sorted, (hipStream_t)stream);
   }
+  if (out_index || in_sorted) return FF_ERR_UNSUPPORTED;  // only the fused kernel has these
   st = layer_generic_launch(feats, out, n, perm, group_offsets, num_groups, max_groups, w, G, dtype, out_f32,
                             workspace, workspace_bytes, (hipStream_t)stream);
   if (st != FF_OK || !drop || n == 0) return st;
   // The row kernels above wrote every row; the rows of no group get the input back.
   return rows_copy_ungrouped_launch(feats, out, n, perm, group_offsets, num_groups, max_groups, w->C, G, dtype,
                                     out_f32, (hipStream_t)stream);
+}
+}  // namespace
+
+extern "C" {
+
+int ff_group_attention(const void* feats, void* out, int64_t n, const int32_t* perm,
+                       const int32_t* group_offsets, const int32_t* num_groups, int32_t max_groups,
+                       const ff_layer_weights* w, int G, int dtype, uint32_t flags,
+                       void* workspace, size_t workspace_bytes, void* stream) {
+  return group_attention(feats, out, n, perm, group_offsets, num_groups, max_groups, w, G, dtype, flags, workspace,
+                         workspace_bytes, nullptr, 0, stream);
 }
 
 int ff_gather(const void* src, void* dst, const int32_t* perm, int64_t n, int C, int dtype, void* stream) {
@@ -119,13 +141,19 @@ int ff_scatter(const void* src, void* dst, const int32_t* perm, int64_t n, int C
 }
 
 // Workspace layout of ff_fwa_block:
-//   [flatten scratch][perm x S][group_offsets x S][num_groups x S][feature buffer A][feature buffer B][layer scratch]
+//   [flatten scratch][perm x S][inverse perm x S][group_offsets x S][num_groups x S][feature buffer A]
+//   [feature buffer B][layer scratch][packed weights]
 // with S = number of distinct (axis, shift) pairs the schedule uses (at most 4).
+// When every layer runs on the fused kernel the features travel from layer to layer in sorted order:
+// layer l writes row inverse_perm_{l+1}[pillar], which is where layer l+1 finds the members of its
+// groups side by side, so only the first layer gathers through an index and only the last one
+// writes pillar order.
 namespace {
 struct BlockPlan {
   int sorts;  // distinct sort configurations used by layers 0..L-1 (schedule order x, y, sx, sy)
   int64_t max_groups;
-  size_t off_flat, off_perm, off_goff, off_ng, off_a, off_b, off_layer, off_packed, total;
+  size_t off_flat, off_perm, off_inv, off_goff, off_ng, off_a, off_b, off_layer, off_packed, total;
+  bool chain;  // features are handed on in sorted order
   size_t flat_bytes, layer_bytes, packed_stride;  // packed_stride == 0: nothing to pre-pack
 };
 
@@ -150,6 +178,9 @@ int make_block_plan(int64_t n, const ff_geom* g, int G, const ff_layer_weights* 
   size_t off = 0;
   p->off_flat = off;  off += align_up(p->flat_bytes, 256);
   p->off_perm = off;  off += p->sorts * align_up((size_t)n * 4, 256);
+  p->chain = num_layers > 1;
+  for (int l = 0; l < num_layers; ++l) p->chain = p->chain && takes_fused_path(&layers[l], G, dtype, 0);
+  p->off_inv = off;   off += (p->chain ? p->sorts : 0) * align_up((size_t)n * 4, 256);
   p->off_goff = off;  off += p->sorts * align_up((size_t)(p->max_groups + 1) * 4, 256);
   p->off_ng = off;    off += 256;
   p->off_a = off;     off += feat_bytes;
@@ -192,10 +223,11 @@ int ff_fwa_block(const int32_t* coords, int64_t n, const ff_geom* g, int G, int 
   const size_t goff_stride = align_up((size_t)(p.max_groups + 1) * 4, 256);
   {  // all sort configurations of the schedule in one batched flatten
     int axis[4], shift[4];
-    int32_t *perm[4], *goff[4], *ng[4];
+    int32_t *perm[4], *inv[4], *goff[4], *ng[4];
     for (int s = 0; s < p.sorts; ++s) {
       axis[s] = s % 2; shift[s] = (s / 2) % 2;
       perm[s] = (int32_t*)(ws + p.off_perm + s * perm_stride);
+      inv[s] = (int32_t*)(ws + p.off_inv + s * perm_stride);
       goff[s] = (int32_t*)(ws + p.off_goff + s * goff_stride);
       ng[s] = (int32_t*)(ws + p.off_ng) + s;
     }
@@ -204,7 +236,7 @@ int ff_fwa_block(const int32_t* coords, int64_t n, const ff_geom* g, int G, int 
     PackJob job;
     const bool ride = p.packed_stride && n > 0 && num_layers <= kPackBatch;
     if (ride) make_pack_job(layers, num_layers, ws + p.off_packed, p.packed_stride, dtype == FF_F16, &job);
-    st = flatten_launch(coords, n, g, p.sorts, axis, shift, G, drop, perm, goff, ng, nullptr, ws + p.off_flat,
+    st = flatten_launch(coords, n, g, p.sorts, axis, shift, G, drop, perm, p.chain ? inv : nullptr, goff, ng, nullptr, ws + p.off_flat,
                         p.flat_bytes, ride ? &job : nullptr, (hipStream_t)stream);
     if (st != FF_OK) return st;
     if (p.packed_stride && n > 0 && !ride) {
@@ -221,10 +253,13 @@ int ff_fwa_block(const int32_t* coords, int64_t n, const ff_geom* g, int G, int 
     void* dst = (l == num_layers - 1) ? feats_out : bufs[l & 1];
     ff_layer_weights wl = layers[l];
     if (p.packed_stride) wl.packed = ws + p.off_packed + (size_t)l * p.packed_stride;
-    st = ff_group_attention(cur, dst, n, (const int32_t*)(ws + p.off_perm + s * perm_stride),
-                            (const int32_t*)(ws + p.off_goff + s * goff_stride), (const int32_t*)(ws + p.off_ng) + s,
-                            (int32_t)p.max_groups, &wl, G, dtype, drop ? FF_FLAG_TAIL_DROP : 0u, ws + p.off_layer,
-                            p.layer_bytes, stream);
+    const bool last = l == num_layers - 1;
+    const int32_t* next_inv = p.chain && !last ? (const int32_t*)(ws + p.off_inv + ((l + 1) % 4) * perm_stride) : nullptr;
+    const int in_sorted = p.chain && l > 0 ? (g->num_frames == 1 ? 2 : 1) : 0;
+    st = group_attention(cur, dst, n, (const int32_t*)(ws + p.off_perm + s * perm_stride),
+                         (const int32_t*)(ws + p.off_goff + s * goff_stride), (const int32_t*)(ws + p.off_ng) + s,
+                         (int32_t)p.max_groups, &wl, G, dtype, drop ? FF_FLAG_TAIL_DROP : 0u, ws + p.off_layer,
+                         p.layer_bytes, next_inv, in_sorted, stream);
     if (st != FF_OK) return st;
     cur = dst;
   }

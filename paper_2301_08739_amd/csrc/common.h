@@ -61,9 +61,9 @@ size_t flatten_workspace_bytes(int64_t n, const ff_geom* g, int num_sorts);
 // weights to re-tile in extra workgroups of the first kernel (n > 0 only; see pack_weights.h).
 struct PackJob;
 int flatten_launch(const int32_t* coords, int64_t n, const ff_geom* g, int num_sorts, const int* axis,
-                   const int* shift, int G, int drop, int32_t* const* perm, int32_t* const* group_offsets,
-                   int32_t* const* num_groups, uint64_t* const* keys_sorted, void* workspace,
-                   size_t workspace_bytes, const PackJob* pack, hipStream_t stream);
+                   const int* shift, int G, int drop, int32_t* const* perm, int32_t* const* inv_perm /* or nullptr */,
+                   int32_t* const* group_offsets, int32_t* const* num_groups, uint64_t* const* keys_sorted,
+                   void* workspace, size_t workspace_bytes, const PackJob* pack, hipStream_t stream);
 
 int rows_launch(bool scatter, const void* src, void* dst, const int32_t* perm, int64_t n, int C,
                 int dtype, hipStream_t stream);
@@ -83,13 +83,19 @@ int layer_generic_launch(const void* feats, void* out, int64_t n, const int32_t*
 bool layer_mfma_supported(const ff_layer_weights* w, int G);
 size_t layer_mfma_packed_bytes(const ff_layer_weights* w);
 int layer_mfma_pack(const ff_layer_weights* w, int count, void* packed, size_t stride_bytes, hipStream_t stream);
+// out_index: nullptr, or for every pillar the row of `out` its result goes to (instead of its own
+// index).  in_sorted: 0 = feats is in pillar order; 1 = row p of feats is the pillar at sorted
+// position p; 2 = the same, and groups start at multiples of G (one frame), which lets the kernel
+// fetch its rows before it has read the group list.
 int layer_mfma_launch(const void* feats, void* out, int64_t n, const int32_t* perm, const int32_t* group_offsets,
                       const int32_t* num_groups, int32_t max_groups, const ff_layer_weights* w, int G,
-                      bool out_f32, bool drop, const void* packed, int variant, hipStream_t stream);
+                      bool out_f32, bool drop, const void* packed, int variant, const int32_t* out_index,
+                      int in_sorted, hipStream_t stream);
 // the same two for IEEE half storage (layer_mfma_f16.hip); shapes and packed size do not differ
 int layer_mfma_pack_f16(const ff_layer_weights* w, int count, void* packed, size_t stride_bytes, hipStream_t stream);
 int layer_mfma_launch_f16(const void* feats, void* out, int64_t n, const int32_t* perm, const int32_t* group_offsets,
                           const int32_t* num_groups, int32_t max_groups, const ff_layer_weights* w, int G,
-                          bool out_f32, bool drop, const void* packed, int variant, hipStream_t stream);
+                          bool out_f32, bool drop, const void* packed, int variant, const int32_t* out_index,
+                          int in_sorted, hipStream_t stream);
 
 }  // namespace ff

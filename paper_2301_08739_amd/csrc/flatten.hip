@@ -59,6 +59,7 @@ struct KeyParams {
 struct Batch {
   KeyParams kp[kMaxSorts];
   int32_t* perm[kMaxSorts];
+  int32_t* inv_perm[kMaxSorts];  // nullptr, or sorted position of every pillar (inverse of perm)
   int32_t* group_offsets[kMaxSorts];
   int32_t* num_groups[kMaxSorts];
   uint64_t* keys_sorted[kMaxSorts];
@@ -453,6 +454,7 @@ __global__ __launch_bounds__(kSortThreads) void k_pass(const uint64_t* __restric
 
   // ---- last pass: the output position is final -------------------------------------------------------
   int32_t* __restrict__ const perm_s = bt.perm[s];  // read once: the stores below must not wait for them
+  int32_t* __restrict__ const inv_s = bt.inv_perm[s];
   uint64_t* __restrict__ const keys_s = bt.keys_sorted[s];
   int32_t* __restrict__ const goff_s = bt.group_offsets[s];
   const uint32_t idx_mask = idx_bits >= 32 ? ~0u : (1u << idx_bits) - 1u;  // n < 2^31
@@ -468,6 +470,11 @@ __global__ __launch_bounds__(kSortThreads) void k_pass(const uint64_t* __restric
 #pragma unroll
   for (int r = 0; r < KPT; ++r)
     if ((int64_t)pos_r[r] < n) perm_s[pos_r[r]] = (int32_t)idx_r[r];
+  if (inv_s) {  // the same for the whole workgroup
+#pragma unroll
+    for (int r = 0; r < KPT; ++r)
+      if ((int64_t)pos_r[r] < n) inv_s[idx_r[r]] = (int32_t)pos_r[r];
+  }
   if (keys_s) {  // the same for the whole workgroup
 #pragma unroll
     for (int r = 0; r < KPT; ++r) {
@@ -615,6 +622,7 @@ __global__ __launch_bounds__(256) void k_finalize(const uint64_t* __restrict__ s
   const uint64_t word = sorted[p];
   const uint64_t idx_mask = (1ull << kp.idx_bits) - 1ull;
   bt.perm[s][p] = (int32_t)(word & idx_mask);
+  if (bt.inv_perm[s]) bt.inv_perm[s][word & idx_mask] = (int32_t)p;
   uint64_t k = word >> kp.idx_bits;
   const uint64_t l2 = k & field_mask(kp.bits_l2); k >>= kp.bits_l2;
   const uint64_t l1 = k & field_mask(kp.bits_l1); k >>= kp.bits_l1;
@@ -702,9 +710,9 @@ size_t flatten_workspace_bytes(int64_t n, const ff_geom* g, int num_sorts) {
 }
 
 int flatten_launch(const int32_t* coords, int64_t n, const ff_geom* g, int num_sorts, const int* axis,
-                   const int* shift, int G, int drop, int32_t* const* perm, int32_t* const* group_offsets,
-                   int32_t* const* num_groups, uint64_t* const* keys_sorted, void* workspace,
-                   size_t workspace_bytes, const PackJob* pack, hipStream_t stream) {
+                   const int* shift, int G, int drop, int32_t* const* perm, int32_t* const* inv_perm,
+                   int32_t* const* group_offsets, int32_t* const* num_groups, uint64_t* const* keys_sorted,
+                   void* workspace, size_t workspace_bytes, const PackJob* pack, hipStream_t stream) {
   if (num_sorts < 1 || num_sorts > kMaxSorts || G < 1) return FF_ERR_ARG;
   Batch bt;
   int max_key_bits = 0;
@@ -722,11 +730,13 @@ int flatten_launch(const int32_t* coords, int64_t n, const ff_geom* g, int num_s
     kp.key_bits = plan.key_bits; kp.idx_bits = plan.idx_bits;
     bt.perm[s] = perm[s]; bt.group_offsets[s] = group_offsets[s]; bt.num_groups[s] = num_groups[s];
     bt.keys_sorted[s] = keys_sorted ? keys_sorted[s] : nullptr;
+    bt.inv_perm[s] = inv_perm ? inv_perm[s] : nullptr;
     if (plan.key_bits > max_key_bits) max_key_bits = plan.key_bits;
   }
   for (int s = num_sorts; s < kMaxSorts; ++s) {
     bt.kp[s] = bt.kp[0]; bt.perm[s] = nullptr; bt.group_offsets[s] = nullptr; bt.num_groups[s] = nullptr;
     bt.keys_sorted[s] = nullptr;
+    bt.inv_perm[s] = nullptr;
   }
   if (n > 0 && !coords) return FF_ERR_ARG;
   Layout L;

@@ -209,7 +209,8 @@ __global__ __launch_bounds__(NW * 64, MINW) void k_layer_mfma(const uint16_t* __
                                                                const int32_t* __restrict__ goff,
                                                                const int32_t* __restrict__ num_groups, int max_groups,
                                                                const u32x4* __restrict__ packed, SmallParams sp, float eps,
-                                                               int n, int G, int drop) {
+                                                               int n, int G, int drop,
+                                                               const int32_t* __restrict__ out_index, int in_sorted) {
   constexpr int KB = C / 32;          // 32-wide blocks of the input features
   constexpr int NB = C / 16;          // 16-wide blocks of the output features
   constexpr int HP = C / 32;          // 32-wide head-dim units
@@ -259,6 +260,20 @@ __global__ __launch_bounds__(NW * 64, MINW) void k_layer_mfma(const uint16_t* __
   for (int vb = 0; vb < NVB; ++vb) {
     const int64_t at = (int64_t)g * G + (part * NVB + vb) * 16 + i;
     guess[vb] = perm[at < n ? at : n - 1];
+  }
+  // in_sorted: row p of feats is the pillar at sorted position p (the previous layer of a block wrote
+  // its result in this layer's order), so the rows of a group are contiguous and need no index.
+  // in_sorted == 2 (one frame): they are fetched from the guessed start without waiting for anything.
+  constexpr int NBX = NB;  // raw rows of the early fetch: 8 bytes per 16-feature block
+  uint2 early[NVB][NBX];
+  if (in_sorted == 2) {
+#pragma unroll
+    for (int vb = 0; vb < NVB; ++vb) {
+      const int64_t at = (int64_t)g * G + (part * NVB + vb) * 16 + i;
+#pragma unroll
+      for (int nb = 0; nb < NB; ++nb)
+        early[vb][nb] = *reinterpret_cast<const uint2*>(feats + (at < n ? at : n - 1) * C + 16 * nb + 4 * q);
+    }
   }
   FF_TS_WAIT(16);
   int start = 0, m = 0;
@@ -328,23 +343,42 @@ __global__ __launch_bounds__(NW * 64, MINW) void k_layer_mfma(const uint16_t* __
 
   // ---- gather + LN1 ---------------------------------------------------------------------------------
   f32x4 x1[NVB][NB];  // residual stream of my pillars, accumulator layout
-  int32_t row[NVB];  // pillar index, -1 for padding slots
+  int32_t row[NVB];   // pillar index, -1 for padding slots
+  int32_t orow[NVB];  // row of `out` the result goes to
+  const bool guessed = (int64_t)g * G == start;  // wave-uniform
 #pragma unroll
   for (int vb = 0; vb < NVB; ++vb) {
     const int s = (part * NVB + vb) * 16 + i;
-    if ((int64_t)g * G == start) row[vb] = s < m ? guess[vb] : -1;  // wave-uniform
+    if (guessed) row[vb] = s < m ? guess[vb] : -1;
     else row[vb] = s < m ? perm[start + s] : -1;
   }
   FF_TS_WAIT(17);
+  if (in_sorted == 2 && guessed) {  // the early fetch hit
 #pragma unroll
-  for (int vb = 0; vb < NVB; ++vb) {
+    for (int vb = 0; vb < NVB; ++vb) {
+      const bool live = (part * NVB + vb) * 16 + i < m;
 #pragma unroll
-    for (int nb = 0; nb < NB; ++nb) {
-      float t[4] = {0.f, 0.f, 0.f, 0.f};
-      if (row[vb] >= 0) load4(feats + (int64_t)row[vb] * C + 16 * nb + 4 * q, t);
-      x1[vb][nb] = f32x4{t[0], t[1], t[2], t[3]};
+      for (int nb = 0; nb < NB; ++nb) {
+        const uint2 u = early[vb][nb];
+        x1[vb][nb] = live ? f32x4{el_lo(u.x), el_hi(u.x), el_lo(u.y), el_hi(u.y)} : f32x4{0.f, 0.f, 0.f, 0.f};
+      }
+    }
+  } else {
+#pragma unroll
+    for (int vb = 0; vb < NVB; ++vb) {
+      const int s = (part * NVB + vb) * 16 + i;
+      const int64_t src = in_sorted ? (int64_t)start + s : (int64_t)row[vb];
+#pragma unroll
+      for (int nb = 0; nb < NB; ++nb) {
+        float t[4] = {0.f, 0.f, 0.f, 0.f};
+        if (row[vb] >= 0) load4(feats + src * C + 16 * nb + 4 * q, t);
+        x1[vb][nb] = f32x4{t[0], t[1], t[2], t[3]};
+      }
     }
   }
+  // out_index: the next layer of a block wants its input in its own sorted order
+#pragma unroll
+  for (int vb = 0; vb < NVB; ++vb) orow[vb] = out_index && row[vb] >= 0 ? out_index[row[vb]] : row[vb];
   // Positional embedding of my pillars, still bf16, in the layout of `act` (Eq. (2), second argument
   // of the attention): it is added to the LayerNorm output on the way to the query and key products.
   Frag8 pef[PE ? NVB : 1][PE ? KB : 1];
@@ -369,8 +403,9 @@ __global__ __launch_bounds__(NW * 64, MINW) void k_layer_mfma(const uint16_t* __
       const int sub = lane / LPR, col = (lane % LPR) * 8;
       hi = hi < n ? hi : n;
       for (int p = lo + part * RPW + sub; p < hi; p += WPG * RPW) {
-        const int64_t at = (int64_t)perm[p] * C + col;
-        const u32x4 v = *reinterpret_cast<const u32x4*>(feats + at);
+        const int32_t pillar = perm[p];
+        const u32x4 v = *reinterpret_cast<const u32x4*>(feats + (int64_t)(in_sorted ? p : pillar) * C + col);
+        const int64_t at = (int64_t)(out_index ? out_index[pillar] : pillar) * C + col;
         if constexpr (OUT_F32) {
           float* dst = reinterpret_cast<float*>(out) + at;
 #pragma unroll
@@ -638,13 +673,25 @@ __global__ __launch_bounds__(NW * 64, MINW) void k_layer_mfma(const uint16_t* __
             rowsum[hh][vb] = mfma32(ones, p8, rowsum[hh][vb]);
           }
           if (NKB & 1) {
+            // The odd last key block: a k=32 product whose upper half multiplies zeros.  A k=16
+            // product here was wrong on this chip: issued right behind a k=32 product into the same
+            // accumulator it read the accumulator before that product had written it (row sums of 48
+            // instead of 80, whenever the scheduler put the two back to back), so every product of an
+            // accumulation chain is of one kind.  The k=16 product takes the same 16 cycles anyway.
             constexpr int jb = NKB - 1;
-            Frag4 p4, ones;
-            p4.u[0] = pack2(S[hh][vb][jb][0], S[hh][vb][jb][1]); p4.u[1] = pack2(S[hh][vb][jb][2], S[hh][vb][jb][3]);
-            ones.u[0] = ones.u[1] = kOnePair;
+            Frag8 p8;
+            p8.u[0] = pack2(S[hh][vb][jb][0], S[hh][vb][jb][1]); p8.u[1] = pack2(S[hh][vb][jb][2], S[hh][vb][jb][3]);
+            p8.u[2] = p8.u[3] = 0u;
 #pragma unroll
-            for (int a = 0; a < NA; ++a) O[hh][vb][a] = mfma16(Vget(DH == 16 ? h : a, jb), p4, O[hh][vb][a]);
-            rowsum[hh][vb] = mfma16(ones, p4, rowsum[hh][vb]);
+            for (int a = 0; a < NA; ++a) {
+              const Frag4 v0 = Vget(DH == 16 ? h : a, jb);
+              Frag8 v8;
+              v8.u[0] = v0.u[0]; v8.u[1] = v0.u[1]; v8.u[2] = v8.u[3] = 0u;
+              O[hh][vb][a] = mfma32(v8, p8, O[hh][vb][a]);
+            }
+            Frag8 ones;
+            ones.u[0] = ones.u[1] = ones.u[2] = ones.u[3] = kOnePair;
+            rowsum[hh][vb] = mfma32(ones, p8, rowsum[hh][vb]);
           }
         }
       }
@@ -748,7 +795,7 @@ __global__ __launch_bounds__(NW * 64, MINW) void k_layer_mfma(const uint16_t* __
     if (row[vb] < 0) continue;
 #pragma unroll
     for (int nb = 0; nb < NB; ++nb) {
-      const size_t o = (size_t)row[vb] * C + 16 * nb + 4 * q;
+      const size_t o = (size_t)orow[vb] * C + 16 * nb + 4 * q;
       if (OUT_F32) {
         *reinterpret_cast<float4*>(reinterpret_cast<float*>(out) + o) =
             make_float4(x1[vb][nb][0], x1[vb][nb][1], x1[vb][nb][2], x1[vb][nb][3]);
@@ -779,7 +826,7 @@ template <int C, int DH, int F, int NVB, int WPG, int NW, int MINW>
 int launch_cfg(const void* feats, void* out, const void* pos_embed, const int32_t* perm, const int32_t* goff,
                const int32_t* num_groups,
                int32_t max_groups, const u32x4* packed, const SmallParams& sp, float eps, bool out_f32, int n, int G,
-               int drop, hipStream_t stream) {
+               int drop, const int32_t* out_index, int in_sorted, hipStream_t stream) {
   constexpr int GPW = NW / WPG;
   const size_t lds_bytes = LdsPlan<C, F, NVB, WPG, NW, MINW>::TOTAL;
   const unsigned blocks = (unsigned)((max_groups + GPW - 1) / GPW);
@@ -798,7 +845,7 @@ int launch_cfg(const void* feats, void* out, const void* pos_embed, const int32_
     }
     hipLaunchKernelGGL(kern, dim3(blocks), dim3(NW * 64), lds_bytes, stream, (const uint16_t*)feats, out,
                        (const uint16_t*)pos_embed, perm, goff,
-                       num_groups, (int)max_groups, packed, sp, eps, n, G, drop);
+                       num_groups, (int)max_groups, packed, sp, eps, n, G, drop, out_index, in_sorted);
     return launch_status();
   };
   if (pos_embed) {
@@ -858,7 +905,8 @@ int FF_LAYER_SYM(layer_mfma_pack)(const ff_layer_weights* w, int count, void* pa
 // variant: 0 = chosen from the shape; 1.. = a specific wave/group mapping (tuning and tests).
 int FF_LAYER_SYM(layer_mfma_launch)(const void* feats, void* out, int64_t n, const int32_t* perm, const int32_t* group_offsets,
                       const int32_t* num_groups, int32_t max_groups, const ff_layer_weights* w, int G,
-                      bool out_f32, bool drop, const void* packed, int variant, hipStream_t stream) {
+                      bool out_f32, bool drop, const void* packed, int variant, const int32_t* out_index,
+                      int in_sorted, hipStream_t stream) {
   if (max_groups == 0 || n == 0) return FF_OK;
   SmallParams sp{(const uint16_t*)w->ln1_g, (const uint16_t*)w->ln1_b, (const uint16_t*)w->b_qkv,
                  (const uint16_t*)w->b_o,   (const uint16_t*)w->ln2_g, (const uint16_t*)w->ln2_b,
@@ -866,7 +914,7 @@ int FF_LAYER_SYM(layer_mfma_launch)(const void* feats, void* out, int64_t n, con
   const u32x4* pk = (const u32x4*)packed;
 #define FF_GO(C, DH, F, NVB, WPG, NW, MINW) \
   return launch_cfg<C, DH, F, NVB, WPG, NW, MINW>(feats, out, w->pos_embed, perm, group_offsets, num_groups, max_groups, pk, sp, \
-                                                  w->ln_eps, out_f32, (int)n, G, drop ? 1 : 0, stream)
+                                                  w->ln_eps, out_f32, (int)n, G, drop ? 1 : 0, out_index, in_sorted, stream)
   const int shape = shape_id(w);
   // (pillar blocks per wave, waves per group, waves per workgroup, min waves per SIMD)
   if (shape == 1) {
