@@ -13,7 +13,8 @@ forms, invariants); nothing is "parity unpinned".
 from .flatten import (Geometry, shift_amount, window_tuple, pack_key, sort_tuple_order,
                       flatten, frame_segments)
 from .layer import layer_norm, gelu_erf, softmax_rows, group_layer, layer, stack
+from .pillars import point_cells, voxelize, bev_scatter
 
 __all__ = ["Geometry", "shift_amount", "window_tuple", "pack_key", "sort_tuple_order",
            "flatten", "frame_segments", "layer_norm", "gelu_erf", "softmax_rows",
-           "group_layer", "layer", "stack"]
+           "group_layer", "layer", "stack", "point_cells", "voxelize", "bev_scatter"]
