@@ -144,6 +144,19 @@ def main():
     ms_gather, _ = time_region(lambda: ff.ff_gather(feats, perm, dt, out=gth), reps, 5)
     ms_scatter, _ = time_region(lambda: ff.ff_scatter(gth, perm, dt, out=out), reps, 5)
 
+    # the steps either side of the block: points -> pillars, pillars -> dense map
+    m_pts, cp = 6 * n, 4
+    xy_h, fr_h, pf_h = ffsynth.lidar_points(11, m_pts, c["B"], cp)
+    xy_d, fr_d, pf_d = (torch.from_numpy(v).to(dev) for v in (xy_h, fr_h, pf_h))
+    half = 0.5 * c["grid"] * 0.32
+    vgrid = ff.VoxelGrid(-half, -half, 0.32, 0.32)
+    vws = torch.empty(ff.ff_voxelize_workspace_bytes(m_pts, geom) + 512, dtype=torch.uint8, device=dev)
+    _, _, npil, _ = ff.ff_voxelize(xy_d, fr_d, pf_d, geom, vgrid, want_map=False, workspace=vws)
+    n_vox = int(npil.item())
+    ms_vox, _ = time_region(lambda: ff.ff_voxelize(xy_d, fr_d, pf_d, geom, vgrid, want_map=False, workspace=vws), reps, 5)
+    bev = torch.empty((c["B"], c["grid"], c["grid"], C), dtype=tdt, device=dev)
+    ms_bev, _ = time_region(lambda: ff.ff_bev_scatter(feats, coords, geom, dt, out=bev), reps, 5)
+
     if a.copy_calibration:
         src = torch.empty(256 << 20, dtype=torch.uint8, device=dev)
         dst = torch.empty_like(src)
@@ -160,6 +173,10 @@ def main():
     passes = -(-live // 8)
     bytes_flat = (28 + 24 * passes) * n
     bytes_rows = (2 * C * esz + 4) * n
+    # voxelisation: inputs once, the sort credited like flatten (key = frame, x, y), the pillar rows once
+    live_v = bits(c["B"] + 1) + 2 * bits(c["grid"])
+    bytes_vox = (12 + 4 * cp) * m_pts + (28 + 24 * -(-live_v // 8)) * m_pts + (12 + 4 * cp) * n_vox
+    bytes_bev = c["B"] * c["grid"] * c["grid"] * C * esz + (C * esz + 12) * n
     peak_tf = PEAK_F32_TFLOPS if dt == ff.FF_F32 else PEAK_BF16_TFLOPS
     ach_tf = flops_layer / (ms_layer * 1e-3) / 1e12
 
@@ -185,6 +202,11 @@ def main():
                        "frac_hbm": bytes_rows / (ms_gather * 1e-3) / 1e9 / PEAK_HBM_GBS},
             "scatter": {"ms": ms_scatter, "bytes": bytes_rows, "GBps": bytes_rows / (ms_scatter * 1e-3) / 1e9,
                         "frac_hbm": bytes_rows / (ms_scatter * 1e-3) / 1e9 / PEAK_HBM_GBS},
+            "voxelize": {"ms": ms_vox, "points": m_pts, "pillars": n_vox, "point_feats": cp,
+                         "Mpoints_s": m_pts / ms_vox / 1e3, "bytes": bytes_vox, "GBps": bytes_vox / (ms_vox * 1e-3) / 1e9,
+                         "frac_hbm": bytes_vox / (ms_vox * 1e-3) / 1e9 / PEAK_HBM_GBS},
+            "bev_scatter": {"ms": ms_bev, "bytes": bytes_bev, "GBps": bytes_bev / (ms_bev * 1e-3) / 1e9,
+                            "frac_hbm": bytes_bev / (ms_bev * 1e-3) / 1e9 / PEAK_HBM_GBS},
             "wall_ms_per_step": wall_ms,
         },
     }

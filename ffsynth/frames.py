@@ -121,3 +121,26 @@ def row_major_order(coords):
     `unique` would emit.  Input-order variant for locality measurements."""
     idx = np.lexsort((coords[:, 2], coords[:, 1], coords[:, 0]))
     return np.ascontiguousarray(coords[idx])
+
+
+def lidar_points(seed, m, num_frames=1, feat_dim=4):
+    """Raw points of synthetic LiDAR frames, before any voxelisation: (xy float32 [m, 2] in metres,
+    frame int32 [m], point features float32 [m, feat_dim]).  Same spatial law as `lidar_frame`
+    (exponential range, uniform azimuth, one point in five in one of 50 Gaussian clusters), a few
+    percent of the points fall outside +-74.88 m.  The features are N(0, 1) stand-ins for height,
+    intensity and the like."""
+    rng = np.random.default_rng(seed)
+    frame = rng.integers(0, num_frames, size=m).astype(np.int32)
+    cr = rng.exponential(MEAN_RANGE, size=(num_frames, N_CLUSTERS))
+    ct = rng.uniform(0.0, 2.0 * np.pi, size=(num_frames, N_CLUSTERS))
+    centres = np.stack([cr * np.cos(ct), cr * np.sin(ct)], axis=2)          # [frames, clusters, 2]
+    is_obj = rng.random(m) < CLUSTER_FRACTION
+    r = rng.exponential(MEAN_RANGE, size=m)
+    th = rng.uniform(0.0, 2.0 * np.pi, size=m)
+    which = rng.integers(0, N_CLUSTERS, size=m)
+    jitter = rng.normal(0.0, CLUSTER_SIGMA, size=(m, 2))
+    px = np.where(is_obj, centres[frame, which, 0] + jitter[:, 0], r * np.cos(th))
+    py = np.where(is_obj, centres[frame, which, 1] + jitter[:, 1], r * np.sin(th))
+    xy = np.stack([px, py], axis=1).astype(np.float32)
+    feats = rng.standard_normal((m, feat_dim)).astype(np.float32)
+    return xy, frame, feats

@@ -168,6 +168,43 @@ int ff_group_attention(const void* feats, void* out, int64_t n,
 int ff_gather(const void* src, void* dst, const int32_t* perm, int64_t n, int C, int dtype, void* stream);
 int ff_scatter(const void* src, void* dst, const int32_t* perm, int64_t n, int C, int dtype, void* stream);
 
+/* ---- pillar voxelisation (the step in front of the FWA blocks: Sec. 5.1 'Model' voxelises the point
+ * cloud into sparse bird's-eye-view pillars of 0.32 m x 0.32 m, following PointPillars) -------------
+ * Point i lies in cell ( floor((x_i - x_min) / voxel_x), floor((y_i - y_min) / voxel_y) ) of frame
+ * frame[i] (float32 arithmetic); points outside the grid or with a frame id outside [0, num_frames)
+ * are dropped.  A pillar is a non-empty cell.  Outputs, pillars in ascending (frame, x, y) order:
+ *   coords           (b, x, y) of every pillar                                  [capacity m][3]
+ *   feats            mean of the pillar's points' feature vectors, float32      [capacity m][Cp]
+ *                    (float32 sums in a fixed order: the result does not depend on timing)
+ *   num_pillars      device scalar                                              [1]
+ *   point_to_pillar  NULL, or for every point its pillar, -1 if dropped         [m]
+ * Only the first *num_pillars rows of coords and feats are written.  The learned per-point network
+ * that PointPillars applies before pooling is not part of this entry point.  The window sizes of g
+ * are ignored; num_frames <= 65534, grid_x, grid_y <= 65535.
+ * workspace: ff_voxelize_workspace_bytes(m, g) bytes, 256-byte aligned. */
+typedef struct {
+  float x_min, y_min;     /* lower corner of cell (0, 0), metres   */
+  float voxel_x, voxel_y; /* cell size, metres (> 0)                */
+} ff_voxel_grid;
+
+size_t ff_voxelize_workspace_bytes(int64_t m, const ff_geom* g);
+
+int ff_voxelize(const float* xy /* [m,2] */, const int32_t* frame /* [m], or NULL: all frame 0 */,
+                const float* point_feats /* [m,Cp] */, int64_t m, int Cp,
+                const ff_geom* g, const ff_voxel_grid* v,
+                int32_t* coords, float* feats, int32_t* num_pillars, int32_t* point_to_pillar,
+                void* workspace, size_t workspace_bytes, void* stream);
+
+/* ---- sparse pillars -> dense bird's-eye-view map (the step after the FWA blocks: Sec. 5.1 'Model'
+ * hands the pillar features to a regular BEV encoder, which wants a dense map) ---------------------
+ * bev[b][y][x][c] = feats[i][c] for pillar i with coords (b, x, y), zero in every other cell.
+ * bev: device array [num_frames][grid_y][grid_x][C] of `dtype`, channels last (a pillar's C features
+ * stay contiguous; 16-byte aligned), written completely.  C * sizeof(dtype) must be a multiple of 16.
+ * Coordinates must be unique (what pillar voxelisation produces); with duplicates one of the rows wins,
+ * which one is unspecified.  Pillars outside the geometry are skipped. */
+int ff_bev_scatter(const void* feats /* [n,C] */, const int32_t* coords /* [n,3] (b,x,y) */, int64_t n,
+                   const ff_geom* g, int C, int dtype, void* bev, void* stream);
+
 /* ---- the whole block: sorts computed once and reused, then the layer stack ------------------
  * Layer l sorts along axis l % 2 with the shift on when (l / 2) % 2 == 1 (x, y, shifted x,
  * shifted y, x, ...); each distinct (axis, shift) pair is flattened once and reused by every

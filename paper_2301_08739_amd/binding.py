@@ -35,6 +35,10 @@ class _LayerWeightsC(C.Structure):
                 ("packed", C.c_void_p), ("pos_embed", C.c_void_p)]
 
 
+class VoxelGrid(C.Structure):
+    _fields_ = [("x_min", C.c_float), ("y_min", C.c_float), ("voxel_x", C.c_float), ("voxel_y", C.c_float)]
+
+
 _PARAMS = ("ln1_g", "ln1_b", "w_qkv", "b_qkv", "w_o", "b_o", "ln2_g", "ln2_b", "w1", "b1", "w2", "b2")
 
 
@@ -85,6 +89,12 @@ _SIGS = {
     "ff_pack_weights": (C.c_int, [C.POINTER(_LayerWeightsC), C.c_int, C.c_void_p, C.c_void_p]),
     "ff_gather": (C.c_int, [C.c_void_p, C.c_void_p, C.c_void_p, C.c_int64, C.c_int, C.c_int, C.c_void_p]),
     "ff_scatter": (C.c_int, [C.c_void_p, C.c_void_p, C.c_void_p, C.c_int64, C.c_int, C.c_int, C.c_void_p]),
+    "ff_voxelize_workspace_bytes": (C.c_size_t, [C.c_int64, C.POINTER(Geometry)]),
+    "ff_voxelize": (C.c_int, [C.c_void_p, C.c_void_p, C.c_void_p, C.c_int64, C.c_int, C.POINTER(Geometry),
+                              C.POINTER(VoxelGrid), C.c_void_p, C.c_void_p, C.c_void_p, C.c_void_p, C.c_void_p,
+                              C.c_size_t, C.c_void_p]),
+    "ff_bev_scatter": (C.c_int, [C.c_void_p, C.c_void_p, C.c_int64, C.POINTER(Geometry), C.c_int, C.c_int, C.c_void_p,
+                                 C.c_void_p]),
     "ff_fwa_block_workspace_bytes": (C.c_size_t, [C.c_int64, C.POINTER(Geometry), C.c_int,
                                                    C.POINTER(_LayerWeightsC), C.c_int, C.c_int]),
     "ff_fwa_block": (C.c_int, [C.c_void_p, C.c_int64, C.POINTER(Geometry), C.c_int, C.c_int, C.POINTER(_LayerWeightsC),
@@ -213,6 +223,41 @@ def ff_gather(src, perm, dtype, out=None):
 
 def ff_scatter(src, perm, dtype, out=None):
     return _rows("ff_scatter", src, perm, dtype, out)
+
+
+def ff_voxelize(xy, frame, point_feats, geom, grid, want_map=True, workspace=None):
+    """xy float32 [m,2], frame int32 [m] or None, point_feats float32 [m,Cp] ->
+    (coords int32 [m,3], feats float32 [m,Cp], num_pillars int32 [1], point_to_pillar int32 [m] | None);
+    only the first num_pillars rows of coords / feats are meaningful."""
+    lib = load_library()
+    assert xy.dtype == torch.float32 and xy.is_contiguous() and point_feats.dtype == torch.float32 and point_feats.is_contiguous()
+    m, Cp = point_feats.shape
+    dev = xy.device
+    coords = torch.empty((m, 3), dtype=torch.int32, device=dev)
+    feats = torch.empty((m, Cp), dtype=torch.float32, device=dev)
+    npil = torch.full((1,), -1, dtype=torch.int32, device=dev)
+    p2p = torch.empty(m, dtype=torch.int32, device=dev) if want_map else None
+    need = lib.ff_voxelize_workspace_bytes(m, C.byref(geom))
+    ws = workspace if workspace is not None else _workspace(need, dev)
+    st = lib.ff_voxelize(_ptr(xy), _ptr(frame), _ptr(point_feats), m, Cp, C.byref(geom), C.byref(grid), _ptr(coords),
+                         _ptr(feats), _ptr(npil), _ptr(p2p), C.c_void_p(_aligned_ptr(ws)), ws.numel() - 256, _stream())
+    _check(st, "ff_voxelize")
+    return coords, feats, npil, p2p
+
+
+def ff_voxelize_workspace_bytes(m, geom):
+    return load_library().ff_voxelize_workspace_bytes(int(m), C.byref(geom))
+
+
+def ff_bev_scatter(feats, coords, geom, dtype, out=None):
+    """feats [n,C], coords [n,3] -> dense map [num_frames, grid_y, grid_x, C] (channels last)."""
+    lib = load_library()
+    n, Cc = feats.shape
+    if out is None:
+        out = torch.empty((geom.num_frames, geom.grid_y, geom.grid_x, Cc), dtype=feats.dtype, device=feats.device)
+    st = lib.ff_bev_scatter(_ptr(feats), _ptr(coords), n, C.byref(geom), Cc, dtype, _ptr(out), _stream())
+    _check(st, "ff_bev_scatter")
+    return out
 
 
 def _layer_array(layers, pos_embed=None):

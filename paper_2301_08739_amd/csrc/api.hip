@@ -140,6 +140,20 @@ int ff_scatter(const void* src, void* dst, const int32_t* perm, int64_t n, int C
   return rows_launch(true, src, dst, perm, n, C, dtype, (hipStream_t)stream);
 }
 
+size_t ff_voxelize_workspace_bytes(int64_t m, const ff_geom* g) { return voxelize_workspace_bytes(m, g); }
+
+int ff_voxelize(const float* xy, const int32_t* frame, const float* point_feats, int64_t m, int Cp, const ff_geom* g,
+                const ff_voxel_grid* v, int32_t* coords, float* feats, int32_t* num_pillars, int32_t* point_to_pillar,
+                void* workspace, size_t workspace_bytes, void* stream) {
+  return voxelize_launch(xy, frame, point_feats, m, Cp, g, v, coords, feats, num_pillars, point_to_pillar, workspace,
+                         workspace_bytes, (hipStream_t)stream);
+}
+
+int ff_bev_scatter(const void* feats, const int32_t* coords, int64_t n, const ff_geom* g, int C, int dtype, void* bev,
+                   void* stream) {
+  return bev_scatter_launch(feats, coords, n, g, C, dtype, bev, (hipStream_t)stream);
+}
+
 // Workspace layout of ff_fwa_block:
 //   [flatten scratch][perm x S][inverse perm x S][group_offsets x S][num_groups x S][feature buffer A]
 //   [feature buffer B][layer scratch][packed weights]

@@ -73,6 +73,15 @@ int rows_copy_ungrouped_launch(const void* feats, void* out, int64_t n, const in
                                const int32_t* group_offsets, const int32_t* num_groups, int32_t max_groups, int C,
                                int G, int dtype, bool out_f32, hipStream_t stream);
 
+// bev [num_frames][grid_y][grid_x][C] = rows of feats at their pillars' cells, zero elsewhere
+int bev_scatter_launch(const void* feats, const int32_t* coords, int64_t n, const ff_geom* g, int C, int dtype,
+                       void* bev, hipStream_t stream);
+
+size_t voxelize_workspace_bytes(int64_t m, const ff_geom* g);
+int voxelize_launch(const float* xy, const int32_t* frame, const float* pfeats, int64_t m, int Cp, const ff_geom* g,
+                    const ff_voxel_grid* v, int32_t* coords, float* feats, int32_t* num_pillars,
+                    int32_t* point_to_pillar, void* workspace, size_t workspace_bytes, hipStream_t stream);
+
 size_t layer_generic_workspace_bytes(int64_t n, const ff_layer_weights* w);
 int layer_generic_launch(const void* feats, void* out, int64_t n, const int32_t* perm,
                          const int32_t* group_offsets, const int32_t* num_groups, int32_t max_groups,

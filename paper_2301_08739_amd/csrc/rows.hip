@@ -55,7 +55,52 @@ __global__ __launch_bounds__(256) void k_copy_ungrouped(const T* __restrict__ fe
   }
 }
 
+// ---- sparse pillars -> dense bird's-eye-view map (the step after the FWA blocks, Sec. 5.1 'Model') -----
+// bev[b][y][x][:] = feats[i][:] for pillar i = (b, x, y), zero elsewhere; channels last, so that a
+// pillar's features stay one contiguous row.  Two launches: zero fill (the map is mostly empty:
+// 30k of 219k cells at the paper's resolution), then one 16-byte piece per thread.
+__global__ __launch_bounds__(256) void k_fill_zero(uint4* __restrict__ dst, int64_t pieces) {
+  const uint4 z = make_uint4(0u, 0u, 0u, 0u);
+  for (int64_t i = (int64_t)blockIdx.x * blockDim.x + threadIdx.x; i < pieces; i += (int64_t)gridDim.x * blockDim.x)
+    dst[i] = z;
+}
+
+__global__ __launch_bounds__(256) void k_bev_scatter(const uint4* __restrict__ feats, const int32_t* __restrict__ coords,
+                                                      int64_t n, int vec_per_row, int B, int gx, int gy,
+                                                      uint4* __restrict__ bev) {
+  const int64_t total = n * vec_per_row;
+  for (int64_t i = (int64_t)blockIdx.x * blockDim.x + threadIdx.x; i < total; i += (int64_t)gridDim.x * blockDim.x) {
+    const int64_t p = i / vec_per_row;
+    const int v = (int)(i - p * vec_per_row);
+    const int32_t b = coords[3 * p], x = coords[3 * p + 1], y = coords[3 * p + 2];
+    if ((uint32_t)b >= (uint32_t)B || (uint32_t)x >= (uint32_t)gx || (uint32_t)y >= (uint32_t)gy) continue;  // outside the map
+    bev[(((int64_t)b * gy + y) * gx + x) * vec_per_row + v] = feats[i];
+  }
+}
+
 }  // namespace
+
+int bev_scatter_launch(const void* feats, const int32_t* coords, int64_t n, const ff_geom* g, int C, int dtype,
+                       void* bev, hipStream_t stream) {
+  if (!g || n < 0 || C < 1 || (dtype != FF_F32 && dtype != FF_BF16 && dtype != FF_F16)) return FF_ERR_ARG;
+  if (g->num_frames < 1 || g->grid_x < 1 || g->grid_y < 1 || !bev) return FF_ERR_ARG;
+  const size_t row_bytes = (size_t)C * (dtype == FF_F32 ? 4 : 2);
+  if (row_bytes % 16) return FF_ERR_UNSUPPORTED;
+  if (((uintptr_t)bev & 15) || ((uintptr_t)feats & 15)) return FF_ERR_ARG;
+  if (n > 0 && (!feats || !coords)) return FF_ERR_ARG;
+  const int vec = (int)(row_bytes / 16);
+  const int64_t pieces = (int64_t)g->num_frames * g->grid_x * g->grid_y * vec;
+  int64_t fb = ceil_div(pieces, 256 * 8);
+  if (fb > 256 * 64) fb = 256 * 64;
+  hipLaunchKernelGGL(k_fill_zero, dim3((unsigned)fb), dim3(256), 0, stream, (uint4*)bev, pieces);
+  if (n > 0) {
+    int64_t blocks = ceil_div(n * vec, 256);
+    if (blocks > 256 * 32) blocks = 256 * 32;
+    hipLaunchKernelGGL(k_bev_scatter, dim3((unsigned)blocks), dim3(256), 0, stream, (const uint4*)feats, coords, n, vec,
+                       g->num_frames, g->grid_x, g->grid_y, (uint4*)bev);
+  }
+  return launch_status();
+}
 
 int rows_copy_ungrouped_launch(const void* feats, void* out, int64_t n, const int32_t* perm,
                                const int32_t* group_offsets, const int32_t* num_groups, int32_t max_groups, int C,
