@@ -592,6 +592,8 @@ __global__ __launch_bounds__(NW * 64, MINW) void k_layer_mfma(const uint16_t* __
           for (int jb = 0; jb < NKB; ++jb) {
             const f32x4 z = f32x4{0.f, 0.f, 0.f, 0.f};
             if (DH == 16) {
+              // the only k=16 products left: their accumulator input is zero, so they depend on no
+              // earlier product (see the note at the odd key block below)
               S[hh][vb][jb] = mfma16(Kget(h, jb), Qf[h][v0 + vb], z);
             } else {
               Frag8 k8, q8;
