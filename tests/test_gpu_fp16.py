@@ -118,3 +118,39 @@ def test_block_and_rows(cfg):
     assert out.dtype == torch.float16 and torch.equal(out, cur) and torch.isfinite(out).all()
     gth = ff.ff_gather(x, perm, F16)
     assert torch.equal(gth, x[perm.long()]) and torch.equal(ff.ff_scatter(gth, perm, F16), x)
+
+
+@pytest.mark.parametrize("i", [4, 5])
+def test_full_size_sampled_groups_all_options(cfg, i):
+    """Full-size configurations with every option at once (half storage, dropped short groups,
+    positional embedding), in the launch configuration bench.py times: sampled groups against the
+    oracle one by one, skipped rows exact, everything finite."""
+    c = cfg(i, 1)
+    g, og = geoms(c)
+    n, G = c["n"], c["G"]
+    feats = ffsynth.f16_round(c["feats"])
+    p = _half_params(c["layer_params"][0])
+    pe = ffsynth.f16_round(0.5 * np.random.default_rng(40 + i).standard_normal(feats.shape).astype(np.float32))
+    ct = torch.from_numpy(c["coords"]).to(DEV)
+    perm_d, goff_d, ng_d, _ = ff.ff_flatten(ct, g, 1, 1, G, tail=ff.FF_TAIL_DROP)
+    torch.cuda.synchronize()
+    ng = int(ng_d.item())
+    perm, starts = perm_d.cpu().numpy(), goff_d.cpu().numpy()[:ng]
+    lw = ff.LayerWeights(p, F16, DEV).pack()
+    x, pe_d = to_dev_feats(feats, F16), to_dev_feats(pe, F16)
+    mg = n // G + c["B"]
+    wide = to_host(ff.ff_group_attention(x, perm_d, goff_d, ng_d, mg, lw, G, F16,
+                                         ff.FF_FLAG_OUT_F32 | ff.FF_FLAG_TAIL_DROP, pos_embed=pe_d))
+    narrow = to_host(ff.ff_group_attention(x, perm_d, goff_d, ng_d, mg, lw, G, F16, ff.FF_FLAG_TAIL_DROP, pos_embed=pe_d))
+    pick = sorted(set([0, 1, ng // 2, ng - 1] + np.random.default_rng(i).integers(0, ng, 12).tolist()))
+    rows = np.concatenate([perm[starts[k]:starts[k] + G] for k in pick])
+    want = oracle.layer(feats, perm, starts[pick], p, groups=range(len(pick)), group_size=G, pos_embed=pe)
+    err = np.abs(wide[rows] - want[rows]).max()
+    grouped = np.zeros(n, bool)
+    for s0 in starts:
+        grouped[perm[s0:s0 + G]] = True
+    print(f"cfg{i} fp16 + drop + pos embed: {len(pick)} of {ng} groups, {int((~grouped).sum())} rows skipped, "
+          f"max abs err {err:.3e}", flush=True)
+    assert err <= TOL
+    assert np.array_equal(ffsynth.f16_round(wide.astype(np.float32)).astype(np.float64), narrow)
+    assert np.array_equal(narrow[~grouped], feats[~grouped].astype(np.float64)) and np.isfinite(narrow).all()
