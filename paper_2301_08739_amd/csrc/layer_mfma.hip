@@ -376,9 +376,6 @@ __global__ __launch_bounds__(NW * 64, MINW) void k_layer_mfma(const uint16_t* __
       }
     }
   }
-  // out_index: the next layer of a block wants its input in its own sorted order
-#pragma unroll
-  for (int vb = 0; vb < NVB; ++vb) orow[vb] = out_index && row[vb] >= 0 ? out_index[row[vb]] : row[vb];
   // Positional embedding of my pillars, still bf16, in the layout of `act` (Eq. (2), second argument
   // of the attention): it is added to the LayerNorm output on the way to the query and key products.
   Frag8 pef[PE ? NVB : 1][PE ? KB : 1];
@@ -422,6 +419,10 @@ __global__ __launch_bounds__(NW * 64, MINW) void k_layer_mfma(const uint16_t* __
     if (g < ngroups) copy_rows(start + m, off1);
   }
   sync(0);  // chunks 0 and 1 and the small parameters are in LDS; the rest of the ring is requested
+  // out_index: the next layer of a block wants its input in its own sorted order.  Fetched only now:
+  // the barrier above waits for every load in flight, and this one hangs on the pillar index.
+#pragma unroll
+  for (int vb = 0; vb < NVB; ++vb) orow[vb] = out_index && row[vb] >= 0 ? out_index[row[vb]] : row[vb];
   FF_TS(2);
 
   // The window: fragments j .. j + PF - 1 of the stream are in registers (or on their way) while
