@@ -14,7 +14,9 @@
  *  - Ownership: the caller allocates and owns every buffer, including the
  *    workspace.  The library never allocates or frees device memory and never
  *    synchronises the stream; outputs are valid once the stream reaches the
- *    point after the call.
+ *    point after the call.  Every entry point can therefore be captured into a
+ *    HIP graph; call it once outside a capture first (the first launch of a
+ *    fused layer kernel on a device sets a function attribute).
  *  - Errors: every function returns an ff_status (0 = success, negative =
  *    failure).  Preconditions that can be checked on the host are checked before
  *    anything is launched; on FF_ERR_ARG / FF_ERR_UNSUPPORTED / FF_ERR_WORKSPACE
