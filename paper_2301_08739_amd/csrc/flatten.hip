@@ -43,7 +43,7 @@ namespace ff {
 namespace {
 
 constexpr int kMaxSorts = 4;
-constexpr int kSmallKpt = 4, kSmallMaxTiles = 64;   // small clouds: tiles of 1024 words
+constexpr int kSmallKpt = 4, kSmallMaxTiles = 128;  // small clouds: tiles of 1024 words
 constexpr int kLargeKpt = 16;                       // larger clouds: tiles of 4096 words
 constexpr int kScanThreads = 1024;
 constexpr int kScanStrip = 64;  // digits per workgroup of the column scan (narrower strips were no faster)

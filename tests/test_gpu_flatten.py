@@ -41,7 +41,7 @@ def _rand_coords(n, B, gx, gy, seed, unique=True):
     return np.stack([b, x, y], axis=1).astype(np.int32)
 
 
-@pytest.mark.parametrize("n", [0, 1, 2, 63, 64, 65, 2047, 2048, 2049, 4095, 4096, 4097, 5000, 12288, 65536, 65537])
+@pytest.mark.parametrize("n", [0, 1, 2, 63, 64, 65, 2047, 2048, 2049, 4095, 4096, 4097, 5000, 12288, 65536, 65537, 131072, 131073])
 def test_sizes_around_tile_edges(n):
     gx, gy = (90, 70) if n <= 3 * 90 * 70 else (300, 200)
     coords = _rand_coords(n, 3, gx, gy, seed=n, unique=True)
