@@ -11,10 +11,10 @@ the oracle itself (brute force on tiny inputs, library special cases, closed
 forms, invariants); nothing is "parity unpinned".
 """
 from .flatten import (Geometry, shift_amount, window_tuple, pack_key, sort_tuple_order,
-                      flatten, frame_segments)
+                      flatten, frame_segments, Geometry3, window_tuple3, flatten3d)
 from .layer import layer_norm, gelu_erf, softmax_rows, group_layer, layer, stack
 from .pillars import point_cells, voxelize, bev_scatter
 
 __all__ = ["Geometry", "shift_amount", "window_tuple", "pack_key", "sort_tuple_order",
-           "flatten", "frame_segments", "layer_norm", "gelu_erf", "softmax_rows",
+           "flatten", "frame_segments", "Geometry3", "window_tuple3", "flatten3d", "layer_norm", "gelu_erf", "softmax_rows",
            "group_layer", "layer", "stack", "point_cells", "voxelize", "bev_scatter"]

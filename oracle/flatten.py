@@ -99,3 +99,49 @@ def flatten(coords, geom, axis, shift, G, tail="mask"):
     elif tail != "drop":
         raise ValueError(tail)
     return perm, np.asarray(offsets, dtype=np.int32), keys
+
+
+# ---- three-dimensional windows (footnote of Sec. 4.2.1: the method applies to 3-D point clouds) --------
+# coords[:, 0] frame, coords[:, 1..3] = (x, y, z) voxel indices
+Geometry3 = namedtuple("Geometry3", "num_frames grid_x grid_y grid_z win_x win_y win_z")
+
+
+def window_tuple3(b, x, y, z, geom, axis, shift):
+    """Eq. (1) with a third coordinate: window coordinates, then local coordinates.  The paper
+    states the 3-D case in a footnote only; the reading taken keeps the two-axis alternation of
+    the BEV case and appends z to both halves of the tuple:
+
+    axis 0 -> (b, Wx, Wy, Wz, Lx, Ly, Lz)       axis 1 -> (b, Wy, Wx, Wz, Ly, Lx, Lz)
+    """
+    X = int(x) + shift_amount(geom.win_x, shift)
+    Y = int(y) + shift_amount(geom.win_y, shift)
+    Z = int(z) + shift_amount(geom.win_z, shift)
+    Wx, Wy, Wz = X // geom.win_x, Y // geom.win_y, Z // geom.win_z
+    Lx, Ly, Lz = X - Wx * geom.win_x, Y - Wy * geom.win_y, Z - Wz * geom.win_z
+    if axis == 0:
+        return (int(b), Wx, Wy, Wz, Lx, Ly, Lz)
+    return (int(b), Wy, Wx, Wz, Ly, Lx, Lz)
+
+
+def flatten3d(coords, geom, axis, shift, G, tail="mask"):
+    """`flatten` for voxels with coordinates (b, x, y, z).  Returns (perm, group_offsets); the
+    packed 64-bit key of the BEV case has no room for seven fields and is not produced."""
+    coords = np.asarray(coords)
+    n = coords.shape[0]
+    tuples = [window_tuple3(*coords[i], geom, axis, shift) for i in range(n)]
+    order = sort_tuple_order(tuples)
+    perm = np.asarray(order, dtype=np.int32).reshape(n)
+    sorted_b = [tuples[i][0] for i in order]
+    offsets = []
+    for (s, e) in frame_segments(sorted_b, geom.num_frames):
+        p = s
+        while p < e:
+            if tail == "drop" and e - p < G:
+                break
+            offsets.append(p)
+            p += G
+    if tail == "mask":
+        offsets.append(n)
+    elif tail != "drop":
+        raise ValueError(tail)
+    return perm, np.asarray(offsets, dtype=np.int32)

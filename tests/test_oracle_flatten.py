@@ -261,3 +261,37 @@ def test_generator_shapes(cfg):
     r = ffsynth.bf16_round(x)
     assert r[0] == 1.0 and r[1] == 1.0 and r[2] == np.float32(1.015625)  # ties to even
     assert np.array_equal(ffsynth.bf16_round(r), r)
+
+
+def test_three_dimensional_windows():
+    """3-D windows (footnote of Sec. 4.2.1): reduces to the BEV case for a flat grid, agrees with a
+    lexicographic library sort of the explicit seven-field tuples, keeps the grouping rules."""
+    rng = np.random.default_rng(11)
+    n = 600
+    ids = rng.permutation(2 * 12 * 10 * 6)[:n]
+    b, r = np.divmod(ids, 12 * 10 * 6)
+    x, r = np.divmod(r, 10 * 6)
+    y, z = np.divmod(r, 6)
+    c4 = np.stack([b, x, y, z], 1).astype(np.int32)
+    g3 = oracle.Geometry3(2, 12, 10, 6, 5, 3, 4)
+    for axis in (0, 1):
+        for shift in (0, 1):
+            perm, off = oracle.flatten3d(c4, g3, axis, shift, 17)
+            sx, sy, sz = (5 // 2, 3 // 2, 4 // 2) if shift else (0, 0, 0)
+            X, Y, Z = c4[:, 1] + sx, c4[:, 2] + sy, c4[:, 3] + sz
+            f = [c4[:, 0], X // 5, Y // 3, Z // 4, X % 5, Y % 3, Z % 4]
+            if axis == 1:
+                f = [f[0], f[2], f[1], f[3], f[5], f[4], f[6]]
+            want = np.lexsort(tuple(reversed(f)))                      # library sort, first field most significant
+            assert np.array_equal(perm, want)                          # coordinates are unique: no ties
+            counts = np.bincount(c4[:, 0], minlength=2)
+            assert len(off) - 1 == sum(-(-int(k) // 17) for k in counts) and off[-1] == n
+            _, starts = oracle.flatten3d(c4, g3, axis, shift, 17, tail="drop")
+            assert len(starts) == sum(int(k) // 17 for k in counts)
+    # a grid that is one voxel high with a window one voxel high is the BEV case
+    c3 = _rand_unique(500, 3, 20, 20, seed=12)
+    c4 = np.concatenate([c3, np.zeros((500, 1), np.int32)], axis=1)
+    for axis, shift in [(0, 0), (1, 1)]:
+        p2, o2, _ = oracle.flatten(c3, Geometry(3, 20, 20, 6, 4), axis, shift, 9)
+        p3, o3 = oracle.flatten3d(c4, oracle.Geometry3(3, 20, 20, 1, 6, 4, 1), axis, shift, 9)
+        assert np.array_equal(p2, p3) and np.array_equal(o2, o3)
