@@ -95,6 +95,27 @@ int ff_flatten(const int32_t* coords /* [n,3] (b,x,y) */, int64_t n, const ff_ge
                int32_t* perm, int32_t* group_offsets, int32_t* num_groups,
                uint64_t* keys_sorted, void* workspace, size_t workspace_bytes, void* stream);
 
+/* ---- the same for three-dimensional windows (footnote of Sec. 4.2.1: the method applies to 3-D point
+ * clouds; no configuration of the paper uses it) -----------------------------------------------------
+ * coords [n,4] = (b, x, y, z) voxel indices.  The shift is half a window on all three axes.  The
+ * sort tuple keeps the two-axis alternation of the pillar case and appends z to both halves:
+ * (b, Wx, Wy, Wz, Lx, Ly, Lz) for axis 0 and (b, Wy, Wx, Wz, Ly, Lx, Lz) for axis 1.  Outputs, tail
+ * modes, limits (the seven fields' live bits plus bits(n-1) must fit 64 bits; windows 1..256; at
+ * most 65535 windows per axis) and workspace rules are those of ff_flatten; there is no exported
+ * key (seven fields do not fit its format). */
+typedef struct {
+  int32_t num_frames;
+  int32_t grid_x, grid_y, grid_z;
+  int32_t win_x, win_y, win_z;
+} ff_geom3;
+
+size_t ff_flatten3d_workspace_bytes(int64_t n, const ff_geom3* g);
+
+int ff_flatten3d(const int32_t* coords /* [n,4] (b,x,y,z) */, int64_t n, const ff_geom3* g,
+                 int axis /* 0 | 1 */, int shift /* 0 | 1 */, int G, int tail /* ff_tail */,
+                 int32_t* perm, int32_t* group_offsets, int32_t* num_groups,
+                 void* workspace, size_t workspace_bytes, void* stream);
+
 /* ---- group attention layer (Sec. 4.2.2, Eq. (2)) --------------------------------------------
  *
  *   F'  = F  + MHSA(LN1(F))      softmax(Q K^T / sqrt(d)) V per head, inside each group

@@ -35,6 +35,10 @@ class _LayerWeightsC(C.Structure):
                 ("packed", C.c_void_p), ("pos_embed", C.c_void_p)]
 
 
+class Geometry3(C.Structure):
+    _fields_ = [(k, C.c_int32) for k in ("num_frames", "grid_x", "grid_y", "grid_z", "win_x", "win_y", "win_z")]
+
+
 class VoxelGrid(C.Structure):
     _fields_ = [("x_min", C.c_float), ("y_min", C.c_float), ("voxel_x", C.c_float), ("voxel_y", C.c_float)]
 
@@ -81,6 +85,9 @@ _SIGS = {
     "ff_flatten_workspace_bytes": (C.c_size_t, [C.c_int64, C.POINTER(Geometry)]),
     "ff_flatten": (C.c_int, [C.c_void_p, C.c_int64, C.POINTER(Geometry), C.c_int, C.c_int, C.c_int, C.c_int,
                              C.c_void_p, C.c_void_p, C.c_void_p, C.c_void_p, C.c_void_p, C.c_size_t, C.c_void_p]),
+    "ff_flatten3d_workspace_bytes": (C.c_size_t, [C.c_int64, C.POINTER(Geometry3)]),
+    "ff_flatten3d": (C.c_int, [C.c_void_p, C.c_int64, C.POINTER(Geometry3), C.c_int, C.c_int, C.c_int, C.c_int,
+                               C.c_void_p, C.c_void_p, C.c_void_p, C.c_void_p, C.c_size_t, C.c_void_p]),
     "ff_group_attention_workspace_bytes": (C.c_size_t, [C.c_int64, C.c_int, C.POINTER(_LayerWeightsC), C.c_int]),
     "ff_group_attention": (C.c_int, [C.c_void_p, C.c_void_p, C.c_int64, C.c_void_p, C.c_void_p, C.c_void_p,
                                      C.c_int32, C.POINTER(_LayerWeightsC), C.c_int, C.c_int, C.c_uint32,
@@ -178,6 +185,24 @@ def ff_flatten(coords, geom, axis, shift, G, tail=FF_TAIL_MASK, want_keys=False,
                         _ptr(keys), C.c_void_p(_aligned_ptr(ws)), ws.numel() - 256, _stream())
     _check(st, "ff_flatten")
     return perm, goff, ng, keys
+
+
+def ff_flatten3d(coords, geom, axis, shift, G, tail=FF_TAIL_MASK, workspace=None):
+    """coords: int32 cuda tensor [n,4] (b,x,y,z).  Returns (perm, group_offsets, num_groups)."""
+    lib = load_library()
+    assert coords.dtype == torch.int32 and coords.is_contiguous() and coords.is_cuda and coords.shape[1] == 4
+    n = coords.shape[0]
+    dev = coords.device
+    cap = -(-n // max(G, 1)) + geom.num_frames + 1
+    perm = torch.empty(n, dtype=torch.int32, device=dev)
+    goff = torch.full((cap,), -1, dtype=torch.int32, device=dev)
+    ng = torch.full((1,), -1, dtype=torch.int32, device=dev)
+    need = lib.ff_flatten3d_workspace_bytes(n, C.byref(geom))
+    ws = workspace if workspace is not None else _workspace(need, dev)
+    st = lib.ff_flatten3d(_ptr(coords), n, C.byref(geom), axis, shift, G, tail, _ptr(perm), _ptr(goff), _ptr(ng),
+                          C.c_void_p(_aligned_ptr(ws)), ws.numel() - 256, _stream())
+    _check(st, "ff_flatten3d")
+    return perm, goff, ng
 
 
 def ff_group_attention_workspace_bytes(n, G, weights, dtype):

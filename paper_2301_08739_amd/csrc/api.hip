@@ -37,6 +37,35 @@ int ff_flatten(const int32_t* coords, int64_t n, const ff_geom* g, int axis, int
                         workspace, workspace_bytes, nullptr, (hipStream_t)stream);
 }
 
+namespace {
+int split_geom3(const ff_geom3* g, ff_geom* g2, FlattenZ* z) {
+  if (!g) return FF_ERR_ARG;
+  g2->num_frames = g->num_frames; g2->grid_x = g->grid_x; g2->grid_y = g->grid_y;
+  g2->win_x = g->win_x; g2->win_y = g->win_y;
+  z->grid_z = g->grid_z; z->win_z = g->win_z;
+  return FF_OK;
+}
+}  // namespace
+
+size_t ff_flatten3d_workspace_bytes(int64_t n, const ff_geom3* g) {
+  ff_geom g2;
+  FlattenZ z;
+  if (split_geom3(g, &g2, &z) != FF_OK) return 0;
+  return flatten_workspace_bytes_z(n, &g2, &z, 1);
+}
+
+int ff_flatten3d(const int32_t* coords, int64_t n, const ff_geom3* g, int axis, int shift, int G, int tail,
+                 int32_t* perm, int32_t* group_offsets, int32_t* num_groups, void* workspace, size_t workspace_bytes,
+                 void* stream) {
+  ff_geom g2;
+  FlattenZ z;
+  if (split_geom3(g, &g2, &z) != FF_OK) return FF_ERR_ARG;
+  if (tail != FF_TAIL_MASK && tail != FF_TAIL_DROP) return FF_ERR_ARG;
+  if (shift != 0 && shift != 1) return FF_ERR_ARG;
+  return flatten_launch_z(coords, n, &g2, &z, 1, &axis, &shift, G, tail == FF_TAIL_DROP, &perm, nullptr, &group_offsets,
+                          &num_groups, nullptr, workspace, workspace_bytes, nullptr, (hipStream_t)stream);
+}
+
 size_t ff_pack_weights_bytes(const ff_layer_weights* w, int dtype) {
   if (check_weights(w, dtype) != FF_OK || !is_16bit(dtype)) return 0;
   if (!layer_mfma_supported(w, 1)) return 0;

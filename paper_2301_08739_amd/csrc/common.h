@@ -45,6 +45,7 @@ template <> struct Elem<f16_t> {  // IEEE half, round to nearest even
 // ---- flatten plan (host) -------------------------------------------------------------------------
 struct FlattenPlan {
   int bits_b, bits_w1, bits_w2, bits_l1, bits_l2;  // live bits of each tuple field, in sort priority
+  int bits_w3, bits_l3;                            // the z fields of 3-D windows (0 for pillars)
   int key_bits;                                    // sum of the above
   int idx_bits;                                    // bits of n-1
   int passes;                                      // radix passes of 8 bits over the key bits
@@ -56,6 +57,11 @@ constexpr int kSortThreads = 256;
 
 int make_flatten_plan(int64_t n, const ff_geom* g, int axis, int shift, FlattenPlan* plan);
 size_t flatten_workspace_bytes(int64_t n, const ff_geom* g, int num_sorts);
+// The same with a third voxel coordinate (z == nullptr: pillars).  coords then has four columns
+// (b, x, y, z); z is the last of the window fields and the last of the local fields of the key.
+struct FlattenZ { int32_t grid_z, win_z; };
+int make_flatten_plan_z(int64_t n, const ff_geom* g, const FlattenZ* z, int axis, int shift, FlattenPlan* plan);
+size_t flatten_workspace_bytes_z(int64_t n, const ff_geom* g, const FlattenZ* z, int num_sorts);
 
 // num_sorts (1..4) sort configurations of the same cloud, sorted together.  pack: nullptr, or layer
 // weights to re-tile in extra workgroups of the first kernel (n > 0 only; see pack_weights.h).
@@ -64,6 +70,12 @@ int flatten_launch(const int32_t* coords, int64_t n, const ff_geom* g, int num_s
                    const int* shift, int G, int drop, int32_t* const* perm, int32_t* const* inv_perm /* or nullptr */,
                    int32_t* const* group_offsets, int32_t* const* num_groups, uint64_t* const* keys_sorted,
                    void* workspace, size_t workspace_bytes, const PackJob* pack, hipStream_t stream);
+
+int flatten_launch_z(const int32_t* coords, int64_t n, const ff_geom* g, const FlattenZ* z, int num_sorts,
+                     const int* axis, const int* shift, int G, int drop, int32_t* const* perm,
+                     int32_t* const* inv_perm, int32_t* const* group_offsets, int32_t* const* num_groups,
+                     uint64_t* const* keys_sorted, void* workspace, size_t workspace_bytes, const PackJob* pack,
+                     hipStream_t stream);
 
 int rows_launch(bool scatter, const void* src, void* dst, const int32_t* perm, int64_t n, int C,
                 int dtype, hipStream_t stream);

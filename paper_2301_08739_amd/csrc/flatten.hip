@@ -49,10 +49,10 @@ constexpr int kScanThreads = 1024;
 constexpr int kScanStrip = 64;  // digits per workgroup of the column scan (narrower strips were no faster)
 
 struct KeyParams {
-  int32_t B, win_x, win_y;
-  int32_t sx, sy;                       // shift added to x / y
-  int32_t axis;
-  int32_t bits_b, bits_w1, bits_w2, bits_l1, bits_l2;
+  int32_t B, win_x, win_y, win_z;       // win_z = 1 and stride = 3 for bird's-eye-view pillars
+  int32_t sx, sy, sz;                   // shift added to x / y / z
+  int32_t axis, stride;                 // stride: int32 per row of coords (3: b,x,y; 4: b,x,y,z)
+  int32_t bits_b, bits_w1, bits_w2, bits_w3, bits_l1, bits_l2, bits_l3;  // w3 / l3: the z fields (0 bits in 2-D)
   int32_t key_bits, idx_bits;
 };
 
@@ -105,11 +105,14 @@ __device__ __forceinline__ uint32_t digit_rb(uint64_t word, int idx_bits, int ke
 }
 
 __device__ __forceinline__ uint64_t make_word(const int32_t* __restrict__ coords, int64_t i, const KeyParams& kp) {
-  const uint32_t b = (uint32_t)coords[3 * i + 0];
-  const uint32_t X = (uint32_t)(coords[3 * i + 1] + kp.sx);
-  const uint32_t Y = (uint32_t)(coords[3 * i + 2] + kp.sy);
+  const int32_t* c = coords + (int64_t)kp.stride * i;
+  const uint32_t b = (uint32_t)c[0];
+  const uint32_t X = (uint32_t)(c[1] + kp.sx);
+  const uint32_t Y = (uint32_t)(c[2] + kp.sy);
+  const uint32_t Z = kp.stride > 3 ? (uint32_t)(c[3] + kp.sz) : 0u;
   const uint32_t Wx = X / (uint32_t)kp.win_x, Lx = X - Wx * (uint32_t)kp.win_x;
   const uint32_t Wy = Y / (uint32_t)kp.win_y, Ly = Y - Wy * (uint32_t)kp.win_y;
+  const uint32_t Wz = Z / (uint32_t)kp.win_z, Lz = Z - Wz * (uint32_t)kp.win_z;
   const uint32_t w1 = kp.axis == 0 ? Wx : Wy, w2 = kp.axis == 0 ? Wy : Wx;
   const uint32_t l1 = kp.axis == 0 ? Lx : Ly, l2 = kp.axis == 0 ? Ly : Lx;
   // Fields are masked to their widths so that a coordinate outside the geometry can only
@@ -117,14 +120,18 @@ __device__ __forceinline__ uint64_t make_word(const int32_t* __restrict__ coords
   uint64_t k = b & field_mask(kp.bits_b);
   k = (k << kp.bits_w1) | (w1 & field_mask(kp.bits_w1));
   k = (k << kp.bits_w2) | (w2 & field_mask(kp.bits_w2));
+  k = (k << kp.bits_w3) | (Wz & field_mask(kp.bits_w3));  // 3-D windows: z is the last window and the last local field
   k = (k << kp.bits_l1) | (l1 & field_mask(kp.bits_l1));
   k = (k << kp.bits_l2) | (l2 & field_mask(kp.bits_l2));
+  k = (k << kp.bits_l3) | (Lz & field_mask(kp.bits_l3));
   return (k << kp.idx_bits) | (uint64_t)i;
 }
 
 __device__ __forceinline__ uint64_t exported_key(uint64_t k, const KeyParams& kp, uint32_t* frame) {
+  k >>= kp.bits_l3;  // the exported format has no z fields (it is only produced for 2-D keys)
   const uint64_t l2 = k & field_mask(kp.bits_l2); k >>= kp.bits_l2;
   const uint64_t l1 = k & field_mask(kp.bits_l1); k >>= kp.bits_l1;
+  k >>= kp.bits_w3;
   const uint64_t w2 = k & field_mask(kp.bits_w2); k >>= kp.bits_w2;
   const uint64_t w1 = k & field_mask(kp.bits_w1); k >>= kp.bits_w1;
   const uint64_t b = k & field_mask(kp.bits_b);
@@ -624,8 +631,10 @@ __global__ __launch_bounds__(256) void k_finalize(const uint64_t* __restrict__ s
   bt.perm[s][p] = (int32_t)(word & idx_mask);
   if (bt.inv_perm[s]) bt.inv_perm[s][word & idx_mask] = (int32_t)p;
   uint64_t k = word >> kp.idx_bits;
+  k >>= kp.bits_l3;
   const uint64_t l2 = k & field_mask(kp.bits_l2); k >>= kp.bits_l2;
   const uint64_t l1 = k & field_mask(kp.bits_l1); k >>= kp.bits_l1;
+  k >>= kp.bits_w3;
   const uint64_t w2 = k & field_mask(kp.bits_w2); k >>= kp.bits_w2;
   const uint64_t w1 = k & field_mask(kp.bits_w1); k >>= kp.bits_w1;
   const uint64_t b = k & field_mask(kp.bits_b);
@@ -676,7 +685,12 @@ void make_layout(int64_t n, int S, int num_frames, int max_key_bits, Layout* L) 
 }  // namespace
 
 int make_flatten_plan(int64_t n, const ff_geom* g, int axis, int shift, FlattenPlan* plan) {
+  return make_flatten_plan_z(n, g, nullptr, axis, shift, plan);
+}
+
+int make_flatten_plan_z(int64_t n, const ff_geom* g, const FlattenZ* z, int axis, int shift, FlattenPlan* plan) {
   if (!g || n < 0 || n > 0x7fffffffLL) return FF_ERR_ARG;
+  if (z && (z->grid_z < 1 || z->win_z < 1 || z->win_z > 256)) return FF_ERR_ARG;
   if (g->num_frames < 1 || g->grid_x < 1 || g->grid_y < 1) return FF_ERR_ARG;
   if (g->win_x < 1 || g->win_x > 256 || g->win_y < 1 || g->win_y > 256) return FF_ERR_ARG;
   if (axis != 0 && axis != 1) return FF_ERR_ARG;
@@ -692,7 +706,15 @@ int make_flatten_plan(int64_t n, const ff_geom* g, int axis, int shift, FlattenP
   plan->bits_w2 = axis == 0 ? bwy : bwx;
   plan->bits_l1 = axis == 0 ? blx : bly;
   plan->bits_l2 = axis == 0 ? bly : blx;
-  plan->key_bits = plan->bits_b + plan->bits_w1 + plan->bits_w2 + plan->bits_l1 + plan->bits_l2;
+  plan->bits_w3 = plan->bits_l3 = 0;
+  if (z) {
+    const int64_t nwz = ceil_div((int64_t)z->grid_z + (shift ? z->win_z / 2 : 0), z->win_z);
+    if (nwz > 65535) return FF_ERR_UNSUPPORTED;
+    plan->bits_w3 = bit_width_u64((uint64_t)nwz - 1);
+    plan->bits_l3 = bit_width_u64((uint64_t)z->win_z - 1);
+  }
+  plan->key_bits = plan->bits_b + plan->bits_w1 + plan->bits_w2 + plan->bits_w3 + plan->bits_l1 + plan->bits_l2 +
+                   plan->bits_l3;
   plan->idx_bits = n > 0 ? bit_width_u64((uint64_t)n - 1) : 0;
   if (plan->key_bits + plan->idx_bits > 64) return FF_ERR_UNSUPPORTED;
   plan->passes = (plan->key_bits + kRadixBits - 1) / kRadixBits;
@@ -700,10 +722,14 @@ int make_flatten_plan(int64_t n, const ff_geom* g, int axis, int shift, FlattenP
 }
 
 size_t flatten_workspace_bytes(int64_t n, const ff_geom* g, int num_sorts) {
+  return flatten_workspace_bytes_z(n, g, nullptr, num_sorts);
+}
+
+size_t flatten_workspace_bytes_z(int64_t n, const ff_geom* g, const FlattenZ* z, int num_sorts) {
   // Independent of axis and shift: the shifted plan never has fewer key bits.
   FlattenPlan p;
   if (num_sorts < 1 || num_sorts > kMaxSorts) return 0;
-  if (make_flatten_plan(n, g, 0, 1, &p) != FF_OK) return 0;
+  if (make_flatten_plan_z(n, g, z, 0, 1, &p) != FF_OK) return 0;
   Layout L;
   make_layout(n, num_sorts, g->num_frames, p.key_bits, &L);
   return L.total;
@@ -713,20 +739,31 @@ int flatten_launch(const int32_t* coords, int64_t n, const ff_geom* g, int num_s
                    const int* shift, int G, int drop, int32_t* const* perm, int32_t* const* inv_perm,
                    int32_t* const* group_offsets, int32_t* const* num_groups, uint64_t* const* keys_sorted,
                    void* workspace, size_t workspace_bytes, const PackJob* pack, hipStream_t stream) {
+  return flatten_launch_z(coords, n, g, nullptr, num_sorts, axis, shift, G, drop, perm, inv_perm, group_offsets,
+                          num_groups, keys_sorted, workspace, workspace_bytes, pack, stream);
+}
+
+int flatten_launch_z(const int32_t* coords, int64_t n, const ff_geom* g, const FlattenZ* z, int num_sorts,
+                     const int* axis, const int* shift, int G, int drop, int32_t* const* perm,
+                     int32_t* const* inv_perm, int32_t* const* group_offsets, int32_t* const* num_groups,
+                     uint64_t* const* keys_sorted, void* workspace, size_t workspace_bytes, const PackJob* pack,
+                     hipStream_t stream) {
   if (num_sorts < 1 || num_sorts > kMaxSorts || G < 1) return FF_ERR_ARG;
+  if (z && keys_sorted) return FF_ERR_ARG;  // the exported key format has no room for the z fields
   Batch bt;
   int max_key_bits = 0;
   for (int s = 0; s < num_sorts; ++s) {
     FlattenPlan plan;
-    const int st = make_flatten_plan(n, g, axis[s], shift[s], &plan);
+    const int st = make_flatten_plan_z(n, g, z, axis[s], shift[s], &plan);
     if (st != FF_OK) return st;
     if (!group_offsets[s] || !num_groups[s] || (n > 0 && !perm[s])) return FF_ERR_ARG;
     KeyParams& kp = bt.kp[s];
-    kp.B = g->num_frames; kp.win_x = g->win_x; kp.win_y = g->win_y;
+    kp.B = g->num_frames; kp.win_x = g->win_x; kp.win_y = g->win_y; kp.win_z = z ? z->win_z : 1;
     kp.sx = shift[s] ? g->win_x / 2 : 0; kp.sy = shift[s] ? g->win_y / 2 : 0;
-    kp.axis = axis[s];
-    kp.bits_b = plan.bits_b; kp.bits_w1 = plan.bits_w1; kp.bits_w2 = plan.bits_w2;
-    kp.bits_l1 = plan.bits_l1; kp.bits_l2 = plan.bits_l2;
+    kp.sz = z && shift[s] ? z->win_z / 2 : 0;
+    kp.axis = axis[s]; kp.stride = z ? 4 : 3;
+    kp.bits_b = plan.bits_b; kp.bits_w1 = plan.bits_w1; kp.bits_w2 = plan.bits_w2; kp.bits_w3 = plan.bits_w3;
+    kp.bits_l1 = plan.bits_l1; kp.bits_l2 = plan.bits_l2; kp.bits_l3 = plan.bits_l3;
     kp.key_bits = plan.key_bits; kp.idx_bits = plan.idx_bits;
     bt.perm[s] = perm[s]; bt.group_offsets[s] = group_offsets[s]; bt.num_groups[s] = num_groups[s];
     bt.keys_sorted[s] = keys_sorted ? keys_sorted[s] : nullptr;

@@ -1,0 +1,118 @@
+"""GPU parity: ff_flatten3d (window sort with a third coordinate, footnote of Sec. 4.2.1) must equal the
+oracle bit for bit (perm, group offsets), in both tail modes, on both sort paths."""
+import numpy as np
+import pytest
+import torch
+
+import oracle
+import paper_2301_08739_amd as ff
+
+pytestmark = pytest.mark.gpu
+
+SORTS = [(0, 0), (1, 0), (0, 1), (1, 1)]
+TAILS = [("mask", ff.FF_TAIL_MASK), ("drop", ff.FF_TAIL_DROP)]
+
+
+def _voxels(n, B, gx, gy, gz, seed, unique=True):
+    rng = np.random.default_rng(seed)
+    cells = B * gx * gy * gz
+    ids = rng.permutation(cells)[:n] if unique else rng.integers(0, cells, size=n)
+    b, r = np.divmod(ids, gx * gy * gz)
+    x, r = np.divmod(r, gy * gz)
+    y, z = np.divmod(r, gz)
+    return np.stack([b, x, y, z], axis=1).astype(np.int32)
+
+
+def _gpu(coords, g, axis, shift, G, tail):
+    perm, goff, ng = ff.ff_flatten3d(torch.from_numpy(coords).cuda(), g, axis, shift, G, tail)
+    torch.cuda.synchronize()
+    ng = int(ng.item())
+    return perm.cpu().numpy(), goff.cpu().numpy()[: ng + 1], ng
+
+
+def _check(coords, dims, axis, shift, G, tails=TAILS):
+    g, og = ff.Geometry3(*dims), oracle.Geometry3(*dims)
+    for name, code in tails:
+        perm, off, ng = _gpu(coords, g, axis, shift, G, code)
+        wperm, woff = oracle.flatten3d(coords, og, axis, shift, G, tail=name)
+        if name == "drop":                                      # the oracle lists the full groups' starts only;
+            woff = np.append(woff, len(coords)).astype(np.int32)  # the library closes the list with n
+        assert ng == len(woff) - 1
+        assert np.array_equal(off, woff)
+        assert np.array_equal(perm, wperm)
+
+
+@pytest.mark.parametrize("n", [0, 1, 65, 4097, 20000])
+def test_small_path_sizes(n):
+    coords = _voxels(n, 3, 40, 30, 12, seed=n)
+    for axis, shift in SORTS:
+        print(f"flatten3d n={n} axis={axis} shift={shift}", flush=True)
+        _check(coords, (3, 40, 30, 12, 7, 5, 3), axis, shift, 10)
+
+
+def test_large_path():
+    n = 150001                                                  # above the three-launch path's limit
+    coords = _voxels(n, 2, 200, 200, 20, seed=6)
+    for axis, shift in [(0, 1), (1, 0)]:
+        print(f"flatten3d n={n} axis={axis} shift={shift}", flush=True)
+        _check(coords, (2, 200, 200, 20, 9, 9, 4), axis, shift, 69)
+
+
+def test_duplicates_and_single_cell():
+    coords = _voxels(15000, 2, 8, 8, 8, seed=7, unique=False)   # about 15 voxels per cell: index order decides
+    for axis, shift in SORTS:
+        _check(coords, (2, 8, 8, 8, 4, 4, 4), axis, shift, 33)
+    same = np.zeros((3000, 4), dtype=np.int32)
+    _check(same, (1, 1, 1, 1, 1, 1, 1), 0, 0, 7)                # zero key bits
+
+
+def test_flat_grid_equals_the_pillar_sort():
+    # one z cell and a z window of one: the key has no z bits, and perm / groups are those of ff_flatten
+    rng = np.random.default_rng(8)
+    n = 30000
+    ids = rng.permutation(2 * 300 * 200)[:n]
+    b, r = np.divmod(ids, 300 * 200)
+    x, y = np.divmod(r, 200)
+    c3 = np.stack([b, x, y], axis=1).astype(np.int32)
+    c4 = np.concatenate([c3, np.zeros((n, 1), np.int32)], axis=1)
+    g2, g3 = ff.Geometry(2, 300, 200, 9, 9), ff.Geometry3(2, 300, 200, 1, 9, 9, 1)
+    for axis, shift in SORTS:
+        for _, code in TAILS:
+            perm, off, ng = _gpu(c4, g3, axis, shift, 69, code)
+            p2, o2, n2, _ = ff.ff_flatten(torch.from_numpy(c3).cuda(), g2, axis, shift, 69, code)
+            torch.cuda.synchronize()
+            assert ng == int(n2.item())
+            assert np.array_equal(perm, p2.cpu().numpy())
+            assert np.array_equal(off, o2.cpu().numpy()[: ng + 1])
+
+
+def test_z_decides_between_equal_xy():
+    # all voxels in one (x, y) column: the order is by z window, then by z inside the window
+    n = 500
+    rng = np.random.default_rng(9)
+    z = rng.permutation(n).astype(np.int32)
+    coords = np.stack([np.zeros(n, np.int32), np.full(n, 3, np.int32), np.full(n, 5, np.int32), z], axis=1)
+    g = ff.Geometry3(1, 8, 8, n, 4, 4, 6)
+    perm, off, ng = _gpu(coords, g, 0, 0, 50, ff.FF_TAIL_MASK)
+    assert np.array_equal(z[perm], np.arange(n))                # unshifted: windows tile z in order
+    _check(coords, (1, 8, 8, n, 4, 4, 6), 1, 1, 50)
+
+
+def test_maximum_widths_and_errors():
+    rng = np.random.default_rng(10)
+    n = 3000
+    # 255 frames, 1024 x 1024 x 65535 windows of 1 x 1 x 1 ... 8+10+10+16 window bits + 12 index bits
+    coords = np.stack([rng.integers(0, 255, n), rng.integers(0, 1024, n), rng.integers(0, 1024, n),
+                       rng.integers(0, 65535, n)], axis=1).astype(np.int32)
+    coords[0] = (254, 1023, 1023, 65534)
+    _check(coords, (255, 1024, 1024, 65535, 1, 1, 1), 0, 0, 3)
+    _check(coords, (255, 1024, 1024, 65535, 2, 4, 256), 1, 1, 3)
+    c = torch.zeros((10, 4), dtype=torch.int32, device="cuda")
+    with pytest.raises(ff.FlatformerError):
+        ff.ff_flatten3d(c, ff.Geometry3(1, 10, 10, 10, 2, 2, 0), 0, 0, 4)      # z window 0
+    with pytest.raises(ff.FlatformerError):
+        ff.ff_flatten3d(c, ff.Geometry3(1, 10, 10, 0, 2, 2, 2), 0, 0, 4)       # empty z grid
+    with pytest.raises(ff.FlatformerError):
+        ff.ff_flatten3d(c, ff.Geometry3(1, 10, 10, 10, 2, 2, 2), 2, 0, 4)      # axis 2
+    with pytest.raises(ff.FlatformerError):                                    # 16+16+16+16 window bits + index
+        ff.ff_flatten3d(c, ff.Geometry3(65535, 65535, 65535, 65535, 1, 1, 1), 0, 0, 4)

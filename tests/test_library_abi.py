@@ -63,6 +63,16 @@ def test_argument_errors_are_reported_before_any_launch():
     assert lib.ff_flatten(one, 10, gp, 0, 0, 0, 0, one, one, one, null, one, 1 << 20, null) == -1
     assert lib.ff_flatten(one, 10, gp, 0, 0, 4, 0, one, null, one, null, one, 1 << 20, null) == -1
     assert lib.ff_flatten(one, 10, gp, 0, 0, 4, 0, one, one, one, null, one, 16, null) == -3     # workspace too small
+    # the same with a third coordinate: bad tail, bad z window, key too wide, workspace too small
+    g3 = ff.Geometry3(1, 468, 468, 40, 13, 13, 4)
+    g3p = ctypes.byref(g3)
+    assert lib.ff_flatten3d(one, 10, g3p, 0, 0, 4, 7, one, one, one, one, 1 << 20, null) == -1
+    assert lib.ff_flatten3d(one, 10, ctypes.byref(ff.Geometry3(1, 468, 468, 40, 13, 13, 0)), 0, 0, 4, 0, one, one, one,
+                            one, 1 << 20, null) == -1
+    assert lib.ff_flatten3d(one, 10, ctypes.byref(ff.Geometry3(65535, 65535, 65535, 65535, 1, 1, 1)), 0, 0, 4, 0, one,
+                            one, one, one, 1 << 20, null) == -2
+    assert lib.ff_flatten3d(one, 10, g3p, 0, 0, 4, 0, one, one, one, one, 16, null) == -3
+    assert 0 < lib.ff_flatten3d_workspace_bytes(30000, g3p) < lib.ff_flatten3d_workspace_bytes(60000, g3p)
     # layer: incomplete weights, C not divisible by heads, overlapping buffers, workspace missing
     w = _LayerWeightsC()
     wp = ctypes.byref(w)
