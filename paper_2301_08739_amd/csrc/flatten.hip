@@ -109,10 +109,14 @@ __device__ __forceinline__ uint64_t make_word(const int32_t* __restrict__ coords
   const uint32_t b = (uint32_t)c[0];
   const uint32_t X = (uint32_t)(c[1] + kp.sx);
   const uint32_t Y = (uint32_t)(c[2] + kp.sy);
-  const uint32_t Z = kp.stride > 3 ? (uint32_t)(c[3] + kp.sz) : 0u;
   const uint32_t Wx = X / (uint32_t)kp.win_x, Lx = X - Wx * (uint32_t)kp.win_x;
   const uint32_t Wy = Y / (uint32_t)kp.win_y, Ly = Y - Wy * (uint32_t)kp.win_y;
-  const uint32_t Wz = Z / (uint32_t)kp.win_z, Lz = Z - Wz * (uint32_t)kp.win_z;
+  uint32_t Wz = 0u, Lz = 0u;
+  if (kp.stride > 3) {  // uniform: pillars pay for no third division
+    const uint32_t Z = (uint32_t)(c[3] + kp.sz);
+    Wz = Z / (uint32_t)kp.win_z;
+    Lz = Z - Wz * (uint32_t)kp.win_z;
+  }
   const uint32_t w1 = kp.axis == 0 ? Wx : Wy, w2 = kp.axis == 0 ? Wy : Wx;
   const uint32_t l1 = kp.axis == 0 ? Lx : Ly, l2 = kp.axis == 0 ? Ly : Lx;
   // Fields are masked to their widths so that a coordinate outside the geometry can only
