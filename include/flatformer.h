@@ -243,6 +243,16 @@ int ff_fwa_block(const int32_t* coords, int64_t n, const ff_geom* g, int G, int 
                  const void* feats_in, void* feats_out,
                  void* workspace, size_t workspace_bytes, void* stream);
 
+/* The block over voxels with a third coordinate (footnote of Sec. 4.2.1): ff_fwa_block with the sorts
+ * of ff_flatten3d.  coords [n,4] = (b, x, y, z); everything else as above. */
+size_t ff_fwa_block3d_workspace_bytes(int64_t n, const ff_geom3* g, int G,
+                                      const ff_layer_weights* layers, int num_layers, int dtype);
+
+int ff_fwa_block3d(const int32_t* coords, int64_t n, const ff_geom3* g, int G, int tail,
+                   const ff_layer_weights* layers, int num_layers, int dtype,
+                   const void* feats_in, void* feats_out,
+                   void* workspace, size_t workspace_bytes, void* stream);
+
 const char* ff_status_string(int status);
 int ff_version(void);
 

@@ -106,6 +106,11 @@ _SIGS = {
                                                    C.POINTER(_LayerWeightsC), C.c_int, C.c_int]),
     "ff_fwa_block": (C.c_int, [C.c_void_p, C.c_int64, C.POINTER(Geometry), C.c_int, C.c_int, C.POINTER(_LayerWeightsC),
                                C.c_int, C.c_int, C.c_void_p, C.c_void_p, C.c_void_p, C.c_size_t, C.c_void_p]),
+    "ff_fwa_block3d_workspace_bytes": (C.c_size_t, [C.c_int64, C.POINTER(Geometry3), C.c_int,
+                                                     C.POINTER(_LayerWeightsC), C.c_int, C.c_int]),
+    "ff_fwa_block3d": (C.c_int, [C.c_void_p, C.c_int64, C.POINTER(Geometry3), C.c_int, C.c_int,
+                                 C.POINTER(_LayerWeightsC), C.c_int, C.c_int, C.c_void_p, C.c_void_p, C.c_void_p,
+                                 C.c_size_t, C.c_void_p]),
     "ff_status_string": (C.c_char_p, [C.c_int]),
     "ff_version": (C.c_int, []),
 }
@@ -292,24 +297,34 @@ def _layer_array(layers, pos_embed=None):
     return arr
 
 
+def _block_entry(lib, geom):
+    if isinstance(geom, Geometry3):
+        return lib.ff_fwa_block3d_workspace_bytes, lib.ff_fwa_block3d, "ff_fwa_block3d"
+    return lib.ff_fwa_block_workspace_bytes, lib.ff_fwa_block, "ff_fwa_block"
+
+
 def ff_fwa_block_workspace_bytes(n, geom, G, layers, dtype):
+    """geom: Geometry (coords [n,3]) or Geometry3 (coords [n,4]: the ff_fwa_block3d entry points)."""
     arr = _layer_array(layers)
-    return load_library().ff_fwa_block_workspace_bytes(int(n), C.byref(geom), G, arr, len(layers), dtype)
+    return _block_entry(load_library(), geom)[0](int(n), C.byref(geom), G, arr, len(layers), dtype)
 
 
 def ff_fwa_block(coords, geom, G, layers, dtype, feats_in, out=None, workspace=None, tail=FF_TAIL_MASK,
                  pos_embed=None):
-    """pos_embed: None or a tensor like feats_in, handed to every layer of the block."""
+    """pos_embed: None or a tensor like feats_in, handed to every layer of the block.  With a Geometry3
+    and coords [n,4] this calls ff_fwa_block3d."""
     lib = load_library()
     n = coords.shape[0]
+    query, run, name = _block_entry(lib, geom)
+    assert coords.shape[1] == (4 if isinstance(geom, Geometry3) else 3)
     if pos_embed is not None:
         assert pos_embed.shape == feats_in.shape and pos_embed.dtype == feats_in.dtype and pos_embed.is_contiguous()
     arr = _layer_array(layers, pos_embed)
     if out is None:
         out = torch.empty_like(feats_in)
-    need = lib.ff_fwa_block_workspace_bytes(n, C.byref(geom), G, arr, len(layers), dtype)
+    need = query(n, C.byref(geom), G, arr, len(layers), dtype)
     ws = workspace if workspace is not None else _workspace(need, coords.device)
-    st = lib.ff_fwa_block(_ptr(coords), n, C.byref(geom), G, tail, arr, len(layers), dtype, _ptr(feats_in), _ptr(out),
-                          C.c_void_p(_aligned_ptr(ws)), ws.numel() - 256, _stream())
-    _check(st, "ff_fwa_block")
+    st = run(_ptr(coords), n, C.byref(geom), G, tail, arr, len(layers), dtype, _ptr(feats_in), _ptr(out),
+             C.c_void_p(_aligned_ptr(ws)), ws.numel() - 256, _stream())
+    _check(st, name)
     return out

@@ -200,8 +200,8 @@ struct BlockPlan {
   size_t flat_bytes, layer_bytes, packed_stride;  // packed_stride == 0: nothing to pre-pack
 };
 
-int make_block_plan(int64_t n, const ff_geom* g, int G, const ff_layer_weights* layers, int num_layers,
-                    int dtype, BlockPlan* p) {
+int make_block_plan(int64_t n, const ff_geom* g, const FlattenZ* z, int G, const ff_layer_weights* layers,
+                    int num_layers, int dtype, BlockPlan* p) {
   if (n < 0 || n > 0x7fffffffLL || !g || G < 1 || num_layers < 1 || !layers) return FF_ERR_ARG;
   for (int l = 0; l < num_layers; ++l) {
     int st = check_weights(&layers[l], dtype);
@@ -209,8 +209,8 @@ int make_block_plan(int64_t n, const ff_geom* g, int G, const ff_layer_weights* 
     if (layers[l].C != layers[0].C) return FF_ERR_ARG;
   }
   p->sorts = num_layers < 4 ? num_layers : 4;
-  p->flat_bytes = flatten_workspace_bytes(n, g, p->sorts);
-  if (p->flat_bytes == 0) { FlattenPlan fp; int st = make_flatten_plan(n, g, 0, 1, &fp); if (st != FF_OK) return st; }
+  p->flat_bytes = flatten_workspace_bytes_z(n, g, z, p->sorts);
+  if (p->flat_bytes == 0) { FlattenPlan fp; int st = make_flatten_plan_z(n, g, z, 0, 1, &fp); if (st != FF_OK) return st; }
   p->max_groups = ceil_div(n, G) + g->num_frames;
   p->layer_bytes = 0;
   for (int l = 0; l < num_layers; ++l) {
@@ -244,20 +244,14 @@ int make_block_plan(int64_t n, const ff_geom* g, int G, const ff_layer_weights* 
 }
 }  // namespace
 
-size_t ff_fwa_block_workspace_bytes(int64_t n, const ff_geom* g, int G, const ff_layer_weights* layers,
-                                    int num_layers, int dtype) {
-  BlockPlan p;
-  if (make_block_plan(n, g, G, layers, num_layers, dtype, &p) != FF_OK) return 0;
-  return p.total;
-}
-
-int ff_fwa_block(const int32_t* coords, int64_t n, const ff_geom* g, int G, int tail,
-                 const ff_layer_weights* layers, int num_layers, int dtype, const void* feats_in, void* feats_out,
-                 void* workspace, size_t workspace_bytes, void* stream) {
+namespace {
+int fwa_block(const int32_t* coords, int64_t n, const ff_geom* g, const FlattenZ* z, int G, int tail,
+              const ff_layer_weights* layers, int num_layers, int dtype, const void* feats_in, void* feats_out,
+              void* workspace, size_t workspace_bytes, void* stream) {
   if (tail != FF_TAIL_MASK && tail != FF_TAIL_DROP) return FF_ERR_ARG;
   const bool drop = tail == FF_TAIL_DROP;
   BlockPlan p;
-  int st = make_block_plan(n, g, G, layers, num_layers, dtype, &p);
+  int st = make_block_plan(n, g, z, G, layers, num_layers, dtype, &p);
   if (st != FF_OK) return st;
   if (!workspace || ((uintptr_t)workspace & 255) || workspace_bytes < p.total) return FF_ERR_WORKSPACE;
   if (n > 0 && (!coords || !feats_in || !feats_out || feats_in == feats_out)) return FF_ERR_ARG;
@@ -279,8 +273,8 @@ int ff_fwa_block(const int32_t* coords, int64_t n, const ff_geom* g, int G, int 
     PackJob job;
     const bool ride = p.packed_stride && n > 0 && num_layers <= kPackBatch;
     if (ride) make_pack_job(layers, num_layers, ws + p.off_packed, p.packed_stride, dtype == FF_F16, &job);
-    st = flatten_launch(coords, n, g, p.sorts, axis, shift, G, drop, perm, p.chain ? inv : nullptr, goff, ng, nullptr, ws + p.off_flat,
-                        p.flat_bytes, ride ? &job : nullptr, (hipStream_t)stream);
+    st = flatten_launch_z(coords, n, g, z, p.sorts, axis, shift, G, drop, perm, p.chain ? inv : nullptr, goff, ng, nullptr,
+                          ws + p.off_flat, p.flat_bytes, ride ? &job : nullptr, (hipStream_t)stream);
     if (st != FF_OK) return st;
     if (p.packed_stride && n > 0 && !ride) {
       st = dtype == FF_F16
@@ -307,6 +301,41 @@ int ff_fwa_block(const int32_t* coords, int64_t n, const ff_geom* g, int G, int 
     cur = dst;
   }
   return FF_OK;
+}
+}  // namespace
+
+size_t ff_fwa_block_workspace_bytes(int64_t n, const ff_geom* g, int G, const ff_layer_weights* layers,
+                                    int num_layers, int dtype) {
+  BlockPlan p;
+  if (make_block_plan(n, g, nullptr, G, layers, num_layers, dtype, &p) != FF_OK) return 0;
+  return p.total;
+}
+
+int ff_fwa_block(const int32_t* coords, int64_t n, const ff_geom* g, int G, int tail,
+                 const ff_layer_weights* layers, int num_layers, int dtype, const void* feats_in, void* feats_out,
+                 void* workspace, size_t workspace_bytes, void* stream) {
+  return fwa_block(coords, n, g, nullptr, G, tail, layers, num_layers, dtype, feats_in, feats_out, workspace,
+                   workspace_bytes, stream);
+}
+
+size_t ff_fwa_block3d_workspace_bytes(int64_t n, const ff_geom3* g, int G, const ff_layer_weights* layers,
+                                      int num_layers, int dtype) {
+  ff_geom g2;
+  FlattenZ z;
+  BlockPlan p;
+  if (split_geom3(g, &g2, &z) != FF_OK) return 0;
+  if (make_block_plan(n, &g2, &z, G, layers, num_layers, dtype, &p) != FF_OK) return 0;
+  return p.total;
+}
+
+int ff_fwa_block3d(const int32_t* coords, int64_t n, const ff_geom3* g, int G, int tail,
+                   const ff_layer_weights* layers, int num_layers, int dtype, const void* feats_in, void* feats_out,
+                   void* workspace, size_t workspace_bytes, void* stream) {
+  ff_geom g2;
+  FlattenZ z;
+  if (split_geom3(g, &g2, &z) != FF_OK) return FF_ERR_ARG;
+  return fwa_block(coords, n, &g2, &z, G, tail, layers, num_layers, dtype, feats_in, feats_out, workspace,
+                   workspace_bytes, stream);
 }
 
 const char* ff_status_string(int status) {

@@ -116,3 +116,40 @@ def test_maximum_widths_and_errors():
         ff.ff_flatten3d(c, ff.Geometry3(1, 10, 10, 10, 2, 2, 2), 2, 0, 4)      # axis 2
     with pytest.raises(ff.FlatformerError):                                    # 16+16+16+16 window bits + index
         ff.ff_flatten3d(c, ff.Geometry3(65535, 65535, 65535, 65535, 1, 1, 1), 0, 0, 4)
+
+
+@pytest.mark.parametrize("dt,tail", [(ff.FF_BF16, ff.FF_TAIL_MASK), (ff.FF_BF16, ff.FF_TAIL_DROP), (ff.FF_F32, ff.FF_TAIL_MASK)])
+def test_block_over_voxels_equals_flatten3d_plus_layer_calls(dt, tail):
+    """ff_fwa_block3d (the layer stack over 3-D windows) must equal ff_flatten3d + ff_group_attention
+    called layer by layer, bit for bit; the first layer is also held against the oracle on the
+    oracle's own 3-D sort."""
+    import ffsynth
+    n, G, C, F, heads = 20000, 64, 128, 256, 8
+    dims = (2, 60, 60, 10, 6, 6, 3)
+    coords = _voxels(n, 2, 60, 60, 10, seed=11)
+    g = ff.Geometry3(*dims)
+    ct = torch.from_numpy(coords).cuda()
+    bf = dt == ff.FF_BF16
+    params = ffsynth.stack_params(C, F, heads, 4, bf16=bf)
+    rng = np.random.default_rng(12)
+    x_h = rng.standard_normal((n, C)).astype(np.float32)
+    x_h = ffsynth.bf16_round(x_h) if bf else x_h
+    x = torch.from_numpy(x_h).cuda().to(torch.bfloat16 if bf else torch.float32)
+    layers = [ff.LayerWeights(p, dt, "cuda") for p in params]
+    flag = ff.FF_FLAG_TAIL_DROP if tail == ff.FF_TAIL_DROP else 0
+    out = ff.ff_fwa_block(ct, g, G, layers, dt, x, tail=tail)
+    cur = x
+    for l, (axis, shift) in enumerate(ffsynth.layer_schedule(4)):
+        perm, goff, ng = ff.ff_flatten3d(ct, g, axis, shift, G, tail)
+        nxt = ff.ff_group_attention(cur, perm, goff, ng, -(-n // G) + dims[0], layers[l], G, dt, flag)
+        if l == 0:
+            wperm, woff = oracle.flatten3d(coords, oracle.Geometry3(*dims), axis, shift, G,
+                                           tail="drop" if flag else "mask")
+            want = oracle.layer(x_h, wperm, woff, params[0], group_size=G if flag else None)
+            err = np.abs(nxt.float().cpu().numpy().astype(np.float64) - want)
+            tol = 2e-2 + 2.0 ** -9 * np.abs(want) if bf else 1e-4
+            print(f"3-D block dt={dt} tail={tail}: first layer max abs err {err.max():.3e}", flush=True)
+            assert np.all(err <= tol)
+        cur = nxt
+    torch.cuda.synchronize()
+    assert torch.equal(out, cur)

@@ -73,6 +73,8 @@ def test_argument_errors_are_reported_before_any_launch():
                             one, one, one, 1 << 20, null) == -2
     assert lib.ff_flatten3d(one, 10, g3p, 0, 0, 4, 0, one, one, one, one, 16, null) == -3
     assert 0 < lib.ff_flatten3d_workspace_bytes(30000, g3p) < lib.ff_flatten3d_workspace_bytes(60000, g3p)
+    assert lib.ff_fwa_block3d(one, 10, g3p, 64, 9, ctypes.byref(_LayerWeightsC()), 1, 1, one, ctypes.c_void_p(1 << 20), one,
+                              1 << 30, null) == -1
     # layer: incomplete weights, C not divisible by heads, overlapping buffers, workspace missing
     w = _LayerWeightsC()
     wp = ctypes.byref(w)
