@@ -65,3 +65,25 @@ def test_headline_block_end_to_end_against_the_oracle(cfg):
     print(f"cfg2 block end to end: max abs err {err.max():.4e}, mean {err.mean():.3e}, max |ref| {np.abs(cur).max():.2f}",
           flush=True)
     assert np.all(err <= bound)
+
+
+@pytest.mark.parametrize("num_layers", [1, 2, 3, 5, 9, 17])
+def test_layer_counts(cfg, num_layers):
+    """One layer (no chaining), fewer layers than sort configurations, counts that are no multiple of
+    four, and more layers than one weight re-tiling launch takes (16)."""
+    c = cfg(2, num_layers)
+    n = 5000
+    coords = np.ascontiguousarray(c["coords"][:n])
+    g, _ = geoms(c)
+    ct = torch.from_numpy(coords).to(DEV)
+    layers = [ff.LayerWeights(p, ff.FF_BF16, DEV) for p in c["layer_params"]]
+    assert len(layers) == num_layers
+    x = to_dev_feats(c["feats"][:n], ff.FF_BF16)
+    out = ff.ff_fwa_block(ct, g, c["G"], layers, ff.FF_BF16, x)
+    cur = x
+    for l, key in enumerate(ffsynth.layer_schedule(num_layers)):
+        perm, goff, ng, _ = ff.ff_flatten(ct, g, key[0], key[1], c["G"])
+        cur = ff.ff_group_attention(cur, perm, goff, ng, -(-n // c["G"]) + c["B"], layers[l], c["G"], ff.FF_BF16)
+    torch.cuda.synchronize()
+    assert torch.isfinite(out.float()).all()
+    assert torch.equal(out, cur)
