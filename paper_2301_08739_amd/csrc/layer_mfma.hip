@@ -45,7 +45,6 @@ typedef _Float16 el4 __attribute__((ext_vector_type(4)));
 typedef _Float16 el2 __attribute__((ext_vector_type(2)));
 constexpr uint32_t kOnePair = 0x3c003c00u;  // two ones
 __device__ __forceinline__ float el_to_f32(uint16_t h) { return (float)__builtin_bit_cast(_Float16, h); }
-__device__ __forceinline__ uint16_t f32_to_el(float f) { return __builtin_bit_cast(uint16_t, (_Float16)f); }
 __device__ __forceinline__ float el_lo(uint32_t u) { return el_to_f32((uint16_t)(u & 0xffffu)); }
 __device__ __forceinline__ float el_hi(uint32_t u) { return el_to_f32((uint16_t)(u >> 16)); }
 #define FF_LAYER_SYM(name) name##_f16
@@ -55,7 +54,6 @@ typedef short el4 __attribute__((ext_vector_type(4)));
 typedef __bf16 el2 __attribute__((ext_vector_type(2)));
 constexpr uint32_t kOnePair = 0x3f803f80u;  // two ones
 __device__ __forceinline__ float el_to_f32(uint16_t h) { return bf16_to_f32(h); }
-__device__ __forceinline__ uint16_t f32_to_el(float f) { return f32_to_bf16(f); }
 __device__ __forceinline__ float el_lo(uint32_t u) { return __uint_as_float(u << 16); }
 __device__ __forceinline__ float el_hi(uint32_t u) { return __uint_as_float(u & 0xffff0000u); }
 #define FF_LAYER_SYM(name) name
@@ -887,8 +885,7 @@ static size_t layer_mfma_frag_count(const ff_layer_weights* w) {
 
 #ifndef FF_LAYER_F16
 size_t layer_mfma_packed_bytes(const ff_layer_weights* w) {
-  const int C = w->C, F = w->F;
-  return layer_mfma_frag_count(w) * (size_t)1024 + (size_t)C * 4;
+  return layer_mfma_frag_count(w) * (size_t)1024 + (size_t)w->C * 4;
 }
 #endif
 

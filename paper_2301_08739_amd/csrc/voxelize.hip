@@ -6,7 +6,7 @@
 //   k_point_cells   cell of every point (float32: floor((x - x_min) / voxel)), dropped points -> frame B
 //   flatten         the radix argsort of flatten.hip with 1 x 1 windows: points ordered by (frame, x, y)
 //   k_seg_count     per 1024 sorted points: how many cells start there
-//   k_seg_scan      exclusive prefix over those counts, total = number of pillars
+//   k_seg_scan      exclusive prefix over those counts, total = number of pillars (above 262,144 points only)
 //   k_seg_starts    numbers the cell starts: start position and cell of every pillar
 //   k_seg_mean      sixteen lanes per pillar: mean of its points' features, point -> pillar
 #include "common.h"
@@ -15,6 +15,7 @@ namespace ff {
 namespace {
 
 constexpr int kSegBlock = 1024;
+constexpr int kSegDirectBlocks = 256;  // up to 262,144 points the blocks' prefixes need no launch of their own
 
 __global__ __launch_bounds__(256) void k_point_cells(const float* __restrict__ xy, const int32_t* __restrict__ frame,
                                                       int64_t m, int B, int gx, int gy, float x_min, float y_min,
@@ -36,8 +37,9 @@ __device__ __forceinline__ bool starts_cell(const uint64_t* __restrict__ keys, i
 }
 
 __global__ __launch_bounds__(256) void k_seg_count(const uint64_t* __restrict__ keys, int64_t m, int B,
-                                                    uint32_t* __restrict__ block_counts) {
+                                                    uint32_t* __restrict__ block_counts, int32_t* __restrict__ kept) {
   __shared__ uint32_t wave_sums[4];
+  if (blockIdx.x == 0 && threadIdx.x == 0) *kept = (int32_t)m;  // lowered by k_seg_starts
   const int64_t p0 = (int64_t)blockIdx.x * kSegBlock;
   uint32_t c = 0;
 #pragma unroll
@@ -52,9 +54,10 @@ __global__ __launch_bounds__(256) void k_seg_count(const uint64_t* __restrict__ 
   if (threadIdx.x == 0) block_counts[blockIdx.x] = wave_sums[0] + wave_sums[1] + wave_sums[2] + wave_sums[3];
 }
 
-// One workgroup: block_counts -> exclusive prefixes in place, total -> *num_pillars.
-__global__ __launch_bounds__(1024) void k_seg_scan(uint32_t* __restrict__ block_counts, int64_t nb, int64_t m,
-                                                    int32_t* __restrict__ num_pillars, int32_t* __restrict__ kept) {
+// One workgroup: block_counts -> exclusive prefixes in place, total -> *num_pillars.  Only for more
+// blocks than k_seg_starts adds up by itself.
+__global__ __launch_bounds__(1024) void k_seg_scan(uint32_t* __restrict__ block_counts, int64_t nb,
+                                                    int32_t* __restrict__ num_pillars) {
   __shared__ uint32_t wave_sums[16];
   __shared__ uint32_t carry_s;
   if (threadIdx.x == 0) carry_s = 0;
@@ -83,16 +86,40 @@ __global__ __launch_bounds__(1024) void k_seg_scan(uint32_t* __restrict__ block_
     if (threadIdx.x == 0) carry_s += total;
     __syncthreads();
   }
-  if (threadIdx.x == 0) { *num_pillars = (int32_t)carry_s; *kept = (int32_t)m; }  // kept: lowered by k_seg_starts
+  if (threadIdx.x == 0) *num_pillars = (int32_t)carry_s;
 }
 
 // Cell starts get their pillar numbers (block-local scan on top of the block's prefix): writes where
 // each pillar's run of sorted points starts, its cell, and -1 for the points that were dropped.
+// SCANNED: block_base holds exclusive prefixes (k_seg_scan ran).  Otherwise it holds the blocks'
+// counts and every workgroup adds up the ones before it (a few KB from L2: cheaper than a dependent
+// launch); workgroup 0 also writes the total.
+template <bool SCANNED>
 __global__ __launch_bounds__(256) void k_seg_starts(const uint64_t* __restrict__ keys, const int32_t* __restrict__ perm,
-                                                     int64_t m, int B, const uint32_t* __restrict__ block_base,
+                                                     int64_t m, int B, const uint32_t* __restrict__ block_base, int nb,
+                                                     int32_t* __restrict__ num_pillars,
                                                      int32_t* __restrict__ starts, int32_t* __restrict__ kept,
                                                      int32_t* __restrict__ coords, int32_t* __restrict__ point_to_pillar) {
   __shared__ uint32_t wave_sums[4];
+  __shared__ uint32_t base_sums[4][2];
+  uint32_t base = 0;
+  if (SCANNED) {
+    base = block_base[blockIdx.x];
+  } else {
+    uint32_t before = 0, all = 0;
+    for (int i = threadIdx.x; i < nb; i += 256) {
+      const uint32_t c = block_base[i];
+      all += c;
+      if (i < (int)blockIdx.x) before += c;
+    }
+#pragma unroll
+    for (int d = 32; d >= 1; d >>= 1) { before += __shfl_xor(before, d, 64); all += __shfl_xor(all, d, 64); }
+    if ((threadIdx.x & 63) == 0) { base_sums[threadIdx.x >> 6][0] = before; base_sums[threadIdx.x >> 6][1] = all; }
+    __syncthreads();
+    base = base_sums[0][0] + base_sums[1][0] + base_sums[2][0] + base_sums[3][0];
+    if (blockIdx.x == 0 && threadIdx.x == 0)
+      *num_pillars = (int32_t)(base_sums[0][1] + base_sums[1][1] + base_sums[2][1] + base_sums[3][1]);
+  }
   const int64_t p0 = (int64_t)blockIdx.x * kSegBlock;
   const int lane = threadIdx.x & 63, w = threadIdx.x >> 6;
   // thread t owns positions p0 + 4t .. p0 + 4t + 3, so that cell starts are numbered in sorted order
@@ -112,7 +139,7 @@ __global__ __launch_bounds__(256) void k_seg_starts(const uint64_t* __restrict__
   }
   if (lane == 63) wave_sums[w] = inc;
   __syncthreads();
-  uint32_t pid = block_base[blockIdx.x] + inc - mine;
+  uint32_t pid = base + inc - mine;
   for (int k = 0; k < w; ++k) pid += wave_sums[k];
 #pragma unroll
   for (int r = 0; r < 4; ++r) {
@@ -234,12 +261,17 @@ int voxelize_launch(const float* xy, const int32_t* frame, const float* pfeats, 
   st = flatten_launch(cells, m, &L.geom, 1, &axis, &shift, 0x40000000, 0, &perm, nullptr, &goff, &ng, &keys,
                       ws + L.off_flat, L.flat_bytes, nullptr, stream);
   if (st != FF_OK) return st;
-  hipLaunchKernelGGL(k_seg_count, dim3((unsigned)L.nb), dim3(256), 0, stream, keys, m, g->num_frames, blocks);
   int32_t* starts = (int32_t*)(ws + L.off_starts);
   int32_t* kept = ng + 1;  // number of points inside the grid (a spare word beside the sort's group count)
-  hipLaunchKernelGGL(k_seg_scan, dim3(1), dim3(1024), 0, stream, blocks, L.nb, m, num_pillars, kept);
-  hipLaunchKernelGGL(k_seg_starts, dim3((unsigned)L.nb), dim3(256), 0, stream, keys, perm, m, g->num_frames, blocks,
-                     starts, kept, coords, point_to_pillar);
+  hipLaunchKernelGGL(k_seg_count, dim3((unsigned)L.nb), dim3(256), 0, stream, keys, m, g->num_frames, blocks, kept);
+  if (L.nb <= kSegDirectBlocks) {
+    hipLaunchKernelGGL(k_seg_starts<false>, dim3((unsigned)L.nb), dim3(256), 0, stream, keys, perm, m, g->num_frames,
+                       blocks, (int)L.nb, num_pillars, starts, kept, coords, point_to_pillar);
+  } else {
+    hipLaunchKernelGGL(k_seg_scan, dim3(1), dim3(1024), 0, stream, blocks, L.nb, num_pillars);
+    hipLaunchKernelGGL(k_seg_starts<true>, dim3((unsigned)L.nb), dim3(256), 0, stream, keys, perm, m, g->num_frames,
+                       blocks, (int)L.nb, num_pillars, starts, kept, coords, point_to_pillar);
+  }
   int64_t mean_blocks = ceil_div(m > 0 ? m : 1, 16);  // a pillar per sixteen lanes; there are at most m pillars
   if (mean_blocks > 256 * 32) mean_blocks = 256 * 32;
   hipLaunchKernelGGL(k_seg_mean, dim3((unsigned)mean_blocks), dim3(256), 0, stream, perm, pfeats, Cp, num_pillars, starts,
