@@ -225,7 +225,7 @@ def sweep(ff, torch, c, dt, dev):
     esz = 4 if dt == ff.FF_F32 else 2
     tdt = {ff.FF_F32: torch.float32, ff.FF_BF16: torch.bfloat16, ff.FF_F16: torch.float16}[dt]
     lw = ff.LayerWeights(c["layer_params"][0], dt, dev).pack()
-    for B in (1, 8, 32, 128):
+    for B in (1, 8, 32, 128, 512):
         coords = np.tile(c["coords"], (B, 1))
         coords[:, 0] = np.repeat(np.arange(B, dtype=np.int32), n1)
         rng = np.random.default_rng(B)
@@ -246,7 +246,7 @@ def sweep(ff, torch, c, dt, dev):
         perm, goff, ng, _ = ff.ff_flatten(ct, geom, 0, 1, G, workspace=fws)
         torch.cuda.synchronize()
         mg = -(-n // G) + B
-        reps = 20 if B <= 32 else 8
+        reps = 20 if B <= 32 else (8 if B <= 128 else 4)
         def bits(v):
             return int(v - 1).bit_length() if v > 1 else 0
         nw = -(-(c["grid"] + c["window"] // 2) // c["window"])
