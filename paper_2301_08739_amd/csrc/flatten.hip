@@ -47,6 +47,11 @@ constexpr int kSmallKpt = 4, kSmallMaxTiles = 128;  // small clouds: tiles of 10
 constexpr int kLargeKpt = 16;                       // larger clouds: tiles of 4096 words
 constexpr int kScanThreads = 1024;
 constexpr int kScanStrip = 64;  // digits per workgroup of the column scan (narrower strips were no faster)
+// Above 1024 tiles (4 M words) a thread of the 64-digit strip would own more rows than it keeps in
+// registers; strips of 16 digits give four times the workgroups and keep every thread within 64 rows
+// up to 4096 tiles.
+constexpr int kScanNarrow = 16;
+constexpr int kScanWideTiles = 1024;
 
 struct KeyParams {
   int32_t B, win_x, win_y, win_z;       // win_z = 1 and stride = 3 for bird's-eye-view pillars
@@ -815,8 +820,12 @@ int flatten_launch_z(const int32_t* coords, int64_t n, const ff_geom* g, const F
           if (pass > 0)                                                                                              \
             hipLaunchKernelGGL((k_tile_counts<RB, KPT>), grid, block, 0, stream, buf[cur], n, bt, pass, P, pp.tiles, \
                                counts);                                                                              \
-          hipLaunchKernelGGL((k_scan_cols<RB, kScanStrip>), dim3((1u << RB) / kScanStrip, (unsigned)num_sorts), dim3(kScanThreads), 0,    \
-                             stream, counts, totals, pass, P, pp.tiles);                                             \
+          if (pp.tiles > kScanWideTiles)                                                                             \
+            hipLaunchKernelGGL((k_scan_cols<RB, kScanNarrow>), dim3((1u << RB) / kScanNarrow, (unsigned)num_sorts),  \
+                               dim3(kScanThreads), 0, stream, counts, totals, pass, P, pp.tiles);                   \
+          else                                                                                                       \
+            hipLaunchKernelGGL((k_scan_cols<RB, kScanStrip>), dim3((1u << RB) / kScanStrip, (unsigned)num_sorts),    \
+                               dim3(kScanThreads), 0, stream, counts, totals, pass, P, pp.tiles);                   \
         }                                                                                                            \
         if (fuse && pass == pp.passes - 1)                                                                           \
           hipLaunchKernelGGL((k_pass<RB, KPT, true, SCANNED>), pass == 0 ? grid_pack : grid, block, 0, stream,      \

@@ -108,3 +108,14 @@ def test_errors_and_determinism():
     a = gpu_flatten(c, g, 0, 1, 64)
     b = gpu_flatten(c, g, 0, 1, 64)
     assert np.array_equal(a[0], b[0]) and np.array_equal(a[1], b[1]) and np.array_equal(a[3], b[3])
+
+
+def test_more_than_1024_tiles():
+    """4.2 M pillars: the digit tables have more than 1024 rows, which the column scan takes in
+    narrower strips.  One sort configuration against the oracle's tuple sort (about half a minute of
+    host time)."""
+    n = 4200001
+    coords = _rand_coords(n, 8, 1024, 1024, seed=6)
+    g, og = ff.Geometry(8, 1024, 1024, 13, 13), oracle.Geometry(8, 1024, 1024, 13, 13)
+    print(f"flatten n={n}: oracle sort running", flush=True)
+    _check(coords, g, og, 1, 1, 64)
