@@ -82,10 +82,13 @@ __global__ __launch_bounds__(256) void k_ln_qkv(const T* __restrict__ feats, con
 
 // One workgroup per (group, head); one thread per query row (looping when the group is larger
 // than the workgroup).  Plain two-pass softmax over the group's real members.
-template <int DMAX>
+// EXACT: d == DMAX, so the loops over the head dimension carry no bound test (with one, every element
+// became a branch and a load of its own).
+template <int DMAX, bool STAGED, bool EXACT>
 __global__ __launch_bounds__(256) void k_attention(const float* __restrict__ qkv, const int32_t* __restrict__ group_offsets,
                                                     const int32_t* __restrict__ num_groups, int C, int d, int G,
                                                     float* __restrict__ o) {
+  extern __shared__ float kv_s[];  // STAGED: the group's K and V slices of this head, [m][d] each
   const int g = blockIdx.x, h = blockIdx.y;
   if (g >= *num_groups) return;
   const int64_t start = group_offsets[g];
@@ -93,35 +96,48 @@ __global__ __launch_bounds__(256) void k_attention(const float* __restrict__ qkv
   m = m < G ? m : G;  // a list of full groups only: the next start may lie beyond this group's end
   const float scale = 1.0f / sqrtf((float)d);
   const int64_t ld = 3 * (int64_t)C;
+  // Every query of the group walks over the same keys and values: from LDS when they fit (one trip
+  // to memory for the whole workgroup), else straight from memory.
+  const float* kbase = qkv + start * ld + C + h * d;
+  int64_t kld = ld, voff = C;
+  if (STAGED) {
+    for (int t = threadIdx.x; t < m * d; t += blockDim.x) {
+      const int j = t / d, c = t - j * d;
+      kv_s[t] = kbase[j * ld + c];
+      kv_s[G * d + t] = kbase[j * ld + C + c];
+    }
+    __syncthreads();
+    kbase = kv_s; kld = d; voff = (int64_t)G * d;
+  }
   for (int i = threadIdx.x; i < m; i += blockDim.x) {
     float q[DMAX], acc[DMAX];
     const float* qrow = qkv + (start + i) * ld + h * d;
 #pragma unroll
-    for (int c = 0; c < DMAX; ++c) { q[c] = c < d ? qrow[c] : 0.f; acc[c] = 0.f; }
+    for (int c = 0; c < DMAX; ++c) { q[c] = EXACT || c < d ? qrow[c] : 0.f; acc[c] = 0.f; }
     float mx = -INFINITY;
     for (int j = 0; j < m; ++j) {
-      const float* krow = qkv + (start + j) * ld + C + h * d;
+      const float* krow = kbase + j * kld;
       float s = 0.f;
 #pragma unroll
-      for (int c = 0; c < DMAX; ++c) if (c < d) s = fmaf(q[c], krow[c], s);
+      for (int c = 0; c < DMAX; ++c) if (EXACT || c < d) s = fmaf(q[c], krow[c], s);
       mx = fmaxf(mx, s * scale);
     }
     float sum = 0.f;
     for (int j = 0; j < m; ++j) {
-      const float* krow = qkv + (start + j) * ld + C + h * d;
-      const float* vrow = krow + C;
+      const float* krow = kbase + j * kld;
+      const float* vrow = krow + voff;
       float s = 0.f;
 #pragma unroll
-      for (int c = 0; c < DMAX; ++c) if (c < d) s = fmaf(q[c], krow[c], s);
+      for (int c = 0; c < DMAX; ++c) if (EXACT || c < d) s = fmaf(q[c], krow[c], s);
       const float e = expf(s * scale - mx);
       sum += e;
 #pragma unroll
-      for (int c = 0; c < DMAX; ++c) if (c < d) acc[c] = fmaf(e, vrow[c], acc[c]);
+      for (int c = 0; c < DMAX; ++c) if (EXACT || c < d) acc[c] = fmaf(e, vrow[c], acc[c]);
     }
     const float inv = 1.0f / sum;
     float* orow = o + (start + i) * (int64_t)C + h * d;
 #pragma unroll
-    for (int c = 0; c < DMAX; ++c) if (c < d) orow[c] = acc[c] * inv;
+    for (int c = 0; c < DMAX; ++c) if (EXACT || c < d) orow[c] = acc[c] * inv;
   }
 }
 
@@ -211,10 +227,25 @@ int launch_typed(const void* feats, void* out, int64_t n, const int32_t* perm, c
                      (const T*)w->ln1_g, (const T*)w->ln1_b, w->ln_eps, (const T*)w->w_qkv,
                      (const T*)w->b_qkv, (const T*)w->pos_embed, qkv);
   dim3 ga((unsigned)max_groups, (unsigned)w->heads);
-  if (d <= 16)       hipLaunchKernelGGL((k_attention<16>), ga, dim3(256), 0, stream, qkv, group_offsets, num_groups, C, d, G, o);
-  else if (d <= 32)  hipLaunchKernelGGL((k_attention<32>), ga, dim3(256), 0, stream, qkv, group_offsets, num_groups, C, d, G, o);
-  else if (d <= 64)  hipLaunchKernelGGL((k_attention<64>), ga, dim3(256), 0, stream, qkv, group_offsets, num_groups, C, d, G, o);
-  else               hipLaunchKernelGGL((k_attention<128>), ga, dim3(256), 0, stream, qkv, group_offsets, num_groups, C, d, G, o);
+  const size_t lds_kv = (size_t)2 * G * d * 4;  // G can be far larger than any group: then no staging
+  const bool staged = (int64_t)G * d * 8 <= 48 * 1024;
+#define FF_ATT(D)                                                                                                     \
+  do {                                                                                                                \
+    if (staged && d == D)                                                                                             \
+      hipLaunchKernelGGL((k_attention<D, true, true>), ga, dim3(256), lds_kv, stream, qkv, group_offsets, num_groups, \
+                         C, d, G, o);                                                                                 \
+    else if (staged)                                                                                                  \
+      hipLaunchKernelGGL((k_attention<D, true, false>), ga, dim3(256), lds_kv, stream, qkv, group_offsets,            \
+                         num_groups, C, d, G, o);                                                                     \
+    else                                                                                                              \
+      hipLaunchKernelGGL((k_attention<D, false, false>), ga, dim3(256), 0, stream, qkv, group_offsets, num_groups, C, \
+                         d, G, o);                                                                                    \
+  } while (0)
+  if (d <= 16) FF_ATT(16);
+  else if (d <= 32) FF_ATT(32);
+  else if (d <= 64) FF_ATT(64);
+  else FF_ATT(128);
+#undef FF_ATT
   hipLaunchKernelGGL((k_out_ffn<T, TO>), dim3(row_blocks), dim3(256), lds_c, stream, (const T*)feats, perm, n, C, F, o,
                      (const T*)w->w_o, (const T*)w->b_o, (const T*)w->ln2_g, (const T*)w->ln2_b, w->ln_eps,
                      (const T*)w->w1, (const T*)w->b1, (const T*)w->w2, (const T*)w->b2, (TO*)out);
