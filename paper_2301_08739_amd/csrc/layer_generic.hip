@@ -6,6 +6,7 @@
 // exponential and erf in fp32 on the vector ALUs.  It serves dtype FF_F32 and any shape the
 // MFMA kernels do not cover.  Three kernels, intermediates in the caller's workspace:
 //   k_ln_qkv    rows of the sorted order: gather, LN1, packed QKV projection   -> qkv [n, 3C] f32
+//               (weights staged through LDS from 8192 rows on)
 //   k_attention one workgroup per (group, head): softmax(Q K^T / sqrt(d)) V     -> o   [n, C]  f32
 //   k_out_ffn   rows: out-proj + residual, LN2, Linear+GELU, Linear + residual, scatter
 #include "common.h"
@@ -13,7 +14,10 @@
 namespace ff {
 namespace {
 
-constexpr int RB = 4;  // sorted rows per workgroup in the row kernels
+constexpr int RB = 4;            // sorted rows per workgroup in the row kernels ...
+constexpr int kRowsWide = 16;    // ... or sixteen, from kRowsWideMin rows on (512 workgroups)
+constexpr int64_t kRowsWideMin = 8192;
+constexpr size_t kRowLdsMax = 64 * 1024;
 
 __device__ __forceinline__ float wave_sum(float v) {
 #pragma unroll
@@ -36,48 +40,97 @@ __device__ __forceinline__ void ln_rows(const float* src, float* dst, int C, int
   }
 }
 
-template <typename T>
+// acc[r] = sum over k of in[r * ld + k] * W[j * K + k] for the workgroup's RBT rows (in LDS) and every
+// output feature j < N, thread t owning features t, t + 256, ...; the sum runs over k in ascending
+// order whatever the staging.  TILED: the weights pass through LDS in tiles of 256 features x KT
+// inputs, read from memory along k by neighbouring threads (a thread streaming its own weight row
+// touches a cache line of its own per load, 64 lines per wavefront instruction).  `in(j)` names the
+// LDS rows feature j multiplies, `ep(j, acc)` takes the sums.  Every thread of the workgroup must call.
+constexpr int KT = 16;
+template <typename T, int RBT, bool TILED, typename In, typename Ep>
+__device__ __forceinline__ void rows_by_weights(const T* __restrict__ W, int N, int K, int ld, float* wt, In in, Ep ep) {
+  for (int j0 = 0; j0 < N; j0 += 256) {
+    const int j = j0 + (int)threadIdx.x;
+    float acc[RBT];
+#pragma unroll
+    for (int r = 0; r < RBT; ++r) acc[r] = 0.f;
+    if (TILED) {
+      const float* src = in(j < N ? j : N - 1);
+      const float* mine = wt + threadIdx.x * (KT + 1);
+      for (int k0 = 0; k0 < K; k0 += KT) {
+        __syncthreads();  // the previous tile has been used
+        for (int t = threadIdx.x; t < 256 * KT; t += 256) {
+          const int jj = t / KT, kk = t - jj * KT;
+          wt[jj * (KT + 1) + kk] =
+              j0 + jj < N && k0 + kk < K ? Elem<T>::load(W + (int64_t)(j0 + jj) * K + k0 + kk) : 0.f;
+        }
+        __syncthreads();
+        if (j >= N) continue;
+        if (k0 + KT <= K) {
+#pragma unroll
+          for (int kk = 0; kk < KT; ++kk) {
+            const float wv = mine[kk];
+#pragma unroll
+            for (int r = 0; r < RBT; ++r) acc[r] = fmaf(src[r * ld + k0 + kk], wv, acc[r]);
+          }
+        } else {
+          for (int kk = 0; k0 + kk < K; ++kk) {
+            const float wv = mine[kk];
+#pragma unroll
+            for (int r = 0; r < RBT; ++r) acc[r] = fmaf(src[r * ld + k0 + kk], wv, acc[r]);
+          }
+        }
+      }
+    } else if (j < N) {
+      const float* src = in(j);
+      const T* wrow = W + (int64_t)j * K;
+#pragma unroll 8
+      for (int k = 0; k < K; ++k) {  // eight weight loads in flight
+        const float wv = Elem<T>::load(wrow + k);
+#pragma unroll
+        for (int r = 0; r < RBT; ++r) acc[r] = fmaf(src[r * ld + k], wv, acc[r]);
+      }
+    }
+    if (j < N) ep(j, acc);
+  }
+}
+
+template <typename T, int RBT, bool TILED>
 __global__ __launch_bounds__(256) void k_ln_qkv(const T* __restrict__ feats, const int32_t* __restrict__ perm,
                                                  int64_t n, int C, const T* __restrict__ ln_g,
                                                  const T* __restrict__ ln_b, float eps,
                                                  const T* __restrict__ w_qkv, const T* __restrict__ b_qkv,
                                                  const T* __restrict__ pos_embed, float* __restrict__ qkv) {
   extern __shared__ float lds[];
-  float* X = lds;              // [RB][C]
-  float* U = X + RB * C;       // [RB][C]
-  float* gs = U + RB * C;      // [C]
+  float* X = lds;              // [RBT][C]
+  float* U = X + RBT * C;      // [RBT][C]
+  float* gs = U + RBT * C;     // [C]
   float* bs = gs + C;          // [C]
-  const int64_t p0 = (int64_t)blockIdx.x * RB;
-  const int rows = (int)((n - p0) < RB ? (n - p0) : RB);
+  float* wt = bs + C;          // TILED: [256][KT + 1]
+  const int64_t p0 = (int64_t)blockIdx.x * RBT;
+  const int rows = (int)((n - p0) < RBT ? (n - p0) : RBT);
   for (int i = threadIdx.x; i < C; i += blockDim.x) { gs[i] = Elem<T>::load(ln_g + i); bs[i] = Elem<T>::load(ln_b + i); }
-  for (int i = threadIdx.x; i < rows * C; i += blockDim.x) {
+  for (int i = threadIdx.x; i < RBT * C; i += blockDim.x) {
     const int r = i / C, k = i - r * C;
-    X[i] = Elem<T>::load(feats + (int64_t)perm[p0 + r] * C + k);
+    X[i] = r < rows ? Elem<T>::load(feats + (int64_t)perm[p0 + r] * C + k) : 0.f;
   }
   __syncthreads();
   ln_rows(X, U, C, rows, gs, bs, eps);
+  for (int i = threadIdx.x + rows * C; i < RBT * C; i += blockDim.x) U[i] = 0.f;  // rows beyond n
   __syncthreads();
   if (pos_embed) {  // queries and keys are projected from LN(F) + PE (kept in X), values from LN(F)
-    for (int i = threadIdx.x; i < RB * C; i += blockDim.x) {
+    for (int i = threadIdx.x; i < RBT * C; i += blockDim.x) {
       const int r = i / C, k = i - r * C;
       X[i] = r < rows ? U[i] + Elem<T>::load(pos_embed + (int64_t)perm[p0 + r] * C + k) : 0.f;
     }
     __syncthreads();
   }
-  for (int j = threadIdx.x; j < 3 * C; j += blockDim.x) {
-    float acc[RB];
-#pragma unroll
-    for (int r = 0; r < RB; ++r) acc[r] = 0.f;
-    const T* wrow = w_qkv + (int64_t)j * C;
-    const float* in = pos_embed && j < 2 * C ? X : U;
-    for (int k = 0; k < C; ++k) {
-      const float wv = Elem<T>::load(wrow + k);
-#pragma unroll
-      for (int r = 0; r < RB; ++r) acc[r] = fmaf(in[r * C + k], wv, acc[r]);
-    }
-    const float bj = Elem<T>::load(b_qkv + j);
-    for (int r = 0; r < rows; ++r) qkv[(p0 + r) * 3 * (int64_t)C + j] = acc[r] + bj;
-  }
+  rows_by_weights<T, RBT, TILED>(
+      w_qkv, 3 * C, C, C, wt, [&](int j) { return pos_embed && j < 2 * C ? X : U; },
+      [&](int j, const float* acc) {
+        const float bj = Elem<T>::load(b_qkv + j);
+        for (int r = 0; r < rows; ++r) qkv[(p0 + r) * 3 * (int64_t)C + j] = acc[r] + bj;
+      });
 }
 
 // One workgroup per (group, head); one thread per query row (looping when the group is larger
@@ -141,7 +194,7 @@ __global__ __launch_bounds__(256) void k_attention(const float* __restrict__ qkv
   }
 }
 
-template <typename T, typename TO>
+template <typename T, typename TO, int RBT, bool TILED>
 __global__ __launch_bounds__(256) void k_out_ffn(const T* __restrict__ feats, const int32_t* __restrict__ perm,
                                                   int64_t n, int C, int F, const float* __restrict__ o,
                                                   const T* __restrict__ w_o, const T* __restrict__ b_o,
@@ -150,69 +203,61 @@ __global__ __launch_bounds__(256) void k_out_ffn(const T* __restrict__ feats, co
                                                   const T* __restrict__ w2, const T* __restrict__ b2,
                                                   TO* __restrict__ out) {
   extern __shared__ float lds[];
-  float* O = lds;               // [RB][C]
-  float* X1 = O + RB * C;       // [RB][C]
-  float* U = X1 + RB * C;       // [RB][C]
-  float* H = U + RB * C;        // [RB][F]
-  float* gs = H + RB * F;       // [C]
+  float* O = lds;               // [RBT][C]
+  float* X1 = O + RBT * C;      // [RBT][C]
+  float* U = X1 + RBT * C;      // [RBT][C]
+  float* H = U + RBT * C;       // [RBT][F]
+  float* gs = H + RBT * F;      // [C]
   float* bs = gs + C;           // [C]
-  const int64_t p0 = (int64_t)blockIdx.x * RB;
-  const int rows = (int)((n - p0) < RB ? (n - p0) : RB);
+  float* wt = bs + C;           // TILED: [256][KT + 1]
+  const int64_t p0 = (int64_t)blockIdx.x * RBT;
+  const int rows = (int)((n - p0) < RBT ? (n - p0) : RBT);
   for (int i = threadIdx.x; i < C; i += blockDim.x) { gs[i] = Elem<T>::load(ln_g + i); bs[i] = Elem<T>::load(ln_b + i); }
-  for (int i = threadIdx.x; i < RB * C; i += blockDim.x) O[i] = i < rows * C ? o[p0 * C + i] : 0.f;
+  for (int i = threadIdx.x; i < RBT * C; i += blockDim.x) O[i] = i < rows * C ? o[p0 * C + i] : 0.f;
   __syncthreads();
-  for (int j = threadIdx.x; j < C; j += blockDim.x) {
-    float acc[RB];
+  rows_by_weights<T, RBT, TILED>(
+      w_o, C, C, C, wt, [&](int) { return O; },
+      [&](int j, const float* acc) {
+        const float bj = Elem<T>::load(b_o + j);
 #pragma unroll
-    for (int r = 0; r < RB; ++r) acc[r] = 0.f;
-    const T* wrow = w_o + (int64_t)j * C;
-    for (int k = 0; k < C; ++k) {
-      const float wv = Elem<T>::load(wrow + k);
-#pragma unroll
-      for (int r = 0; r < RB; ++r) acc[r] = fmaf(O[r * C + k], wv, acc[r]);
-    }
-    const float bj = Elem<T>::load(b_o + j);
-#pragma unroll
-    for (int r = 0; r < RB; ++r) {
-      float x = r < rows ? Elem<T>::load(feats + (int64_t)perm[p0 + r] * C + j) : 0.f;
-      X1[r * C + j] = x + (acc[r] + bj);
-    }
-  }
+        for (int r = 0; r < RBT; ++r) {
+          const float x = r < rows ? Elem<T>::load(feats + (int64_t)perm[p0 + r] * C + j) : 0.f;
+          X1[r * C + j] = x + (acc[r] + bj);
+        }
+      });
   __syncthreads();
-  ln_rows(X1, U, C, RB, gs, bs, eps);
+  ln_rows(X1, U, C, RBT, gs, bs, eps);
   __syncthreads();
-  for (int f = threadIdx.x; f < F; f += blockDim.x) {
-    float acc[RB];
+  rows_by_weights<T, RBT, TILED>(
+      w1, F, C, C, wt, [&](int) { return U; },
+      [&](int f, const float* acc) {
+        const float bf = Elem<T>::load(b1 + f);
 #pragma unroll
-    for (int r = 0; r < RB; ++r) acc[r] = 0.f;
-    const T* wrow = w1 + (int64_t)f * C;
-    for (int k = 0; k < C; ++k) {
-      const float wv = Elem<T>::load(wrow + k);
-#pragma unroll
-      for (int r = 0; r < RB; ++r) acc[r] = fmaf(U[r * C + k], wv, acc[r]);
-    }
-    const float bf = Elem<T>::load(b1 + f);
-#pragma unroll
-    for (int r = 0; r < RB; ++r) {
-      const float v = acc[r] + bf;
-      H[r * F + f] = 0.5f * v * (1.0f + erff(v * 0.70710678118654752440f));
-    }
-  }
+        for (int r = 0; r < RBT; ++r) {
+          const float v = acc[r] + bf;
+          H[r * F + f] = 0.5f * v * (1.0f + erff(v * 0.70710678118654752440f));
+        }
+      });
   __syncthreads();
-  for (int j = threadIdx.x; j < C; j += blockDim.x) {
-    float acc[RB];
-#pragma unroll
-    for (int r = 0; r < RB; ++r) acc[r] = 0.f;
-    const T* wrow = w2 + (int64_t)j * F;
-    for (int k = 0; k < F; ++k) {
-      const float wv = Elem<T>::load(wrow + k);
-#pragma unroll
-      for (int r = 0; r < RB; ++r) acc[r] = fmaf(H[r * F + k], wv, acc[r]);
-    }
-    const float bj = Elem<T>::load(b2 + j);
-    for (int r = 0; r < rows; ++r)
-      Elem<TO>::store(out + (int64_t)perm[p0 + r] * C + j, X1[r * C + j] + (acc[r] + bj));
-  }
+  rows_by_weights<T, RBT, TILED>(
+      w2, C, F, F, wt, [&](int) { return H; },
+      [&](int j, const float* acc) {
+        const float bj = Elem<T>::load(b2 + j);
+        for (int r = 0; r < rows; ++r)
+          Elem<TO>::store(out + (int64_t)perm[p0 + r] * C + j, X1[r * C + j] + (acc[r] + bj));
+      });
+}
+
+// The QKV kernel takes sixteen rows per workgroup with staged weights when there are enough rows to
+// fill the chip that way and its LDS fits (measured at 30k rows, C = 128: 1102 -> 181 us); four rows
+// with weights straight from memory otherwise (faster below a few thousand rows).  The out-proj / FFN
+// kernel always runs the latter form: staged, its three narrower products (half the threads idle
+// when a product has 128 outputs, two workgroups per compute unit) were slower, 445 against 309 us.
+struct RowPlan { int rb; bool tiled; size_t lds; };
+RowPlan qkv_plan(int64_t n, int C) {
+  const size_t wide = ((size_t)2 * kRowsWide * C + 2 * C + 256 * (KT + 1)) * 4;
+  if (n >= kRowsWideMin && wide <= kRowLdsMax) return {kRowsWide, true, wide};
+  return {RB, false, ((size_t)2 * RB * C + 2 * C) * 4};
 }
 
 template <typename T, typename TO>
@@ -220,12 +265,14 @@ int launch_typed(const void* feats, void* out, int64_t n, const int32_t* perm, c
                  const int32_t* num_groups, int32_t max_groups, const ff_layer_weights* w, int d, int G,
                  float* qkv, float* o, hipStream_t stream) {
   const int C = w->C, F = w->F;
-  const unsigned row_blocks = (unsigned)ceil_div(n, RB);
-  const size_t lds_a = (size_t)(2 * RB * C + 2 * C) * 4;
-  const size_t lds_c = (size_t)(3 * RB * C + RB * F + 2 * C) * 4;
-  hipLaunchKernelGGL((k_ln_qkv<T>), dim3(row_blocks), dim3(256), lds_a, stream, (const T*)feats, perm, n, C,
-                     (const T*)w->ln1_g, (const T*)w->ln1_b, w->ln_eps, (const T*)w->w_qkv,
-                     (const T*)w->b_qkv, (const T*)w->pos_embed, qkv);
+  const RowPlan pa = qkv_plan(n, C);
+  auto run_qkv = [&](auto kern) {
+    hipLaunchKernelGGL(kern, dim3((unsigned)ceil_div(n, pa.rb)), dim3(256), pa.lds, stream, (const T*)feats, perm, n, C,
+                       (const T*)w->ln1_g, (const T*)w->ln1_b, w->ln_eps, (const T*)w->w_qkv, (const T*)w->b_qkv,
+                       (const T*)w->pos_embed, qkv);
+  };
+  if (pa.tiled) run_qkv(k_ln_qkv<T, kRowsWide, true>);
+  else run_qkv(k_ln_qkv<T, RB, false>);
   dim3 ga((unsigned)max_groups, (unsigned)w->heads);
   const size_t lds_kv = (size_t)2 * G * d * 4;  // G can be far larger than any group: then no staging
   const bool staged = (int64_t)G * d * 8 <= 48 * 1024;
@@ -246,7 +293,8 @@ int launch_typed(const void* feats, void* out, int64_t n, const int32_t* perm, c
   else if (d <= 64) FF_ATT(64);
   else FF_ATT(128);
 #undef FF_ATT
-  hipLaunchKernelGGL((k_out_ffn<T, TO>), dim3(row_blocks), dim3(256), lds_c, stream, (const T*)feats, perm, n, C, F, o,
+  hipLaunchKernelGGL((k_out_ffn<T, TO, RB, false>), dim3((unsigned)ceil_div(n, RB)), dim3(256),
+                     ((size_t)3 * RB * C + (size_t)RB * F + 2 * C) * 4, stream, (const T*)feats, perm, n, C, F, o,
                      (const T*)w->w_o, (const T*)w->b_o, (const T*)w->ln2_g, (const T*)w->ln2_b, w->ln_eps,
                      (const T*)w->w1, (const T*)w->b1, (const T*)w->w2, (const T*)w->b2, (TO*)out);
   return launch_status();
