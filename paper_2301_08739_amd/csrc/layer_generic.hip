@@ -251,8 +251,9 @@ __global__ __launch_bounds__(256) void k_out_ffn(const T* __restrict__ feats, co
 // The QKV kernel takes sixteen rows per workgroup with staged weights when there are enough rows to
 // fill the chip that way and its LDS fits (measured at 30k rows, C = 128: 1102 -> 181 us); four rows
 // with weights straight from memory otherwise (faster below a few thousand rows).  The out-proj / FFN
-// kernel always runs the latter form: staged, its three narrower products (half the threads idle
-// when a product has 128 outputs, two workgroups per compute unit) were slower, 445 against 309 us.
+// kernel never stages: its three narrower products (half the threads idle when a product has 128
+// outputs, two workgroups per compute unit) were slower that way, 445 against 309 us; it takes
+// sixteen rows where its LDS fits (225 us) and four otherwise.
 struct RowPlan { int rb; bool tiled; size_t lds; };
 RowPlan qkv_plan(int64_t n, int C) {
   const size_t wide = ((size_t)2 * kRowsWide * C + 2 * C + 256 * (KT + 1)) * 4;
@@ -293,10 +294,15 @@ int launch_typed(const void* feats, void* out, int64_t n, const int32_t* perm, c
   else if (d <= 64) FF_ATT(64);
   else FF_ATT(128);
 #undef FF_ATT
-  hipLaunchKernelGGL((k_out_ffn<T, TO, RB, false>), dim3((unsigned)ceil_div(n, RB)), dim3(256),
-                     ((size_t)3 * RB * C + (size_t)RB * F + 2 * C) * 4, stream, (const T*)feats, perm, n, C, F, o,
-                     (const T*)w->w_o, (const T*)w->b_o, (const T*)w->ln2_g, (const T*)w->ln2_b, w->ln_eps,
-                     (const T*)w->w1, (const T*)w->b1, (const T*)w->w2, (const T*)w->b2, (TO*)out);
+  const size_t ffn_wide = ((size_t)3 * kRowsWide * C + (size_t)kRowsWide * F + 2 * C) * 4;
+  auto run_ffn = [&](auto kern, int rb) {
+    hipLaunchKernelGGL(kern, dim3((unsigned)ceil_div(n, rb)), dim3(256),
+                       ((size_t)3 * rb * C + (size_t)rb * F + 2 * C) * 4, stream, (const T*)feats, perm, n, C, F, o,
+                       (const T*)w->w_o, (const T*)w->b_o, (const T*)w->ln2_g, (const T*)w->ln2_b, w->ln_eps,
+                       (const T*)w->w1, (const T*)w->b1, (const T*)w->w2, (const T*)w->b2, (TO*)out);
+  };
+  if (n >= kRowsWideMin && ffn_wide <= kRowLdsMax) run_ffn(k_out_ffn<T, TO, kRowsWide, false>, kRowsWide);
+  else run_ffn(k_out_ffn<T, TO, RB, false>, RB);
   return launch_status();
 }
 
