@@ -202,3 +202,28 @@ def test_bf16_wide_layer_group_sizes(cfg, G):
         print(f"C=256 G={G} variant {variant}", flush=True)
         v = to_host(ff.ff_group_attention(x, dev[0], dev[1], dev[2], mg, lw, G, ff.FF_BF16, fl))
         assert np.abs(v - want).max() <= 2e-2, (variant, np.abs(v - want).max())
+
+
+@pytest.mark.parametrize("C,F,heads,G", [(128, 256, 8, 64), (64, 128, 4, 32), (96, 160, 3, 50)])
+def test_fp32_many_rows(cfg, C, F, heads, G):
+    """From 8192 rows on the plain kernels take sixteen rows per workgroup (the QKV kernel with its
+    weights staged through LDS): 20,003 rows leave a ragged last block; the third shape has a width
+    that is no multiple of the staging tile, heads of 32 and a group size of its own."""
+    c = cfg(2, 1)
+    n = 20003
+    coords = np.ascontiguousarray(c["coords"][:n])
+    rng = np.random.default_rng(C + G)
+    feats = rng.standard_normal((n, C)).astype(np.float32)
+    pe = (0.5 * rng.standard_normal((n, C))).astype(np.float32)
+    p = ffsynth.layer_params(C, F, heads, seed=77)
+    g, og = geoms(c)
+    perm, off, ng, _, dev = gpu_flatten(coords, g, 0, 1, G, want_keys=False)
+    lw = ff.LayerWeights(p, ff.FF_F32, DEV)
+    x = to_dev_feats(feats, ff.FF_F32)
+    got = to_host(ff.ff_group_attention(x, dev[0], dev[1], dev[2], -(-n // G) + 1, lw, G, ff.FF_F32))
+    err = np.abs(got - oracle.layer(feats, perm, off, p)).max()
+    got_pe = to_host(ff.ff_group_attention(x, dev[0], dev[1], dev[2], -(-n // G) + 1, lw, G, ff.FF_F32,
+                                           pos_embed=to_dev_feats(pe, ff.FF_F32)))
+    err_pe = np.abs(got_pe - oracle.layer(feats, perm, off, p, pos_embed=pe)).max()
+    print(f"fp32 n={n} C={C} F={F} heads={heads} G={G}: max abs err {err:.2e}, with embedding {err_pe:.2e}", flush=True)
+    assert err <= 1e-4 and err_pe <= 1e-4
