@@ -15,6 +15,7 @@ namespace ff {
 namespace {
 
 constexpr int kSegBlock = 1024;
+constexpr int kPointsInFlight = 8;  // per lane of k_seg_mean
 constexpr int kSegDirectBlocks = 256;  // up to 262,144 points the blocks' prefixes need no launch of their own
 
 __global__ __launch_bounds__(256) void k_point_cells(const float* __restrict__ xy, const int32_t* __restrict__ frame,
@@ -174,20 +175,20 @@ __global__ __launch_bounds__(256) void k_seg_mean(const int32_t* __restrict__ pe
       for (int q = lo + sub; q < hi; q += 16) point_to_pillar[perm[q]] = (int32_t)pid;
     for (int c0 = 0; c0 < Cp; c0 += 4) {  // four features at a time
       float acc[4] = {0.f, 0.f, 0.f, 0.f};
-      // four points per lane and round, their loads in flight together: a pillar of several hundred
+      // eight points per lane and round, their loads in flight together: a pillar of several hundred
       // points (a dense object, the cell under the sensor) is a chain of dependent round trips otherwise
-      for (int q = lo + sub; q < hi; q += 64) {
-        int32_t src[4];
+      for (int q = lo + sub; q < hi; q += 16 * kPointsInFlight) {
+        int32_t src[kPointsInFlight];
 #pragma unroll
-        for (int u = 0; u < 4; ++u) src[u] = q + 16 * u < hi ? perm[q + 16 * u] : -1;
-        float v[4][4];
+        for (int u = 0; u < kPointsInFlight; ++u) src[u] = q + 16 * u < hi ? perm[q + 16 * u] : -1;
+        float v[kPointsInFlight][4];
 #pragma unroll
-        for (int u = 0; u < 4; ++u)
+        for (int u = 0; u < kPointsInFlight; ++u)
 #pragma unroll
           for (int j = 0; j < 4; ++j)
             v[u][j] = src[u] >= 0 && c0 + j < Cp ? pfeats[(int64_t)src[u] * Cp + c0 + j] : 0.f;
 #pragma unroll
-        for (int u = 0; u < 4; ++u)
+        for (int u = 0; u < kPointsInFlight; ++u)
 #pragma unroll
           for (int j = 0; j < 4; ++j) acc[j] += v[u][j];
       }
