@@ -323,21 +323,36 @@ __global__ __launch_bounds__(NW * 64, MINW) void k_layer_mfma(const uint16_t* __
   issue(1);
   issued = 2;
 
-  // small parameters -> LDS as fp32
-  for (int t = tid; t < PO::TOTAL; t += NT) {
+  // Small parameters -> LDS as fp32.  Their loads are issued here, all of them before anything waits,
+  // and written to LDS once the rows of the gather are on their way too (below): a wait between two
+  // loads costs a whole trip to memory, and this prologue is a chain of such trips.
+  constexpr int PIT = (PO::TOTAL + NT - 1) / NT;
+  uint16_t par_raw[PIT];
+  float bo_raw = 0.f;
+#pragma unroll
+  for (int it = 0; it < PIT; ++it) {
+    const int t = tid + it * NT;
+    const int tc = t < PO::TOTAL ? t : PO::TOTAL - 1;
     const uint16_t* src;
     int o;
-    if (t >= PO::BO && t < PO::BO + C) {  // folded output bias, fp32, behind the fragments
-      par[t] = reinterpret_cast<const float*>(packed + (size_t)NCHUNK * CF * 64)[t - PO::BO];
-      continue;
-    }
-    if (t < 2 * C) { src = t < C ? sp.ln1_g : sp.ln1_b; o = t < C ? t : t - C; }
-    else if (t < 3 * C) { src = sp.b_qkv; o = t - 2 * C; }
-    else if (t < 6 * C) { src = t < 5 * C ? sp.ln2_g : sp.ln2_b; o = t < 5 * C ? t - 4 * C : t - 5 * C; }
-    else if (t < 7 * C) { src = sp.b2; o = t - 6 * C; }
-    else { src = sp.b1; o = t - 7 * C; }
-    par[t] = el_to_f32(src[o]);
+    if (tc < 2 * C) { src = tc < C ? sp.ln1_g : sp.ln1_b; o = tc < C ? tc : tc - C; }
+    else if (tc < 3 * C) { src = sp.b_qkv; o = tc - 2 * C; }
+    else if (tc < 4 * C) { src = sp.ln1_g; o = 0; }  // the folded output bias comes from the packed stream
+    else if (tc < 6 * C) { src = tc < 5 * C ? sp.ln2_g : sp.ln2_b; o = tc < 5 * C ? tc - 4 * C : tc - 5 * C; }
+    else if (tc < 7 * C) { src = sp.b2; o = tc - 6 * C; }
+    else { src = sp.b1; o = tc - 7 * C; }
+    par_raw[it] = src[o];
   }
+  static_assert(C <= NT, "one thread per feature of the folded bias");
+  bo_raw = reinterpret_cast<const float*>(packed + (size_t)NCHUNK * CF * 64)[tid < C ? tid : C - 1];
+  auto store_params = [&]() {
+#pragma unroll
+    for (int it = 0; it < PIT; ++it) {
+      const int t = tid + it * NT;
+      if (t < PO::TOTAL && !(t >= PO::BO && t < PO::BO + C)) par[t] = el_to_f32(par_raw[it]);
+    }
+    if (tid < C) par[PO::BO + tid] = bo_raw;
+  };
 
   // ---- gather + LN1 ---------------------------------------------------------------------------------
   f32x4 x1[NVB][NB];  // residual stream of my pillars, accumulator layout
@@ -352,6 +367,7 @@ __global__ __launch_bounds__(NW * 64, MINW) void k_layer_mfma(const uint16_t* __
   }
   FF_TS_WAIT(17);
   if (in_sorted == 2 && guessed) {  // the early fetch hit
+    store_params();
 #pragma unroll
     for (int vb = 0; vb < NVB; ++vb) {
       const bool live = (part * NVB + vb) * 16 + i < m;
@@ -362,17 +378,25 @@ __global__ __launch_bounds__(NW * 64, MINW) void k_layer_mfma(const uint16_t* __
       }
     }
   } else {
+    // every lane loads (padding slots read a valid row and drop it): loads under a condition of their
+    // own are waited for one by one
+    uint2 raw[NVB][NB];
 #pragma unroll
     for (int vb = 0; vb < NVB; ++vb) {
       const int s = (part * NVB + vb) * 16 + i;
-      const int64_t src = in_sorted ? (int64_t)start + s : (int64_t)row[vb];
+      int64_t src = in_sorted ? (int64_t)start + s : (int64_t)row[vb];
+      src = row[vb] >= 0 ? src : 0;
+#pragma unroll
+      for (int nb = 0; nb < NB; ++nb) raw[vb][nb] = *reinterpret_cast<const uint2*>(feats + src * C + 16 * nb + 4 * q);
+    }
+    store_params();
+#pragma unroll
+    for (int vb = 0; vb < NVB; ++vb)
 #pragma unroll
       for (int nb = 0; nb < NB; ++nb) {
-        float t[4] = {0.f, 0.f, 0.f, 0.f};
-        if (row[vb] >= 0) load4(feats + src * C + 16 * nb + 4 * q, t);
-        x1[vb][nb] = f32x4{t[0], t[1], t[2], t[3]};
+        const uint2 u = raw[vb][nb];
+        x1[vb][nb] = row[vb] >= 0 ? f32x4{el_lo(u.x), el_hi(u.x), el_lo(u.y), el_hi(u.y)} : f32x4{0.f, 0.f, 0.f, 0.f};
       }
-    }
   }
   // Positional embedding of my pillars, still bf16, in the layout of `act` (Eq. (2), second argument
   // of the attention): it is added to the LayerNorm output on the way to the query and key products.
@@ -382,10 +406,9 @@ __global__ __launch_bounds__(NW * 64, MINW) void k_layer_mfma(const uint16_t* __
     for (int vb = 0; vb < NVB; ++vb)
 #pragma unroll
       for (int nb = 0; nb < NB; ++nb) {
-        uint2 u = make_uint2(0u, 0u);
-        if (row[vb] >= 0) u = *reinterpret_cast<const uint2*>(pos_embed + (int64_t)row[vb] * C + 16 * nb + 4 * q);
-        pef[vb][nb / 2].u[(nb & 1) * 2 + 0] = u.x;
-        pef[vb][nb / 2].u[(nb & 1) * 2 + 1] = u.y;
+        const uint2 u = *reinterpret_cast<const uint2*>(pos_embed + (int64_t)(row[vb] >= 0 ? row[vb] : 0) * C + 16 * nb + 4 * q);
+        pef[vb][nb / 2].u[(nb & 1) * 2 + 0] = row[vb] >= 0 ? u.x : 0u;
+        pef[vb][nb / 2].u[(nb & 1) * 2 + 1] = row[vb] >= 0 ? u.y : 0u;
       }
   }
   FF_TS(1);
