@@ -32,9 +32,16 @@ __global__ __launch_bounds__(256) void k_point_cells(const float* __restrict__ x
 }
 
 // exported key of the sort: frame << 48 | x << 32 | y << 16 (window 1 x 1: no local fields)
-__device__ __forceinline__ bool starts_cell(const uint64_t* __restrict__ keys, int64_t p, int B) {
-  const uint64_t k = keys[p];
-  return (int)(k >> 48) < B && (p == 0 || keys[p - 1] != k);
+// The key at sorted position p and the one before it, loaded without conditions (positions clamped
+// into the array) so that a thread's loads travel together; starts_cell then tells whether p is the
+// first point of a cell inside the grid.
+struct KeyPair { uint64_t k, before; };
+__device__ __forceinline__ KeyPair load_pair(const uint64_t* __restrict__ keys, int64_t p, int64_t m) {
+  const int64_t pc = p < m ? p : m - 1;
+  return {keys[pc], keys[pc > 0 ? pc - 1 : 0]};
+}
+__device__ __forceinline__ bool starts_cell(const KeyPair& kp, int64_t p, int64_t m, int B) {
+  return p < m && (int)(kp.k >> 48) < B && (p == 0 || kp.before != kp.k);
 }
 
 __global__ __launch_bounds__(256) void k_seg_count(const uint64_t* __restrict__ keys, int64_t m, int B,
@@ -43,10 +50,13 @@ __global__ __launch_bounds__(256) void k_seg_count(const uint64_t* __restrict__ 
   if (blockIdx.x == 0 && threadIdx.x == 0) *kept = (int32_t)m;  // lowered by k_seg_starts
   const int64_t p0 = (int64_t)blockIdx.x * kSegBlock;
   uint32_t c = 0;
+  if (m > 0) {  // the same for every thread
+    KeyPair kp[kSegBlock / 256];
 #pragma unroll
-  for (int r = 0; r < kSegBlock / 256; ++r) {
-    const int64_t p = p0 + r * 256 + threadIdx.x;
-    if (p < m && starts_cell(keys, p, B)) ++c;
+    for (int r = 0; r < kSegBlock / 256; ++r) kp[r] = load_pair(keys, p0 + r * 256 + threadIdx.x, m);
+#pragma unroll
+    for (int r = 0; r < kSegBlock / 256; ++r)
+      if (starts_cell(kp[r], p0 + r * 256 + threadIdx.x, m, B)) ++c;
   }
 #pragma unroll
   for (int d = 32; d >= 1; d >>= 1) c += __shfl_xor(c, d, 64);
@@ -125,11 +135,13 @@ __global__ __launch_bounds__(256) void k_seg_starts(const uint64_t* __restrict__
   const int lane = threadIdx.x & 63, w = threadIdx.x >> 6;
   // thread t owns positions p0 + 4t .. p0 + 4t + 3, so that cell starts are numbered in sorted order
   bool head[4];
+  KeyPair kp[4];
   uint32_t mine = 0;
 #pragma unroll
+  for (int r = 0; r < 4; ++r) kp[r] = m > 0 ? load_pair(keys, p0 + 4 * threadIdx.x + r, m) : KeyPair{0, 0};
+#pragma unroll
   for (int r = 0; r < 4; ++r) {
-    const int64_t p = p0 + 4 * threadIdx.x + r;
-    head[r] = p < m && starts_cell(keys, p, B);
+    head[r] = starts_cell(kp[r], p0 + 4 * threadIdx.x + r, m, B);
     mine += head[r] ? 1u : 0u;
   }
   uint32_t inc = mine;
@@ -146,10 +158,10 @@ __global__ __launch_bounds__(256) void k_seg_starts(const uint64_t* __restrict__
   for (int r = 0; r < 4; ++r) {
     const int64_t p = p0 + 4 * threadIdx.x + r;
     if (p >= m) continue;
-    const uint64_t k = keys[p];
+    const uint64_t k = kp[r].k;
     if ((int)(k >> 48) >= B) {  // dropped points sort behind all pillars
       if (point_to_pillar) point_to_pillar[perm[p]] = -1;
-      if (p == 0 || (int)(keys[p - 1] >> 48) < B) *kept = (int32_t)p;
+      if (p == 0 || (int)(kp[r].before >> 48) < B) *kept = (int32_t)p;
     }
     if (!head[r]) continue;
     starts[pid] = (int32_t)p;
