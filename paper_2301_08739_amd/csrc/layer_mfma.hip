@@ -288,9 +288,25 @@ __global__ __launch_bounds__(NW * 64, MINW) void k_layer_mfma(const uint16_t* __
     for (int t = 0; t < (CF + NW - 1) / NW; ++t) {
       const int f = wu + t * NW;
       if ((t + 1) * NW <= CF || f < CF) {  // wave-uniform
-        __builtin_amdgcn_global_load_lds(
-            (const __attribute__((address_space(1))) void*)(packed + ((size_t)chunk * CF + f) * 64 + lane),
-            (__attribute__((address_space(3))) void*)(ring + ((chunk % RING) * CF + f) * 64), 16, 0, 0);
+        if constexpr (LEAN) {  // at 168 registers the operands of the assembly form cost three spilled registers
+          __builtin_amdgcn_global_load_lds(
+              (const __attribute__((address_space(1))) void*)(packed + ((size_t)chunk * CF + f) * 64 + lane),
+              (__attribute__((address_space(3))) void*)(ring + ((chunk % RING) * CF + f) * 64), 16, 0, 0);
+        } else {
+          // The copy is written in assembly so that the compiler does not know of it: while it sees an
+          // LDS-writing load in flight it waits for every counter to drain at each use of an LDS value
+          // (lgkmcnt(0) after every refill of the register window, one exposed LDS latency each time).
+          // The protocol above already orders these copies against the reads of the ring (vmcnt(0) and a
+          // barrier before a chunk is read), and a vmcnt the compiler computes for its own loads only
+          // waits longer with copies in flight that it does not count.
+          const uint64_t src = reinterpret_cast<uint64_t>(packed + ((size_t)chunk * CF + f) * 64);  // wave-uniform
+          const uint32_t dst = (uint32_t)reinterpret_cast<uintptr_t>(
+              (__attribute__((address_space(3))) void*)(ring + ((chunk % RING) * CF + f) * 64));     // LDS byte address
+          asm volatile("s_mov_b32 m0, %0\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %1, %2"
+                       :
+                       : "s"(dst), "v"(lane * 16), "s"(src)
+                       : "memory", "m0");
+        }
       }
     }
   };
