@@ -490,10 +490,23 @@ __global__ __launch_bounds__(NW * 64, MINW) void k_layer_mfma(const uint16_t* __
       sc[vb] = rsqrtf(var + eps);
       sh[vb] = -mu * sc[vb];
     }
+    // the affine parameters come from LDS four feature blocks at a time, all eight reads of a batch
+    // issued before the first is used (read, wait, use per block exposed the LDS latency every time)
+    constexpr int NBG = LEAN ? 1 : 4;  // the lean mapping has no registers for a batch
+    static_assert(NB % NBG == 0, "feature blocks per parameter batch");
 #pragma unroll
-    for (int nb = 0; nb < NB; ++nb) {
-      const f32x4 gm = *reinterpret_cast<const f32x4*>(par + goff_f + 16 * nb + 4 * q);
-      const f32x4 bt = *reinterpret_cast<const f32x4*>(par + boff_f + 16 * nb + 4 * q);
+    for (int nb0 = 0; nb0 < NB; nb0 += NBG) {
+      f32x4 gmv[NBG], btv[NBG];
+#pragma unroll
+      for (int u = 0; u < NBG; ++u) {
+        gmv[u] = *reinterpret_cast<const f32x4*>(par + goff_f + 16 * (nb0 + u) + 4 * q);
+        btv[u] = *reinterpret_cast<const f32x4*>(par + boff_f + 16 * (nb0 + u) + 4 * q);
+      }
+      __builtin_amdgcn_sched_barrier(0);
+#pragma unroll
+      for (int u = 0; u < NBG; ++u) {
+      const int nb = nb0 + u;
+      const f32x4 gm = gmv[u], bt = btv[u];
 #pragma unroll
       for (int vb = 0; vb < NVB; ++vb) {
         float y[4];
@@ -511,14 +524,20 @@ __global__ __launch_bounds__(NW * 64, MINW) void k_layer_mfma(const uint16_t* __
           }
         }
       }
+      }
     }
   };
   auto add_bias_rows = [&](int off_f) {  // x1 += per-feature vector
+    constexpr int NBG = LEAN ? 1 : 8;  // reads of a batch issued together, as in layer_norm
 #pragma unroll
-    for (int nb = 0; nb < NB; ++nb) {
-      const f32x4 b = *reinterpret_cast<const f32x4*>(par + off_f + 16 * nb + 4 * q);
+    for (int nb0 = 0; nb0 < NB; nb0 += NBG) {
+      f32x4 b[NBG];
 #pragma unroll
-      for (int vb = 0; vb < NVB; ++vb) x1[vb][nb] += b;
+      for (int u = 0; u < NBG; ++u) b[u] = *reinterpret_cast<const f32x4*>(par + off_f + 16 * (nb0 + u) + 4 * q);
+#pragma unroll
+      for (int u = 0; u < NBG; ++u)
+#pragma unroll
+        for (int vb = 0; vb < NVB; ++vb) x1[vb][nb0 + u] += b[u];
     }
   };
   // Bias of the Q rows of a unit (accumulator layout).  K and V start from zero: the key bias has no
