@@ -288,10 +288,15 @@ __global__ __launch_bounds__(NW * 64, MINW) void k_layer_mfma(const uint16_t* __
     for (int t = 0; t < (CF + NW - 1) / NW; ++t) {
       const int f = wu + t * NW;
       if ((t + 1) * NW <= CF || f < CF) {  // wave-uniform
-        if constexpr (LEAN) {  // at 168 registers the operands of the assembly form cost three spilled registers
-          __builtin_amdgcn_global_load_lds(
-              (const __attribute__((address_space(1))) void*)(packed + ((size_t)chunk * CF + f) * 64 + lane),
-              (__attribute__((address_space(3))) void*)(ring + ((chunk % RING) * CF + f) * 64), 16, 0, 0);
+        if constexpr (LEAN) {  // per-lane address form of the copy below: at 168 registers the scalar operands
+                               // of the other form cost three spilled registers
+          const u32x4* srcv = packed + ((size_t)chunk * CF + f) * 64 + lane;
+          const uint32_t dst = (uint32_t)reinterpret_cast<uintptr_t>(
+              (__attribute__((address_space(3))) void*)(ring + ((chunk % RING) * CF + f) * 64));
+          asm volatile("s_mov_b32 m0, %0\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %1, off"
+                       :
+                       : "s"(dst), "v"(srcv)
+                       : "memory", "m0");
         } else {
           // The copy is written in assembly so that the compiler does not know of it: while it sees an
           // LDS-writing load in flight it waits for every counter to drain at each use of an LDS value
