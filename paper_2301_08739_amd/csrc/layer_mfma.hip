@@ -262,15 +262,32 @@ __global__ __launch_bounds__(NW * 64, MINW) void k_layer_mfma(const uint16_t* __
   // in_sorted: row p of feats is the pillar at sorted position p (the previous layer of a block wrote
   // its result in this layer's order), so the rows of a group are contiguous and need no index.
   // in_sorted == 2 (one frame): they are fetched from the guessed start without waiting for anything.
-  constexpr int NBX = NB;  // raw rows of the early fetch: 8 bytes per 16-feature block
+  // Rows are fetched whole when the wavefront has LDS to turn them around in (STAGE): lane (q, i) takes
+  // the i-th 16 bytes of row 4k + q in its k-th load, so that an instruction reads four complete rows.
+  // With 8 bytes per lane in the accumulator layout (16 rows x 32 bytes per instruction) every row was
+  // touched by eight instructions, and the burst of all wavefronts at kernel start took 2.1 us instead
+  // of 0.8 to drain.  The rows then go through the wavefront's share of the K/V exchange buffer (not in
+  // use yet), 16-byte pieces swizzled by row so that neither the writes nor the reads conflict.
+  constexpr bool STAGE = C == 128 && WPG > 1;
+  constexpr int NRL = STAGE ? 4 * NVB : 1;  // 16-byte loads per lane
+  constexpr int NBX = STAGE ? 1 : NB;       // raw rows of the early fetch without staging: 8 bytes per 16-feature block
   uint2 early[NVB][NBX];
+  u32x4 rowv[NRL];
   if (in_sorted == 2) {
+    if constexpr (STAGE) {
 #pragma unroll
-    for (int vb = 0; vb < NVB; ++vb) {
-      const int64_t at = (int64_t)g * G + (part * NVB + vb) * 16 + i;
+      for (int k = 0; k < NRL; ++k) {
+        const int64_t at = (int64_t)g * G + part * NVB * 16 + 4 * k + q;
+        rowv[k] = *reinterpret_cast<const u32x4*>(feats + (at < n ? at : n - 1) * C + 8 * i);
+      }
+    } else {
 #pragma unroll
-      for (int nb = 0; nb < NB; ++nb)
-        early[vb][nb] = *reinterpret_cast<const uint2*>(feats + (at < n ? at : n - 1) * C + 16 * nb + 4 * q);
+      for (int vb = 0; vb < NVB; ++vb) {
+        const int64_t at = (int64_t)g * G + (part * NVB + vb) * 16 + i;
+#pragma unroll
+        for (int nb = 0; nb < NB; ++nb)
+          early[vb][nb] = *reinterpret_cast<const uint2*>(feats + (at < n ? at : n - 1) * C + 16 * nb + 4 * q);
+      }
     }
   }
   FF_TS_WAIT(16);
@@ -387,14 +404,41 @@ __global__ __launch_bounds__(NW * 64, MINW) void k_layer_mfma(const uint16_t* __
     else row[vb] = s < m ? perm[start + s] : -1;
   }
   FF_TS_WAIT(17);
+  // rowv (whole rows, 16 bytes per lane) -> raw (accumulator layout) through the wavefront's LDS share
+  auto turn_rows = [&](uint2 (&raw)[NVB][NB]) {
+    u32x4* stg = reinterpret_cast<u32x4*>(kvx) + wu * (NVB * 256);  // [row][16-byte piece ^ (row & 15)]
+#pragma unroll
+    for (int k = 0; k < NRL; ++k) {
+      const int r = 4 * k + q;
+      stg[r * 16 + (i ^ (r & 15))] = rowv[k];
+    }
+    // no barrier: the pieces are this wavefront's own, and its LDS instructions execute in order
+#pragma unroll
+    for (int vb = 0; vb < NVB; ++vb)
+#pragma unroll
+      for (int nb = 0; nb < NB; ++nb) {
+        const int piece = 2 * nb + (q >> 1);
+        raw[vb][nb] = *reinterpret_cast<const uint2*>(
+            reinterpret_cast<const char*>(stg + (vb * 16 + i) * 16 + (piece ^ i)) + (q & 1) * 8);
+      }
+  };
   if (in_sorted == 2 && guessed) {  // the early fetch hit
     store_params();
+    uint2 raw[NVB][NB];
+    if constexpr (STAGE) {
+      turn_rows(raw);
+    } else {
+#pragma unroll
+      for (int vb = 0; vb < NVB; ++vb)
+#pragma unroll
+        for (int nb = 0; nb < NB; ++nb) raw[vb][nb] = early[vb][nb];
+    }
 #pragma unroll
     for (int vb = 0; vb < NVB; ++vb) {
       const bool live = (part * NVB + vb) * 16 + i < m;
 #pragma unroll
       for (int nb = 0; nb < NB; ++nb) {
-        const uint2 u = early[vb][nb];
+        const uint2 u = raw[vb][nb];
         x1[vb][nb] = live ? f32x4{el_lo(u.x), el_hi(u.x), el_lo(u.y), el_hi(u.y)} : f32x4{0.f, 0.f, 0.f, 0.f};
       }
     }
@@ -402,15 +446,28 @@ __global__ __launch_bounds__(NW * 64, MINW) void k_layer_mfma(const uint16_t* __
     // every lane loads (padding slots read a valid row and drop it): loads under a condition of their
     // own are waited for one by one
     uint2 raw[NVB][NB];
+    int32_t srcv[NVB];  // row of feats for my pillar of block vb
 #pragma unroll
     for (int vb = 0; vb < NVB; ++vb) {
       const int s = (part * NVB + vb) * 16 + i;
-      int64_t src = in_sorted ? (int64_t)start + s : (int64_t)row[vb];
-      src = row[vb] >= 0 ? src : 0;
-#pragma unroll
-      for (int nb = 0; nb < NB; ++nb) raw[vb][nb] = *reinterpret_cast<const uint2*>(feats + src * C + 16 * nb + 4 * q);
+      srcv[vb] = row[vb] >= 0 ? (in_sorted ? start + s : row[vb]) : 0;
     }
-    store_params();
+    if constexpr (STAGE) {
+#pragma unroll
+      for (int k = 0; k < NRL; ++k) {  // row 4k + q of the wavefront: its index is held by lane 4 (k % 4) + q
+        const int32_t sr = __shfl(srcv[k / 4], 4 * (k % 4) + q, 64);
+        rowv[k] = *reinterpret_cast<const u32x4*>(feats + (int64_t)sr * C + 8 * i);
+      }
+      store_params();
+      turn_rows(raw);
+    } else {
+#pragma unroll
+      for (int vb = 0; vb < NVB; ++vb)
+#pragma unroll
+        for (int nb = 0; nb < NB; ++nb)
+          raw[vb][nb] = *reinterpret_cast<const uint2*>(feats + (int64_t)srcv[vb] * C + 16 * nb + 4 * q);
+      store_params();
+    }
 #pragma unroll
     for (int vb = 0; vb < NVB; ++vb)
 #pragma unroll
