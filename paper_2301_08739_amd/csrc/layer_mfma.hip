@@ -911,18 +911,39 @@ __global__ __launch_bounds__(NW * 64, MINW) void k_layer_mfma(const uint16_t* __
   FF_TS(14);
 
   // ---- scatter -------------------------------------------------------------------------------------
+  if constexpr (STAGE && !OUT_F32) {
+    // The way the rows came in: through the wavefront's LDS share (free again since the attention
+    // ended), so that a store instruction writes four complete rows instead of 32 bytes of sixteen.
+    u32x4* stg = reinterpret_cast<u32x4*>(kvx) + wu * (NVB * 256);
 #pragma unroll
-  for (int vb = 0; vb < NVB; ++vb) {
-    if (row[vb] < 0) continue;
+    for (int vb = 0; vb < NVB; ++vb)
 #pragma unroll
-    for (int nb = 0; nb < NB; ++nb) {
-      const size_t o = (size_t)orow[vb] * C + 16 * nb + 4 * q;
-      if (OUT_F32) {
-        *reinterpret_cast<float4*>(reinterpret_cast<float*>(out) + o) =
-            make_float4(x1[vb][nb][0], x1[vb][nb][1], x1[vb][nb][2], x1[vb][nb][3]);
-      } else {
-        *reinterpret_cast<uint2*>(reinterpret_cast<uint16_t*>(out) + o) =
+      for (int nb = 0; nb < NB; ++nb) {
+        const int piece = 2 * nb + (q >> 1);
+        *reinterpret_cast<uint2*>(reinterpret_cast<char*>(stg + (vb * 16 + i) * 16 + (piece ^ i)) + (q & 1) * 8) =
             make_uint2(pack2(x1[vb][nb][0], x1[vb][nb][1]), pack2(x1[vb][nb][2], x1[vb][nb][3]));
+      }
+#pragma unroll
+    for (int k = 0; k < NRL; ++k) {
+      const int r = 4 * k + q;
+      const int32_t orw = __shfl(orow[k / 4], 4 * (k % 4) + q, 64);  // output row of row r: held by lane r % 16
+      const u32x4 v = stg[r * 16 + (i ^ (r & 15))];
+      if (orw >= 0) *reinterpret_cast<u32x4*>(reinterpret_cast<uint16_t*>(out) + (size_t)orw * C + 8 * i) = v;
+    }
+  } else {
+#pragma unroll
+    for (int vb = 0; vb < NVB; ++vb) {
+      if (row[vb] < 0) continue;
+#pragma unroll
+      for (int nb = 0; nb < NB; ++nb) {
+        const size_t o = (size_t)orow[vb] * C + 16 * nb + 4 * q;
+        if (OUT_F32) {
+          *reinterpret_cast<float4*>(reinterpret_cast<float*>(out) + o) =
+              make_float4(x1[vb][nb][0], x1[vb][nb][1], x1[vb][nb][2], x1[vb][nb][3]);
+        } else {
+          *reinterpret_cast<uint2*>(reinterpret_cast<uint16_t*>(out) + o) =
+              make_uint2(pack2(x1[vb][nb][0], x1[vb][nb][1]), pack2(x1[vb][nb][2], x1[vb][nb][3]));
+        }
       }
     }
   }
