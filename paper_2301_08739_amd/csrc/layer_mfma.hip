@@ -268,8 +268,13 @@ __global__ __launch_bounds__(NW * 64, MINW) void k_layer_mfma(const uint16_t* __
   // touched by eight instructions, and the burst of all wavefronts at kernel start took 2.1 us instead
   // of 0.8 to drain.  The rows then go through the wavefront's share of the K/V exchange buffer (not in
   // use yet), 16-byte pieces swizzled by row so that neither the writes nor the reads conflict.
-  constexpr bool STAGE = C == 128 && WPG > 1;
-  constexpr int NRL = STAGE ? 4 * NVB : 1;  // 16-byte loads per lane
+  // C = 256: a row is 32 pieces, a load instruction reads two rows, and the 4 KB share turns the rows
+  // around in two phases of sixteen pieces each (a lane's piece belongs to phase `ph`).
+  constexpr bool STAGE = (C == 128 || C == 256) && WPG > 1 && !(LEAN && OUT_F32);  // (the lean mapping with fp32
+                                                                                    // output has no registers for it)
+  constexpr int LPR = C / 8, RPI = 64 / LPR, PH = C / 128;  // lanes per row, rows per instruction, phases
+  constexpr int NRL = STAGE ? 16 * NVB / RPI : 1;            // 16-byte loads per lane
+  const int lr = lane / LPR, piece32 = lane % LPR, ph = piece32 >> 4;  // my row within an instruction, my piece
   constexpr int NBX = STAGE ? 1 : NB;       // raw rows of the early fetch without staging: 8 bytes per 16-feature block
   uint2 early[NVB][NBX];
   u32x4 rowv[NRL];
@@ -277,8 +282,8 @@ __global__ __launch_bounds__(NW * 64, MINW) void k_layer_mfma(const uint16_t* __
     if constexpr (STAGE) {
 #pragma unroll
       for (int k = 0; k < NRL; ++k) {
-        const int64_t at = (int64_t)g * G + part * NVB * 16 + 4 * k + q;
-        rowv[k] = *reinterpret_cast<const u32x4*>(feats + (at < n ? at : n - 1) * C + 8 * i);
+        const int64_t at = (int64_t)g * G + part * NVB * 16 + RPI * k + lr;
+        rowv[k] = *reinterpret_cast<const u32x4*>(feats + (at < n ? at : n - 1) * C + 8 * piece32);
       }
     } else {
 #pragma unroll
@@ -408,19 +413,25 @@ __global__ __launch_bounds__(NW * 64, MINW) void k_layer_mfma(const uint16_t* __
   auto turn_rows = [&](uint2 (&raw)[NVB][NB]) {
     u32x4* stg = reinterpret_cast<u32x4*>(kvx) + wu * (NVB * 256);  // [row][16-byte piece ^ (row & 15)]
 #pragma unroll
-    for (int k = 0; k < NRL; ++k) {
-      const int r = 4 * k + q;
-      stg[r * 16 + (i ^ (r & 15))] = rowv[k];
-    }
-    // no barrier: the pieces are this wavefront's own, and its LDS instructions execute in order
+    for (int p = 0; p < PH; ++p) {
 #pragma unroll
-    for (int vb = 0; vb < NVB; ++vb)
-#pragma unroll
-      for (int nb = 0; nb < NB; ++nb) {
-        const int piece = 2 * nb + (q >> 1);
-        raw[vb][nb] = *reinterpret_cast<const uint2*>(
-            reinterpret_cast<const char*>(stg + (vb * 16 + i) * 16 + (piece ^ i)) + (q & 1) * 8);
+      for (int k = 0; k < NRL; ++k) {
+        const int r = RPI * k + lr;
+        if (PH == 1 || ph == p) stg[r * 16 + (i ^ (r & 15))] = rowv[k];
       }
+      // No barrier: the pieces are this wavefront's own, and its LDS instructions execute in order.  The
+      // compiler must keep that order too (it sees stores and loads of different types).
+      asm volatile("" ::: "memory");
+#pragma unroll
+      for (int vb = 0; vb < NVB; ++vb)
+#pragma unroll
+        for (int nb = 8 * p; nb < 8 * p + 8; ++nb) {
+          const int piece = 2 * (nb - 8 * p) + (q >> 1);
+          raw[vb][nb] = *reinterpret_cast<const uint2*>(
+              reinterpret_cast<const char*>(stg + (vb * 16 + i) * 16 + (piece ^ i)) + (q & 1) * 8);
+        }
+      asm volatile("" ::: "memory");
+    }
   };
   if (in_sorted == 2 && guessed) {  // the early fetch hit
     store_params();
@@ -454,9 +465,9 @@ __global__ __launch_bounds__(NW * 64, MINW) void k_layer_mfma(const uint16_t* __
     }
     if constexpr (STAGE) {
 #pragma unroll
-      for (int k = 0; k < NRL; ++k) {  // row 4k + q of the wavefront: its index is held by lane 4 (k % 4) + q
-        const int32_t sr = __shfl(srcv[k / 4], 4 * (k % 4) + q, 64);
-        rowv[k] = *reinterpret_cast<const u32x4*>(feats + (int64_t)sr * C + 8 * i);
+      for (int k = 0; k < NRL; ++k) {  // row RPI k + lr of the wavefront: its index is held by the lane of that number
+        const int32_t sr = __shfl(srcv[RPI * k / 16], (RPI * k) % 16 + lr, 64);
+        rowv[k] = *reinterpret_cast<const u32x4*>(feats + (int64_t)sr * C + 8 * piece32);
       }
       store_params();
       turn_rows(raw);
@@ -916,19 +927,26 @@ __global__ __launch_bounds__(NW * 64, MINW) void k_layer_mfma(const uint16_t* __
     // ended), so that a store instruction writes four complete rows instead of 32 bytes of sixteen.
     u32x4* stg = reinterpret_cast<u32x4*>(kvx) + wu * (NVB * 256);
 #pragma unroll
-    for (int vb = 0; vb < NVB; ++vb)
+    for (int p = 0; p < PH; ++p) {
 #pragma unroll
-      for (int nb = 0; nb < NB; ++nb) {
-        const int piece = 2 * nb + (q >> 1);
-        *reinterpret_cast<uint2*>(reinterpret_cast<char*>(stg + (vb * 16 + i) * 16 + (piece ^ i)) + (q & 1) * 8) =
-            make_uint2(pack2(x1[vb][nb][0], x1[vb][nb][1]), pack2(x1[vb][nb][2], x1[vb][nb][3]));
+      for (int vb = 0; vb < NVB; ++vb)
+#pragma unroll
+        for (int nb = 8 * p; nb < 8 * p + 8; ++nb) {
+          const int piece = 2 * (nb - 8 * p) + (q >> 1);
+          *reinterpret_cast<uint2*>(reinterpret_cast<char*>(stg + (vb * 16 + i) * 16 + (piece ^ i)) + (q & 1) * 8) =
+              make_uint2(pack2(x1[vb][nb][0], x1[vb][nb][1]), pack2(x1[vb][nb][2], x1[vb][nb][3]));
+        }
+      asm volatile("" ::: "memory");  // keeps the order of the LDS stores above and the loads below
+#pragma unroll
+      for (int k = 0; k < NRL; ++k) {
+        const int r = RPI * k + lr;
+        const int32_t orw = __shfl(orow[RPI * k / 16], (RPI * k) % 16 + lr, 64);  // output row of row r
+        if (PH == 1 || ph == p) {
+          const u32x4 v = stg[r * 16 + (i ^ (r & 15))];
+          if (orw >= 0) *reinterpret_cast<u32x4*>(reinterpret_cast<uint16_t*>(out) + (size_t)orw * C + 8 * piece32) = v;
+        }
       }
-#pragma unroll
-    for (int k = 0; k < NRL; ++k) {
-      const int r = 4 * k + q;
-      const int32_t orw = __shfl(orow[k / 4], 4 * (k % 4) + q, 64);  // output row of row r: held by lane r % 16
-      const u32x4 v = stg[r * 16 + (i ^ (r & 15))];
-      if (orw >= 0) *reinterpret_cast<u32x4*>(reinterpret_cast<uint16_t*>(out) + (size_t)orw * C + 8 * i) = v;
+      asm volatile("" ::: "memory");
     }
   } else {
 #pragma unroll
