@@ -179,6 +179,7 @@ __global__ __launch_bounds__(256) void k_seg_mean(const int32_t* __restrict__ pe
                                                    const int32_t* __restrict__ starts, const int32_t* __restrict__ kept,
                                                    float* __restrict__ feats, int32_t* __restrict__ point_to_pillar) {
   const int np = *num_pillars, sub = threadIdx.x & 15;
+  const bool vec4 = Cp % 4 == 0 && (reinterpret_cast<uintptr_t>(pfeats) & 15) == 0;
   const int64_t stride = (int64_t)gridDim.x * (blockDim.x / 16);
   for (int64_t pid = (int64_t)blockIdx.x * (blockDim.x / 16) + (threadIdx.x >> 4); pid < np; pid += stride) {
     const int lo = starts[pid], hi = pid + 1 < np ? starts[pid + 1] : *kept;
@@ -194,11 +195,20 @@ __global__ __launch_bounds__(256) void k_seg_mean(const int32_t* __restrict__ pe
 #pragma unroll
         for (int u = 0; u < kPointsInFlight; ++u) src[u] = q + 16 * u < hi ? perm[q + 16 * u] : -1;
         float v[kPointsInFlight][4];
+        if (vec4) {  // four features of a point in one 16-byte load (the same for every thread)
 #pragma unroll
-        for (int u = 0; u < kPointsInFlight; ++u)
+          for (int u = 0; u < kPointsInFlight; ++u) {
+            const float4 t = *reinterpret_cast<const float4*>(pfeats + (int64_t)(src[u] >= 0 ? src[u] : 0) * Cp + c0);
+            v[u][0] = src[u] >= 0 ? t.x : 0.f; v[u][1] = src[u] >= 0 ? t.y : 0.f;
+            v[u][2] = src[u] >= 0 ? t.z : 0.f; v[u][3] = src[u] >= 0 ? t.w : 0.f;
+          }
+        } else {
 #pragma unroll
-          for (int j = 0; j < 4; ++j)
-            v[u][j] = src[u] >= 0 && c0 + j < Cp ? pfeats[(int64_t)src[u] * Cp + c0 + j] : 0.f;
+          for (int u = 0; u < kPointsInFlight; ++u)
+#pragma unroll
+            for (int j = 0; j < 4; ++j)
+              v[u][j] = src[u] >= 0 && c0 + j < Cp ? pfeats[(int64_t)src[u] * Cp + c0 + j] : 0.f;
+        }
 #pragma unroll
         for (int u = 0; u < kPointsInFlight; ++u)
 #pragma unroll
