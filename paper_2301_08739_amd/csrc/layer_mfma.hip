@@ -491,13 +491,31 @@ __global__ __launch_bounds__(NW * 64, MINW) void k_layer_mfma(const uint16_t* __
   // of the attention): it is added to the LayerNorm output on the way to the query and key products.
   Frag8 pef[PE ? NVB : 1][PE ? KB : 1];
   if constexpr (PE) {
+    uint2 praw[NVB][NB];
+    if constexpr (STAGE && C == 128 && MINW <= 2) {  // whole rows through the LDS turn-around, like the features
+                                                      // (where the registers allow it)
+      int32_t prow[NVB];
+#pragma unroll
+      for (int vb = 0; vb < NVB; ++vb) prow[vb] = row[vb] >= 0 ? row[vb] : 0;
+#pragma unroll
+      for (int k = 0; k < NRL; ++k) {
+        const int32_t sr = __shfl(prow[RPI * k / 16], (RPI * k) % 16 + lr, 64);
+        rowv[k] = *reinterpret_cast<const u32x4*>(pos_embed + (int64_t)sr * C + 8 * piece32);
+      }
+      turn_rows(praw);
+    } else {
+#pragma unroll
+      for (int vb = 0; vb < NVB; ++vb)
+#pragma unroll
+        for (int nb = 0; nb < NB; ++nb)
+          praw[vb][nb] = *reinterpret_cast<const uint2*>(pos_embed + (int64_t)(row[vb] >= 0 ? row[vb] : 0) * C + 16 * nb + 4 * q);
+    }
 #pragma unroll
     for (int vb = 0; vb < NVB; ++vb)
 #pragma unroll
       for (int nb = 0; nb < NB; ++nb) {
-        const uint2 u = *reinterpret_cast<const uint2*>(pos_embed + (int64_t)(row[vb] >= 0 ? row[vb] : 0) * C + 16 * nb + 4 * q);
-        pef[vb][nb / 2].u[(nb & 1) * 2 + 0] = row[vb] >= 0 ? u.x : 0u;
-        pef[vb][nb / 2].u[(nb & 1) * 2 + 1] = row[vb] >= 0 ? u.y : 0u;
+        pef[vb][nb / 2].u[(nb & 1) * 2 + 0] = row[vb] >= 0 ? praw[vb][nb].x : 0u;
+        pef[vb][nb / 2].u[(nb & 1) * 2 + 1] = row[vb] >= 0 ? praw[vb][nb].y : 0u;
       }
   }
   FF_TS(1);
