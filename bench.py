@@ -23,7 +23,7 @@ PEAK_F32_TFLOPS = 157.3        # fp32 vector / MFMA
 
 # HBM bytes per launch of the fused layer kernel, from rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE scaled by
 # a plain copy of known size (profiles/fwa_layer_cfg2_hbm_counters.txt): config id -> bytes.
-MEASURED_LAYER_TRAFFIC = {2: 18506444}
+MEASURED_LAYER_TRAFFIC = {2: 18385323}
 
 
 def layer_flops_per_voxel(C, F, G):
@@ -162,8 +162,25 @@ def main():
     ms_flat, _ = time_region(lambda: ff.ff_flatten(coords, geom, 0, 1, G, tail=tail, workspace=fws), reps, 5)
     lpk = ff.LayerWeights(c["layer_params"][0], dt, dev).pack()       # exactly one kernel in the timed region
     vflag = ff.FF_FLAG_VARIANT(a.variant) | (ff.FF_FLAG_TAIL_DROP if a.tail == "drop" else 0)
-    ms_layer, _ = time_region(lambda: ff.ff_group_attention(feats, perm, goff, ng, max_groups, lpk, G, dt, vflag,
-                                                            out=out, workspace=lws, pos_embed=pe), reps, 5)
+    # The layer kernel as the method runs it: every launch reads the rows the launch before it wrote, grouped
+    # by the next sort of the schedule (x, y, shifted x, shifted y), so its input comes from what other
+    # XCDs wrote.  (The same launch repeated on a buffer nothing writes finds its rows in the local L2 and
+    # is about 2 us faster: reported as ms_warm_input, not used for the roofline.)
+    sorts4 = [ff.ff_flatten(coords, geom, k % 2, (k // 2) % 2, G, tail=tail)[:3] for k in range(4)]
+    torch.cuda.synchronize()
+    ping = [torch.empty_like(feats), torch.empty_like(feats)]
+    ping[1].copy_(feats)
+
+    def layer_chain():
+        for k in range(4):
+            p_, g_, n_ = sorts4[k]
+            ff.ff_group_attention(ping[(k + 1) & 1], p_, g_, n_, max_groups, lpk, G, dt, vflag, out=ping[k & 1],
+                                  workspace=lws, pos_embed=pe)
+
+    ms_chain, _ = time_region(layer_chain, max(reps // 4, 5), 2)
+    ms_layer = ms_chain / 4
+    ms_layer_warm, _ = time_region(lambda: ff.ff_group_attention(feats, perm, goff, ng, max_groups, lpk, G, dt, vflag,
+                                                                 out=out, workspace=lws, pos_embed=pe), reps, 5)
     ms_gather, _ = time_region(lambda: ff.ff_gather(feats, perm, dt, out=gth), reps, 5)
     ms_scatter, _ = time_region(lambda: ff.ff_scatter(gth, perm, dt, out=out), reps, 5)
 
@@ -214,10 +231,11 @@ def main():
                                f"{len(dict.fromkeys(c['schedule']))} sorts + {L} layers per step"
                                + (", short groups dropped" if a.tail == "drop" else "")
                                + (", with positional embedding" if a.pos_embed else "")},
-        "roofline": {"bound": "mfma", "kernel": "group attention layer (ff_group_attention, one launch)",
+        "roofline": {"bound": "mfma", "kernel": "group attention layer (ff_group_attention, one launch; mean over launches chained through the four sorts)",
                      "achieved": ach_tf, "peak": peak_tf, "unit": "TFLOP/s", "frac": ach_tf / peak_tf,
                      "traffic": MEASURED_LAYER_TRAFFIC.get(a.config) if a.variant == 0 and a.tail == "mask" and not a.pos_embed and not a.f16 else None,
-                     "algorithmic_bytes": bytes_rows, "ms": ms_layer, "flops": flops_layer},
+                     "algorithmic_bytes": bytes_rows, "ms": ms_layer, "ms_warm_input": ms_layer_warm,
+                     "flops": flops_layer},
         "parts": {
             "flatten": {"ms": ms_flat, "bytes": bytes_flat, "GBps": bytes_flat / (ms_flat * 1e-3) / 1e9,
                         "frac_hbm": bytes_flat / (ms_flat * 1e-3) / 1e9 / PEAK_HBM_GBS, "radix_passes_credited": passes},
