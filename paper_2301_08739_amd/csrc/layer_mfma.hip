@@ -283,7 +283,8 @@ __global__ __launch_bounds__(NW * 64, MINW) void k_layer_mfma(const uint16_t* __
 #pragma unroll
       for (int k = 0; k < NRL; ++k) {
         const int64_t at = (int64_t)g * G + part * NVB * 16 + RPI * k + lr;
-        rowv[k] = *reinterpret_cast<const u32x4*>(feats + (at < n ? at : n - 1) * C + 8 * piece32);
+        // (non-temporal: a row is read once per layer, and what arrives was written by another XCD)
+        rowv[k] = __builtin_nontemporal_load(reinterpret_cast<const u32x4*>(feats + (at < n ? at : n - 1) * C + 8 * piece32));
       }
     } else {
 #pragma unroll
@@ -467,7 +468,7 @@ __global__ __launch_bounds__(NW * 64, MINW) void k_layer_mfma(const uint16_t* __
 #pragma unroll
       for (int k = 0; k < NRL; ++k) {  // row RPI k + lr of the wavefront: its index is held by the lane of that number
         const int32_t sr = __shfl(srcv[RPI * k / 16], (RPI * k) % 16 + lr, 64);
-        rowv[k] = *reinterpret_cast<const u32x4*>(feats + (int64_t)sr * C + 8 * piece32);
+        rowv[k] = __builtin_nontemporal_load(reinterpret_cast<const u32x4*>(feats + (int64_t)sr * C + 8 * piece32));
       }
       store_params();
       turn_rows(raw);
@@ -961,7 +962,8 @@ __global__ __launch_bounds__(NW * 64, MINW) void k_layer_mfma(const uint16_t* __
         const int32_t orw = __shfl(orow[RPI * k / 16], (RPI * k) % 16 + lr, 64);  // output row of row r
         if (PH == 1 || ph == p) {
           const u32x4 v = stg[r * 16 + (i ^ (r & 15))];
-          if (orw >= 0) *reinterpret_cast<u32x4*>(reinterpret_cast<uint16_t*>(out) + (size_t)orw * C + 8 * piece32) = v;
+          if (orw >= 0)  // non-temporal: the next reader is another XCD, and the kernel's end has less to write back
+            __builtin_nontemporal_store(v, reinterpret_cast<u32x4*>(reinterpret_cast<uint16_t*>(out) + (size_t)orw * C + 8 * piece32));
         }
       }
       asm volatile("" ::: "memory");
