@@ -68,9 +68,25 @@ __device__ __forceinline__ void pack_weights_block(const PackBatch& pb, int laye
     const int u = t - total_frags * 64, o = u >> 3, seg = u & 7, len = C / 8;
     float acc = 0.f;
     if (o < C) {
+      // the lane's C/8 products, sixteen bytes of each operand per load and all loads before the first
+      // product (C is a multiple of 64 here): these few workgroups end the launch they ride on
       const uint16_t* __restrict__ bv = pb.b_qkv[layer] + 2 * C;
-      for (int k = seg * len; k < (seg + 1) * len; ++k)
-        acc = fmaf(pack_el_to_f32<HALF>(w_o[(size_t)o * C + k]), pack_el_to_f32<HALF>(bv[k]), acc);
+      const uint4* wv = reinterpret_cast<const uint4*>(w_o + (size_t)o * C + seg * len);
+      const uint4* bvv = reinterpret_cast<const uint4*>(bv + seg * len);
+      uint4 wq[4], bq[4];
+#pragma unroll
+      for (int v = 0; v < 4; ++v)
+        if (v * 8 < len) { wq[v] = wv[v]; bq[v] = bvv[v]; }
+#pragma unroll
+      for (int v = 0; v < 4; ++v)
+        if (v * 8 < len) {
+          const uint32_t wu[4] = {wq[v].x, wq[v].y, wq[v].z, wq[v].w}, bu[4] = {bq[v].x, bq[v].y, bq[v].z, bq[v].w};
+#pragma unroll
+          for (int e = 0; e < 4; ++e) {  // ascending k, as before
+            acc = fmaf(pack_el_to_f32<HALF>((uint16_t)(wu[e] & 0xffffu)), pack_el_to_f32<HALF>((uint16_t)(bu[e] & 0xffffu)), acc);
+            acc = fmaf(pack_el_to_f32<HALF>((uint16_t)(wu[e] >> 16)), pack_el_to_f32<HALF>((uint16_t)(bu[e] >> 16)), acc);
+          }
+        }
     }
     acc += __shfl_xor(acc, 1);
     acc += __shfl_xor(acc, 2);
