@@ -184,6 +184,7 @@ struct ParamOff {  // float offsets inside the small-parameter area
 
 constexpr int kChunkFrags = 16;        // fragments per staged chunk (16 KB)
 constexpr int kLdsBytes = 160 * 1024;  // LDS of one compute unit
+constexpr int kComputeUnits = 256;      // of an MI355X
 constexpr int kWindow = 8;             // weight fragments a wavefront keeps in flight (LDS -> registers)
 
 template <int C, int F, int NVB, int WPG, int NW, int MINW>
@@ -1099,7 +1100,15 @@ int FF_LAYER_SYM(layer_mfma_launch)(const void* feats, void* out, int64_t n, con
   if (shape == 1) {
     // many groups: three groups per workgroup (three waves per SIMD) hide more latency than the unrolled
     // two-group mapping gains from constant folding
-    if (variant == 0) variant = G <= 32 ? 10 : G <= 64 ? (max_groups >= 1500 ? 11 : 7) : 9;
+    if (variant == 0) {
+      // G <= 64: two groups per workgroup (8 wavefronts, one workgroup per compute unit, about 16.8 us a
+      // round at this shape) or three (12 wavefronts, 22.8 us a round).  Three win by a tenth once there
+      // are many rounds; below that the number of rounds decides (measured: 937 groups 34 vs 46 us,
+      // 1406 groups 49 vs 48, 1875 groups 68 vs 71, 2343 groups 79 vs 89, 2812 groups 94 vs 90).
+      const int64_t rounds2 = ceil_div(ceil_div((int64_t)max_groups, 2), kComputeUnits);
+      const int64_t rounds3 = ceil_div(ceil_div((int64_t)max_groups, 3), kComputeUnits);
+      variant = G <= 32 ? 10 : G <= 64 ? (rounds3 * 228 < rounds2 * 168 ? 11 : 7) : 9;
+    }
     switch (variant) {
       case 1: if (G <= 32) FF_GO(128, 16, 256, 2, 1, 4, 2); break;
       case 2: if (G <= 64) FF_GO(128, 16, 256, 2, 2, 4, 1); break;  // 512 registers
