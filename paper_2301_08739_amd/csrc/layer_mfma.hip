@@ -347,10 +347,13 @@ __global__ __launch_bounds__(NW * 64, MINW) void k_layer_mfma(const uint16_t* __
     const int lim = consumed + RING < NCHUNK ? consumed + RING : NCHUNK;
     while (issued < lim) { issue(issued); ++issued; }
   };
-  // Before the first read of chunk cn.  voluntary: also stop when free slots could be refilled.
+  // Before the first read of chunk cn.  voluntary: also stop when free slots could be refilled: two of
+  // them, or all that is left of the stream (a barrier for a single slot is one barrier more in the
+  // FFN, where nothing else needs one).
   auto boundary = [&](int cn, int consumed, bool voluntary) {
     if (cn >= NCHUNK) return;
-    if (voluntary && issued < NCHUNK && issued < consumed + RING) sync(consumed);
+    const int lim = consumed + RING < NCHUNK ? consumed + RING : NCHUNK;
+    if (voluntary && lim > issued && (lim - issued >= 2 || lim == NCHUNK)) sync(consumed);
     while (cn >= visible) sync(consumed);
   };
   // An LDS read reaches 64 KB beyond its base register through the immediate offset; the ring can be
