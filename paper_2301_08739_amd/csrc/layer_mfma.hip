@@ -687,11 +687,14 @@ __global__ __launch_bounds__(NW * 64, MINW) void k_layer_mfma(const uint16_t* __
           if (WPG > 1 && ch >= 2) kv[(((ch >= 4 ? 1 : 0) * 2 + a) * NKB + part * NVB + vb) * 64] = dst.d;
         }
       };
+      // Stream order (kQkvOrder): K and V first, so that their way to LDS overlaps the Q products
+      // instead of standing between the last product and the barrier.
 #pragma unroll
-      for (int ch = 0; ch < 6; ++ch) {
+      for (int p = 0; p < 6; ++p) {
+        const int ch = kQkvOrder[p];
 #pragma unroll
         for (int kb = 0; kb < KB; ++kb) {
-          const int j = ch * KB + kb;
+          const int j = p * KB + kb;
           const Frag8 wf = win[j % PF];
           if (kb == 0) {  // the accumulator starts from the bias
 #pragma unroll
@@ -702,11 +705,11 @@ __global__ __launch_bounds__(NW * 64, MINW) void k_layer_mfma(const uint16_t* __
           for (int vb = 0; vb < NVB; ++vb)
             acc[ch & 1][vb] = ch < 4 ? mfma32(wf, PE ? actqk[PE ? vb : 0][PE ? kb : 0] : act[vb][kb], acc[ch & 1][vb])
                                      : mfma32(act[vb][kb], wf, acc[ch & 1][vb]);
-          if (kb == 0 && ch > 0) finish(ch - 1);
+          if (kb == 0 && p > 0) finish(kQkvOrder[p - 1]);
           refill(j);
         }
       }
-      finish(5);
+      finish(kQkvOrder[5]);
     }
     if (hp == 0) FF_TS(4);
     if (WPG > 1) sync(c0 + (6 * KB) / CF);  // K/V of the group are in LDS

@@ -7,10 +7,12 @@
 
 namespace ff {
 
-// Stream order: for each 32-wide head-dim unit hp: Q rows (2 x KB fragments), K rows, V rows,
+// Stream order: for each 32-wide head-dim unit hp: K rows (2 x KB fragments), V rows, Q rows,
 // W_o column slice (NB fragments); then for each 32-wide hidden unit fc: W1 rows (2 x KB), W2
 // column slice (NB).  A fragment is 16 output features x 32 inputs; lane (i, q) owns 16 bytes:
 // row i, inputs kbase + 16*(s/4) + 4q + (s%4) for slot s = 0..7.
+// The six row blocks of a unit (Q a=0,1; K a=0,1; V a=0,1 numbered 0..5) come in this order:
+__device__ constexpr int kQkvOrder[6] = {2, 3, 4, 5, 0, 1};
 constexpr int kPackBatch = 16;
 struct PackBatch {  // up to 16 layers of identical shape packed by one launch
   const uint16_t *w_qkv[kPackBatch], *w_o[kPackBatch], *w1[kPackBatch], *w2[kPackBatch];
@@ -102,7 +104,7 @@ __device__ __forceinline__ void pack_weights_block(const PackBatch& pb, int laye
   if (frag < n_hp * fr_hp) {
     const int hp = frag / fr_hp, r = frag % fr_hp;
     if (r < 6 * KB) {
-      const int which = r / (2 * KB), rr = r % (2 * KB), a = rr / KB, kb = rr % KB;
+      const int lc = kQkvOrder[r / KB], which = lc / 2, a = lc % 2, kb = r % KB;
       src = w_qkv + (size_t)(which * C + 32 * hp + 16 * a + i) * C;
       kbase = 32 * kb;
     } else {
