@@ -23,7 +23,7 @@ PEAK_F32_TFLOPS = 157.3        # fp32 vector / MFMA
 
 # HBM bytes per launch of the fused layer kernel, from rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE scaled by
 # a plain copy of known size (profiles/fwa_layer_cfg2_hbm_counters.txt): config id -> bytes.
-MEASURED_LAYER_TRAFFIC = {2: 18385284}
+MEASURED_LAYER_TRAFFIC = {2: 18374656}
 
 
 def layer_flops_per_voxel(C, F, G):
