@@ -38,7 +38,7 @@ int ff_flatten(const int32_t* coords, int64_t n, const ff_geom* g, int axis, int
 }
 
 namespace {
-int split_geom3(const ff_geom3* g, ff_geom* g2, FlattenZ* z) {
+static int split_geom3(const ff_geom3* g, ff_geom* g2, FlattenZ* z) {
   if (!g) return FF_ERR_ARG;
   g2->num_frames = g->num_frames; g2->grid_x = g->grid_x; g2->grid_y = g->grid_y;
   g2->win_x = g->win_x; g2->win_y = g->win_y;
@@ -200,7 +200,7 @@ struct BlockPlan {
   size_t flat_bytes, layer_bytes, packed_stride;  // packed_stride == 0: nothing to pre-pack
 };
 
-int make_block_plan(int64_t n, const ff_geom* g, const FlattenZ* z, int G, const ff_layer_weights* layers,
+static int make_block_plan(int64_t n, const ff_geom* g, const FlattenZ* z, int G, const ff_layer_weights* layers,
                     int num_layers, int dtype, BlockPlan* p) {
   if (n < 0 || n > 0x7fffffffLL || !g || G < 1 || num_layers < 1 || !layers) return FF_ERR_ARG;
   for (int l = 0; l < num_layers; ++l) {
@@ -245,7 +245,7 @@ int make_block_plan(int64_t n, const ff_geom* g, const FlattenZ* z, int G, const
 }  // namespace
 
 namespace {
-int fwa_block(const int32_t* coords, int64_t n, const ff_geom* g, const FlattenZ* z, int G, int tail,
+static int fwa_block(const int32_t* coords, int64_t n, const ff_geom* g, const FlattenZ* z, int G, int tail,
               const ff_layer_weights* layers, int num_layers, int dtype, const void* feats_in, void* feats_out,
               void* workspace, size_t workspace_bytes, void* stream) {
   if (tail != FF_TAIL_MASK && tail != FF_TAIL_DROP) return FF_ERR_ARG;

@@ -2,6 +2,8 @@
 import ctypes
 import os
 import re
+import shutil
+import subprocess
 
 import pytest
 
@@ -28,6 +30,12 @@ def test_library_exports_every_declared_symbol():
     for name in _declared():
         assert hasattr(lib, name), name
     assert set(_declared()) == set(ff.exported_symbols())
+    # and nothing else with C linkage leaks out of the library
+    nm = shutil.which("nm")
+    if nm:
+        out = subprocess.run([nm, "-D", "--defined-only", ff.library_path()], capture_output=True, text=True, check=True).stdout
+        c_funcs = {ln.split()[2] for ln in out.splitlines() if len(ln.split()) == 3 and ln.split()[1] == "T" and not ln.split()[2].startswith("_")}
+        assert c_funcs == set(_declared()), sorted(c_funcs ^ set(_declared()))
     ff.load_library()
     assert ff.ff_version() >= 100
     assert ff.ff_status_string(0) == "ok" and "unsupported" in ff.ff_status_string(-2)
