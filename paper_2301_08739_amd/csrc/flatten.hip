@@ -14,13 +14,13 @@
 //     holds in the order the pass reads them.  Key generation writes the rows of the first pass
 //     (plain stores) and zeroes the others; each pass adds, for every word it places, one to the
 //     row of the tile the word lands in for the next pass.  Nothing has to be cleared beforehand.
-//   * Small clouds (at most 64 tiles of 1024 words: launch and latency bound): digits of up to 10
+//   * Small clouds (at most 128 tiles of 1024 words: launch and latency bound): digits of up to 10
 //     bits, and a pass reads the whole table of its pass itself (column sums = global digit
 //     starts, rows of earlier tiles = its own offsets): key generation + one launch per pass.
-//   * Larger clouds (tiles of 4096 words, 8-bit digits: bandwidth bound): per-word atomics would
-//     dominate, so passes after the first count their tiles in a kernel of their own, and a small
-//     scan kernel turns the table of a pass into exclusive prefixes over the tiles plus per-digit
-//     totals.
+//   * Larger clouds (bandwidth bound): per-word atomics would dominate, so passes after the first
+//     count their tiles in a kernel of their own, and a small scan kernel turns the table of a pass
+//     into exclusive prefixes over the tiles plus per-digit totals.  Tiles of 1024, 2048 or 4096
+//     words by cloud size, so that clouds of a few hundred thousand words still fill the chip.
 //   * A tile ranks its words with per-wavefront ballot matching and LDS counters and scatters
 //     through an LDS stage so that global writes come out in runs.
 //   * The last pass writes perm, exported keys and group offsets itself when its digit contains
@@ -45,6 +45,12 @@ namespace {
 constexpr int kMaxSorts = 4;
 constexpr int kSmallKpt = 4, kSmallMaxTiles = 128;  // small clouds: tiles of 1024 words
 constexpr int kLargeKpt = 16;                       // larger clouds: tiles of 4096 words
+// In between, the tables are scanned by their own kernel as for larger clouds, but tiles of 4096 words
+// would leave most compute units without a workgroup.  Tiles of 1024 words up to 256 K words, of 2048
+// words up to 1.5 M (measured: 140 K words 63 -> 52 us, 400 K 68 -> 58, 1 M 73 -> 67, 1.5 M 80 -> 75;
+// from 2 M words on the large tiles are ahead).
+constexpr int kMidKptA = 4, kMidMaxTilesA = 256;
+constexpr int kMidKptB = 8, kMidMaxTilesB = 768;
 constexpr int kScanThreads = 1024;
 constexpr int kScanStrip = 64;  // digits per workgroup of the column scan (narrower strips were no faster)
 // Above 1024 tiles (4 M words) a thread of the 64-digit strip would own more rows than it keeps in
@@ -658,7 +664,9 @@ struct PassPlan { bool small; int kpt, rb, passes; int64_t tiles; };
 inline PassPlan pass_plan(int64_t n, int key_bits) {
   PassPlan pp;
   pp.small = ceil_div(n > 0 ? n : 1, (int64_t)kSortThreads * kSmallKpt) <= kSmallMaxTiles;
-  pp.kpt = pp.small ? kSmallKpt : kLargeKpt;
+  pp.kpt = pp.small ? kSmallKpt
+         : ceil_div(n, (int64_t)kSortThreads * kMidKptA) <= kMidMaxTilesA ? kMidKptA
+         : ceil_div(n, (int64_t)kSortThreads * kMidKptB) <= kMidMaxTilesB ? kMidKptB : kLargeKpt;
   pp.passes = (key_bits + 9) / 10;
   // the narrowest digit that still needs no extra pass: smaller tables, longer runs per digit
   pp.rb = 8 * pp.passes >= key_bits ? 8 : 9 * pp.passes >= key_bits ? 9 : 10;
@@ -838,7 +846,13 @@ int flatten_launch_z(const int32_t* coords, int64_t n, const ff_geom* g, const F
         cur ^= 1;                                                                                                    \
       }                                                                                                              \
     } while (0)
-    if (!pp.small && pp.rb == 8) FF_PASSES(8, kLargeKpt, true);
+    if (!pp.small && pp.kpt == kMidKptA && pp.rb == 8) FF_PASSES(8, kMidKptA, true);
+    else if (!pp.small && pp.kpt == kMidKptA && pp.rb == 9) FF_PASSES(9, kMidKptA, true);
+    else if (!pp.small && pp.kpt == kMidKptA) FF_PASSES(10, kMidKptA, true);
+    else if (pp.kpt == kMidKptB && pp.rb == 8) FF_PASSES(8, kMidKptB, true);
+    else if (pp.kpt == kMidKptB && pp.rb == 9) FF_PASSES(9, kMidKptB, true);
+    else if (pp.kpt == kMidKptB) FF_PASSES(10, kMidKptB, true);
+    else if (!pp.small && pp.rb == 8) FF_PASSES(8, kLargeKpt, true);
     else if (!pp.small && pp.rb == 9) FF_PASSES(9, kLargeKpt, true);
     else if (!pp.small) FF_PASSES(10, kLargeKpt, true);
     else if (pp.rb == 8) FF_PASSES(8, kSmallKpt, false);

@@ -110,6 +110,16 @@ def test_errors_and_determinism():
     assert np.array_equal(a[0], b[0]) and np.array_equal(a[1], b[1]) and np.array_equal(a[3], b[3])
 
 
+@pytest.mark.parametrize("n", [262144, 262145, 700001, 1572864, 1572865])
+def test_tile_size_changes_with_cloud_size(n):
+    """The sort picks tiles of 1024, 2048 or 4096 words by the number of pillars: both sides of each change."""
+    coords = _rand_coords(n, 8, 512, 512, seed=n)
+    g, og = ff.Geometry(8, 512, 512, 13, 13), oracle.Geometry(8, 512, 512, 13, 13)
+    print(f"flatten n={n}", flush=True)
+    _check(coords, g, og, 0, 1, 64)
+    _check(coords, g, og, 1, 0, 69)
+
+
 def test_more_than_1024_tiles():
     """4.2 M pillars: the digit tables have more than 1024 rows, which the column scan takes in
     narrower strips.  One sort configuration against the oracle's tuple sort (about half a minute of
