@@ -184,8 +184,6 @@ __global__ __launch_bounds__(256) void k_seg_mean(const int32_t* __restrict__ pe
   for (int64_t pid = (int64_t)blockIdx.x * (blockDim.x / 16) + (threadIdx.x >> 4); pid < np; pid += stride) {
     const int lo = starts[pid], hi = pid + 1 < np ? starts[pid + 1] : *kept;
     const float inv = 1.0f / (float)(hi - lo);
-    if (point_to_pillar)
-      for (int q = lo + sub; q < hi; q += 16) point_to_pillar[perm[q]] = (int32_t)pid;
     for (int c0 = 0; c0 < Cp; c0 += 4) {  // four features at a time
       float acc[4] = {0.f, 0.f, 0.f, 0.f};
       // eight points per lane and round, their loads in flight together: a pillar of several hundred
@@ -194,6 +192,11 @@ __global__ __launch_bounds__(256) void k_seg_mean(const int32_t* __restrict__ pe
         int32_t src[kPointsInFlight];
 #pragma unroll
         for (int u = 0; u < kPointsInFlight; ++u) src[u] = q + 16 * u < hi ? perm[q + 16 * u] : -1;
+        if (point_to_pillar && c0 == 0) {  // the point indices are at hand here (Cp >= 1: this round always runs)
+#pragma unroll
+          for (int u = 0; u < kPointsInFlight; ++u)
+            if (src[u] >= 0) point_to_pillar[src[u]] = (int32_t)pid;
+        }
         float v[kPointsInFlight][4];
         if (vec4) {  // four features of a point in one 16-byte load (the same for every thread)
 #pragma unroll
