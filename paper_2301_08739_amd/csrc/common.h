@@ -77,6 +77,19 @@ int flatten_launch_z(const int32_t* coords, int64_t n, const ff_geom* g, const F
                      uint64_t* const* keys_sorted, void* workspace, size_t workspace_bytes, const PackJob* pack,
                      hipStream_t stream);
 
+// The same sort fed by raw points instead of integer coordinates: key generation computes the cell of
+// point i itself, (frame, floor((x - x_min) / voxel_x), floor((y - y_min) / voxel_y)) in float32, and puts a
+// point outside the grid or the frame range into frame B at cell (0, 0) (g->num_frames counts that frame).
+struct PointCells {
+  const float* xy;        // [n, 2]
+  const int32_t* frame;   // [n] or nullptr (all points in frame 0)
+  int32_t B, grid_x, grid_y;
+  float x_min, y_min, voxel_x, voxel_y;
+};
+int flatten_launch_points(const PointCells* pts, int64_t n, const ff_geom* g, int32_t* perm, int32_t* group_offsets,
+                          int32_t* num_groups, uint64_t* keys_sorted, void* workspace, size_t workspace_bytes,
+                          hipStream_t stream);
+
 int rows_launch(bool scatter, const void* src, void* dst, const int32_t* perm, int64_t n, int C,
                 int dtype, hipStream_t stream);
 // out[perm[p], :] = feats[perm[p], :] for every sorted position p outside all groups, a group being

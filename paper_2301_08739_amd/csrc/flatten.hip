@@ -115,8 +115,22 @@ __device__ __forceinline__ uint32_t digit_rb(uint64_t word, int idx_bits, int ke
   return (uint32_t)(word >> (idx_bits + lo)) & ((1u << nb) - 1u);
 }
 
+// Cell of point i (see PointCells).  Comparisons with NaN fail, so such a point is dropped.
+__device__ __forceinline__ void point_cell(const PointCells& pt, int64_t i, int32_t* c) {
+  const float cx = floorf((pt.xy[2 * i] - pt.x_min) / pt.voxel_x), cy = floorf((pt.xy[2 * i + 1] - pt.y_min) / pt.voxel_y);
+  const int b = pt.frame ? pt.frame[i] : 0;
+  const bool keep = cx >= 0.f && cx < (float)pt.grid_x && cy >= 0.f && cy < (float)pt.grid_y && b >= 0 && b < pt.B;
+  c[0] = keep ? b : pt.B;
+  c[1] = keep ? (int)cx : 0;
+  c[2] = keep ? (int)cy : 0;
+  c[3] = 0;
+}
+
+__device__ __forceinline__ uint64_t make_word_at(const int32_t* __restrict__ c, int64_t i, const KeyParams& kp);
 __device__ __forceinline__ uint64_t make_word(const int32_t* __restrict__ coords, int64_t i, const KeyParams& kp) {
-  const int32_t* c = coords + (int64_t)kp.stride * i;
+  return make_word_at(coords + (int64_t)kp.stride * i, i, kp);
+}
+__device__ __forceinline__ uint64_t make_word_at(const int32_t* __restrict__ c, int64_t i, const KeyParams& kp) {
   const uint32_t b = (uint32_t)c[0];
   const uint32_t X = (uint32_t)(c[1] + kp.sx);
   const uint32_t Y = (uint32_t)(c[2] + kp.sy);
@@ -170,7 +184,7 @@ __device__ __forceinline__ void pack_tail(const PackJob& pack, int id) {
 template <int RB, int KPT>
 __global__ __launch_bounds__(kSortThreads) void k_keygen(const int32_t* __restrict__ coords, int64_t n, Batch bt, int P,
                                                           int64_t tiles, uint64_t* __restrict__ words,
-                                                          uint32_t* __restrict__ counts, PackJob pack) {
+                                                          uint32_t* __restrict__ counts, PackJob pack, PointCells pts) {
   constexpr int BINS = 1 << RB, TILE = kSortThreads * KPT;
   static_assert(kSortThreads == 256, "pack_weights_block works in workgroups of 256 threads");
   const int64_t wg = (int64_t)blockIdx.y * gridDim.x + blockIdx.x;  // dispatch order
@@ -188,7 +202,14 @@ __global__ __launch_bounds__(kSortThreads) void k_keygen(const int32_t* __restri
   for (int r = 0; r < KPT; ++r) {
     const int64_t i = tile * TILE + r * kSortThreads + tid;
     if (i < n) {
-      const uint64_t word = make_word(coords, i, kp);
+      uint64_t word;
+      if (pts.xy) {  // the same for every thread
+        int32_t cell[4];
+        point_cell(pts, i, cell);
+        word = make_word_at(cell, i, kp);
+      } else {
+        word = make_word(coords, i, kp);
+      }
       words[(int64_t)s * n + i] = word;
       atomicAdd(&h[digit_rb(word, kp.idx_bits, kp.key_bits, 0, RB)], 1u);
     }
@@ -760,11 +781,35 @@ int flatten_launch(const int32_t* coords, int64_t n, const ff_geom* g, int num_s
                           num_groups, keys_sorted, workspace, workspace_bytes, pack, stream);
 }
 
+static int flatten_launch_impl(const int32_t* coords, const PointCells* pts, int64_t n, const ff_geom* g,
+                               const FlattenZ* z, int num_sorts, const int* axis, const int* shift, int G, int drop,
+                               int32_t* const* perm, int32_t* const* inv_perm, int32_t* const* group_offsets,
+                               int32_t* const* num_groups, uint64_t* const* keys_sorted, void* workspace,
+                               size_t workspace_bytes, const PackJob* pack, hipStream_t stream);
+
 int flatten_launch_z(const int32_t* coords, int64_t n, const ff_geom* g, const FlattenZ* z, int num_sorts,
                      const int* axis, const int* shift, int G, int drop, int32_t* const* perm,
                      int32_t* const* inv_perm, int32_t* const* group_offsets, int32_t* const* num_groups,
                      uint64_t* const* keys_sorted, void* workspace, size_t workspace_bytes, const PackJob* pack,
                      hipStream_t stream) {
+  return flatten_launch_impl(coords, nullptr, n, g, z, num_sorts, axis, shift, G, drop, perm, inv_perm, group_offsets,
+                             num_groups, keys_sorted, workspace, workspace_bytes, pack, stream);
+}
+
+int flatten_launch_points(const PointCells* pts, int64_t n, const ff_geom* g, int32_t* perm, int32_t* group_offsets,
+                          int32_t* num_groups, uint64_t* keys_sorted, void* workspace, size_t workspace_bytes,
+                          hipStream_t stream) {
+  if (!pts || (n > 0 && !pts->xy)) return FF_ERR_ARG;
+  const int axis = 0, shift = 0;
+  return flatten_launch_impl(nullptr, pts, n, g, nullptr, 1, &axis, &shift, 0x40000000, 0, &perm, nullptr,
+                             &group_offsets, &num_groups, &keys_sorted, workspace, workspace_bytes, nullptr, stream);
+}
+
+static int flatten_launch_impl(const int32_t* coords, const PointCells* pts, int64_t n, const ff_geom* g,
+                               const FlattenZ* z, int num_sorts, const int* axis, const int* shift, int G, int drop,
+                               int32_t* const* perm, int32_t* const* inv_perm, int32_t* const* group_offsets,
+                               int32_t* const* num_groups, uint64_t* const* keys_sorted, void* workspace,
+                               size_t workspace_bytes, const PackJob* pack, hipStream_t stream) {
   if (num_sorts < 1 || num_sorts > kMaxSorts || G < 1) return FF_ERR_ARG;
   if (z && keys_sorted) return FF_ERR_ARG;  // the exported key format has no room for the z fields
   Batch bt;
@@ -792,7 +837,8 @@ int flatten_launch_z(const int32_t* coords, int64_t n, const ff_geom* g, const F
     bt.keys_sorted[s] = nullptr;
     bt.inv_perm[s] = nullptr;
   }
-  if (n > 0 && !coords) return FF_ERR_ARG;
+  if (n > 0 && !coords && !pts) return FF_ERR_ARG;
+  const PointCells point_src = pts ? *pts : PointCells();  // xy == nullptr: integer coordinates
   Layout L;
   make_layout(n, num_sorts, g->num_frames, max_key_bits, &L);
   if (!workspace || ((uintptr_t)workspace & 255) || workspace_bytes < L.total) return FF_ERR_WORKSPACE;
@@ -822,7 +868,7 @@ int flatten_launch_z(const int32_t* coords, int64_t n, const ff_geom* g, const F
 #define FF_PASSES(RB, KPT, SCANNED)                                                                                  \
     do {                                                                                                             \
       hipLaunchKernelGGL((k_keygen<RB, KPT>), pp.passes > 0 ? grid : grid_pack, block, 0, stream, coords, n, bt, P,  \
-                         pp.tiles, buf[0], counts, pp.passes > 0 ? no_job : job);                                     \
+                         pp.tiles, buf[0], counts, pp.passes > 0 ? no_job : job, point_src);                          \
       for (int pass = 0; pass < pp.passes; ++pass) {                                                                 \
         if (SCANNED) {                                                                                               \
           if (pass > 0)                                                                                              \

@@ -3,8 +3,9 @@
 // pillar is a non-empty cell, its feature vector the mean of its points' feature vectors, pillars
 // come out in ascending (frame, x, y) order; the learned per-point network of PointPillars is not
 // part of it.  HBM/latency bound integer work that reuses the window sort:
-//   k_point_cells   cell of every point (float32: floor((x - x_min) / voxel)), dropped points -> frame B
-//   flatten         the radix argsort of flatten.hip with 1 x 1 windows: points ordered by (frame, x, y)
+//   flatten         the radix argsort of flatten.hip with 1 x 1 windows, its key generation fed by the points:
+//                   cell of every point (float32: floor((x - x_min) / voxel)), dropped points -> frame B,
+//                   points ordered by (frame, x, y)
 //   k_seg_count     per 1024 sorted points: how many cells start there
 //   k_seg_scan      exclusive prefix over those counts, total = number of pillars (above 262,144 points only)
 //   k_seg_starts    numbers the cell starts: start position and cell of every pillar
@@ -17,19 +18,6 @@ namespace {
 constexpr int kSegBlock = 1024;
 constexpr int kPointsInFlight = 8;  // per lane of k_seg_mean
 constexpr int kSegDirectBlocks = 256;  // up to 262,144 points the blocks' prefixes need no launch of their own
-
-__global__ __launch_bounds__(256) void k_point_cells(const float* __restrict__ xy, const int32_t* __restrict__ frame,
-                                                      int64_t m, int B, int gx, int gy, float x_min, float y_min,
-                                                      float voxel_x, float voxel_y, int32_t* __restrict__ cells) {
-  const int64_t i = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
-  if (i >= m) return;
-  const float cx = floorf((xy[2 * i] - x_min) / voxel_x), cy = floorf((xy[2 * i + 1] - y_min) / voxel_y);
-  const int b = frame ? frame[i] : 0;
-  const bool keep = cx >= 0.f && cx < (float)gx && cy >= 0.f && cy < (float)gy && b >= 0 && b < B;  // NaN fails
-  cells[3 * i + 0] = keep ? b : B;  // an extra frame behind the real ones collects the dropped points
-  cells[3 * i + 1] = keep ? (int)cx : 0;
-  cells[3 * i + 2] = keep ? (int)cy : 0;
-}
 
 // exported key of the sort: frame << 48 | x << 32 | y << 16 (window 1 x 1: no local fields)
 // The key at sorted position p and the one before it, loaded without conditions (positions clamped
@@ -229,7 +217,7 @@ __global__ __launch_bounds__(256) void k_seg_mean(const int32_t* __restrict__ pe
 
 struct VoxLayout {
   ff_geom geom;  // the geometry the sort sees: one extra frame, 1 x 1 windows
-  size_t off_cells, off_perm, off_keys, off_goff, off_ng, off_blocks, off_starts, off_flat, flat_bytes, total;
+  size_t off_perm, off_keys, off_goff, off_ng, off_blocks, off_starts, off_flat, flat_bytes, total;
   int64_t nb;
 };
 
@@ -245,7 +233,6 @@ int make_vox_layout(int64_t m, const ff_geom* g, VoxLayout* L) {
   if (L->flat_bytes == 0) return FF_ERR_UNSUPPORTED;
   L->nb = ceil_div(m > 0 ? m : 1, kSegBlock);
   size_t off = 0;
-  L->off_cells = off;  off += align_up((size_t)m * 12, 256);
   L->off_perm = off;   off += align_up((size_t)m * 4, 256);
   L->off_keys = off;   off += align_up((size_t)m * 8, 256);
   L->off_goff = off;   off += align_up((size_t)(L->geom.num_frames + 2) * 4, 256);  // one group per frame
@@ -274,18 +261,14 @@ int voxelize_launch(const float* xy, const int32_t* frame, const float* pfeats, 
   if (m > 0 && (!xy || !pfeats || !coords || !feats)) return FF_ERR_ARG;
   if (!workspace || ((uintptr_t)workspace & 255) || workspace_bytes < L.total) return FF_ERR_WORKSPACE;
   char* ws = (char*)workspace;
-  int32_t* cells = (int32_t*)(ws + L.off_cells);
   int32_t* perm = (int32_t*)(ws + L.off_perm);
   uint64_t* keys = (uint64_t*)(ws + L.off_keys);
   int32_t* goff = (int32_t*)(ws + L.off_goff);
   int32_t* ng = (int32_t*)(ws + L.off_ng);
   uint32_t* blocks = (uint32_t*)(ws + L.off_blocks);
-  if (m > 0)
-    hipLaunchKernelGGL(k_point_cells, dim3((unsigned)ceil_div(m, 256)), dim3(256), 0, stream, xy, frame, m,
-                       g->num_frames, g->grid_x, g->grid_y, v->x_min, v->y_min, v->voxel_x, v->voxel_y, cells);
-  const int axis = 0, shift = 0;
-  st = flatten_launch(cells, m, &L.geom, 1, &axis, &shift, 0x40000000, 0, &perm, nullptr, &goff, &ng, &keys,
-                      ws + L.off_flat, L.flat_bytes, nullptr, stream);
+  // key generation computes the cells itself: no array of cells, no launch for it
+  const PointCells pts{xy, frame, g->num_frames, g->grid_x, g->grid_y, v->x_min, v->y_min, v->voxel_x, v->voxel_y};
+  st = flatten_launch_points(&pts, m, &L.geom, perm, goff, ng, keys, ws + L.off_flat, L.flat_bytes, stream);
   if (st != FF_OK) return st;
   int32_t* starts = (int32_t*)(ws + L.off_starts);
   int32_t* kept = ng + 1;  // number of points inside the grid (a spare word beside the sort's group count)
