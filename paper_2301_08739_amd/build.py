@@ -20,9 +20,9 @@ def sources():
     return sorted(glob.glob(os.path.join(HERE, "csrc", "*.hip")))
 
 
-# Per-file flags.  The fused layer kernel takes maxima of matrix-core results; without the promise
+# Per-file flags (both builds of the fused layer kernel get the same set).  It takes maxima of matrix-core results; without the promise
 # that no NaN is involved every such maximum costs an extra canonicalising instruction.
-EXTRA_FLAGS = {"layer_mfma.hip": ["-fno-honor-nans"]}
+EXTRA_FLAGS = {"layer_mfma.hip": ["-fno-honor-nans"], "layer_mfma_f16.hip": ["-fno-honor-nans"]}
 
 
 def _run(cmd, verbose):

@@ -20,6 +20,12 @@ int check_weights(const ff_layer_weights* w, int dtype) {
 }
 
 size_t elem_size(int dtype) { return dtype == FF_F32 ? 4 : 2; }
+// Do the byte ranges [a, a + an) and [b, b + bn) share a byte?  (Empty ranges and null pointers never do.)
+bool overlaps(const void* a, size_t an, const void* b, size_t bn) {
+  if (!a || !b || an == 0 || bn == 0) return false;
+  const uintptr_t x = (uintptr_t)a, y = (uintptr_t)b;
+  return x < y + bn && y < x + an;
+}
 bool is_16bit(int dtype) { return dtype == FF_BF16 || dtype == FF_F16; }  // the types with a fused matrix-core kernel
 
 }  // namespace
@@ -112,11 +118,12 @@ int group_attention(const void* feats, void* out, int64_t n, const int32_t* perm
   if (G > 1024) return FF_ERR_UNSUPPORTED;
   if (n > 0 && (!feats || !out || !perm || !group_offsets || !num_groups)) return FF_ERR_ARG;
   if ((uintptr_t)w->pos_embed & 15) return FF_ERR_ARG;
-  if (n > 0) {  // overlap of the two [n, C] buffers
+  if (n > 0) {  // the two [n, C] buffers must not share a byte, nor may either reach into the workspace
     const size_t in_bytes = (size_t)n * w->C * elem_size(dtype);
     const size_t out_bytes = (size_t)n * w->C * ((flags & FF_FLAG_OUT_F32) ? 4 : elem_size(dtype));
-    const char *a = (const char*)feats, *b = (const char*)out;
-    if (a < b + out_bytes && b < a + in_bytes) return FF_ERR_ARG;
+    if (overlaps(feats, in_bytes, out, out_bytes)) return FF_ERR_ARG;
+    if (overlaps(workspace, workspace_bytes, feats, in_bytes) || overlaps(workspace, workspace_bytes, out, out_bytes))
+      return FF_ERR_ARG;
   }
   const bool out_f32 = (flags & FF_FLAG_OUT_F32) != 0;
   const bool drop = (flags & FF_FLAG_TAIL_DROP) != 0;
@@ -254,7 +261,13 @@ static int fwa_block(const int32_t* coords, int64_t n, const ff_geom* g, const F
   int st = make_block_plan(n, g, z, G, layers, num_layers, dtype, &p);
   if (st != FF_OK) return st;
   if (!workspace || ((uintptr_t)workspace & 255) || workspace_bytes < p.total) return FF_ERR_WORKSPACE;
-  if (n > 0 && (!coords || !feats_in || !feats_out || feats_in == feats_out)) return FF_ERR_ARG;
+  if (n > 0 && (!coords || !feats_in || !feats_out)) return FF_ERR_ARG;
+  {  // input, output and workspace must be three disjoint byte ranges
+    const size_t fb = (size_t)n * layers[0].C * elem_size(dtype);
+    if (overlaps(feats_in, fb, feats_out, fb) || overlaps(workspace, p.total, feats_in, fb) ||
+        overlaps(workspace, p.total, feats_out, fb))
+      return FF_ERR_ARG;
+  }
   char* ws = (char*)workspace;
   const size_t perm_stride = align_up((size_t)n * 4, 256);
   const size_t goff_stride = align_up((size_t)(p.max_groups + 1) * 4, 256);

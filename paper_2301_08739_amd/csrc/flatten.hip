@@ -28,16 +28,6 @@
 #include "common.h"
 #include "pack_weights.h"
 
-#ifdef FF_PROBE
-__device__ long long ff_probe_flat[64];
-extern "C" int ff_debug_read_probe_flat(long long* host_out) {
-  return (int)hipMemcpyFromSymbol(host_out, HIP_SYMBOL(ff_probe_flat), sizeof(long long) * 64);
-}
-#define FP_TS(k) do { if (threadIdx.x == 0 && blockIdx.x == gridDim.x / 2 && blockIdx.y == 0) ff_probe_flat[(FUSE ? 32 : 0) + (k)] = wall_clock64(); } while (0)
-#else
-#define FP_TS(k) do { } while (0)
-#endif
-
 namespace ff {
 
 namespace {
@@ -75,6 +65,13 @@ struct Batch {
   int32_t* num_groups[kMaxSorts];
   uint64_t* keys_sorted[kMaxSorts];
 };
+
+// Groups a frame of `count` pillars is cut into: ceil(count / G), or floor when short groups are dropped.
+// (count + G - 1 would overflow for a G near the top of the int range.)
+__device__ __forceinline__ uint32_t groups_of(uint32_t count, int G, int drop) {
+  const uint32_t full = count / (uint32_t)G;
+  return drop || full * (uint32_t)G == count ? full : full + 1u;
+}
 
 __device__ __forceinline__ uint32_t field_mask(int bits) { return bits >= 32 ? 0xffffffffu : ((1u << bits) - 1u); }
 
@@ -347,8 +344,6 @@ __global__ __launch_bounds__(kSortThreads) void k_pass(const uint64_t* __restric
   uint64_t* out = out_all + (int64_t)s * n;
   const uint32_t* cnt_tab = counts + ((size_t)s * P + pass) * tiles * BINS;
   uint32_t* next_tab = counts + ((size_t)s * P + pass + 1) * tiles * BINS;
-
-  FP_TS(0);
   const int64_t tile_start = tile * TILE;
   const int tile_count = (int)((n - tile_start) < (int64_t)TILE ? (n - tile_start) : (int64_t)TILE);
   // Element order inside the tile: wave-major, then round, then lane.  Each wave owns a contiguous
@@ -397,8 +392,6 @@ __global__ __launch_bounds__(kSortThreads) void k_pass(const uint64_t* __restric
         }
     }
   }
-
-  FP_TS(1);
 #pragma unroll
   for (int i = 0; i < WAVES; ++i)
 #pragma unroll
@@ -424,7 +417,6 @@ __global__ __launch_bounds__(kSortThreads) void k_pass(const uint64_t* __restric
     rank[r] = prev + below;
   }
   __syncthreads();
-  FP_TS(2);
 
   uint32_t total[BPT];
   uint32_t tsum = 0, gsum = 0;
@@ -474,7 +466,6 @@ __global__ __launch_bounds__(kSortThreads) void k_pass(const uint64_t* __restric
     if (FUSE) gdig[tid * BPT + k] = gd[k];
   }
   __syncthreads();
-  FP_TS(3);
 
   if (!FUSE) {
 #pragma unroll
@@ -491,7 +482,6 @@ __global__ __launch_bounds__(kSortThreads) void k_pass(const uint64_t* __restric
         }
       }
     }
-    FP_TS(4);
     return;
   }
 
@@ -545,7 +535,7 @@ __global__ __launch_bounds__(kSortThreads) void k_pass(const uint64_t* __restric
     if (b < B) {
       lo = gdig[(uint32_t)b << fshift];
       const uint32_t hi = b + 1 < B ? gdig[(uint32_t)(b + 1) << fshift] : (uint32_t)n;
-      c = (hi - lo + (drop ? 0u : (uint32_t)G - 1u)) / (uint32_t)G;
+      c = groups_of(hi - lo, G, drop);
     }
     gcount[k] = c;
     fs[k] = lo;
@@ -568,7 +558,6 @@ __global__ __launch_bounds__(kSortThreads) void k_pass(const uint64_t* __restric
     }
     goff_s[gi] = (int32_t)(fstart[lo] + ((uint32_t)gi - fgroup[lo]) * (uint32_t)G);
   }
-  FP_TS(4);
   if (tile == 0 && tid == 0) {
     *bt.num_groups[s] = (int32_t)ng_total;
     goff_s[ng_total] = (int32_t)n;
@@ -603,7 +592,7 @@ __global__ __launch_bounds__(256) void k_frames(const uint64_t* __restrict__ sor
   for (int base = 0; base < B; base += 256) {
     const int b = base + tid;
     uint32_t g = 0;
-    if (b < B) g = (uint32_t)((frame_start[b + 1] - frame_start[b] + (drop ? 0 : G - 1)) / G);
+    if (b < B) g = groups_of((uint32_t)(frame_start[b + 1] - frame_start[b]), G, drop);
     uint32_t total;
     const uint32_t ex = block_exclusive_scan<256>(g, wave_totals, &total);
     const uint32_t carry = carry_s;
@@ -630,7 +619,7 @@ __global__ __launch_bounds__(256) void k_finalize(const uint64_t* __restrict__ s
   const int32_t* fstart = fstart_s;
   const int32_t* gbase = gbase_s;
   if (B == 1) {
-    if (tid == 0) { fstart_s[0] = 0; fstart_s[1] = (int32_t)n; gbase_s[0] = 0; gbase_s[1] = (int32_t)((n + (drop ? 0 : G - 1)) / G); }
+    if (tid == 0) { fstart_s[0] = 0; fstart_s[1] = (int32_t)n; gbase_s[0] = 0; gbase_s[1] = (int32_t)groups_of((uint32_t)n, G, drop); }
     __syncthreads();
   } else if (B <= 256 && n <= 65536) {
     if (tid == 0) fstart_s[B] = (int32_t)n;
@@ -645,7 +634,7 @@ __global__ __launch_bounds__(256) void k_finalize(const uint64_t* __restrict__ s
     }
     __syncthreads();
     uint32_t g = 0;
-    if (tid < B) g = (uint32_t)((fstart_s[tid + 1] - fstart_s[tid] + (drop ? 0 : G - 1)) / G);
+    if (tid < B) g = groups_of((uint32_t)(fstart_s[tid + 1] - fstart_s[tid]), G, drop);
     uint32_t total;
     const uint32_t ex = block_exclusive_scan<256>(g, wave_totals, &total);
     if (tid < B) gbase_s[tid] = (int32_t)ex;

@@ -28,11 +28,6 @@
 #include "pack_weights.h"
 #include <atomic>
 
-#ifdef FF_PROBE
-__device__ long long ff_probe_ts_global[2][64];
-__device__ long long ff_probe_blk[2][2048];  // wall-clock start and end of wave 0 of every workgroup
-#endif
-
 namespace ff {
 namespace {
 
@@ -129,33 +124,6 @@ __device__ __forceinline__ float gelu2_fast(float v) {
   return v + fmaf(-t, e, t);
 }
 
-#ifdef FF_PROBE
-// Development aid (not part of product builds): cycle stamps of wave 0 of two workgroups, kept in
-// registers and written out when the kernel ends.
-#define ff_probe_ts ff_probe_ts_global
-#define FF_TS(k) do { ff_tsw[k] = wall_clock64(); ff_tsc[k] = clock64(); } while (0)
-#define FF_TS_DECL long long ff_tsw[24] = {0}, ff_tsc[24] = {0};
-#define FF_TS_WAIT(k) do { asm volatile("s_waitcnt vmcnt(0) lgkmcnt(0)" ::: "memory"); FF_TS(k); } while (0)
-#define FF_TS_DUMP                                                                        \
-  do {                                                                                    \
-    if (threadIdx.x == 0 && blockIdx.x < 2048) {                                          \
-      ff_probe_blk[0][blockIdx.x] = ff_tsw[0];                                            \
-      ff_probe_blk[1][blockIdx.x] = wall_clock64();                                       \
-    }                                                                                     \
-    if ((threadIdx.x == 0) && (blockIdx.x == 0 || blockIdx.x == gridDim.x / 2)) {         \
-      for (int k = 0; k < 24; ++k) {                                                      \
-        ff_probe_ts[blockIdx.x == 0 ? 0 : 1][k] = ff_tsw[k];                              \
-        ff_probe_ts[blockIdx.x == 0 ? 0 : 1][32 + k] = ff_tsc[k];                         \
-      }                                                                                   \
-    }                                                                                     \
-  } while (0)
-#else
-#define FF_TS(k) do { } while (0)
-#define FF_TS_WAIT(k) do { } while (0)
-#define FF_TS_DECL
-#define FF_TS_DUMP do { } while (0)
-#endif
-
 struct SmallParams {  // per-feature vectors, bf16, read straight from the caller's arrays
   const uint16_t *ln1_g, *ln1_b, *b_qkv, *b_o, *ln2_g, *ln2_b, *b1, *b2;
 };
@@ -247,8 +215,6 @@ __global__ __launch_bounds__(NW * 64, MINW) void k_layer_mfma(const uint16_t* __
   const int g = blockIdx.x * GPW + gl;
   // group_offsets has at least max_groups + 1 entries: read this group's bounds without waiting
   // for num_groups, so that the loads travel together.
-  FF_TS_DECL
-  FF_TS(0);
   const int gc = g < max_groups ? g : max_groups - 1;
   const int off0 = goff[gc], off1 = goff[gc + 1];
   const int ngroups = *num_groups;
@@ -297,7 +263,6 @@ __global__ __launch_bounds__(NW * 64, MINW) void k_layer_mfma(const uint16_t* __
       }
     }
   }
-  FF_TS_WAIT(16);
   int start = 0, m = 0;
   // A list of full groups only ('Drop Residual') has the next start beyond this group's end.
   if (g < ngroups) { start = off0; m = off1 - off0 < G ? off1 - off0 : G; }
@@ -413,7 +378,6 @@ __global__ __launch_bounds__(NW * 64, MINW) void k_layer_mfma(const uint16_t* __
     if (guessed) row[vb] = s < m ? guess[vb] : -1;
     else row[vb] = s < m ? perm[start + s] : -1;
   }
-  FF_TS_WAIT(17);
   // rowv (whole rows, 16 bytes per lane) -> raw (accumulator layout) through the wavefront's LDS share
   auto turn_rows = [&](uint2 (&raw)[NVB][NB]) {
     u32x4* stg = reinterpret_cast<u32x4*>(kvx) + wu * (NVB * 256);  // [row][16-byte piece ^ (row & 15)]
@@ -523,7 +487,6 @@ __global__ __launch_bounds__(NW * 64, MINW) void k_layer_mfma(const uint16_t* __
         pef[vb][nb / 2].u[(nb & 1) * 2 + 1] = row[vb] >= 0 ? praw[vb][nb].y : 0u;
       }
   }
-  FF_TS(1);
   if (drop) {
     // Pillars of no group skip the layer: their rows are copied.  The wavefronts of group g take the
     // sorted positions between its end and the next group's start, those of group index 0 also the
@@ -556,7 +519,6 @@ __global__ __launch_bounds__(NW * 64, MINW) void k_layer_mfma(const uint16_t* __
   // the barrier above waits for every load in flight, and this one hangs on the pillar index.
 #pragma unroll
   for (int vb = 0; vb < NVB; ++vb) orow[vb] = out_index && row[vb] >= 0 ? out_index[row[vb]] : row[vb];
-  FF_TS(2);
 
   // The window: fragments j .. j + PF - 1 of the stream are in registers (or on their way) while
   // fragment j is being used.
@@ -647,10 +609,10 @@ __global__ __launch_bounds__(NW * 64, MINW) void k_layer_mfma(const uint16_t* __
   layer_norm(PO::LN1G, PO::LN1B, true);
   add_bias_rows(PO::BO);  // residual + output-projection bias
   if (LEAN) { __builtin_amdgcn_sched_barrier(0); fill_window(); }
-
-  FF_TS(3);
   const float qscale = rsqrtf((float)DH) * 1.44269504088896340736f;  // 1/sqrt(d) * log2(e)
-  const bool short_group = m < NKB * 16;  // wave-uniform: some key slots are padding
+  // wave-uniform: some key slots are padding.  A wavefront past the last group (m == 0) keeps all its
+  // (zero) keys instead, so that it computes finite numbers it never stores rather than -inf - -inf.
+  const bool short_group = m > 0 && m < NKB * 16;
 
   // ---- attention: one 32-wide head-dim unit per iteration (two heads of 16 or one head of 32) --------
 #pragma unroll FULL_UNROLL
@@ -711,9 +673,7 @@ __global__ __launch_bounds__(NW * 64, MINW) void k_layer_mfma(const uint16_t* __
       }
       finish(kQkvOrder[5]);
     }
-    if (hp == 0) FF_TS(4);
     if (WPG > 1) sync(c0 + (6 * KB) / CF);  // K/V of the group are in LDS
-    if (hp == 0) FF_TS(5);
     if (!LEAN) load_unit_bias(hp + 1 < HP ? hp + 1 : hp);
     auto Kget = [&](int a, int jb) -> Frag4 {
       if (WPG == 1) return Kf[a][jb];
@@ -723,8 +683,6 @@ __global__ __launch_bounds__(NW * 64, MINW) void k_layer_mfma(const uint16_t* __
       if (WPG == 1) return Vf[a][jb];
       Frag4 f; f.d = kv[((1 * 2 + a) * NKB + jb) * 64]; return f;
     };
-
-    if (hp == 0) FF_TS(6);
     Frag8 Of[NVB];  // attention output of this unit as B operand of the output projection
     constexpr int NH = 32 / DH;   // heads in this unit
     constexpr int NA = DH / 16;   // 16-blocks of head dims per head
@@ -868,7 +826,6 @@ __global__ __launch_bounds__(NW * 64, MINW) void k_layer_mfma(const uint16_t* __
         }
       }
     }
-    if (hp == 0) FF_TS(7);
     // output projection of this unit, accumulated into the residual stream
 #pragma unroll
     for (int nb = 0; nb < NB; ++nb) {
@@ -878,9 +835,7 @@ __global__ __launch_bounds__(NW * 64, MINW) void k_layer_mfma(const uint16_t* __
       for (int vb = 0; vb < NVB; ++vb) x1[vb][nb] = mfma32(wf, Of[vb], x1[vb][nb]);
       refill(j);
     }
-    if (hp == 0) FF_TS(8);
   }
-  FF_TS(10);
 
   // ---- FFN ------------------------------------------------------------------------------------------
   f32x4 b1r[2];
@@ -891,7 +846,6 @@ __global__ __launch_bounds__(NW * 64, MINW) void k_layer_mfma(const uint16_t* __
   if (!LEAN) load_b1(0);
   layer_norm(PO::LN2G, PO::LN2B, false);
   add_bias_rows(PO::B2);
-  FF_TS(11);
 #pragma unroll FULL_UNROLL
   for (int fc = 0; fc < FC; ++fc) {
     const int c0 = HP * CPH + fc * CPF;
@@ -943,9 +897,7 @@ __global__ __launch_bounds__(NW * 64, MINW) void k_layer_mfma(const uint16_t* __
       for (int vb = 0; vb < NVB; ++vb) x1[vb][nb] = mfma32(wf, Hf[vb], x1[vb][nb]);
       refill(j);
     }
-    if (fc == 0) FF_TS(12);
   }
-  FF_TS(14);
 
   // ---- scatter -------------------------------------------------------------------------------------
   if constexpr (STAGE && !OUT_F32) {
@@ -992,22 +944,7 @@ __global__ __launch_bounds__(NW * 64, MINW) void k_layer_mfma(const uint16_t* __
       }
     }
   }
-  FF_TS(15);
-  FF_TS_DUMP;
 }
-
-#ifdef FF_PROBE
-}  // namespace
-}  // namespace ff
-extern "C" int ff_debug_read_probe(long long* host_out) {
-  return (int)hipMemcpyFromSymbol(host_out, HIP_SYMBOL(ff_probe_ts_global), sizeof(long long) * 128);
-}
-extern "C" int ff_debug_read_probe_blocks(long long* host_out) {
-  return (int)hipMemcpyFromSymbol(host_out, HIP_SYMBOL(ff_probe_blk), sizeof(long long) * 4096);
-}
-namespace ff {
-namespace {
-#endif
 
 template <int C, int DH, int F, int NVB, int WPG, int NW, int MINW>
 int launch_cfg(const void* feats, void* out, const void* pos_embed, const int32_t* perm, const int32_t* goff,

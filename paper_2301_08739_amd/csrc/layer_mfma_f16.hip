@@ -3,5 +3,4 @@
 // precision the paper runs its model in (Sec. 5.1 'Training and inference'); accumulation,
 // statistics, softmax and GELU stay fp32 exactly as in the bfloat16 build.
 #define FF_LAYER_F16 1
-#undef FF_PROBE
 #include "layer_mfma.hip"

@@ -35,3 +35,19 @@ def gpu_flatten(coords, g, axis, shift, G, want_keys=True, tail=ff.FF_TAIL_MASK)
     k = int(ng.item())
     return (perm.cpu().numpy(), goff.cpu().numpy()[:k + 1], k,
             None if keys is None else keys.cpu().numpy().view(np.uint64), (perm, goff, ng))
+
+
+def assert_bf16_bar(wide, narrow, want, rows=None):
+    """The bf16 bar of the layer tests: (a) the result before storage rounding within 2e-2 of the oracle
+    everywhere, (c) the bf16 buffer within 2e-2 + half an ulp of the stored value everywhere and within plain
+    2e-2 where |reference| < 2.  ((b), buffer == RNE(wide), is asserted by the caller that produced both.)
+    Returns (max error of wide, max error of narrow)."""
+    if rows is not None:
+        wide, narrow, want = wide[rows], narrow[rows], want[rows]
+    e_wide = np.abs(wide - want).max()
+    assert e_wide <= 2e-2, e_wide
+    err = np.abs(narrow - want)
+    assert np.all(err <= 2e-2 + 2.0 ** -9 * np.abs(narrow))
+    small = np.abs(want) < 2.0
+    assert err[small].max() <= 2e-2, err[small].max()
+    return e_wide, err.max()
