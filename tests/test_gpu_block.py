@@ -10,7 +10,7 @@ import torch
 import ffsynth
 import oracle
 import paper_2301_08739_amd as ff
-from gpu_util import DEV, geoms, to_dev_feats, to_host
+from gpu_util import DEV, bf16_half_ulp, geoms, to_dev_feats, to_host
 
 pytestmark = pytest.mark.gpu
 
@@ -61,7 +61,7 @@ def test_headline_block_end_to_end_against_the_oracle(cfg):
     torch.cuda.synchronize()
     got = to_host(out)
     err = np.abs(got - cur)
-    bound = 4 * (2e-2 + 2.0 ** -9 * np.abs(cur))
+    bound = 4 * (2e-2 + bf16_half_ulp(cur))
     print(f"cfg2 block end to end: max abs err {err.max():.4e}, mean {err.mean():.3e}, max |ref| {np.abs(cur).max():.2f}",
           flush=True)
     assert np.all(err <= bound)

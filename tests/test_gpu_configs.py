@@ -18,7 +18,7 @@ import torch
 import ffsynth
 import oracle
 import paper_2301_08739_amd as ff
-from gpu_util import DEV, assert_bf16_bar, geoms, to_dev_feats, to_host
+from gpu_util import DEV, assert_bf16_bar, bf16_half_ulp, geoms, to_dev_feats, to_host
 
 pytestmark = [pytest.mark.gpu, pytest.mark.timeout(900)]
 
@@ -88,8 +88,8 @@ def test_layer_on_the_oracles_chain(cfg, i, l):
 def test_block_end_to_end_on_the_oracles_chain(cfg, i):
     """ff_fwa_block (8 layers, bf16 buffers between them, weights re-tiled inside the call) against the last
     activation of the oracle's chain.  A layer's own error is at most 2e-2 plus the storage rounding of its
-    output, 2^-9 |y|; the residual path hands the error of the layers before it on with gain one, so the bound
-    for L layers is L times the per-layer one: here 8 x (2e-2 + 2^-9 |y|)."""
+    output (half an ulp); the residual path hands the error of the layers before it on with gain one, so the
+    bound for L layers is L times the per-layer one: here 8 x (2e-2 + half an ulp of |y|)."""
     ch = _chain(cfg, i)
     c = ch.c
     L = len(c["schedule"])
@@ -101,7 +101,7 @@ def test_block_end_to_end_on_the_oracles_chain(cfg, i):
                           to_dev_feats(c["feats"], ff.FF_BF16))
     torch.cuda.synchronize()
     err = np.abs(to_host(out) - ref)
-    bound = L * (2e-2 + 2.0 ** -9 * np.abs(ref))
+    bound = L * (2e-2 + bf16_half_ulp(ref))
     print(f"cfg{i} block end to end, {L} layers: max abs err {err.max():.4e}, mean {err.mean():.3e}, "
           f"max |ref| {np.abs(ref).max():.2f}, worst err/bound {float((err / bound).max()):.3f}", flush=True)
     assert np.all(err <= bound)

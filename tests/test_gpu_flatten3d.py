@@ -6,6 +6,7 @@ import torch
 
 import oracle
 import paper_2301_08739_amd as ff
+from gpu_util import bf16_half_ulp
 
 pytestmark = pytest.mark.gpu
 
@@ -147,7 +148,7 @@ def test_block_over_voxels_equals_flatten3d_plus_layer_calls(dt, tail):
                                            tail="drop" if flag else "mask")
             want = oracle.layer(x_h, wperm, woff, params[0], group_size=G if flag else None)
             err = np.abs(nxt.float().cpu().numpy().astype(np.float64) - want)
-            tol = 2e-2 + 2.0 ** -9 * np.abs(want) if bf else 1e-4
+            tol = 2e-2 + bf16_half_ulp(want) if bf else 1e-4
             print(f"3-D block dt={dt} tail={tail}: first layer max abs err {err.max():.3e}", flush=True)
             assert np.all(err <= tol)
         cur = nxt
