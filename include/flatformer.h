@@ -95,6 +95,26 @@ int ff_flatten(const int32_t* coords /* [n,3] (b,x,y) */, int64_t n, const ff_ge
                int32_t* perm, int32_t* group_offsets, int32_t* num_groups,
                uint64_t* keys_sorted, void* workspace, size_t workspace_bytes, void* stream);
 
+/* ---- ff_flatten without a workspace, for callers that cannot allocate device memory: code under HIP graph
+ * capture, tight serving loops that must not call hipMalloc, harnesses that forbid it.  Arguments, outputs
+ * and errors are ff_flatten's; the scratch memory of the sort is a static device array of
+ * FF_NOALLOC_SCRATCH_BYTES inside the library (each GPU the library runs on holds its own copy until the
+ * process ends).  The call allocates and frees nothing and does not synchronise.
+ *  - Limit: ff_flatten_workspace_bytes(n, g) must not exceed FF_NOALLOC_SCRATCH_BYTES, else
+ *    FF_ERR_UNSUPPORTED and nothing is written (a 468 x 468 grid with 13 x 13 windows fits up to
+ *    about 400,000 pillars).
+ *  - Every call on a GPU uses that GPU's one array: calls that overlap in time on the same GPU (two
+ *    streams, two threads) race with each other; serialise them.  Nothing in the array has to be cleared
+ *    between calls, and nothing of a call is kept in it afterwards.
+ *  - The first call on a device looks up the array's address there (hipGetSymbolAddress); make that call
+ *    outside a graph capture. */
+#define FF_NOALLOC_SCRATCH_BYTES (8u << 20)
+
+int ff_flatten_noalloc(const int32_t* coords /* [n,3] (b,x,y) */, int64_t n, const ff_geom* g,
+                       int axis, int shift, int G, int tail /* ff_tail */,
+                       int32_t* perm, int32_t* group_offsets, int32_t* num_groups,
+                       uint64_t* keys_sorted /* or NULL */, void* stream);
+
 /* ---- the same for three-dimensional windows (footnote of Sec. 4.2.1: the method applies to 3-D point
  * clouds; no configuration of the paper uses it) -----------------------------------------------------
  * coords [n,4] = (b, x, y, z) voxel indices.  The shift is half a window on all three axes.  The

@@ -85,6 +85,8 @@ _SIGS = {
     "ff_flatten_workspace_bytes": (C.c_size_t, [C.c_int64, C.POINTER(Geometry)]),
     "ff_flatten": (C.c_int, [C.c_void_p, C.c_int64, C.POINTER(Geometry), C.c_int, C.c_int, C.c_int, C.c_int,
                              C.c_void_p, C.c_void_p, C.c_void_p, C.c_void_p, C.c_void_p, C.c_size_t, C.c_void_p]),
+    "ff_flatten_noalloc": (C.c_int, [C.c_void_p, C.c_int64, C.POINTER(Geometry), C.c_int, C.c_int, C.c_int, C.c_int,
+                                     C.c_void_p, C.c_void_p, C.c_void_p, C.c_void_p, C.c_void_p]),
     "ff_flatten3d_workspace_bytes": (C.c_size_t, [C.c_int64, C.POINTER(Geometry3)]),
     "ff_flatten3d": (C.c_int, [C.c_void_p, C.c_int64, C.POINTER(Geometry3), C.c_int, C.c_int, C.c_int, C.c_int,
                                C.c_void_p, C.c_void_p, C.c_void_p, C.c_void_p, C.c_size_t, C.c_void_p]),
@@ -190,6 +192,20 @@ def ff_flatten(coords, geom, axis, shift, G, tail=FF_TAIL_MASK, want_keys=False,
                         _ptr(keys), C.c_void_p(_aligned_ptr(ws)), ws.numel() - 256, _stream())
     _check(st, "ff_flatten")
     return perm, goff, ng, keys
+
+
+FF_NOALLOC_SCRATCH_BYTES = 8 << 20
+
+
+def ff_flatten_noalloc(coords, geom, axis, shift, G, perm, group_offsets, num_groups, keys=None, tail=FF_TAIL_MASK):
+    """ff_flatten on the library's static scratch array: every buffer is the caller's (perm int32 [n],
+    group_offsets int32 [ceil(n/G)+num_frames+1], num_groups int32 [1], keys int64 [n] or None) and the call
+    allocates nothing."""
+    lib = load_library()
+    assert coords.dtype == torch.int32 and coords.is_contiguous() and coords.is_cuda
+    st = lib.ff_flatten_noalloc(_ptr(coords), coords.shape[0], C.byref(geom), axis, shift, G, tail, _ptr(perm),
+                                _ptr(group_offsets), _ptr(num_groups), _ptr(keys), _stream())
+    _check(st, "ff_flatten_noalloc")
 
 
 def ff_flatten3d(coords, geom, axis, shift, G, tail=FF_TAIL_MASK, workspace=None):

@@ -2,6 +2,7 @@
 // here; see flatten.hip, rows.hip, layer_generic.hip, layer_mfma.hip.
 #include "common.h"
 #include "pack_weights.h"
+#include <atomic>
 
 using namespace ff;
 
@@ -41,6 +42,47 @@ int ff_flatten(const int32_t* coords, int64_t n, const ff_geom* g, int axis, int
   if (shift != 0 && shift != 1) return FF_ERR_ARG;
   return flatten_launch(coords, n, g, 1, &axis, &shift, G, tail == FF_TAIL_DROP, &perm, nullptr, &group_offsets, &num_groups, &keys_sorted,
                         workspace, workspace_bytes, nullptr, (hipStream_t)stream);
+}
+
+// ---- ff_flatten for callers that cannot allocate ----------------------------------------------------------
+// The sort's scratch (two word buffers, digit tables, frame table) lives in this array instead of a caller's
+// workspace.  Every device the library runs on holds its own copy, at its own address, until the process
+// ends; host code never uses the array's name as an address, only what hipGetSymbolAddress returned for the
+// current device.
+static __device__ __align__(256) unsigned char scratch[FF_NOALLOC_SCRATCH_BYTES];
+
+namespace {
+constexpr int kMaxDevices = 64;
+static std::atomic<void*> scratch_ptr[kMaxDevices];  // per device: address of `scratch` there (nullptr: not asked yet)
+
+static int scratch_on_current_device(void** out) {
+  int dev = 0;
+  if (hipGetDevice(&dev) != hipSuccess || dev < 0 || dev >= kMaxDevices) return FF_ERR_LAUNCH;
+  void* p = scratch_ptr[dev].load(std::memory_order_acquire);
+  if (!p) {
+    if (hipGetSymbolAddress(&p, HIP_SYMBOL(scratch)) != hipSuccess || !p) return FF_ERR_LAUNCH;
+    scratch_ptr[dev].store(p, std::memory_order_release);
+  }
+  *out = p;
+  return FF_OK;
+}
+}  // namespace
+
+int ff_flatten_noalloc(const int32_t* coords, int64_t n, const ff_geom* g, int axis, int shift, int G, int tail,
+                       int32_t* perm, int32_t* group_offsets, int32_t* num_groups, uint64_t* keys_sorted,
+                       void* stream) {
+  const size_t need = flatten_workspace_bytes(n, g, 1);
+  if (need == 0) {  // the geometry or n is invalid: report it the way ff_flatten does
+    FlattenPlan fp;
+    const int st = make_flatten_plan(n, g, axis == 1 ? 1 : 0, 1, &fp);
+    return st != FF_OK ? st : FF_ERR_ARG;
+  }
+  if (need > (size_t)FF_NOALLOC_SCRATCH_BYTES) return FF_ERR_UNSUPPORTED;  // the cloud is too large for the array
+  void* ws = nullptr;
+  const int st = scratch_on_current_device(&ws);
+  if (st != FF_OK) return st;
+  return ff_flatten(coords, n, g, axis, shift, G, tail, perm, group_offsets, num_groups, keys_sorted, ws,
+                    (size_t)FF_NOALLOC_SCRATCH_BYTES, stream);
 }
 
 namespace {
