@@ -95,6 +95,21 @@ int ff_flatten(const int32_t* coords /* [n,3] (b,x,y) */, int64_t n, const ff_ge
                int32_t* perm, int32_t* group_offsets, int32_t* num_groups,
                uint64_t* keys_sorted, void* workspace, size_t workspace_bytes, void* stream);
 
+/* ---- several sort configurations of one cloud in one call ('Reuse Sorting', Sec. 4.3: the coordinates do
+ * not change inside a stage, so each (axis, shift) pair is sorted once and reused by every layer and block
+ * that needs it).  num_sorts (1..4) configurations axis[s], shift[s] are sorted together, one launch set for
+ * all of them; perm / group_offsets / num_groups are HOST arrays of num_sorts device pointers, each as in
+ * ff_flatten.  This is what ff_fwa_block runs in front of its layers; a caller that keeps the results can
+ * run later blocks on the same cloud through ff_group_attention without sorting again.
+ * workspace: ff_flatten_batch_workspace_bytes(n, g, num_sorts) bytes, 256-byte aligned. */
+size_t ff_flatten_batch_workspace_bytes(int64_t n, const ff_geom* g, int num_sorts);
+
+int ff_flatten_batch(const int32_t* coords /* [n,3] (b,x,y) */, int64_t n, const ff_geom* g, int num_sorts,
+                     const int* axis /* host [num_sorts] */, const int* shift /* host [num_sorts] */,
+                     int G, int tail /* ff_tail */,
+                     int32_t* const* perm, int32_t* const* group_offsets, int32_t* const* num_groups,
+                     void* workspace, size_t workspace_bytes, void* stream);
+
 /* ---- ff_flatten without a workspace, for callers that cannot allocate device memory: code under HIP graph
  * capture, tight serving loops that must not call hipMalloc, harnesses that forbid it.  Arguments, outputs
  * and errors are ff_flatten's; the scratch memory of the sort is a static device array of
@@ -204,6 +219,15 @@ int ff_group_attention(const void* feats, void* out, int64_t n,
                        const int32_t* num_groups, int32_t max_groups,
                        const ff_layer_weights* w, int G, int dtype, uint32_t flags,
                        void* workspace, size_t workspace_bytes, void* stream);
+
+/* Which kernels a call of ff_group_attention with these weights, group size, dtype and flags would run
+ * (host-side, launches nothing): FF_PATH_FUSED, the single matrix-core kernel (16-bit dtypes; shapes
+ * (C, head dim, F) = (128, 16, 256), (256, 32, 512) and (64, 16, 128) with G <= 128), or FF_PATH_PLAIN, the
+ * three fp32-arithmetic kernels that serve every other shape, FF_F32 and FF_FLAG_FORCE_GENERIC, at a
+ * fraction of the speed.  A negative value is the ff_status the call itself would return for these arguments. */
+#define FF_PATH_PLAIN 0
+#define FF_PATH_FUSED 1
+int ff_group_attention_path(const ff_layer_weights* w, int G, int dtype, uint32_t flags);
 
 /* ---- row gather / scatter (the 'reshape' of Sec. 4.2.1 made explicit) ---------------------------
  * gather:  dst[p, :] = src[perm[p], :]     scatter:  dst[perm[p], :] = src[p, :]

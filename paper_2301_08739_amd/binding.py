@@ -85,6 +85,11 @@ _SIGS = {
     "ff_flatten_workspace_bytes": (C.c_size_t, [C.c_int64, C.POINTER(Geometry)]),
     "ff_flatten": (C.c_int, [C.c_void_p, C.c_int64, C.POINTER(Geometry), C.c_int, C.c_int, C.c_int, C.c_int,
                              C.c_void_p, C.c_void_p, C.c_void_p, C.c_void_p, C.c_void_p, C.c_size_t, C.c_void_p]),
+    "ff_flatten_batch_workspace_bytes": (C.c_size_t, [C.c_int64, C.POINTER(Geometry), C.c_int]),
+    "ff_flatten_batch": (C.c_int, [C.c_void_p, C.c_int64, C.POINTER(Geometry), C.c_int, C.POINTER(C.c_int),
+                                   C.POINTER(C.c_int), C.c_int, C.c_int, C.POINTER(C.c_void_p), C.POINTER(C.c_void_p),
+                                   C.POINTER(C.c_void_p), C.c_void_p, C.c_size_t, C.c_void_p]),
+    "ff_group_attention_path": (C.c_int, [C.POINTER(_LayerWeightsC), C.c_int, C.c_int, C.c_uint32]),
     "ff_flatten_noalloc": (C.c_int, [C.c_void_p, C.c_int64, C.POINTER(Geometry), C.c_int, C.c_int, C.c_int, C.c_int,
                                      C.c_void_p, C.c_void_p, C.c_void_p, C.c_void_p, C.c_void_p]),
     "ff_flatten3d_workspace_bytes": (C.c_size_t, [C.c_int64, C.POINTER(Geometry3)]),
@@ -192,6 +197,42 @@ def ff_flatten(coords, geom, axis, shift, G, tail=FF_TAIL_MASK, want_keys=False,
                         _ptr(keys), C.c_void_p(_aligned_ptr(ws)), ws.numel() - 256, _stream())
     _check(st, "ff_flatten")
     return perm, goff, ng, keys
+
+
+def ff_flatten_batch_workspace_bytes(n, geom, num_sorts):
+    return load_library().ff_flatten_batch_workspace_bytes(int(n), C.byref(geom), int(num_sorts))
+
+
+def ff_flatten_batch(coords, geom, sorts, G, tail=FF_TAIL_MASK, workspace=None, out=None):
+    """sorts: up to four (axis, shift) pairs, sorted together.  Returns a list of (perm, group_offsets,
+    num_groups) device tensors, one triple per pair (out: such a list to write into instead of new tensors)."""
+    lib = load_library()
+    assert coords.dtype == torch.int32 and coords.is_contiguous() and coords.is_cuda
+    n, dev, S = coords.shape[0], coords.device, len(sorts)
+    cap = -(-n // max(G, 1)) + geom.num_frames + 1
+    if out is None:
+        out = [(torch.empty(n, dtype=torch.int32, device=dev), torch.full((cap,), -1, dtype=torch.int32, device=dev),
+                torch.full((1,), -1, dtype=torch.int32, device=dev)) for _ in range(S)]
+    axis = (C.c_int * S)(*[int(a) for a, _ in sorts])
+    shift = (C.c_int * S)(*[int(b) for _, b in sorts])
+    ptrs = [(C.c_void_p * S)(*[t[k].data_ptr() for t in out]) for k in range(3)]
+    ws = workspace if workspace is not None else _workspace(lib.ff_flatten_batch_workspace_bytes(n, C.byref(geom), S), dev)
+    st = lib.ff_flatten_batch(_ptr(coords), n, C.byref(geom), S, axis, shift, G, tail, ptrs[0], ptrs[1], ptrs[2],
+                              C.c_void_p(_aligned_ptr(ws)), ws.numel() - 256, _stream())
+    _check(st, "ff_flatten_batch")
+    return out
+
+
+FF_PATH_PLAIN, FF_PATH_FUSED = 0, 1
+
+
+def ff_group_attention_path(weights, G, dtype, flags=0):
+    """FF_PATH_FUSED or FF_PATH_PLAIN: the kernels ff_group_attention would run for these arguments."""
+    s = weights.struct()
+    st = load_library().ff_group_attention_path(C.byref(s), int(G), int(dtype), int(flags))
+    if st < 0:
+        _check(st, "ff_group_attention_path")
+    return st
 
 
 FF_NOALLOC_SCRATCH_BYTES = 8 << 20
@@ -306,10 +347,23 @@ def ff_bev_scatter(feats, coords, geom, dtype, out=None):
     return out
 
 
+_ARRAY_CACHE = {}
+
+
 def _layer_array(layers, pos_embed=None):
+    """The ff_layer_weights array of a block's layers.  Built once per (layer objects, packed state, embedding
+    buffer) and kept: a serving loop calls the block with the same layers every frame."""
+    key = (tuple(id(l) for l in layers), tuple(l.packed for l in layers),
+           None if pos_embed is None else pos_embed.data_ptr())
+    hit = _ARRAY_CACHE.get(key)
+    if hit is not None and all(a is b for a, b in zip(hit[1], layers)):
+        return hit[0]
     arr = (_LayerWeightsC * len(layers))()
     for i, l in enumerate(layers):
         arr[i] = l.struct(pos_embed)
+    if len(_ARRAY_CACHE) > 64:
+        _ARRAY_CACHE.clear()
+    _ARRAY_CACHE[key] = (arr, list(layers))
     return arr
 
 
@@ -338,8 +392,8 @@ def ff_fwa_block(coords, geom, G, layers, dtype, feats_in, out=None, workspace=N
     arr = _layer_array(layers, pos_embed)
     if out is None:
         out = torch.empty_like(feats_in)
-    need = query(n, C.byref(geom), G, arr, len(layers), dtype)
-    ws = workspace if workspace is not None else _workspace(need, coords.device)
+    ws = workspace if workspace is not None else _workspace(query(n, C.byref(geom), G, arr, len(layers), dtype),
+                                                              coords.device)   # (the call itself checks the size)
     st = run(_ptr(coords), n, C.byref(geom), G, tail, arr, len(layers), dtype, _ptr(feats_in), _ptr(out),
              C.c_void_p(_aligned_ptr(ws)), ws.numel() - 256, _stream())
     _check(st, name)

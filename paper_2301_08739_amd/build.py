@@ -7,6 +7,7 @@ import sys
 HERE = os.path.dirname(os.path.abspath(__file__))
 ROOT = os.path.dirname(HERE)
 LIB = os.path.join(HERE, "libflatformer.so")
+PEAKS_LIB = os.path.join(HERE, "libffpeaks.so")   # bench-only: stream copy and MFMA issue loop (csrc/bench/peaks.hip)
 
 HIPCC_FLAGS = [
     "--offload-arch=gfx950", "-O3", "-std=c++17", "-fPIC", "-shared",
@@ -59,6 +60,8 @@ def build(verbose=False):
             print(err, file=sys.stderr)
     _run([hipcc, "--offload-arch=gfx950", "-shared", "-fPIC"] + objs + ["-o", LIB + ".tmp"], verbose)
     os.replace(LIB + ".tmp", LIB)
+    _run([hipcc] + HIPCC_FLAGS + [os.path.join(HERE, "csrc", "bench", "peaks.hip"), "-o", PEAKS_LIB + ".tmp"], verbose)
+    os.replace(PEAKS_LIB + ".tmp", PEAKS_LIB)
     return LIB
 
 

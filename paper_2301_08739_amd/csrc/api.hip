@@ -44,6 +44,21 @@ int ff_flatten(const int32_t* coords, int64_t n, const ff_geom* g, int axis, int
                         workspace, workspace_bytes, nullptr, (hipStream_t)stream);
 }
 
+size_t ff_flatten_batch_workspace_bytes(int64_t n, const ff_geom* g, int num_sorts) {
+  return flatten_workspace_bytes(n, g, num_sorts);
+}
+
+int ff_flatten_batch(const int32_t* coords, int64_t n, const ff_geom* g, int num_sorts, const int* axis,
+                     const int* shift, int G, int tail, int32_t* const* perm, int32_t* const* group_offsets,
+                     int32_t* const* num_groups, void* workspace, size_t workspace_bytes, void* stream) {
+  if (tail != FF_TAIL_MASK && tail != FF_TAIL_DROP) return FF_ERR_ARG;
+  if (num_sorts < 1 || num_sorts > 4 || !axis || !shift || !perm || !group_offsets || !num_groups) return FF_ERR_ARG;
+  for (int s = 0; s < num_sorts; ++s)
+    if (shift[s] != 0 && shift[s] != 1) return FF_ERR_ARG;
+  return flatten_launch(coords, n, g, num_sorts, axis, shift, G, tail == FF_TAIL_DROP, perm, nullptr, group_offsets,
+                        num_groups, nullptr, workspace, workspace_bytes, nullptr, (hipStream_t)stream);
+}
+
 // ---- ff_flatten for callers that cannot allocate ----------------------------------------------------------
 // The sort's scratch (two word buffers, digit tables, frame table) lives in this array instead of a caller's
 // workspace.  Every device the library runs on holds its own copy, at its own address, until the process
@@ -208,6 +223,14 @@ int ff_group_attention(const void* feats, void* out, int64_t n, const int32_t* p
                        void* workspace, size_t workspace_bytes, void* stream) {
   return group_attention(feats, out, n, perm, group_offsets, num_groups, max_groups, w, G, dtype, flags, workspace,
                          workspace_bytes, nullptr, 0, stream);
+}
+
+int ff_group_attention_path(const ff_layer_weights* w, int G, int dtype, uint32_t flags) {
+  const int st = check_weights(w, dtype);
+  if (st != FF_OK) return st;
+  if (G < 1) return FF_ERR_ARG;
+  if (G > 1024) return FF_ERR_UNSUPPORTED;
+  return takes_fused_path(w, G, dtype, flags) ? FF_PATH_FUSED : FF_PATH_PLAIN;
 }
 
 int ff_gather(const void* src, void* dst, const int32_t* perm, int64_t n, int C, int dtype, void* stream) {

@@ -124,10 +124,6 @@ __device__ __forceinline__ float gelu2_fast(float v) {
   return v + fmaf(-t, e, t);
 }
 
-struct SmallParams {  // per-feature vectors, bf16, read straight from the caller's arrays
-  const uint16_t *ln1_g, *ln1_b, *b_qkv, *b_o, *ln2_g, *ln2_b, *b1, *b2;
-};
-
 // Number of 1 KB fragments of the packed weight stream of one layer.
 __host__ __device__ constexpr int frags_per_hp(int C) { return 6 * (C / 32) + C / 16; }
 __host__ __device__ constexpr int frags_per_fc(int C) { return 2 * (C / 32) + C / 16; }
@@ -150,7 +146,9 @@ struct ParamOff {  // float offsets inside the small-parameter area
                        B1 = 7 * C, TOTAL = 7 * C + F;
 };
 
-constexpr int kChunkFrags = 16;        // fragments per staged chunk (16 KB)
+// Fragments per staged chunk: 16 (16 KB), or 8 for the narrow layer, whose hidden unit is 8 fragments (units are
+// whole chunks).
+__host__ __device__ constexpr int chunk_frags(int C) { return C >= 128 ? 16 : 8; }
 constexpr int kLdsBytes = 160 * 1024;  // LDS of one compute unit
 constexpr int kComputeUnits = 256;      // of an MI355X
 constexpr int kWindow = 8;             // weight fragments a wavefront keeps in flight (LDS -> registers)
@@ -159,13 +157,13 @@ template <int C, int F, int NVB, int WPG, int NW, int MINW>
 struct LdsPlan {
   static constexpr int NKB = NVB * WPG, GPW = NW / WPG;
   static constexpr int WGS = (MINW * 4 / NW) > 1 ? (MINW * 4 / NW) : 1;  // workgroups meant to share a compute unit
-  static constexpr int PARAMS = ParamOff<C, F>::TOTAL * 4;
+  static constexpr int PARAMS = pack_param_bytes(C, F);   // padded to whole 1 KB pieces
   static constexpr int KVX_ONE = 2 * 2 * NKB * 64 * 8;                     // K and V of one group, one unit
   static constexpr int KVX = WPG > 1 ? 2 * GPW * KVX_ONE : 0;              // double buffered
-  static constexpr int NCHUNK = ((C / 32) * (6 * (C / 32) + C / 16) + (F / 32) * (2 * (C / 32) + C / 16)) / kChunkFrags;
-  static constexpr int FIT = (kLdsBytes / WGS - PARAMS - KVX) / (kChunkFrags * 1024);
+  static constexpr int NCHUNK = ((C / 32) * (6 * (C / 32) + C / 16) + (F / 32) * (2 * (C / 32) + C / 16)) / chunk_frags(C);
+  static constexpr int FIT = (kLdsBytes / WGS - PARAMS - KVX) / (chunk_frags(C) * 1024);
   static constexpr int RING = FIT < NCHUNK ? FIT : NCHUNK;
-  static constexpr int TOTAL = RING * kChunkFrags * 1024 + PARAMS + KVX;
+  static constexpr int TOTAL = RING * chunk_frags(C) * 1024 + PARAMS + KVX;
   static_assert(RING >= 2, "weight ring");
 };
 
@@ -175,7 +173,7 @@ __global__ __launch_bounds__(NW * 64, MINW) void k_layer_mfma(const uint16_t* __
                                                                const int32_t* __restrict__ perm,
                                                                const int32_t* __restrict__ goff,
                                                                const int32_t* __restrict__ num_groups, int max_groups,
-                                                               const u32x4* __restrict__ packed, SmallParams sp, float eps,
+                                                               const u32x4* __restrict__ packed, float eps,
                                                                int n, int G, int drop,
                                                                const int32_t* __restrict__ out_index, int in_sorted) {
   constexpr int KB = C / 32;          // 32-wide blocks of the input features
@@ -185,7 +183,7 @@ __global__ __launch_bounds__(NW * 64, MINW) void k_layer_mfma(const uint16_t* __
   constexpr int NKB = NVB * WPG;      // key blocks of a group
   constexpr int NT = NW * 64;
   constexpr int GPW = NW / WPG;       // groups per workgroup
-  constexpr int CF = kChunkFrags;
+  constexpr int CF = chunk_frags(C);
   constexpr int FH = 6 * KB + NB;     // fragments of one head-dim unit: Q, K, V rows, W_o slice
   constexpr int FF = 2 * KB + NB;     // fragments of one hidden unit: W1 rows, W2 slice
   constexpr int CPH = FH / CF, CPF = FF / CF;
@@ -207,7 +205,7 @@ __global__ __launch_bounds__(NW * 64, MINW) void k_layer_mfma(const uint16_t* __
   uint32_t par_units = RING * CF * 64;
   asm volatile("" : "+v"(par_units));
   float* par = reinterpret_cast<float*>(lds + par_units);       // [PO::TOTAL]
-  u32x2* kvx = reinterpret_cast<u32x2*>(par + PO::TOTAL);       // K/V exchange, only when WPG > 1
+  u32x2* kvx = reinterpret_cast<u32x2*>(reinterpret_cast<char*>(par) + LP::PARAMS);  // K/V exchange, only when WPG > 1
 
   const int tid = threadIdx.x, lane = tid & 63, w = tid >> 6, i = lane & 15, q = lane >> 4;
   const int wu = __builtin_amdgcn_readfirstlane(w);
@@ -223,8 +221,9 @@ __global__ __launch_bounds__(NW * 64, MINW) void k_layer_mfma(const uint16_t* __
   int32_t guess[NVB];
 #pragma unroll
   for (int vb = 0; vb < NVB; ++vb) {
-    const int64_t at = (int64_t)g * G + (part * NVB + vb) * 16 + i;
-    guess[vb] = perm[at < n ? at : n - 1];
+    // (unsigned 32-bit: g * G stays below n + num_frames * G, and one minimum clamps it)
+    const uint32_t at = (uint32_t)g * (uint32_t)G + (uint32_t)((part * NVB + vb) * 16 + i);
+    guess[vb] = perm[at < (uint32_t)n ? at : (uint32_t)n - 1u];
   }
   // in_sorted: row p of feats is the pillar at sorted position p (the previous layer of a block wrote
   // its result in this layer's order), so the rows of a group are contiguous and need no index.
@@ -249,17 +248,18 @@ __global__ __launch_bounds__(NW * 64, MINW) void k_layer_mfma(const uint16_t* __
     if constexpr (STAGE) {
 #pragma unroll
       for (int k = 0; k < NRL; ++k) {
-        const int64_t at = (int64_t)g * G + part * NVB * 16 + RPI * k + lr;
+        const uint32_t at = (uint32_t)g * (uint32_t)G + (uint32_t)(part * NVB * 16 + RPI * k + lr);
         // (non-temporal: a row is read once per layer, and what arrives was written by another XCD)
-        rowv[k] = __builtin_nontemporal_load(reinterpret_cast<const u32x4*>(feats + (at < n ? at : n - 1) * C + 8 * piece32));
+        rowv[k] = __builtin_nontemporal_load(reinterpret_cast<const u32x4*>(
+            feats + (size_t)(at < (uint32_t)n ? at : (uint32_t)n - 1u) * C + 8 * piece32));
       }
     } else {
 #pragma unroll
       for (int vb = 0; vb < NVB; ++vb) {
-        const int64_t at = (int64_t)g * G + (part * NVB + vb) * 16 + i;
+        const uint32_t at = (uint32_t)g * (uint32_t)G + (uint32_t)((part * NVB + vb) * 16 + i);
 #pragma unroll
         for (int nb = 0; nb < NB; ++nb)
-          early[vb][nb] = *reinterpret_cast<const uint2*>(feats + (at < n ? at : n - 1) * C + 16 * nb + 4 * q);
+          early[vb][nb] = *reinterpret_cast<const uint2*>(feats + (size_t)(at < (uint32_t)n ? at : (uint32_t)n - 1u) * C + 16 * nb + 4 * q);
       }
     }
   }
@@ -336,36 +336,32 @@ __global__ __launch_bounds__(NW * 64, MINW) void k_layer_mfma(const uint16_t* __
   issue(1);
   issued = 2;
 
-  // Small parameters -> LDS as fp32.  Their loads are issued here, all of them before anything waits,
-  // and written to LDS once the rows of the gather are on their way too (below): a wait between two
-  // loads costs a whole trip to memory, and this prologue is a chain of such trips.
-  constexpr int PIT = (PO::TOTAL + NT - 1) / NT;
-  uint16_t par_raw[PIT];
-  float bo_raw = 0.f;
+  // The per-feature vectors (LayerNorm scales and shifts, biases) follow the fragments in the packed buffer as
+  // fp32 in the order of ParamOff: they go to LDS the way the weights do, 1 KB per instruction, spread over the
+  // wavefronts, and are there for everyone after the first barrier.
+  {
+    constexpr int PIECES = LP::PARAMS / 1024;
 #pragma unroll
-  for (int it = 0; it < PIT; ++it) {
-    const int t = tid + it * NT;
-    const int tc = t < PO::TOTAL ? t : PO::TOTAL - 1;
-    const uint16_t* src;
-    int o;
-    if (tc < 2 * C) { src = tc < C ? sp.ln1_g : sp.ln1_b; o = tc < C ? tc : tc - C; }
-    else if (tc < 3 * C) { src = sp.b_qkv; o = tc - 2 * C; }
-    else if (tc < 4 * C) { src = sp.ln1_g; o = 0; }  // the folded output bias comes from the packed stream
-    else if (tc < 6 * C) { src = tc < 5 * C ? sp.ln2_g : sp.ln2_b; o = tc < 5 * C ? tc - 4 * C : tc - 5 * C; }
-    else if (tc < 7 * C) { src = sp.b2; o = tc - 6 * C; }
-    else { src = sp.b1; o = tc - 7 * C; }
-    par_raw[it] = src[o];
-  }
-  static_assert(C <= NT, "one thread per feature of the folded bias");
-  bo_raw = reinterpret_cast<const float*>(packed + (size_t)NCHUNK * CF * 64)[tid < C ? tid : C - 1];
-  auto store_params = [&]() {
-#pragma unroll
-    for (int it = 0; it < PIT; ++it) {
-      const int t = tid + it * NT;
-      if (t < PO::TOTAL && !(t >= PO::BO && t < PO::BO + C)) par[t] = el_to_f32(par_raw[it]);
+    for (int t = 0; t < (PIECES + NW - 1) / NW; ++t) {
+      const int piece = wu + t * NW;
+      if ((t + 1) * NW <= PIECES || piece < PIECES) {  // wave-uniform
+        const u32x4* srcp = packed + ((size_t)NCHUNK * CF + piece) * 64;
+        // (LDS byte address from the ring's base: the pointer `par` sits in a vector register)
+        const uint32_t dst = (uint32_t)reinterpret_cast<uintptr_t>((__attribute__((address_space(3))) void*)ring) +
+                             (uint32_t)(RING * CF + piece) * 1024u;
+        if constexpr (LEAN) {
+          const u32x4* srcv = srcp + lane;
+          asm volatile("s_mov_b32 m0, %0\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %1, off" : : "s"(dst), "v"(srcv) : "memory", "m0");
+        } else {
+          const uint64_t src = reinterpret_cast<uint64_t>(srcp);  // wave-uniform
+          asm volatile("s_mov_b32 m0, %0\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %1, %2"
+                       :
+                       : "s"(dst), "v"(lane * 16), "s"(src)
+                       : "memory", "m0");
+        }
+      }
     }
-    if (tid < C) par[PO::BO + tid] = bo_raw;
-  };
+  }
 
   // ---- gather + LN1 ---------------------------------------------------------------------------------
   f32x4 x1[NVB][NB];  // residual stream of my pillars, accumulator layout
@@ -403,7 +399,6 @@ __global__ __launch_bounds__(NW * 64, MINW) void k_layer_mfma(const uint16_t* __
     }
   };
   if (in_sorted == 2 && guessed) {  // the early fetch hit
-    store_params();
     uint2 raw[NVB][NB];
     if constexpr (STAGE) {
       turn_rows(raw);
@@ -419,7 +414,10 @@ __global__ __launch_bounds__(NW * 64, MINW) void k_layer_mfma(const uint16_t* __
 #pragma unroll
       for (int nb = 0; nb < NB; ++nb) {
         const uint2 u = raw[vb][nb];
-        x1[vb][nb] = live ? f32x4{el_lo(u.x), el_hi(u.x), el_lo(u.y), el_hi(u.y)} : f32x4{0.f, 0.f, 0.f, 0.f};
+        // (padding slots: the bits are cleared before the conversion, two instructions per block instead of a
+        // branch around each block)
+        const uint32_t keep = live ? 0xffffffffu : 0u;
+        x1[vb][nb] = f32x4{el_lo(u.x & keep), el_hi(u.x & keep), el_lo(u.y & keep), el_hi(u.y & keep)};
       }
     }
   } else {
@@ -438,22 +436,21 @@ __global__ __launch_bounds__(NW * 64, MINW) void k_layer_mfma(const uint16_t* __
         const int32_t sr = __shfl(srcv[RPI * k / 16], (RPI * k) % 16 + lr, 64);
         rowv[k] = __builtin_nontemporal_load(reinterpret_cast<const u32x4*>(feats + (int64_t)sr * C + 8 * piece32));
       }
-      store_params();
-      turn_rows(raw);
+        turn_rows(raw);
     } else {
 #pragma unroll
       for (int vb = 0; vb < NVB; ++vb)
 #pragma unroll
         for (int nb = 0; nb < NB; ++nb)
           raw[vb][nb] = *reinterpret_cast<const uint2*>(feats + (int64_t)srcv[vb] * C + 16 * nb + 4 * q);
-      store_params();
-    }
+      }
 #pragma unroll
     for (int vb = 0; vb < NVB; ++vb)
 #pragma unroll
       for (int nb = 0; nb < NB; ++nb) {
         const uint2 u = raw[vb][nb];
-        x1[vb][nb] = row[vb] >= 0 ? f32x4{el_lo(u.x), el_hi(u.x), el_lo(u.y), el_hi(u.y)} : f32x4{0.f, 0.f, 0.f, 0.f};
+        const uint32_t keep = row[vb] >= 0 ? 0xffffffffu : 0u;
+        x1[vb][nb] = f32x4{el_lo(u.x & keep), el_hi(u.x & keep), el_lo(u.y & keep), el_hi(u.y & keep)};
       }
   }
   // Positional embedding of my pillars, still bf16, in the layout of `act` (Eq. (2), second argument
@@ -949,7 +946,7 @@ __global__ __launch_bounds__(NW * 64, MINW) void k_layer_mfma(const uint16_t* __
 template <int C, int DH, int F, int NVB, int WPG, int NW, int MINW>
 int launch_cfg(const void* feats, void* out, const void* pos_embed, const int32_t* perm, const int32_t* goff,
                const int32_t* num_groups,
-               int32_t max_groups, const u32x4* packed, const SmallParams& sp, float eps, bool out_f32, int n, int G,
+               int32_t max_groups, const u32x4* packed, float eps, bool out_f32, int n, int G,
                int drop, const int32_t* out_index, int in_sorted, hipStream_t stream) {
   constexpr int GPW = NW / WPG;
   const size_t lds_bytes = LdsPlan<C, F, NVB, WPG, NW, MINW>::TOTAL;
@@ -969,7 +966,7 @@ int launch_cfg(const void* feats, void* out, const void* pos_embed, const int32_
     }
     hipLaunchKernelGGL(kern, dim3(blocks), dim3(NW * 64), lds_bytes, stream, (const uint16_t*)feats, out,
                        (const uint16_t*)pos_embed, perm, goff,
-                       num_groups, (int)max_groups, packed, sp, eps, n, G, drop, out_index, in_sorted);
+                       num_groups, (int)max_groups, packed, eps, n, G, drop, out_index, in_sorted);
     return launch_status();
   };
   if (pos_embed) {
@@ -989,11 +986,12 @@ int launch_cfg(const void* feats, void* out, const void* pos_embed, const int32_
 
 }  // namespace
 
-// Shapes with a fused kernel: (C, head dim, F) = (128, 16, 256) and (256, 32, 512), G <= 128.
+// Shapes with a fused kernel: (C, head dim, F) = (128, 16, 256), (256, 32, 512) and (64, 16, 128), G <= 128.
 static int shape_id(const ff_layer_weights* w) {
   const int C = w->C, F = w->F, d = C / w->heads;
   if (C == 128 && d == 16 && F == 256) return 1;
   if (C == 256 && d == 32 && F == 512) return 2;
+  if (C == 64 && d == 16 && F == 128) return 3;
   return 0;
 }
 
@@ -1008,7 +1006,7 @@ static size_t layer_mfma_frag_count(const ff_layer_weights* w) {
 
 #ifndef FF_LAYER_F16
 size_t layer_mfma_packed_bytes(const ff_layer_weights* w) {
-  return layer_mfma_frag_count(w) * (size_t)1024 + (size_t)w->C * 4;
+  return layer_mfma_frag_count(w) * (size_t)1024 + (size_t)pack_param_bytes(w->C, w->F);
 }
 #endif
 
@@ -1031,12 +1029,9 @@ int FF_LAYER_SYM(layer_mfma_launch)(const void* feats, void* out, int64_t n, con
                       bool out_f32, bool drop, const void* packed, int variant, const int32_t* out_index,
                       int in_sorted, hipStream_t stream) {
   if (max_groups == 0 || n == 0) return FF_OK;
-  SmallParams sp{(const uint16_t*)w->ln1_g, (const uint16_t*)w->ln1_b, (const uint16_t*)w->b_qkv,
-                 (const uint16_t*)w->b_o,   (const uint16_t*)w->ln2_g, (const uint16_t*)w->ln2_b,
-                 (const uint16_t*)w->b1,    (const uint16_t*)w->b2};
   const u32x4* pk = (const u32x4*)packed;
 #define FF_GO(C, DH, F, NVB, WPG, NW, MINW) \
-  return launch_cfg<C, DH, F, NVB, WPG, NW, MINW>(feats, out, w->pos_embed, perm, group_offsets, num_groups, max_groups, pk, sp, \
+  return launch_cfg<C, DH, F, NVB, WPG, NW, MINW>(feats, out, w->pos_embed, perm, group_offsets, num_groups, max_groups, pk, \
                                                   w->ln_eps, out_f32, (int)n, G, drop ? 1 : 0, out_index, in_sorted, stream)
   const int shape = shape_id(w);
   // (pillar blocks per wave, waves per group, waves per workgroup, min waves per SIMD)
@@ -1073,6 +1068,14 @@ int FF_LAYER_SYM(layer_mfma_launch)(const void* feats, void* out, int64_t n, con
       case 4: if (G <= 128) FF_GO(256, 32, 512, 1, 8, 8, 2); break;
       case 5: if (G <= 64) FF_GO(256, 32, 512, 2, 2, 4, 1); break;
       case 6: if (G <= 80) FF_GO(256, 32, 512, 1, 5, 5, 1); break;
+      default: break;
+    }
+  } else if (shape == 3) {  // the narrow layer (64 features, 4 heads): the whole 64 KB weight stream stays in the ring
+    if (variant == 0) variant = G <= 32 ? 1 : G <= 64 ? 2 : 4;
+    switch (variant) {
+      case 1: if (G <= 32) FF_GO(64, 16, 128, 1, 2, 8, 2); break;
+      case 2: if (G <= 64) FF_GO(64, 16, 128, 1, 4, 8, 2); break;
+      case 4: if (G <= 128) FF_GO(64, 16, 128, 1, 8, 8, 2); break;
       default: break;
     }
   }

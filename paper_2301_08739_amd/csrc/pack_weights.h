@@ -17,6 +17,7 @@ constexpr int kPackBatch = 16;
 struct PackBatch {  // up to 16 layers of identical shape packed by one launch
   const uint16_t *w_qkv[kPackBatch], *w_o[kPackBatch], *w1[kPackBatch], *w2[kPackBatch];
   const uint16_t *b_qkv[kPackBatch], *b_o[kPackBatch];
+  const uint16_t *ln1_g[kPackBatch], *ln1_b[kPackBatch], *ln2_g[kPackBatch], *ln2_b[kPackBatch], *b1[kPackBatch], *b2[kPackBatch];
   uint4* out[kPackBatch];
 };
 // What a launch needs to know to pack `layers` layers: `blocks` workgroups of 256 threads per layer.
@@ -32,12 +33,16 @@ inline void make_pack_job(const ff_layer_weights* w, int count, void* packed, si
                           PackJob* job) {
   job->layers = count; job->C = w->C; job->F = w->F; job->half = half ? 1 : 0;
   job->total_frags = pack_frag_count(w->C, w->F);
-  job->blocks = (job->total_frags * 64 + 8 * w->C + 255) / 256;
+  // one thread per 16 bytes of a fragment, eight per folded bias element, one per other small parameter
+  job->blocks = (job->total_frags * 64 + 8 * w->C + 6 * w->C + w->F + 255) / 256;
   for (int l = 0; l < kPackBatch; ++l) {
     const ff_layer_weights* wl = &w[l < count ? l : 0];
     job->pb.w_qkv[l] = (const uint16_t*)wl->w_qkv; job->pb.w_o[l] = (const uint16_t*)wl->w_o;
     job->pb.w1[l] = (const uint16_t*)wl->w1; job->pb.w2[l] = (const uint16_t*)wl->w2;
     job->pb.b_qkv[l] = (const uint16_t*)wl->b_qkv; job->pb.b_o[l] = (const uint16_t*)wl->b_o;
+    job->pb.ln1_g[l] = (const uint16_t*)wl->ln1_g; job->pb.ln1_b[l] = (const uint16_t*)wl->ln1_b;
+    job->pb.ln2_g[l] = (const uint16_t*)wl->ln2_g; job->pb.ln2_b[l] = (const uint16_t*)wl->ln2_b;
+    job->pb.b1[l] = (const uint16_t*)wl->b1; job->pb.b2[l] = (const uint16_t*)wl->b2;
     job->pb.out[l] = (uint4*)((char*)packed + (size_t)(l < count ? l : 0) * stride_bytes);
   }
 }
@@ -51,10 +56,16 @@ template <bool HALF> __device__ __forceinline__ uint16_t pack_f32_to_el(float f)
   else return f32_to_bf16(f);
 }
 
-// After the fragments the packed buffer holds C floats: the output-projection bias with the value
-// bias folded in.  Every softmax row sums to one, so P (V + 1 b_v^T) W_o^T = P V W_o^T + (W_o b_v)^T:
-// the value bias is a constant row added after the projection.  (The key bias shifts all scores
-// of a query by the same amount and drops out of the softmax altogether.)
+// After the fragments the packed buffer holds the layer's per-feature vectors as 7C + F floats, in the order
+// the kernel keeps them in LDS (pack_param_*): LayerNorm 1 scale and shift, query bias, output-projection
+// bias, LayerNorm 2 scale and shift, second and first FFN bias.  The kernel copies that block to LDS as it is.
+// The output-projection bias has the value bias folded in.  Every softmax row sums to one, so
+// P (V + 1 b_v^T) W_o^T = P V W_o^T + (W_o b_v)^T: the value bias is a constant row added after the
+// projection.  (The key bias shifts all scores of a query by the same amount and drops out of the softmax
+// altogether.)
+__host__ __device__ constexpr int pack_param_count(int C, int F) { return 7 * C + F; }
+// bytes of the parameter block, padded to whole 1 KB pieces (the unit of the kernel's copy to LDS)
+__host__ __device__ constexpr int pack_param_bytes(int C, int F) { return (pack_param_count(C, F) * 4 + 1023) / 1024 * 1024; }
 // Work of workgroup `block` (256 threads) of layer `layer`.
 template <bool HALF>
 __device__ __forceinline__ void pack_weights_block(const PackBatch& pb, int layer, int block, int C, int F,
@@ -66,6 +77,22 @@ __device__ __forceinline__ void pack_weights_block(const PackBatch& pb, int laye
   uint4* __restrict__ out = pb.out[layer];
   const int t = block * 256 + (int)threadIdx.x;
   const int frag = t >> 6, lane = t & 63, i = lane & 15, q = lane >> 4;
+  if (frag >= total_frags && t - total_frags * 64 >= 8 * C) {  // the other per-feature vectors, one thread each
+    const int pidx = t - total_frags * 64 - 8 * C;             // 0 .. 6C + F - 1; the folded bias sits at [3C, 4C)
+    if (pidx >= 6 * C + F) return;
+    const int dst = pidx < 3 * C ? pidx : pidx + C;
+    const uint16_t* src;
+    int o;
+    if (dst < C) { src = pb.ln1_g[layer]; o = dst; }
+    else if (dst < 2 * C) { src = pb.ln1_b[layer]; o = dst - C; }
+    else if (dst < 3 * C) { src = pb.b_qkv[layer]; o = dst - 2 * C; }
+    else if (dst < 5 * C) { src = pb.ln2_g[layer]; o = dst - 4 * C; }
+    else if (dst < 6 * C) { src = pb.ln2_b[layer]; o = dst - 5 * C; }
+    else if (dst < 7 * C) { src = pb.b2[layer]; o = dst - 6 * C; }
+    else { src = pb.b1[layer]; o = dst - 7 * C; }
+    reinterpret_cast<float*>(out + (size_t)total_frags * 64)[dst] = pack_el_to_f32<HALF>(src[o]);
+    return;
+  }
   if (frag >= total_frags) {  // folded output bias: eight lanes per output feature
     const int u = t - total_frags * 64, o = u >> 3, seg = u & 7, len = C / 8;
     float acc = 0.f;
@@ -94,7 +121,7 @@ __device__ __forceinline__ void pack_weights_block(const PackBatch& pb, int laye
     acc += __shfl_xor(acc, 2);
     acc += __shfl_xor(acc, 4);
     if (o < C && seg == 0)
-      reinterpret_cast<float*>(out + (size_t)total_frags * 64)[o] = acc + pack_el_to_f32<HALF>(pb.b_o[layer][o]);
+      reinterpret_cast<float*>(out + (size_t)total_frags * 64)[3 * C + o] = acc + pack_el_to_f32<HALF>(pb.b_o[layer][o]);
     return;
   }
   const int KB = C / 32, NB = C / 16, fr_hp = 6 * KB + NB, fr_fc = 2 * KB + NB, n_hp = C / 32;

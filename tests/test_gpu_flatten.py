@@ -129,3 +129,25 @@ def test_more_than_1024_tiles():
     g, og = ff.Geometry(8, 1024, 1024, 13, 13), oracle.Geometry(8, 1024, 1024, 13, 13)
     print(f"flatten n={n}: oracle sort running", flush=True)
     _check(coords, g, og, 1, 1, 64)
+
+
+@pytest.mark.parametrize("i,tail", [(1, ff.FF_TAIL_MASK), (2, ff.FF_TAIL_MASK), (2, ff.FF_TAIL_DROP), (5, ff.FF_TAIL_MASK)])
+def test_batched_sorts_equal_single_sorts(cfg, i, tail):
+    """ff_flatten_batch (the four sort configurations of a block in one launch set, 'Reuse Sorting') gives
+    what four ff_flatten calls give; those are held against the oracle above."""
+    c = cfg(i, 1)
+    g, _ = geoms(c)
+    ct = torch.from_numpy(c["coords"]).to("cuda")
+    sorts = [(0, 0), (1, 0), (0, 1), (1, 1)]
+    for S in (4, 3, 1):
+        got = ff.ff_flatten_batch(ct, g, sorts[:S], c["G"], tail=tail)
+        torch.cuda.synchronize()
+        for (axis, shift), (perm, goff, ng) in zip(sorts, got):
+            wperm, wgoff, wng, _ = ff.ff_flatten(ct, g, axis, shift, c["G"], tail=tail)
+            k = int(wng.item())
+            assert int(ng.item()) == k
+            assert torch.equal(perm, wperm) and torch.equal(goff[:k + 1], wgoff[:k + 1])
+    with pytest.raises(ff.FlatformerError):
+        ff.ff_flatten_batch(ct, g, sorts + [(0, 0)], c["G"])
+    with pytest.raises(ff.FlatformerError):
+        ff.ff_flatten_batch(ct, g, [(0, 2)], c["G"])
