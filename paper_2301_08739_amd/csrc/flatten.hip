@@ -172,8 +172,10 @@ __device__ __forceinline__ uint64_t exported_key(uint64_t k, const KeyParams& kp
 // a launch of its own in front of the first layer.  Such a launch has a wider grid; the workgroups
 // are numbered in dispatch order, the first tiles * sorts of them sort, the rest pack.
 __device__ __forceinline__ void pack_tail(const PackJob& pack, int id) {
-  const int layer = id / pack.blocks, blk = id - layer * pack.blocks;
+  int layer = id / pack.blocks;
+  const int blk = id - layer * pack.blocks;
   if (layer >= pack.layers) return;
+  layer += pack.first;
   if (pack.half) pack_weights_block<true>(pack.pb, layer, blk, pack.C, pack.F, pack.total_frags);
   else pack_weights_block<false>(pack.pb, layer, blk, pack.C, pack.F, pack.total_frags);
 }
@@ -471,6 +473,7 @@ __global__ __launch_bounds__(kSortThreads) void k_pass(const uint64_t* __restric
 #pragma unroll
     for (int r = 0; r < KPT; ++r) {
       const int j = r * kSortThreads + tid;
+      uint32_t slot = 0xffffffffu;  // table entry of the next pass this word counts for (none: no word here)
       if (j < tile_count) {
         const uint64_t k = stage[j];
         const uint32_t d = digit_rb(k, idx_bits, key_bits, pass, RB);
@@ -478,7 +481,21 @@ __global__ __launch_bounds__(kSortThreads) void k_pass(const uint64_t* __restric
         if (pos < n) {
           out[pos] = k;
           if (!SCANNED && pass + 1 < P)  // small clouds: the next pass finds this word in tile pos / TILE
-            atomicAdd(&next_tab[(size_t)(pos / TILE) * BINS + digit_rb(k, idx_bits, key_bits, pass + 1, RB)], 1u);
+            slot = (uint32_t)(pos / TILE) * BINS + digit_rb(k, idx_bits, key_bits, pass + 1, RB);
+        }
+      }
+      if (!SCANNED && pass + 1 < P) {
+        // One atomic per run of neighbouring lanes that count the same table entry.  Words next to each other in
+        // the stage share this pass's digit and land side by side; when the cloud arrives in an order that
+        // follows the grid (a voxeliser's row-major output) they mostly share the next digit as well, and
+        // one atomic per word then queues up on a few addresses.
+        const uint32_t prev = __shfl_up(slot, 1, 64);
+        const bool head = lane == 0 || prev != slot;
+        const uint64_t heads = __ballot(head);
+        if (head && slot != 0xffffffffu) {
+          const uint64_t later = lane == 63 ? 0ull : (heads >> (lane + 1));
+          const uint32_t run = later ? (uint32_t)__builtin_ctzll(later) + 1u : 64u - (uint32_t)lane;
+          atomicAdd(&next_tab[slot], run);
         }
       }
     }
@@ -853,11 +870,22 @@ static int flatten_launch_impl(const int32_t* coords, const PointCells* pts, int
     PackJob no_job = PackJob();
     no_job.layers = 0; no_job.blocks = 1;
     const PackJob job = pack ? *pack : no_job;
-    const dim3 grid_pack((unsigned)(pp.tiles + ceil_div((int64_t)job.layers * job.blocks, num_sorts)), (unsigned)num_sorts);
+    // With radix passes to run, the layers are shared out between key generation and the first pass (both
+    // launches are short and leave most compute units idle; one of them alone would be stretched by the packing).
+    PackJob job_a = job, job_b = no_job;   // job_a: key generation (everything when there is no pass), job_b: first pass
+    if (pp.passes > 0 && job.layers > 0) {
+      job_a.layers = job.layers / 2;
+      job_b = job;
+      job_b.first = job_a.layers;
+      job_b.layers = job.layers - job_a.layers;
+      if (job_a.layers == 0) job_a = no_job;
+    }
+    const dim3 grid_a((unsigned)(pp.tiles + ceil_div((int64_t)job_a.layers * job_a.blocks, num_sorts)), (unsigned)num_sorts);
+    const dim3 grid_pack((unsigned)(pp.tiles + ceil_div((int64_t)job_b.layers * job_b.blocks, num_sorts)), (unsigned)num_sorts);
 #define FF_PASSES(RB, KPT, SCANNED)                                                                                  \
     do {                                                                                                             \
-      hipLaunchKernelGGL((k_keygen<RB, KPT>), pp.passes > 0 ? grid : grid_pack, block, 0, stream, coords, n, bt, P,  \
-                         pp.tiles, buf[0], counts, pp.passes > 0 ? no_job : job, point_src);                          \
+      hipLaunchKernelGGL((k_keygen<RB, KPT>), grid_a, block, 0, stream, coords, n, bt, P, pp.tiles, buf[0], counts,  \
+                         job_a, point_src);                                                                          \
       for (int pass = 0; pass < pp.passes; ++pass) {                                                                 \
         if (SCANNED) {                                                                                               \
           if (pass > 0)                                                                                              \
@@ -873,11 +901,11 @@ static int flatten_launch_impl(const int32_t* coords, const PointCells* pts, int
         if (fuse && pass == pp.passes - 1)                                                                           \
           hipLaunchKernelGGL((k_pass<RB, KPT, true, SCANNED>), pass == 0 ? grid_pack : grid, block, 0, stream,      \
                              buf[cur], buf[cur ^ 1], n, bt, pass, P, pp.tiles, G, drop, counts, totals,              \
-                             pass == 0 ? job : no_job);                                                              \
+                             pass == 0 ? job_b : no_job);                                                              \
         else                                                                                                         \
           hipLaunchKernelGGL((k_pass<RB, KPT, false, SCANNED>), pass == 0 ? grid_pack : grid, block, 0, stream,     \
                              buf[cur], buf[cur ^ 1], n, bt, pass, P, pp.tiles, G, drop, counts, totals,              \
-                             pass == 0 ? job : no_job);                                                              \
+                             pass == 0 ? job_b : no_job);                                                              \
         cur ^= 1;                                                                                                    \
       }                                                                                                              \
     } while (0)

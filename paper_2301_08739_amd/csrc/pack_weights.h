@@ -24,6 +24,7 @@ struct PackBatch {  // up to 16 layers of identical shape packed by one launch
 struct PackJob {
   PackBatch pb;
   int layers, C, F, total_frags, blocks, half;  // half: IEEE half elements instead of bfloat16
+  int first;                                    // a launch packs layers first .. first + layers - 1 of the batch
 };
 
 inline int pack_frag_count(int C, int F) { return (C / 32) * (6 * (C / 32) + C / 16) + (F / 32) * (2 * (C / 32) + C / 16); }
@@ -31,6 +32,7 @@ inline int pack_frag_count(int C, int F) { return (C / 32) * (6 * (C / 32) + C /
 // Layers w[0..count) (count <= kPackBatch) to packed + l * stride_bytes.
 inline void make_pack_job(const ff_layer_weights* w, int count, void* packed, size_t stride_bytes, bool half,
                           PackJob* job) {
+  job->first = 0;
   job->layers = count; job->C = w->C; job->F = w->F; job->half = half ? 1 : 0;
   job->total_frags = pack_frag_count(w->C, w->F);
   // one thread per 16 bytes of a fragment, eight per folded bias element, one per other small parameter
