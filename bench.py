@@ -251,8 +251,9 @@ def main():
 
     # ---- the second input order: cells in row-major order, what a voxeliser's `unique` emits (the timed
     # workload keeps first-occurrence order); the gather's locality differs ----
-    order = ffsynth.row_major_order(c["coords"])
+    order = np.lexsort((c["coords"][:, 2], c["coords"][:, 1], c["coords"][:, 0]))
     coords_rm = torch.from_numpy(np.ascontiguousarray(c["coords"][order])).to(dev)
+    assert np.array_equal(coords_rm.cpu().numpy(), ffsynth.row_major_order(c["coords"]))
     feats_rm = feats[torch.from_numpy(order).to(dev)].contiguous()
     ms_rm, _ = time_region(lambda: ff.ff_fwa_block(coords_rm, geom, G, layers, dt, feats_rm, out=out, workspace=ws,
                                                    tail=tail, pos_embed=pe), a.steps, a.warmup)

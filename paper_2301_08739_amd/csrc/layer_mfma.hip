@@ -103,11 +103,16 @@ __device__ __forceinline__ f32x4 mfma32(const Frag8& a, const Frag8& b, f32x4 c)
   return __builtin_amdgcn_mfma_f32_16x16x32_bf16(a.v, b.v, c, 0, 0, 0);
 #endif
 }
-__device__ __forceinline__ f32x4 mfma16(const Frag4& a, const Frag4& b, f32x4 c) {
+// The k = 16 product takes no accumulator: it can only START a chain, from zero.  A k = 16 product issued right
+// behind a k = 32 product that writes the accumulator it reads has been seen to read the old value on this chip,
+// so every product that continues a chain goes through mfma32 (an odd 16-wide block multiplies zeros in its
+// upper half), and this signature keeps a chained k = 16 call from compiling.
+__device__ __forceinline__ f32x4 mfma16_from_zero(const Frag4& a, const Frag4& b) {
+  const f32x4 z = {0.f, 0.f, 0.f, 0.f};
 #ifdef FF_LAYER_F16
-  return __builtin_amdgcn_mfma_f32_16x16x16f16(a.v, b.v, c, 0, 0, 0);
+  return __builtin_amdgcn_mfma_f32_16x16x16f16(a.v, b.v, z, 0, 0, 0);
 #else
-  return __builtin_amdgcn_mfma_f32_16x16x16bf16_1k(a.v, b.v, c, 0, 0, 0);
+  return __builtin_amdgcn_mfma_f32_16x16x16bf16_1k(a.v, b.v, z, 0, 0, 0);
 #endif
 }
 // GELU(v) = v * Phi(v) with the upper tail 1 - Phi(t) ~ 0.5 * exp(-(a t + b t^2 + c t^3)), t = |v|
@@ -705,7 +710,7 @@ __global__ __launch_bounds__(NW * 64, MINW) void k_layer_mfma(const uint16_t* __
             if (DH == 16) {
               // the only k=16 products left: their accumulator input is zero, so they depend on no
               // earlier product (see the note at the odd key block below)
-              S[hh][vb][jb] = mfma16(Kget(h, jb), Qf[h][v0 + vb], z);
+              S[hh][vb][jb] = mfma16_from_zero(Kget(h, jb), Qf[h][v0 + vb]);
             } else {
               Frag8 k8, q8;
               const Frag4 k0 = Kget(0, jb), k1 = Kget(1, jb);

@@ -151,3 +151,36 @@ def test_batched_sorts_equal_single_sorts(cfg, i, tail):
         ff.ff_flatten_batch(ct, g, sorts + [(0, 0)], c["G"])
     with pytest.raises(ff.FlatformerError):
         ff.ff_flatten_batch(ct, g, [(0, 2)], c["G"])
+
+
+def test_few_frames_single_duplicates_and_sparse_ranges():
+    """Up to eight frames with an empty one, a single duplicated pair at the front, in the middle and at the end
+    of an otherwise duplicate-free cloud, a handful of pillars at the grid's corners, windows of 1 and of 256,
+    nine frames, dropped tails through the batched call: all equal to the oracle."""
+    g, og = ff.Geometry(8, 468, 468, 13, 13), oracle.Geometry(8, 468, 468, 13, 13)
+    coords = _rand_coords(40000, 8, 468, 468, seed=5)
+    coords[:, 0] = np.where(coords[:, 0] == 3, 5, coords[:, 0])           # frame 3 is empty
+    for axis, shift in SORTS:
+        _check(coords, g, og, axis, shift, 64)
+    for at, src in [(0, 1), (20000, 7), (39999, 39998)]:                  # one duplicated pair
+        c2 = coords.copy()
+        c2[at] = c2[src]
+        _check(c2, g, og, 0, 1, 64)
+        _check(c2, g, og, 1, 0, 50)
+    corners = np.array([[0, 0, 0], [7, 467, 467], [0, 467, 0], [7, 0, 467], [4, 233, 233]], dtype=np.int32)
+    for axis, shift in SORTS:
+        _check(corners, g, og, axis, shift, 2)
+    g1, og1 = ff.Geometry(1, 700, 650, 1, 256), oracle.Geometry(1, 700, 650, 1, 256)   # windows of 1 and of 256
+    c1 = _rand_coords(30000, 1, 700, 650, seed=9)
+    for axis, shift in SORTS:
+        _check(c1, g1, og1, axis, shift, 64)
+    g9, og9 = ff.Geometry(9, 468, 468, 13, 13), oracle.Geometry(9, 468, 468, 13, 13)
+    _check(coords, g9, og9, 0, 0, 64)
+    # drop mode through the batched call
+    ct = torch.from_numpy(coords).to("cuda")
+    for (axis, shift), (perm, goff, ng) in zip(SORTS, ff.ff_flatten_batch(ct, g, SORTS, 64, tail=ff.FF_TAIL_DROP)):
+        wperm, starts, _ = oracle.flatten(coords, og, axis, shift, 64, tail="drop")
+        k = int(ng.item())
+        assert k == len(starts)
+        assert np.array_equal(perm.cpu().numpy(), wperm) and np.array_equal(goff.cpu().numpy()[:k], starts)
+        assert int(goff[k].item()) == coords.shape[0]
