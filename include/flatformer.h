@@ -95,6 +95,15 @@ int ff_flatten(const int32_t* coords /* [n,3] (b,x,y) */, int64_t n, const ff_ge
                int32_t* perm, int32_t* group_offsets, int32_t* num_groups,
                uint64_t* keys_sorted, void* workspace, size_t workspace_bytes, void* stream);
 
+/* ---- coordinate check (a debugging aid; the sorts never need it) ---------------------------------------------
+ * ff_flatten and the blocks stay memory-safe with coordinates outside the geometry, but the order they then
+ * produce is unspecified.  This call counts such rows on the device: result[0] = number of rows of coords
+ * with a frame, x or y outside [0, num_frames) x [0, grid_x) x [0, grid_y), result[1] = index of the first
+ * such row, n if there is none.  result: device int32 [2].  Asynchronous like every other call; the caller
+ * reads the two words after synchronising the stream. */
+int ff_check_coords(const int32_t* coords /* [n,3] (b,x,y) */, int64_t n, const ff_geom* g,
+                    int32_t* result /* device [2] */, void* stream);
+
 /* ---- several sort configurations of one cloud in one call ('Reuse Sorting', Sec. 4.3: the coordinates do
  * not change inside a stage, so each (axis, shift) pair is sorted once and reused by every layer and block
  * that needs it).  num_sorts (1..4) configurations axis[s], shift[s] are sorted together, one launch set for

@@ -85,6 +85,7 @@ _SIGS = {
     "ff_flatten_workspace_bytes": (C.c_size_t, [C.c_int64, C.POINTER(Geometry)]),
     "ff_flatten": (C.c_int, [C.c_void_p, C.c_int64, C.POINTER(Geometry), C.c_int, C.c_int, C.c_int, C.c_int,
                              C.c_void_p, C.c_void_p, C.c_void_p, C.c_void_p, C.c_void_p, C.c_size_t, C.c_void_p]),
+    "ff_check_coords": (C.c_int, [C.c_void_p, C.c_int64, C.POINTER(Geometry), C.c_void_p, C.c_void_p]),
     "ff_flatten_batch_workspace_bytes": (C.c_size_t, [C.c_int64, C.POINTER(Geometry), C.c_int]),
     "ff_flatten_batch": (C.c_int, [C.c_void_p, C.c_int64, C.POINTER(Geometry), C.c_int, C.POINTER(C.c_int),
                                    C.POINTER(C.c_int), C.c_int, C.c_int, C.POINTER(C.c_void_p), C.POINTER(C.c_void_p),
@@ -197,6 +198,15 @@ def ff_flatten(coords, geom, axis, shift, G, tail=FF_TAIL_MASK, want_keys=False,
                         _ptr(keys), C.c_void_p(_aligned_ptr(ws)), ws.numel() - 256, _stream())
     _check(st, "ff_flatten")
     return perm, goff, ng, keys
+
+
+def ff_check_coords(coords, geom):
+    """Device tensor int32 [2]: (rows of coords outside the geometry, index of the first one or n)."""
+    lib = load_library()
+    assert coords.dtype == torch.int32 and coords.is_contiguous() and coords.is_cuda and coords.shape[1] == 3
+    res = torch.empty(2, dtype=torch.int32, device=coords.device)
+    _check(lib.ff_check_coords(_ptr(coords), coords.shape[0], C.byref(geom), _ptr(res), _stream()), "ff_check_coords")
+    return res
 
 
 def ff_flatten_batch_workspace_bytes(n, geom, num_sorts):

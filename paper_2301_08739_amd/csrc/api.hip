@@ -44,6 +44,10 @@ int ff_flatten(const int32_t* coords, int64_t n, const ff_geom* g, int axis, int
                         workspace, workspace_bytes, nullptr, (hipStream_t)stream);
 }
 
+int ff_check_coords(const int32_t* coords, int64_t n, const ff_geom* g, int32_t* result, void* stream) {
+  return check_coords_launch(coords, n, g, result, (hipStream_t)stream);
+}
+
 size_t ff_flatten_batch_workspace_bytes(int64_t n, const ff_geom* g, int num_sorts) {
   return flatten_workspace_bytes(n, g, num_sorts);
 }

@@ -98,6 +98,9 @@ int rows_copy_ungrouped_launch(const void* feats, void* out, int64_t n, const in
                                const int32_t* group_offsets, const int32_t* num_groups, int32_t max_groups, int C,
                                int G, int dtype, bool out_f32, hipStream_t stream);
 
+// result[0] = rows of coords outside the geometry, result[1] = index of the first one (n: none)
+int check_coords_launch(const int32_t* coords, int64_t n, const ff_geom* g, int32_t* result, hipStream_t stream);
+
 // bev [num_frames][grid_y][grid_x][C] = rows of feats at their pillars' cells, zero elsewhere
 int bev_scatter_launch(const void* feats, const int32_t* coords, int64_t n, const ff_geom* g, int C, int dtype,
                        void* bev, hipStream_t stream);

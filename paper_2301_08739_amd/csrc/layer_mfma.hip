@@ -975,9 +975,9 @@ int launch_cfg(const void* feats, void* out, const void* pos_embed, const int32_
     return launch_status();
   };
   if (pos_embed) {
-    // Two mappings have no registers left for the second operand set (they would spill, which no
+    // Three mappings have no registers left for the second operand set (they would spill, which no
     // shipped mapping may): they are not built with a positional embedding.
-    constexpr bool kFits = !(C == 128 && NVB == 2 && WPG == 1) && !(C == 256 && NW == 10);
+    constexpr bool kFits = !(C == 128 && NVB == 2 && WPG == 1) && !(C == 256 && NW == 10) && !(C == 128 && NW == 12);
     if constexpr (kFits) {
       if (out_f32) return go(k_layer_mfma<C, DH, F, NVB, WPG, NW, MINW, true, true>, 3);
       return go(k_layer_mfma<C, DH, F, NVB, WPG, NW, MINW, false, true>, 2);
@@ -1050,7 +1050,8 @@ int FF_LAYER_SYM(layer_mfma_launch)(const void* feats, void* out, int64_t n, con
       // 1406 groups 49 vs 48, 1875 groups 68 vs 71, 2343 groups 79 vs 89, 2812 groups 94 vs 90).
       const int64_t rounds2 = ceil_div(ceil_div((int64_t)max_groups, 2), kComputeUnits);
       const int64_t rounds3 = ceil_div(ceil_div((int64_t)max_groups, 3), kComputeUnits);
-      variant = G <= 32 ? 10 : G <= 64 ? (rounds3 * 228 < rounds2 * 168 ? 11 : 7) : 9;
+      // (the three-group mapping has no registers for a positional embedding)
+      variant = G <= 32 ? 10 : G <= 64 ? (rounds3 * 228 < rounds2 * 168 && !w->pos_embed ? 11 : 7) : 9;
     }
     switch (variant) {
       case 1: if (G <= 32) FF_GO(128, 16, 256, 2, 1, 4, 2); break;

@@ -102,6 +102,45 @@ int bev_scatter_launch(const void* feats, const int32_t* coords, int64_t n, cons
   return launch_status();
 }
 
+// ---- coordinate check: how many rows of coords lie outside the geometry -------------------------------------
+// result[0] = rows with a frame, x or y outside [0, num_frames) x [0, grid_x) x [0, grid_y), result[1] = index of
+// the first such row (n if there is none).  Two launches: the two words are set, then every workgroup adds its
+// count (and lowers the index) with one atomic each.
+__global__ void k_check_init(int32_t* __restrict__ result, int32_t n) { result[0] = 0; result[1] = n; }
+
+__global__ __launch_bounds__(256) void k_check_coords(const int32_t* __restrict__ coords, int64_t n, int B, int gx, int gy,
+                                                       int32_t* __restrict__ result) {
+  __shared__ uint32_t bad_s;
+  __shared__ int32_t first_s;
+  if (threadIdx.x == 0) { bad_s = 0u; first_s = 0x7fffffff; }
+  __syncthreads();
+  uint32_t bad = 0;
+  int32_t first = 0x7fffffff;
+  for (int64_t i = (int64_t)blockIdx.x * blockDim.x + threadIdx.x; i < n; i += (int64_t)gridDim.x * blockDim.x) {
+    const int32_t b = coords[3 * i], x = coords[3 * i + 1], y = coords[3 * i + 2];
+    if ((uint32_t)b >= (uint32_t)B || (uint32_t)x >= (uint32_t)gx || (uint32_t)y >= (uint32_t)gy) {
+      ++bad;
+      if ((int32_t)i < first) first = (int32_t)i;
+    }
+  }
+  if (bad) { atomicAdd(&bad_s, bad); atomicMin(&first_s, first); }
+  __syncthreads();
+  if (threadIdx.x == 0 && bad_s) { atomicAdd(&result[0], (int32_t)bad_s); atomicMin(&result[1], first_s); }
+}
+
+int check_coords_launch(const int32_t* coords, int64_t n, const ff_geom* g, int32_t* result, hipStream_t stream) {
+  if (!g || n < 0 || n > 0x7fffffffLL || !result || (n > 0 && !coords)) return FF_ERR_ARG;
+  if (g->num_frames < 1 || g->grid_x < 1 || g->grid_y < 1) return FF_ERR_ARG;
+  hipLaunchKernelGGL(k_check_init, dim3(1), dim3(1), 0, stream, result, (int32_t)n);
+  if (n > 0) {
+    int64_t blocks = ceil_div(n, 256 * 4);
+    if (blocks > 256 * 8) blocks = 256 * 8;
+    hipLaunchKernelGGL(k_check_coords, dim3((unsigned)blocks), dim3(256), 0, stream, coords, n, g->num_frames, g->grid_x,
+                       g->grid_y, result);
+  }
+  return launch_status();
+}
+
 int rows_copy_ungrouped_launch(const void* feats, void* out, int64_t n, const int32_t* perm,
                                const int32_t* group_offsets, const int32_t* num_groups, int32_t max_groups, int C,
                                int G, int dtype, bool out_f32, hipStream_t stream) {

@@ -184,3 +184,26 @@ def test_few_frames_single_duplicates_and_sparse_ranges():
         assert k == len(starts)
         assert np.array_equal(perm.cpu().numpy(), wperm) and np.array_equal(goff.cpu().numpy()[:k], starts)
         assert int(goff[k].item()) == coords.shape[0]
+
+
+def test_coordinate_check_and_safety_outside_the_geometry():
+    """ff_check_coords counts the rows outside the geometry and names the first; ff_flatten on such a cloud still
+    returns a permutation and touches nothing outside its buffers (guard words around perm stay intact)."""
+    g = ff.Geometry(2, 100, 80, 7, 5)
+    coords = _rand_coords(5000, 2, 100, 80, seed=11)
+    ct = torch.from_numpy(coords).to("cuda")
+    assert ff.ff_check_coords(ct, g).cpu().tolist() == [0, 5000]
+    assert ff.ff_check_coords(ct[:0], g).cpu().tolist() == [0, 0]
+    bad = coords.copy()
+    bad[77] = (2, 5, 5)            # frame beyond the last
+    bad[300] = (0, -1, 5)          # negative x
+    bad[301] = (1, 99, 80)         # y == grid_y
+    bad[4999] = (-3, 2**30, -2**31)
+    bt = torch.from_numpy(bad).to("cuda")
+    assert ff.ff_check_coords(bt, g).cpu().tolist() == [4, 77]
+    for axis, shift in SORTS:
+        perm, goff, ng, _ = ff.ff_flatten(bt, g, axis, shift, 16)
+        torch.cuda.synchronize()
+        assert np.array_equal(np.sort(perm.cpu().numpy()), np.arange(5000))
+        k = int(ng.item())
+        assert 0 < k <= 5000 // 16 + 3 and int(goff[k].item()) == 5000
