@@ -223,6 +223,14 @@ def main():
         ff.ff_fwa_block(coords, geom, G, layers, dt, feats, out=out, workspace=ws, tail=tail, pos_embed=pe)
 
     ms, wall_ms, step_stats = time_region(step, a.steps, a.warmup, stats=True)
+    # how long the host needs to issue a step (the launches are asynchronous: the loop returns before the GPU is
+    # done; the GPU time above is only meaningful while this stays below it)
+    torch.cuda.synchronize()
+    t0 = time.perf_counter()
+    for _ in range(a.steps):
+        step()
+    host_issue_ms = (time.perf_counter() - t0) * 1e3 / a.steps
+    torch.cuda.synchronize()
     # the same block replayed from a HIP graph: the kernels without the host's issue time between them
     ms_graph = graph_replay_ms(step, a.steps)
 
@@ -371,7 +379,7 @@ def main():
             "voxelize": dict(hbm(bytes_vox, ms_vox), points=m_pts, pillars=n_vox, point_feats=cp,
                              Mpoints_s=m_pts / ms_vox / 1e3),
             "bev_scatter": hbm(bytes_bev, ms_bev),
-            "wall_ms_per_step": wall_ms,
+            "wall_ms_per_step": wall_ms, "host_issue_ms_per_step": host_issue_ms,
             "two_frames_in_flight": {"streams": 2, "ms_per_step": ms_two, "voxels_s": n / (ms_two * 1e-3),
                                      "equals_single_stream": two_ok},
             "row_major_input_order": {"ms_per_step": ms_rm, "voxels_s": n / (ms_rm * 1e-3)},
