@@ -106,3 +106,12 @@ def test_argument_errors_are_reported_before_any_launch():
     assert lib.ff_voxelize(one, null, one, 10, 4, gp, ctypes.byref(v), one, one, one, null, one, 1 << 30, null) == -1
     assert lib.ff_fwa_block(one, 10, gp, 64, 9, wp, 1, 1, one, ctypes.c_void_p(1 << 20), one, 1 << 30, null) == -1   # tail mode
     assert lib.ff_fwa_block(one, 10, gp, 64, 0, wp, 1, 1, one, ctypes.c_void_p(1 << 20), one, 16, null) == -3
+
+
+def test_bench_only_library_exports_its_two_entry_points():
+    import paper_2301_08739_amd as ff
+    path = os.path.join(os.path.dirname(ff.library_path()), "libffpeaks.so")
+    if not os.path.exists(path):
+        pytest.skip("library not built (run __graft_entry__.build())")
+    lib = ctypes.CDLL(path)
+    assert hasattr(lib, "ffpeak_stream_copy") and hasattr(lib, "ffpeak_mfma_bf16")
