@@ -410,7 +410,7 @@ def main():
     print(json.dumps(res), flush=True)
     if a.sweep:
         for B in (1, 8, 32, 128, 512):
-            line = saturation_point(ff, torch, c, dt, dev, B, (0,) if dt == ff.FF_F32 else (6, 7, 11))
+            line = saturation_point(ff, torch, c, dt, dev, B, (0,) if dt == ff.FF_F32 else (6, 7, 11, 12))
             print(json.dumps(line), file=sys.stderr, flush=True)
 
 

@@ -195,7 +195,8 @@ __global__ __launch_bounds__(NW * 64, MINW) void k_layer_mfma(const uint16_t* __
   // C = 128: the unit loops are unrolled completely, which turns the ring bookkeeping into constants
   // (about 30 KB of code).  Wider layers keep rolled loops.
   constexpr int FULL_UNROLL = C <= 128 && NW <= 8 ? 16 : 1;  // more waves per SIMD leave too few registers for it
-  constexpr bool LEAN = (NW + 3) / 4 >= 3 && MINW <= 2 && C >= 256;  // three wavefronts on a SIMD: 168 registers each
+  constexpr bool LEAN = ((NW + 3) / 4 >= 3 && MINW <= 2 && C >= 256) || MINW >= 4;  // C = 256 with three wavefronts on a SIMD
+                                                                              // (168 registers each), C = 128 with four (128)
   constexpr int PF = LEAN ? 4 : kWindow;
   using LP = LdsPlan<C, F, NVB, WPG, NW, MINW>;
   constexpr int NCHUNK = LP::NCHUNK, RING = LP::RING;
@@ -692,7 +693,7 @@ __global__ __launch_bounds__(NW * 64, MINW) void k_layer_mfma(const uint16_t* __
     // lockstep stages so that the long per-instance dependency chains interleave.  HJ heads are
     // staged jointly, limited by the registers the score tiles take.
     constexpr int VJ = NVB * NKB <= 16 ? NVB : (16 / NKB >= 1 ? 16 / NKB : 1);
-    constexpr int HJ = (NH * VJ * NKB <= 16) ? NH : 1;
+    constexpr int HJ = (NH * VJ * NKB <= 16 && MINW < 4) ? NH : 1;
     static_assert(NVB % VJ == 0, "pillar blocks per stage");
 #pragma unroll
     for (int v0 = 0; v0 < NVB; v0 += VJ)
@@ -1041,17 +1042,18 @@ int FF_LAYER_SYM(layer_mfma_launch)(const void* feats, void* out, int64_t n, con
   const int shape = shape_id(w);
   // (pillar blocks per wave, waves per group, waves per workgroup, min waves per SIMD)
   if (shape == 1) {
-    // many groups: three groups per workgroup (three waves per SIMD) hide more latency than the unrolled
-    // two-group mapping gains from constant folding
     if (variant == 0) {
-      // G <= 64: two groups per workgroup (8 wavefronts, one workgroup per compute unit, about 16.8 us a
-      // round at this shape) or three (12 wavefronts, 22.8 us a round).  Three win by a tenth once there
-      // are many rounds; below that the number of rounds decides (measured: 937 groups 34 vs 46 us,
-      // 1406 groups 49 vs 48, 1875 groups 68 vs 71, 2343 groups 79 vs 89, 2812 groups 94 vs 90).
-      const int64_t rounds2 = ceil_div(ceil_div((int64_t)max_groups, 2), kComputeUnits);
-      const int64_t rounds3 = ceil_div(ceil_div((int64_t)max_groups, 3), kComputeUnits);
+      // G <= 64: two, three or four groups per workgroup (8, 12, 16 wavefronts; one workgroup per compute unit).
+      // More wavefronts on a SIMD hide more of each other's stalls, but a round (one workgroup per compute
+      // unit) takes longer and the loops are no longer unrolled: 16.4, 24.0 and 29.3 us a round at this shape.
+      // Many rounds: four groups lead (60,000 groups: 1.77, 1.69, 1.60 ms); few: the number of rounds decides
+      // (measured, in us: 938 groups 34 / 47 / 31, 1407: 49 / 51 / 59, 1875: 65 / 73 / 60, 2344: 81 / 94 / 86,
+      // 3750: 130 / 129 / 119, 7500: 255 / 240 / 228).
+      auto rounds = [&](int per_wg) { return ceil_div(ceil_div((int64_t)max_groups, per_wg), kComputeUnits); };
+      const int64_t c2 = rounds(2) * 164, c4 = rounds(4) * 293;
       // (the three-group mapping has no registers for a positional embedding)
-      variant = G <= 32 ? 10 : G <= 64 ? (rounds3 * 228 < rounds2 * 168 && !w->pos_embed ? 11 : 7) : 9;
+      const int64_t c3 = w->pos_embed ? INT64_MAX : rounds(3) * 240;
+      variant = G <= 32 ? 10 : G > 64 ? 9 : (c2 <= c3 && c2 <= c4) ? 7 : c3 <= c4 ? 11 : 12;
     }
     switch (variant) {
       case 1: if (G <= 32) FF_GO(128, 16, 256, 2, 1, 4, 2); break;
@@ -1062,6 +1064,7 @@ int FF_LAYER_SYM(layer_mfma_launch)(const void* feats, void* out, int64_t n, con
       case 9: if (G <= 128) FF_GO(128, 16, 256, 1, 8, 8, 2); break;
       case 10: if (G <= 32) FF_GO(128, 16, 256, 1, 2, 8, 2); break;
       case 11: if (G <= 64) FF_GO(128, 16, 256, 1, 4, 12, 3); break;  // three groups, three waves per SIMD
+      case 12: if (G <= 64) FF_GO(128, 16, 256, 1, 4, 16, 4); break;  // four groups, four waves per SIMD
       default: break;
     }
   } else if (shape == 2) {

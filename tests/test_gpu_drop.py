@@ -85,7 +85,7 @@ def test_layer_fp32_plain_kernels(cfg):
         print(f"drop fp32 n={n} B={B} G={G}: {int((~grouped).sum())} rows skipped", flush=True)
 
 
-@pytest.mark.parametrize("i,G,variants", [(2, 32, (0, 1, 10)), (2, 64, (0, 2, 6, 7, 11)), (2, 100, (0, 4, 9)),
+@pytest.mark.parametrize("i,G,variants", [(2, 32, (0, 1, 10)), (2, 64, (0, 2, 6, 7, 11, 12)), (2, 100, (0, 4, 9)),
                                           (5, 64, (0, 2, 5)), (5, 80, (0, 3, 6)), (5, 128, (0, 4))])
 def test_layer_bf16_fused_kernel(cfg, i, G, variants):
     c = cfg(i, 1)

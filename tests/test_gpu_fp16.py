@@ -39,7 +39,7 @@ def _check(wide, narrow, want, what):
     assert np.array_equal(ffsynth.f16_round(wide.astype(np.float32)).astype(np.float64), narrow), what
 
 
-@pytest.mark.parametrize("i,G,variants", [(2, 32, (0, 1, 10)), (2, 64, (0, 2, 6, 7, 11)), (2, 100, (0, 4, 9)),
+@pytest.mark.parametrize("i,G,variants", [(2, 32, (0, 1, 10)), (2, 64, (0, 2, 6, 7, 11, 12)), (2, 100, (0, 4, 9)),
                                           (5, 64, (0, 2, 5)), (5, 69, (0, 3, 6)), (5, 128, (0, 4))])
 def test_fused_kernel_mappings(cfg, i, G, variants):
     c = cfg(i, 1)

@@ -153,7 +153,7 @@ def test_bf16_group_sizes_and_tails(cfg, G):
     assert np.abs(plain - want).max() <= 2e-2
     assert torch.equal(packed, narrow)                      # pre-packed weights change nothing
     # every wave-to-group mapping that can hold G
-    for variant, slots in [(1, 32), (2, 64), (4, 128), (6, 64), (7, 64), (9, 128), (10, 32), (11, 64)]:
+    for variant, slots in [(1, 32), (2, 64), (4, 128), (6, 64), (7, 64), (9, 128), (10, 32), (11, 64), (12, 64)]:
         fl = ff.FF_FLAG_OUT_F32 | ff.FF_FLAG_VARIANT(variant)
         if G > slots:
             with pytest.raises(ff.FlatformerError):
@@ -218,3 +218,56 @@ def test_fp32_many_rows(cfg, C, F, heads, G):
     err_pe = np.abs(got_pe - oracle.layer(feats, perm, off, p, pos_embed=pe)).max()
     print(f"fp32 n={n} C={C} F={F} heads={heads} G={G}: max abs err {err:.2e}, with embedding {err_pe:.2e}", flush=True)
     assert err <= 1e-4 and err_pe <= 1e-4
+
+
+def test_many_groups_take_the_wider_mappings(cfg):
+    """A batch of four frames (1,876 groups of 64): the library then picks four groups per workgroup.  Every G <= 64
+    mapping gives the same bits; sampled groups, every frame's short tail among them, are held against the
+    oracle; the block (features chained in sorted order across frames) equals its layer calls under the
+    two-group mapping."""
+    c = cfg(2)
+    B, n1, G = 4, c["n"], c["G"]
+    rng = np.random.default_rng(41)
+    coords = np.tile(c["coords"], (B, 1))
+    coords[:, 0] = np.repeat(np.arange(B, dtype=np.int32), n1)
+    shift = rng.integers(0, c["grid"], size=(B, 2))
+    coords[:, 1:] = (coords[:, 1:] + np.repeat(shift, n1, axis=0)) % c["grid"]
+    coords = np.ascontiguousarray(coords[rng.permutation(B * n1)])
+    n = coords.shape[0]
+    feats = ffsynth.bf16_round(rng.standard_normal((n, c["C"])).astype(np.float32)).astype(np.float64)
+    g = ff.Geometry(B, c["grid"], c["grid"], c["window"], c["window"])
+    og = oracle.Geometry(B, c["grid"], c["grid"], c["window"], c["window"])
+    p = c["layer_params"][0]
+    perm, off, ng, _, dev = gpu_flatten(coords, g, 1, 1, G, want_keys=False)
+    o_perm, o_off, _ = oracle.flatten(coords, og, 1, 1, G)
+    assert np.array_equal(perm, o_perm) and np.array_equal(off, o_off)
+    lw = ff.LayerWeights(p, ff.FF_BF16, DEV).pack()
+    x = to_dev_feats(feats, ff.FF_BF16)
+    mg = -(-n // G) + B
+    outs = {}
+    for v in (0, 7, 11, 12):
+        print(f"{ng} groups, mapping {v}", flush=True)
+        outs[v] = ff.ff_group_attention(x, dev[0], dev[1], dev[2], mg, lw, G, ff.FF_BF16,
+                                        ff.FF_FLAG_OUT_F32 | ff.FF_FLAG_VARIANT(v))
+    torch.cuda.synchronize()
+    for v in (0, 11, 12):
+        assert torch.equal(outs[v], outs[7]), v
+    sizes = np.diff(o_off)
+    short = np.flatnonzero(sizes < G)
+    assert len(short) == B                                   # one short tail per frame
+    pick = np.unique(np.concatenate([short, rng.choice(ng, 40, replace=False), [0, ng - 1]]))
+    got = to_host(outs[0])
+    for k in pick:
+        rows = o_perm[o_off[k]:o_off[k + 1]]
+        want = oracle.group_layer(feats[rows], p)
+        assert np.abs(got[rows] - want).max() <= 2e-2, k
+    # the block on the same batch: its layers run under the automatic choice, in sorted order
+    layers = [ff.LayerWeights(q, ff.FF_BF16, DEV) for q in c["layer_params"]]
+    ct = torch.from_numpy(coords).to(DEV)
+    blk = ff.ff_fwa_block(ct, g, G, layers, ff.FF_BF16, x)
+    cur = x
+    for l, key in enumerate(c["schedule"]):
+        pm, go, nn, _ = ff.ff_flatten(ct, g, key[0], key[1], G)
+        cur = ff.ff_group_attention(cur, pm, go, nn, mg, layers[l], G, ff.FF_BF16, ff.FF_FLAG_VARIANT(7))
+    torch.cuda.synchronize()
+    assert torch.equal(blk, cur)

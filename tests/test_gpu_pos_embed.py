@@ -41,7 +41,7 @@ def test_fp32_layers_and_block(cfg):
     assert np.abs(to_host(out) - trace[-1]).max() <= 1e-4
 
 
-@pytest.mark.parametrize("i,G,variants", [(2, 32, (0, 10)), (2, 64, (0, 2, 6, 7)), (2, 100, (0, 4, 9)),
+@pytest.mark.parametrize("i,G,variants", [(2, 32, (0, 10)), (2, 64, (0, 2, 6, 7, 12)), (2, 100, (0, 4, 9)),
                                           (5, 64, (0, 2, 5)), (5, 69, (0, 6)), (5, 128, (0, 4))])
 def test_bf16_fused_kernel(cfg, i, G, variants):
     c = dict(cfg(i, 1))
