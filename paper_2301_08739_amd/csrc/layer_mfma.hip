@@ -167,7 +167,11 @@ struct LdsPlan {
   static constexpr int KVX = WPG > 1 ? 2 * GPW * KVX_ONE : 0;              // double buffered
   static constexpr int NCHUNK = ((C / 32) * (6 * (C / 32) + C / 16) + (F / 32) * (2 * (C / 32) + C / 16)) / chunk_frags(C);
   static constexpr int FIT = (kLdsBytes / WGS - PARAMS - KVX) / (chunk_frags(C) * 1024);
-  static constexpr int RING = FIT < NCHUNK ? FIT : NCHUNK;
+  static constexpr int RING0 = FIT < NCHUNK ? FIT : NCHUNK;
+  // Mappings with rolled loops (more than two wavefronts per SIMD at C = 128) compute ring slots at run time: a
+  // power of two keeps that to a mask.
+  static constexpr bool ROLLED_128 = C == 128 && NW > 8;
+  static constexpr int RING = ROLLED_128 && RING0 >= 4 && RING0 < 8 ? 4 : RING0;
   static constexpr int TOTAL = RING * chunk_frags(C) * 1024 + PARAMS + KVX;
   static_assert(RING >= 2, "weight ring");
 };
@@ -194,7 +198,11 @@ __global__ __launch_bounds__(NW * 64, MINW) void k_layer_mfma(const uint16_t* __
   constexpr int CPH = FH / CF, CPF = FF / CF;
   // C = 128: the unit loops are unrolled completely, which turns the ring bookkeeping into constants
   // (about 30 KB of code).  Wider layers keep rolled loops.
-  constexpr int FULL_UNROLL = C <= 128 && NW <= 8 ? 16 : 1;  // more waves per SIMD leave too few registers for it
+  constexpr int FULL_UNROLL = C <= 128 && NW <= 8 ? 16 : 1;  // more waves per SIMD leave too few registers for it:
+  // with three or four, the hidden units are still unrolled completely (their chunk numbers and ring slots become
+  // constants) and the head-dim units in pairs (the ring of four slots repeats every two units)
+  constexpr int FFN_UNROLL = C <= 128 && MINW >= 3 ? 16 : FULL_UNROLL;
+  constexpr int ATT_UNROLL = C <= 128 && MINW >= 3 ? 2 : FULL_UNROLL;
   constexpr bool LEAN = ((NW + 3) / 4 >= 3 && MINW <= 2 && C >= 256) || MINW >= 4;  // C = 256 with three wavefronts on a SIMD
                                                                               // (168 registers each), C = 128 with four (128)
   constexpr int PF = LEAN ? 4 : kWindow;
@@ -618,7 +626,7 @@ __global__ __launch_bounds__(NW * 64, MINW) void k_layer_mfma(const uint16_t* __
   const bool short_group = m > 0 && m < NKB * 16;
 
   // ---- attention: one 32-wide head-dim unit per iteration (two heads of 16 or one head of 32) --------
-#pragma unroll FULL_UNROLL
+#pragma unroll ATT_UNROLL
   for (int hp = 0; hp < HP; ++hp) {
     const int c0 = hp * CPH;
     const u32x4* pb[CPH + 1];
@@ -849,7 +857,7 @@ __global__ __launch_bounds__(NW * 64, MINW) void k_layer_mfma(const uint16_t* __
   if (!LEAN) load_b1(0);
   layer_norm(PO::LN2G, PO::LN2B, false);
   add_bias_rows(PO::B2);
-#pragma unroll FULL_UNROLL
+#pragma unroll FFN_UNROLL
   for (int fc = 0; fc < FC; ++fc) {
     const int c0 = HP * CPH + fc * CPF;
     const u32x4* pb[CPF + 1];
@@ -1045,14 +1053,14 @@ int FF_LAYER_SYM(layer_mfma_launch)(const void* feats, void* out, int64_t n, con
     if (variant == 0) {
       // G <= 64: two, three or four groups per workgroup (8, 12, 16 wavefronts; one workgroup per compute unit).
       // More wavefronts on a SIMD hide more of each other's stalls, but a round (one workgroup per compute
-      // unit) takes longer and the loops are no longer unrolled: 16.4, 24.0 and 29.3 us a round at this shape.
-      // Many rounds: four groups lead (60,000 groups: 1.77, 1.69, 1.60 ms); few: the number of rounds decides
-      // (measured, in us: 938 groups 34 / 47 / 31, 1407: 49 / 51 / 59, 1875: 65 / 73 / 60, 2344: 81 / 94 / 86,
-      // 3750: 130 / 129 / 119, 7500: 255 / 240 / 228).
+      // unit) takes longer and the attention loop is no longer unrolled completely: 16.4, 23.2 and 28.8 us a
+      // round at this shape.  Many rounds: four groups lead (60,000 groups: 1.76, 1.61, 1.56 ms); few: the
+      // number of rounds decides (measured, in us: 938 groups 33 / 44 / 30, 1407: 49 / 48 / 56, 1875: 65 / 69 /
+      // 60, 2344: 81 / 89 / 81, 3750: 128 / 120 / 115, 7500: 256 / 228 / 219, 15,000: 477 / 419 / 390).
       auto rounds = [&](int per_wg) { return ceil_div(ceil_div((int64_t)max_groups, per_wg), kComputeUnits); };
-      const int64_t c2 = rounds(2) * 164, c4 = rounds(4) * 293;
+      const int64_t c2 = rounds(2) * 164, c4 = rounds(4) * 288;
       // (the three-group mapping has no registers for a positional embedding)
-      const int64_t c3 = w->pos_embed ? INT64_MAX : rounds(3) * 240;
+      const int64_t c3 = w->pos_embed ? INT64_MAX : rounds(3) * 232;
       variant = G <= 32 ? 10 : G > 64 ? 9 : (c2 <= c3 && c2 <= c4) ? 7 : c3 <= c4 ? 11 : 12;
     }
     switch (variant) {
