@@ -271,3 +271,26 @@ def test_many_groups_take_the_wider_mappings(cfg):
         cur = ff.ff_group_attention(cur, pm, go, nn, mg, layers[l], G, ff.FF_BF16, ff.FF_FLAG_VARIANT(7))
     torch.cuda.synchronize()
     assert torch.equal(blk, cur)
+
+
+def test_one_large_frame_chains_in_sorted_order_under_the_four_group_mapping(cfg):
+    """One frame of 60,000 pillars (938 groups: the four-group mapping is chosen) through ff_fwa_block: the layers
+    after the first read their rows from the guessed group start; the result equals the layer calls under the
+    two-group mapping in pillar order."""
+    c = cfg(2)
+    n, G = 60000, c["G"]
+    coords = ffsynth.unique_uniform_cells(n, c["grid"], 77)
+    rng = np.random.default_rng(78)
+    x = to_dev_feats(rng.standard_normal((n, c["C"])).astype(np.float32), ff.FF_BF16)
+    g = ff.Geometry(1, c["grid"], c["grid"], c["window"], c["window"])
+    ct = torch.from_numpy(coords).to(DEV)
+    layers = [ff.LayerWeights(q, ff.FF_BF16, DEV) for q in c["layer_params"]]
+    print(f"n={n}: {-(-n // G)} groups", flush=True)
+    blk = ff.ff_fwa_block(ct, g, G, layers, ff.FF_BF16, x)
+    cur = x
+    for l, key in enumerate(c["schedule"]):
+        pm, go, nn, _ = ff.ff_flatten(ct, g, key[0], key[1], G)
+        cur = ff.ff_group_attention(cur, pm, go, nn, -(-n // G) + 1, layers[l], G, ff.FF_BF16, ff.FF_FLAG_VARIANT(7))
+    torch.cuda.synchronize()
+    assert torch.isfinite(blk.float()).all()
+    assert torch.equal(blk, cur)
